@@ -1,0 +1,237 @@
+/*
+ * dsk.h -- C ABI of the DynSplit-KV hot path for AMD MI355X (gfx950).
+ *
+ * Three calls make up the path:
+ *   dsk_compress            KV-cache compression pass: delimiter candidates, delimiter
+ *                           importance (Alg. 1, Sec. 3), DD-Select segmentation (Sec. 4.1),
+ *                           variable-to-fixed slot map and min/max block summaries (Sec. 4.2).
+ *   dsk_select_topk         per decode step: query x block-summary scores, top-k over the
+ *                           block-to-slot mapped scores (Sec. 4.2; App. B.2 Step 1).
+ *   dsk_sparse_decode_attn  per decode step: attention over the K/V of the selected slots
+ *                           (App. B.2 Steps 2-3).
+ *
+ * Conventions that hold for every call
+ *   - Pointers marked [dev] are device (HBM) addresses, [host] are host addresses.
+ *     The caller owns every buffer; the library allocates nothing, frees nothing and
+ *     keeps no pointer after the call returns.  Scratch memory comes from the
+ *     caller-provided `workspace` ([dev], 256-byte aligned) whose size the matching
+ *     *_workspace_bytes() query reports for the same argument struct.
+ *   - All work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to
+ *     void*; NULL is the default stream).  No call synchronises the device.
+ *   - Argument validation is synchronous and happens before anything is enqueued: a
+ *     negative dsk_status means nothing was launched.  Data-dependent problems found on
+ *     the device (block capacity exceeded, bad per-sequence parameters) are written to
+ *     the `dev_status` word ([dev], optional) as a dsk_status value; outputs are then
+ *     truncated but every kernel still terminates.
+ *   - Tokens of a ragged batch are flattened: sequence s owns global token positions
+ *     cu_seqlens[s] .. cu_seqlens[s+1]-1.  Block boundaries, slot numbers and selected
+ *     token spans are all expressed in these global coordinates.
+ *   - K, V, q and summaries are bf16 (raw 16-bit patterns), head_dim D must be 128.
+ *   - Same inputs give bit-identical outputs (fixed reduction orders, no float atomics).
+ *   - Non-finite K/V/q values give unspecified results but never hang.
+ */
+#ifndef DSK_H_
+#define DSK_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DSK_ABI_VERSION 1u
+#define DSK_HEAD_DIM 128
+#define DSK_MAX_CLASSES 64
+
+typedef enum dsk_status {
+  DSK_OK = 0,
+  DSK_ERR_NULL = -1,      /* a required pointer is NULL */
+  DSK_ERR_SHAPE = -2,     /* B, heads, D, lengths or strides are not usable */
+  DSK_ERR_PARAM = -3,     /* C, delta, alpha, b, budget, M, W, R out of range */
+  DSK_ERR_ALIGN = -4,     /* K/V/q/summary/workspace pointer or stride not 16-byte aligned */
+  DSK_ERR_WORKSPACE = -5, /* workspace missing or smaller than *_workspace_bytes() */
+  DSK_ERR_CAPACITY = -6,  /* more blocks/candidates produced than the outputs can hold */
+  DSK_ERR_LAUNCH = -7,    /* the HIP runtime refused a launch */
+  DSK_ERR_VERSION = -8    /* struct_size does not match this library */
+} dsk_status;
+
+/* Stages of dsk_compress (bit mask).  A stage that is not run takes its inputs from the
+ * buffers the earlier stage would have written. */
+enum {
+  DSK_STAGE_CANDIDATES = 1, /* token_ids + delim_ids -> cand_pos/cand_class/cand_cu (+ samp_pos) */
+  DSK_STAGE_IMPORTANCE = 2, /* samp_pos + qwin + K -> class_weight_q (Alg. 1) */
+  DSK_STAGE_SEGMENT = 4,    /* candidates + class_weight_q -> block_start/cu_blocks/slot_base */
+  DSK_STAGE_SUMMARIES = 8,  /* block_start + K (+V) -> ksum (+vsum) */
+  DSK_STAGE_ALL = 15
+};
+
+/* ------------------------------------------------------------------------------------------
+ * dsk_compress -- the compression pass.
+ *
+ * Stage CANDIDATES (input set D of Alg. 1; the semantic boundary tokens of Sec. 4.1):
+ *   every token whose id is in delim_ids is a candidate; its class is the index of the id
+ *   in delim_ids.  Output lists are ascending in global position.  Also chooses the
+ *   sampled candidates for Alg. 1: per sequence and class the first M occurrences whose
+ *   sequence-local position t satisfies R <= t <= L-1-W.
+ * Stage IMPORTANCE (Alg. 1 and the equation of Sec. 3, on the one layer given):
+ *   for each sampled candidate t, each query head and each of the W queries following t,
+ *   the causal softmax row over keys 0..q is split into the retained region
+ *   {max(0,t-R+1)..t} and the discarded region {0..max(0,t-R)};
+ *   s_t = mean(retained mass - alpha_imp * discarded mass).  Class means are mapped to
+ *   [0,1] by (mean + alpha_imp) / (1 + alpha_imp), clamped, and rounded half-up to tenths.
+ *   Classes without a sample keep the value already in class_weight_q.
+ * Stage SEGMENT (Sec. 4.1, Dynamic Segmentation Procedure; Sec. 4.2 variable-to-fixed map):
+ *   a candidate at position t offers the boundary e = t+1.  From s_c (0 at first):
+ *   s_e = s_c + C; if s_e >= L the last chunk ends at L; else the offered boundary in
+ *   [s_e-delta, min(L, s_e+delta)] maximising
+ *       alpha_num*wq*D' + (alpha_den-alpha_num)*10*(D' - |e-s_e|),  D' = max(delta,1)
+ *   (ties: smallest e) ends the chunk, or s_e if none is offered.  Integer arithmetic.
+ *   Block i of the batch covers [block_start[i], block_start[i+1]); it owns the
+ *   ceil(len/b) slots slot_base[i] .. slot_base[i+1]-1, each b tokens, the last one
+ *   possibly shorter.
+ * Stage SUMMARIES (Sec. 4.2, KVCache Compression): element-wise minimum and maximum of K
+ *   (and of V when vsum != NULL) over the tokens of every block, exact in bf16.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct dsk_compress_args {
+  uint32_t struct_size;        /* sizeof(dsk_compress_args) */
+  uint32_t stages;             /* DSK_STAGE_* mask */
+
+  /* geometry */
+  int32_t B;                   /* sequences, >= 1 */
+  int32_t Hq, Hkv, D;          /* query heads, KV heads (Hq % Hkv == 0), head dim (128) */
+  int32_t total_tokens;        /* [host copy] cu_seqlens[B] */
+  int32_t max_seqlen;          /* [host copy] max_s (cu_seqlens[s+1]-cu_seqlens[s]) */
+  const int32_t* cu_seqlens;   /* [dev] [B+1], non-decreasing, cu_seqlens[0] == 0 */
+
+  /* KV cache, bf16; element strides; dim stride is 1.  V may be NULL when vsum is NULL. */
+  const void* K;               /* [dev] K[h*k_stride_head + t*k_stride_tok + d] */
+  const void* V;               /* [dev] */
+  int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head; /* multiples of 8 */
+
+  /* candidates */
+  const int32_t* token_ids;    /* [dev] [total_tokens]            (stage CANDIDATES in) */
+  const int32_t* delim_ids;    /* [dev] [n_class] distinct ids    (stage CANDIDATES in) */
+  int32_t n_class;             /* 1..DSK_MAX_CLASSES */
+  int32_t max_cand_total;      /* capacity of cand_pos / cand_class */
+  int32_t* cand_pos;           /* [dev] [max_cand_total] global positions, ascending (out of
+                                  CANDIDATES, in of SEGMENT) */
+  uint8_t* cand_class;         /* [dev] [max_cand_total] */
+  int32_t* cand_cu;            /* [dev] [B+1] candidate range of each sequence */
+
+  /* importance */
+  int32_t M, W, R;             /* samples per class (<= 64), future window, retained size */
+  float alpha_imp;             /* penalty on discarded mass (paper: 1) */
+  float imp_scale;             /* logit scale; 0 -> D^-1/2 */
+  int32_t* samp_pos;           /* [dev] [B, n_class, M] global position or -1 (out of
+                                  CANDIDATES, in of IMPORTANCE) */
+  const void* qwin;            /* [dev] bf16 [B, n_class*M, W, Hq, D]: qwin[s, c*M+m, w, h, :]
+                                  is the query of head h at position samp_pos[s,c,m]+1+w */
+  uint8_t* class_weight_q;     /* [dev] [B, n_class] weights in tenths, 0..10 (in/out) */
+  float* class_mean;           /* [dev] [B, n_class] optional out: class mean score, NaN if
+                                  the class had no sample */
+  float* samp_score;           /* [dev] [B, n_class, M] optional out: s_t per sample */
+
+  /* segmentation */
+  int32_t C, delta;            /* base chunk size, max deviation: C >= 1, 0 <= delta < C,
+                                  C + delta <= 8192.  With per-sequence arrays these are
+                                  upper bounds of the per-sequence values. */
+  const int32_t* C_per_seq;    /* [dev] [B] or NULL */
+  const int32_t* delta_per_seq;/* [dev] [B] or NULL */
+  int32_t alpha_num, alpha_den;/* alpha_sel = alpha_num/alpha_den in [0,1], alpha_den in 1..1000 */
+  int32_t b;                   /* fixed mapped block (slot) length, 1..1024 */
+  int32_t max_blocks_total;    /* capacity (in blocks) of the outputs below */
+  int32_t* block_start;        /* [dev] [max_blocks_total+1] */
+  int32_t* cu_blocks;          /* [dev] [B+1] block range of each sequence */
+  int32_t* slot_base;          /* [dev] [max_blocks_total+1] */
+
+  /* summaries: [Hkv, max_blocks_total, 2, D] bf16; [.., 0, :] = min, [.., 1, :] = max */
+  void* ksum;                  /* [dev] */
+  void* vsum;                  /* [dev] or NULL */
+
+  int32_t* dev_status;         /* [dev] optional; must be zeroed by the caller */
+  void* workspace;             /* [dev] */
+  size_t workspace_bytes;
+} dsk_compress_args;
+
+/* ------------------------------------------------------------------------------------------
+ * dsk_select_topk -- block scores and slot top-k for one decode step.
+ *
+ *   score[hq, i] = sum_d max(q_d*kmax[hk,i,d], q_d*kmin[hk,i,d]),  hk = hq / (Hq/Hkv)
+ *   (Sec. 4.2 "query-compressed vector product" for a (min,max) summary), fp32 accumulate.
+ *   Every slot inherits its block's score (Sec. 4.2 block-to-token mapping at slot
+ *   granularity; b = 1 is the token-level mapping).  Per (sequence, query head) the
+ *   min(k, slots of the sequence) best slots are selected, k = budget / b, ranked by
+ *   (score descending, slot index ascending), and returned in ascending slot order.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct dsk_select_args {
+  uint32_t struct_size;
+  int32_t B, Hq, Hkv, D;
+  int32_t max_blocks_total;    /* capacity used when ksum / block tables were allocated */
+  const int32_t* cu_blocks;    /* [dev] [B+1] */
+  const int32_t* block_start;  /* [dev] */
+  const int32_t* slot_base;    /* [dev] */
+  const void* ksum;            /* [dev] bf16 [Hkv, max_blocks_total, 2, D] */
+  const void* q;               /* [dev] bf16 [B, Hq, D] */
+  int32_t b;                   /* slot length used by dsk_compress */
+  int32_t budget;              /* token budget per sequence; k = budget / b >= 1 */
+  int32_t* sel_slot;           /* [dev] [B, Hq, k] global slot index, ascending; -1 padding */
+  int32_t* sel_start;          /* [dev] [B, Hq, k] first global token of the slot */
+  int32_t* sel_len;            /* [dev] [B, Hq, k] tokens in the slot (1..b); 0 padding */
+  int32_t* sel_count;          /* [dev] [B, Hq] number of selected slots */
+  float* scores;               /* [dev] optional out [Hq, max_blocks_total] block scores */
+  void* workspace;             /* [dev] */
+  size_t workspace_bytes;
+} dsk_select_args;
+
+/* ------------------------------------------------------------------------------------------
+ * dsk_sparse_decode_attn -- attention of one decode query per (sequence, head) over the
+ * tokens of the selected slots (App. B.2 Steps 2-3):
+ *   z_t = q.K[hk,t] * scale;  out = sum_t softmax(z)_t V[hk,t];  lse = log sum_t exp(z_t)
+ * fp32 accumulation, split over slots with an online-softmax merge in a fixed order.
+ * A (sequence, head) with no selected token gets out = 0 and lse = -inf.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct dsk_attn_args {
+  uint32_t struct_size;
+  int32_t B, Hq, Hkv, D;
+  const void* q;               /* [dev] bf16 [B, Hq, D] */
+  const void* K;               /* [dev] bf16, strides as in dsk_compress_args */
+  const void* V;               /* [dev] */
+  int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;
+  int32_t total_tokens;        /* [host] tokens per head in K/V; spans outside it are skipped */
+  int32_t k;                   /* slots per (sequence, head) in the sel_* arrays */
+  int32_t b;                   /* upper bound of sel_len entries */
+  const int32_t* sel_start;    /* [dev] [B, Hq, k] */
+  const int32_t* sel_len;      /* [dev] [B, Hq, k] */
+  const int32_t* sel_count;    /* [dev] [B, Hq] */
+  float scale;                 /* 0 -> D^-1/2 */
+  float* out;                  /* [dev] f32 [B, Hq, D] */
+  float* lse;                  /* [dev] f32 [B, Hq], natural log; may be NULL */
+  void* workspace;             /* [dev] */
+  size_t workspace_bytes;
+} dsk_attn_args;
+
+/* Library / ABI version (DSK_ABI_VERSION of the build). */
+uint32_t dsk_version(void);
+
+/* Static, human-readable text for a status code. */
+const char* dsk_strerror(int32_t status);
+
+/* Upper bound on the number of blocks DD-Select can emit for a batch of B sequences with
+ * total_tokens tokens when every non-final chunk has at least min_chunk = C - delta tokens
+ * (Sec. 4.1): floor(total_tokens / min_chunk) + B.  Returns -1 on bad arguments. */
+int64_t dsk_block_capacity(int32_t total_tokens, int32_t B, int32_t min_chunk);
+
+/* Workspace sizes in bytes for the given arguments (0 on invalid geometry). */
+size_t dsk_compress_workspace_bytes(const dsk_compress_args* args);
+size_t dsk_select_workspace_bytes(const dsk_select_args* args);
+size_t dsk_attn_workspace_bytes(const dsk_attn_args* args);
+
+dsk_status dsk_compress(const dsk_compress_args* args, void* stream);
+dsk_status dsk_select_topk(const dsk_select_args* args, void* stream);
+dsk_status dsk_sparse_decode_attn(const dsk_attn_args* args, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSK_H_ */

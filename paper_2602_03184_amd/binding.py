@@ -1,0 +1,398 @@
+"""ctypes binding of libdsk.so: argument marshalling only.
+
+`dsk_compress`, `dsk_select_topk` and `dsk_sparse_decode_attn` take the same argument
+structs as the C ABI (include/dsk.h) and a HIP stream handle; every step of the path runs in
+the HIP kernels.  The helpers below them only allocate device buffers with torch and fill
+the structs.  There is no CPU fallback: importing this module without a built libdsk.so
+raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libdsk.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libdsk.so is not built (%s). Run `python -m paper_2602_03184_amd.build` first; "
+        "the DynSplit-KV path has no fallback implementation." % LIB_PATH)
+_lib = C.CDLL(LIB_PATH)
+
+# ---- status codes / stages (mirror include/dsk.h) ------------------------------------------
+DSK_OK = 0
+DSK_ERR_NULL, DSK_ERR_SHAPE, DSK_ERR_PARAM, DSK_ERR_ALIGN = -1, -2, -3, -4
+DSK_ERR_WORKSPACE, DSK_ERR_CAPACITY, DSK_ERR_LAUNCH, DSK_ERR_VERSION = -5, -6, -7, -8
+DSK_STAGE_CANDIDATES, DSK_STAGE_IMPORTANCE, DSK_STAGE_SEGMENT, DSK_STAGE_SUMMARIES = 1, 2, 4, 8
+DSK_STAGE_ALL = 15
+DSK_HEAD_DIM = 128
+DSK_MAX_CLASSES = 64
+
+_p = C.c_void_p
+
+
+class dsk_compress_args(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("stages", C.c_uint32),
+        ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+        ("total_tokens", C.c_int32), ("max_seqlen", C.c_int32),
+        ("cu_seqlens", _p),
+        ("K", _p), ("V", _p),
+        ("k_stride_tok", C.c_int64), ("k_stride_head", C.c_int64),
+        ("v_stride_tok", C.c_int64), ("v_stride_head", C.c_int64),
+        ("token_ids", _p), ("delim_ids", _p),
+        ("n_class", C.c_int32), ("max_cand_total", C.c_int32),
+        ("cand_pos", _p), ("cand_class", _p), ("cand_cu", _p),
+        ("M", C.c_int32), ("W", C.c_int32), ("R", C.c_int32),
+        ("alpha_imp", C.c_float), ("imp_scale", C.c_float),
+        ("samp_pos", _p), ("qwin", _p), ("class_weight_q", _p), ("class_mean", _p), ("samp_score", _p),
+        ("C", C.c_int32), ("delta", C.c_int32),
+        ("C_per_seq", _p), ("delta_per_seq", _p),
+        ("alpha_num", C.c_int32), ("alpha_den", C.c_int32),
+        ("b", C.c_int32), ("max_blocks_total", C.c_int32),
+        ("block_start", _p), ("cu_blocks", _p), ("slot_base", _p),
+        ("ksum", _p), ("vsum", _p),
+        ("dev_status", _p),
+        ("workspace", _p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
+class dsk_select_args(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+        ("max_blocks_total", C.c_int32),
+        ("cu_blocks", _p), ("block_start", _p), ("slot_base", _p),
+        ("ksum", _p), ("q", _p),
+        ("b", C.c_int32), ("budget", C.c_int32),
+        ("sel_slot", _p), ("sel_start", _p), ("sel_len", _p), ("sel_count", _p),
+        ("scores", _p),
+        ("workspace", _p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
+class dsk_attn_args(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+        ("q", _p), ("K", _p), ("V", _p),
+        ("k_stride_tok", C.c_int64), ("k_stride_head", C.c_int64),
+        ("v_stride_tok", C.c_int64), ("v_stride_head", C.c_int64),
+        ("total_tokens", C.c_int32), ("k", C.c_int32), ("b", C.c_int32),
+        ("sel_start", _p), ("sel_len", _p), ("sel_count", _p),
+        ("scale", C.c_float),
+        ("out", _p), ("lse", _p),
+        ("workspace", _p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
+_lib.dsk_version.restype = C.c_uint32
+_lib.dsk_version.argtypes = []
+_lib.dsk_strerror.restype = C.c_char_p
+_lib.dsk_strerror.argtypes = [C.c_int32]
+_lib.dsk_block_capacity.restype = C.c_int64
+_lib.dsk_block_capacity.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+for _name, _cls in (("compress", dsk_compress_args), ("select", dsk_select_args), ("attn", dsk_attn_args)):
+    _f = getattr(_lib, "dsk_%s_workspace_bytes" % _name)
+    _f.restype = C.c_size_t
+    _f.argtypes = [C.POINTER(_cls)]
+_lib.dsk_compress.restype = C.c_int32
+_lib.dsk_compress.argtypes = [C.POINTER(dsk_compress_args), _p]
+_lib.dsk_select_topk.restype = C.c_int32
+_lib.dsk_select_topk.argtypes = [C.POINTER(dsk_select_args), _p]
+_lib.dsk_sparse_decode_attn.restype = C.c_int32
+_lib.dsk_sparse_decode_attn.argtypes = [C.POINTER(dsk_attn_args), _p]
+
+
+class DskError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (what, dsk_strerror(status), status))
+
+
+# ---- the C ABI, same names -------------------------------------------------------------------
+def dsk_version() -> int:
+    return int(_lib.dsk_version())
+
+
+def dsk_strerror(status: int) -> str:
+    return _lib.dsk_strerror(int(status)).decode()
+
+
+def dsk_block_capacity(total_tokens: int, B: int, min_chunk: int) -> int:
+    return int(_lib.dsk_block_capacity(total_tokens, B, min_chunk))
+
+
+def dsk_compress_workspace_bytes(args: dsk_compress_args) -> int:
+    return int(_lib.dsk_compress_workspace_bytes(C.byref(args)))
+
+
+def dsk_select_workspace_bytes(args: dsk_select_args) -> int:
+    return int(_lib.dsk_select_workspace_bytes(C.byref(args)))
+
+
+def dsk_attn_workspace_bytes(args: dsk_attn_args) -> int:
+    return int(_lib.dsk_attn_workspace_bytes(C.byref(args)))
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def dsk_compress(args: dsk_compress_args, stream=None, check: bool = True) -> int:
+    st = int(_lib.dsk_compress(C.byref(args), _stream_handle(stream)))
+    if check and st != DSK_OK:
+        raise DskError(st, "dsk_compress")
+    return st
+
+
+def dsk_select_topk(args: dsk_select_args, stream=None, check: bool = True) -> int:
+    st = int(_lib.dsk_select_topk(C.byref(args), _stream_handle(stream)))
+    if check and st != DSK_OK:
+        raise DskError(st, "dsk_select_topk")
+    return st
+
+
+def dsk_sparse_decode_attn(args: dsk_attn_args, stream=None, check: bool = True) -> int:
+    st = int(_lib.dsk_sparse_decode_attn(C.byref(args), _stream_handle(stream)))
+    if check and st != DSK_OK:
+        raise DskError(st, "dsk_sparse_decode_attn")
+    return st
+
+
+# ---- marshalling helpers ---------------------------------------------------------------------
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    # torch's caching allocator hands out 512-byte aligned blocks
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def _kv_strides(X: torch.Tensor):
+    """X: bf16 [Hkv, tokens, D] view (any head/token strides, unit channel stride)."""
+    assert X.dim() == 3 and X.stride(2) == 1 and X.dtype == torch.bfloat16
+    return X.stride(1), X.stride(0)
+
+
+@dataclass
+class Compressed:
+    """Device buffers written by dsk_compress plus the geometry they were sized for."""
+    B: int
+    Hq: int
+    Hkv: int
+    b: int
+    total_tokens: int
+    max_blocks_total: int
+    cu_seqlens: torch.Tensor
+    block_start: torch.Tensor
+    cu_blocks: torch.Tensor
+    slot_base: torch.Tensor
+    ksum: Optional[torch.Tensor]
+    vsum: Optional[torch.Tensor]
+    cand_pos: Optional[torch.Tensor]
+    cand_class: Optional[torch.Tensor]
+    cand_cu: Optional[torch.Tensor]
+    samp_pos: Optional[torch.Tensor]
+    class_weight_q: Optional[torch.Tensor]
+    class_mean: Optional[torch.Tensor]
+    samp_score: Optional[torch.Tensor]
+    dev_status: torch.Tensor
+    args: dsk_compress_args
+    keep: tuple
+
+
+def compress(*, cu_seqlens: torch.Tensor, max_seqlen: int, Hq: int, K: Optional[torch.Tensor],
+             V: Optional[torch.Tensor] = None, stages: int = DSK_STAGE_SEGMENT | DSK_STAGE_SUMMARIES,
+             token_ids: Optional[torch.Tensor] = None, delim_ids: Optional[torch.Tensor] = None,
+             n_class: int = 16, cand_pos: Optional[torch.Tensor] = None,
+             cand_class: Optional[torch.Tensor] = None, cand_cu: Optional[torch.Tensor] = None,
+             max_cand_total: Optional[int] = None,
+             M: int = 0, W: int = 8, R: int = 128, alpha_imp: float = 1.0, imp_scale: float = 0.0,
+             samp_pos: Optional[torch.Tensor] = None, qwin: Optional[torch.Tensor] = None,
+             class_weight_q: Optional[torch.Tensor] = None,
+             C_: int = 32, delta: int = 16, C_per_seq: Optional[torch.Tensor] = None,
+             delta_per_seq: Optional[torch.Tensor] = None, min_chunk: Optional[int] = None,
+             alpha_num: int = 5, alpha_den: int = 10, b: int = 16,
+             max_blocks_total: Optional[int] = None, block_start: Optional[torch.Tensor] = None,
+             cu_blocks: Optional[torch.Tensor] = None, slot_base: Optional[torch.Tensor] = None,
+             want_vsum: bool = False, Hkv: Optional[int] = None, total_tokens: Optional[int] = None,
+             stream=None, check: bool = True) -> Compressed:
+    """Allocate outputs / workspace with torch, fill dsk_compress_args and call dsk_compress.
+
+    `total_tokens` defaults to the token extent of K (or of token_ids).  Buffers a skipped
+    stage would have produced must be passed in."""
+    dev = cu_seqlens.device
+    B = cu_seqlens.numel() - 1
+    if Hkv is None:
+        Hkv = K.shape[0]
+    if total_tokens is None:
+        total_tokens = K.shape[1] if K is not None else token_ids.numel()
+    a = dsk_compress_args()
+    a.struct_size = C.sizeof(dsk_compress_args)
+    a.stages = stages
+    a.B, a.Hq, a.Hkv, a.D = B, Hq, Hkv, DSK_HEAD_DIM
+    a.total_tokens, a.max_seqlen = total_tokens, max_seqlen
+    a.cu_seqlens = _ptr(cu_seqlens)
+    if K is not None:
+        a.K = _ptr(K)
+        a.k_stride_tok, a.k_stride_head = _kv_strides(K)
+    if V is not None:
+        a.V = _ptr(V)
+        a.v_stride_tok, a.v_stride_head = _kv_strides(V)
+    a.token_ids, a.delim_ids = _ptr(token_ids), _ptr(delim_ids)
+    a.n_class = n_class
+    i32 = dict(dtype=torch.int32, device=dev)
+    if max_cand_total is None:
+        max_cand_total = cand_pos.numel() if cand_pos is not None else total_tokens
+    if stages & DSK_STAGE_CANDIDATES:
+        cand_pos = torch.empty(max(max_cand_total, 1), **i32)
+        cand_class = torch.empty(max(max_cand_total, 1), dtype=torch.uint8, device=dev)
+        cand_cu = torch.empty(B + 1, **i32)
+        if M > 0:
+            samp_pos = torch.empty(B, n_class, M, **i32)
+    a.max_cand_total = max_cand_total
+    a.cand_pos, a.cand_class, a.cand_cu = _ptr(cand_pos), _ptr(cand_class), _ptr(cand_cu)
+    a.M, a.W, a.R, a.alpha_imp, a.imp_scale = M, W, R, alpha_imp, imp_scale
+    class_mean = samp_score = None
+    if stages & DSK_STAGE_IMPORTANCE:
+        class_mean = torch.empty(B, n_class, dtype=torch.float32, device=dev)
+        samp_score = torch.empty(B, n_class, M, dtype=torch.float32, device=dev)
+    a.samp_pos, a.qwin = _ptr(samp_pos), _ptr(qwin)
+    a.class_weight_q = _ptr(class_weight_q)
+    a.class_mean, a.samp_score = _ptr(class_mean), _ptr(samp_score)
+    a.C, a.delta = C_, delta
+    a.C_per_seq, a.delta_per_seq = _ptr(C_per_seq), _ptr(delta_per_seq)
+    a.alpha_num, a.alpha_den, a.b = alpha_num, alpha_den, b
+    if max_blocks_total is None:
+        if block_start is not None:
+            max_blocks_total = block_start.numel() - 1
+        else:
+            mc = min_chunk if min_chunk is not None else C_ - delta
+            max_blocks_total = dsk_block_capacity(total_tokens, B, mc)
+    if stages & DSK_STAGE_SEGMENT:
+        block_start = torch.empty(max_blocks_total + 1, **i32)
+        slot_base = torch.empty(max_blocks_total + 1, **i32)
+        cu_blocks = torch.empty(B + 1, **i32)
+    a.max_blocks_total = max_blocks_total
+    a.block_start, a.cu_blocks, a.slot_base = _ptr(block_start), _ptr(cu_blocks), _ptr(slot_base)
+    ksum = vsum = None
+    if stages & DSK_STAGE_SUMMARIES:
+        ksum = torch.empty(Hkv, max_blocks_total, 2, DSK_HEAD_DIM, dtype=torch.bfloat16, device=dev)
+        if want_vsum:
+            vsum = torch.empty_like(ksum)
+    a.ksum, a.vsum = _ptr(ksum), _ptr(vsum)
+    dev_status = torch.zeros(1, **i32)
+    a.dev_status = _ptr(dev_status)
+    ws = _ws(dsk_compress_workspace_bytes(a), dev)
+    a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
+    keep = (cu_seqlens, K, V, token_ids, delim_ids, qwin, C_per_seq, delta_per_seq, ws)
+    dsk_compress(a, stream, check=check)
+    return Compressed(B=B, Hq=Hq, Hkv=Hkv, b=b, total_tokens=total_tokens, max_blocks_total=max_blocks_total,
+                      cu_seqlens=cu_seqlens, block_start=block_start, cu_blocks=cu_blocks, slot_base=slot_base,
+                      ksum=ksum, vsum=vsum, cand_pos=cand_pos, cand_class=cand_class, cand_cu=cand_cu,
+                      samp_pos=samp_pos, class_weight_q=class_weight_q, class_mean=class_mean,
+                      samp_score=samp_score, dev_status=dev_status, args=a, keep=keep)
+
+
+@dataclass
+class Selection:
+    k: int
+    b: int
+    sel_slot: torch.Tensor     # int32 [B, Hq, k]
+    sel_start: torch.Tensor
+    sel_len: torch.Tensor
+    sel_count: torch.Tensor    # int32 [B, Hq]
+    scores: Optional[torch.Tensor]
+    args: dsk_select_args
+    keep: tuple
+
+
+def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_scores: bool = False,
+                     out: Optional[Selection] = None) -> Selection:
+    """Fill dsk_select_args for query q (bf16 [B, Hq, D]); buffers are reused from `out`."""
+    dev = q.device
+    B, Hq = comp.B, comp.Hq
+    assert q.shape == (B, Hq, DSK_HEAD_DIM) and q.dtype == torch.bfloat16 and q.is_contiguous()
+    k = budget // comp.b
+    i32 = dict(dtype=torch.int32, device=dev)
+    a = dsk_select_args()
+    a.struct_size = C.sizeof(dsk_select_args)
+    a.B, a.Hq, a.Hkv, a.D = B, Hq, comp.Hkv, DSK_HEAD_DIM
+    a.max_blocks_total = comp.max_blocks_total
+    a.cu_blocks, a.block_start, a.slot_base = _ptr(comp.cu_blocks), _ptr(comp.block_start), _ptr(comp.slot_base)
+    a.ksum, a.q = _ptr(comp.ksum), _ptr(q)
+    a.b, a.budget = comp.b, budget
+    if out is None:
+        sel_slot = torch.empty(B, Hq, max(k, 1), **i32)
+        sel_start = torch.empty(B, Hq, max(k, 1), **i32)
+        sel_len = torch.empty(B, Hq, max(k, 1), **i32)
+        sel_count = torch.empty(B, Hq, **i32)
+        scores = torch.empty(Hq, comp.max_blocks_total, dtype=torch.float32, device=dev) if want_scores else None
+    else:
+        sel_slot, sel_start, sel_len, sel_count, scores = out.sel_slot, out.sel_start, out.sel_len, out.sel_count, out.scores
+    a.sel_slot, a.sel_start, a.sel_len, a.sel_count = _ptr(sel_slot), _ptr(sel_start), _ptr(sel_len), _ptr(sel_count)
+    a.scores = _ptr(scores)
+    ws = _ws(dsk_select_workspace_bytes(a), dev) if out is None else out.keep[-1]
+    a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
+    return Selection(k=k, b=comp.b, sel_slot=sel_slot, sel_start=sel_start, sel_len=sel_len, sel_count=sel_count,
+                     scores=scores, args=a, keep=(comp, q, ws))
+
+
+def select_topk(comp: Compressed, q: torch.Tensor, budget: int, *, want_scores: bool = False, stream=None,
+                check: bool = True) -> Selection:
+    sel = make_select_args(comp, q, budget, want_scores=want_scores)
+    dsk_select_topk(sel.args, stream, check=check)
+    return sel
+
+
+@dataclass
+class AttnOut:
+    out: torch.Tensor   # f32 [B, Hq, D]
+    lse: torch.Tensor   # f32 [B, Hq]
+    args: dsk_attn_args
+    keep: tuple
+
+
+def make_attn_args(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, sel_start: torch.Tensor,
+                   sel_len: torch.Tensor, sel_count: torch.Tensor, b: int, *, scale: float = 0.0,
+                   out: Optional[AttnOut] = None) -> AttnOut:
+    dev = q.device
+    B, Hq, D = q.shape
+    assert D == DSK_HEAD_DIM and q.dtype == torch.bfloat16 and q.is_contiguous()
+    k = sel_start.shape[2]
+    a = dsk_attn_args()
+    a.struct_size = C.sizeof(dsk_attn_args)
+    a.B, a.Hq, a.Hkv, a.D = B, Hq, K.shape[0], D
+    a.q, a.K, a.V = _ptr(q), _ptr(K), _ptr(V)
+    a.k_stride_tok, a.k_stride_head = _kv_strides(K)
+    a.v_stride_tok, a.v_stride_head = _kv_strides(V)
+    a.total_tokens, a.k, a.b = K.shape[1], k, b
+    a.sel_start, a.sel_len, a.sel_count = _ptr(sel_start), _ptr(sel_len), _ptr(sel_count)
+    a.scale = scale
+    if out is None:
+        o = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
+        lse = torch.empty(B, Hq, dtype=torch.float32, device=dev)
+        ws = _ws(dsk_attn_workspace_bytes(a), dev)
+    else:
+        o, lse, ws = out.out, out.lse, out.keep[-1]
+    a.out, a.lse = _ptr(o), _ptr(lse)
+    a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
+    return AttnOut(out=o, lse=lse, args=a, keep=(q, K, V, sel_start, sel_len, sel_count, ws))
+
+
+def sparse_decode_attn(q, K, V, sel_start, sel_len, sel_count, b, *, scale: float = 0.0, stream=None,
+                       check: bool = True) -> AttnOut:
+    r = make_attn_args(q, K, V, sel_start, sel_len, sel_count, b, scale=scale)
+    dsk_sparse_decode_attn(r.args, stream, check=check)
+    return r

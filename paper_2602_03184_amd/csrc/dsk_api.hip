@@ -1,0 +1,222 @@
+// C-ABI entry points of libdsk: synchronous argument validation, workspace layout, and the
+// launch sequence of each call.  No allocation, no synchronisation, no retained pointers.
+#include <hip/hip_runtime.h>
+
+#include "dsk_internal.hpp"
+
+namespace dsk {
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+
+static bool geometry_ok(int B, int Hq, int Hkv, int D) {
+  return B >= 1 && Hq >= 1 && Hkv >= 1 && Hq % Hkv == 0 && D == DSK_HEAD_DIM && B <= 65535 && Hq <= 65535;
+}
+
+CompressWs compress_ws_layout(const dsk_compress_args& a) {
+  CompressWs ws;
+  ws.tiles_per_seq = (a.max_seqlen + kSegTile - 1) / kSegTile;
+  int span = a.C + a.delta;
+  if (span < 1) span = 1;
+  ws.map_row = span < kSegTile ? span : kSegTile;
+  ws.n_cand_tiles = (a.total_tokens + kCandTile - 1) / kCandTile;
+  const size_t n_tiles = (size_t)a.B * ws.tiles_per_seq;
+  size_t off = 0;
+  ws.marker = off;     off += align_up((size_t)a.total_tokens + 1 + 16);
+  ws.tile_map = off;   off += align_up(n_tiles * ws.map_row * sizeof(uint2));
+  ws.tile_info = off;  off += align_up(n_tiles * sizeof(int4));
+  ws.seq_info = off;   off += align_up((size_t)a.B * sizeof(int4));
+  ws.cls_at = off;     off += align_up((size_t)a.total_tokens + 16);
+  ws.tile_count = off; off += align_up(((size_t)ws.n_cand_tiles + 1) * sizeof(int32_t));
+  const size_t n_samp = (size_t)a.B * (a.n_class > 0 ? a.n_class : 0) * (a.M > 0 ? a.M : 0);
+  ws.imp_part = off;   off += align_up(n_samp * (size_t)a.Hkv * 2 * sizeof(float));
+  ws.total = off;
+  return ws;
+}
+
+static dsk_status validate_compress(const dsk_compress_args* a) {
+  if (a == nullptr) return DSK_ERR_NULL;
+  if (a->struct_size != sizeof(dsk_compress_args)) return DSK_ERR_VERSION;
+  if ((a->stages & ~(uint32_t)DSK_STAGE_ALL) != 0 || a->stages == 0) return DSK_ERR_PARAM;
+  if (!geometry_ok(a->B, a->Hq, a->Hkv, a->D)) return DSK_ERR_SHAPE;
+  if (a->total_tokens < 0 || a->max_seqlen < 0 || a->max_seqlen > a->total_tokens) return DSK_ERR_SHAPE;
+  if (a->cu_seqlens == nullptr) return DSK_ERR_NULL;
+  const bool st_cand = a->stages & DSK_STAGE_CANDIDATES, st_imp = a->stages & DSK_STAGE_IMPORTANCE;
+  const bool st_seg = a->stages & DSK_STAGE_SEGMENT, st_sum = a->stages & DSK_STAGE_SUMMARIES;
+
+  if (st_cand || st_imp || st_seg) {
+    if (a->n_class < 1 || a->n_class > DSK_MAX_CLASSES) return DSK_ERR_PARAM;
+  }
+  if (st_cand || st_seg) {
+    if (a->max_cand_total < 0) return DSK_ERR_PARAM;
+    if (a->cand_cu == nullptr) return DSK_ERR_NULL;
+    if (a->max_cand_total > 0 && (a->cand_pos == nullptr || a->cand_class == nullptr)) return DSK_ERR_NULL;
+  }
+  if (st_cand) {
+    if (a->token_ids == nullptr || a->delim_ids == nullptr) return DSK_ERR_NULL;
+    if (a->samp_pos != nullptr && a->M > 0) {
+      if (a->M > kMaxSamplesPerClass || a->W < 1 || a->R < 1) return DSK_ERR_PARAM;
+    }
+  }
+  if (st_imp) {
+    if (a->samp_pos == nullptr || a->qwin == nullptr || a->class_weight_q == nullptr || a->K == nullptr)
+      return DSK_ERR_NULL;
+    if (a->M < 1 || a->M > kMaxSamplesPerClass || a->W < 1 || a->W > 64 || a->R < 1) return DSK_ERR_PARAM;
+    if (!(a->alpha_imp >= 0.0f) || !(a->alpha_imp <= 1.0e6f) || !(a->imp_scale >= 0.0f)) return DSK_ERR_PARAM;
+    if (!aligned16(a->qwin)) return DSK_ERR_ALIGN;
+  }
+  if (st_seg) {
+    if (a->class_weight_q == nullptr) return DSK_ERR_NULL;
+    if (a->C < 1 || a->delta < 0 || a->delta >= a->C || a->C + a->delta > kMaxChunkSpan) return DSK_ERR_PARAM;
+    if (a->alpha_den < 1 || a->alpha_den > 1000 || a->alpha_num < 0 || a->alpha_num > a->alpha_den)
+      return DSK_ERR_PARAM;
+    if (a->b < 1 || a->b > 1024) return DSK_ERR_PARAM;
+  }
+  if (st_seg || st_sum) {
+    if (a->max_blocks_total < 1) return DSK_ERR_PARAM;
+    if (a->block_start == nullptr || a->cu_blocks == nullptr) return DSK_ERR_NULL;
+  }
+  if (st_seg && a->slot_base == nullptr) return DSK_ERR_NULL;
+  if (st_sum) {
+    if (a->K == nullptr || a->ksum == nullptr) return DSK_ERR_NULL;
+    if (a->vsum != nullptr && a->V == nullptr) return DSK_ERR_NULL;
+    if (!aligned16(a->ksum) || (a->vsum && !aligned16(a->vsum))) return DSK_ERR_ALIGN;
+  }
+  if (st_sum || st_imp) {
+    if (!aligned16(a->K) || a->k_stride_tok < DSK_HEAD_DIM || a->k_stride_tok % 8 || a->k_stride_head % 8 ||
+        a->k_stride_head < 0)
+      return a->k_stride_tok < DSK_HEAD_DIM || a->k_stride_head < 0 ? DSK_ERR_SHAPE : DSK_ERR_ALIGN;
+    if (a->Hkv > 1 && a->k_stride_head == 0) return DSK_ERR_SHAPE;
+  }
+  if (st_sum && a->vsum != nullptr) {
+    if (!aligned16(a->V) || a->v_stride_tok % 8 || a->v_stride_head % 8) return DSK_ERR_ALIGN;
+    if (a->v_stride_tok < DSK_HEAD_DIM || a->v_stride_head < 0) return DSK_ERR_SHAPE;
+  }
+  const CompressWs ws = compress_ws_layout(*a);
+  if (st_cand || st_imp || st_seg) {
+    if (a->workspace == nullptr || a->workspace_bytes < ws.total) return DSK_ERR_WORKSPACE;
+    if (!aligned256(a->workspace)) return DSK_ERR_ALIGN;
+  }
+  return DSK_OK;
+}
+
+static dsk_status validate_select(const dsk_select_args* a) {
+  if (a == nullptr) return DSK_ERR_NULL;
+  if (a->struct_size != sizeof(dsk_select_args)) return DSK_ERR_VERSION;
+  if (!geometry_ok(a->B, a->Hq, a->Hkv, a->D)) return DSK_ERR_SHAPE;
+  if (a->max_blocks_total < 1) return DSK_ERR_SHAPE;
+  if (a->b < 1 || a->b > 1024 || a->budget < a->b) return DSK_ERR_PARAM;
+  if (!a->cu_blocks || !a->block_start || !a->slot_base || !a->ksum || !a->q || !a->sel_slot || !a->sel_start ||
+      !a->sel_len || !a->sel_count)
+    return DSK_ERR_NULL;
+  if (!aligned16(a->ksum) || !aligned16(a->q)) return DSK_ERR_ALIGN;
+  if (a->scores == nullptr) {
+    if (a->workspace == nullptr || a->workspace_bytes < dsk_select_workspace_bytes(a)) return DSK_ERR_WORKSPACE;
+    if (!aligned256(a->workspace)) return DSK_ERR_ALIGN;
+  }
+  return DSK_OK;
+}
+
+static dsk_status validate_attn(const dsk_attn_args* a) {
+  if (a == nullptr) return DSK_ERR_NULL;
+  if (a->struct_size != sizeof(dsk_attn_args)) return DSK_ERR_VERSION;
+  if (!geometry_ok(a->B, a->Hq, a->Hkv, a->D)) return DSK_ERR_SHAPE;
+  if (a->total_tokens < 0) return DSK_ERR_SHAPE;
+  if (a->k < 1 || a->b < 1 || a->b > 1024) return DSK_ERR_PARAM;
+  if (!(a->scale >= 0.0f)) return DSK_ERR_PARAM;
+  if (!a->q || !a->K || !a->V || !a->sel_start || !a->sel_len || !a->sel_count || !a->out) return DSK_ERR_NULL;
+  if (a->k_stride_tok < DSK_HEAD_DIM || a->v_stride_tok < DSK_HEAD_DIM || a->k_stride_head < 0 ||
+      a->v_stride_head < 0)
+    return DSK_ERR_SHAPE;
+  if (!aligned16(a->q) || !aligned16(a->K) || !aligned16(a->V) || a->k_stride_tok % 8 || a->k_stride_head % 8 ||
+      a->v_stride_tok % 8 || a->v_stride_head % 8)
+    return DSK_ERR_ALIGN;
+  if (a->workspace == nullptr || a->workspace_bytes < dsk_attn_workspace_bytes(a)) return DSK_ERR_WORKSPACE;
+  if (!aligned256(a->workspace)) return DSK_ERR_ALIGN;
+  return DSK_OK;
+}
+
+}  // namespace dsk
+
+using namespace dsk;
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+uint32_t dsk_version(void) { return DSK_ABI_VERSION; }
+
+const char* dsk_strerror(int32_t status) {
+  switch (status) {
+    case DSK_OK: return "ok";
+    case DSK_ERR_NULL: return "a required pointer is NULL";
+    case DSK_ERR_SHAPE: return "unusable geometry (batch, heads, head_dim, lengths or strides)";
+    case DSK_ERR_PARAM: return "parameter out of range";
+    case DSK_ERR_ALIGN: return "pointer or stride not sufficiently aligned";
+    case DSK_ERR_WORKSPACE: return "workspace missing or too small";
+    case DSK_ERR_CAPACITY: return "output capacity exceeded";
+    case DSK_ERR_LAUNCH: return "HIP launch failed";
+    case DSK_ERR_VERSION: return "argument struct size does not match this library";
+    default: return "unknown status";
+  }
+}
+
+int64_t dsk_block_capacity(int32_t total_tokens, int32_t B, int32_t min_chunk) {
+  if (total_tokens < 0 || B < 1 || min_chunk < 1) return -1;
+  return (int64_t)total_tokens / min_chunk + B;
+}
+
+size_t dsk_compress_workspace_bytes(const dsk_compress_args* a) {
+  if (a == nullptr || a->struct_size != sizeof(dsk_compress_args)) return 0;
+  if (a->B < 1 || a->total_tokens < 0 || a->max_seqlen < 0 || a->Hkv < 1) return 0;
+  return compress_ws_layout(*a).total;
+}
+
+size_t dsk_select_workspace_bytes(const dsk_select_args* a) {
+  if (a == nullptr || a->struct_size != sizeof(dsk_select_args)) return 0;
+  if (a->Hq < 1 || a->max_blocks_total < 1) return 0;
+  return align_up((size_t)a->Hq * a->max_blocks_total * sizeof(float));
+}
+
+size_t dsk_attn_workspace_bytes(const dsk_attn_args* a) {
+  if (a == nullptr || a->struct_size != sizeof(dsk_attn_args)) return 0;
+  if (a->B < 1 || a->Hq < 1 || a->k < 1) return 0;
+  return attn_ws_layout(*a).total;
+}
+
+dsk_status dsk_compress(const dsk_compress_args* a, void* stream) {
+  const dsk_status v = validate_compress(a);
+  if (v != DSK_OK) return v;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const CompressWs ws = compress_ws_layout(*a);
+  if (a->stages & DSK_STAGE_CANDIDATES)
+    if (launch_candidates(*a, ws, st) != hipSuccess) return DSK_ERR_LAUNCH;
+  if (a->stages & DSK_STAGE_IMPORTANCE)
+    if (launch_importance(*a, ws, st) != hipSuccess) return DSK_ERR_LAUNCH;
+  if (a->stages & DSK_STAGE_SEGMENT)
+    if (launch_segment(*a, ws, st) != hipSuccess) return DSK_ERR_LAUNCH;
+  if (a->stages & DSK_STAGE_SUMMARIES)
+    if (launch_summaries(*a, st) != hipSuccess) return DSK_ERR_LAUNCH;
+  return DSK_OK;
+}
+
+dsk_status dsk_select_topk(const dsk_select_args* a, void* stream) {
+  const dsk_status v = validate_select(a);
+  if (v != DSK_OK) return v;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* scores = a->scores ? a->scores : static_cast<float*>(a->workspace);
+  if (launch_scores(*a, scores, st) != hipSuccess) return DSK_ERR_LAUNCH;
+  if (launch_select(*a, scores, st) != hipSuccess) return DSK_ERR_LAUNCH;
+  return DSK_OK;
+}
+
+dsk_status dsk_sparse_decode_attn(const dsk_attn_args* a, void* stream) {
+  const dsk_status v = validate_attn(a);
+  if (v != DSK_OK) return v;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const AttnWs ws = attn_ws_layout(*a);
+  if (launch_attn(*a, ws, st) != hipSuccess) return DSK_ERR_LAUNCH;
+  return DSK_OK;
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

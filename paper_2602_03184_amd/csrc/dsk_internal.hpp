@@ -1,0 +1,56 @@
+// Host-side internals of libdsk: workspace layouts and the per-stage launchers that the
+// C-ABI entry points in dsk_api.hip call.  Nothing here is exported.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/dsk.h"
+
+namespace dsk {
+
+constexpr int kSegTile = 1024;        // positions per DD-Select tile
+constexpr int kMaxChunkSpan = 8192;   // limit on C + delta
+constexpr int kCandTile = 1024;       // tokens per candidate-extraction tile
+constexpr int kAttnSlotsPerWg = 8;    // slots one attention workgroup folds into one partial
+constexpr int kMaxSamplesPerClass = 64;
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// ---- dsk_compress workspace ---------------------------------------------------------------
+struct CompressWs {
+  size_t marker;      // u8  [total_tokens + 1]      boundary -> weight tenths, 255 = none
+  size_t tile_map;    // uint2 [n_tiles * map_row]   entry offset -> (exit offset | blocks<<16, slots)
+  size_t tile_info;   // int4 [n_tiles]              entry position, block offset, slot offset
+  size_t seq_info;    // int4 [B]                    blocks, slots, block base, slot base
+  size_t cls_at;      // u8  [total_tokens]          dense class of each token, 255 = none
+  size_t tile_count;  // i32 [n_cand_tiles + 1]      candidates per tile, then exclusive scan
+  size_t imp_part;    // f32 [B * n_class * M * Hkv] per-(sample, kv head) partial sums
+  size_t total;
+  int tiles_per_seq;  // ceil(max_seqlen / kSegTile)
+  int map_row;        // min(C + delta, kSegTile)
+  int n_cand_tiles;   // ceil(total_tokens / kCandTile)
+};
+CompressWs compress_ws_layout(const dsk_compress_args& a);
+
+hipError_t launch_candidates(const dsk_compress_args& a, const CompressWs& ws, hipStream_t st);
+hipError_t launch_importance(const dsk_compress_args& a, const CompressWs& ws, hipStream_t st);
+hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, hipStream_t st);
+hipError_t launch_summaries(const dsk_compress_args& a, hipStream_t st);
+
+// ---- dsk_select_topk ----------------------------------------------------------------------
+hipError_t launch_scores(const dsk_select_args& a, float* scores, hipStream_t st);
+hipError_t launch_select(const dsk_select_args& a, const float* scores, hipStream_t st);
+
+// ---- dsk_sparse_decode_attn -----------------------------------------------------------------
+struct AttnWs {
+  size_t part_ml;   // float2 [B*Hq*nchunks]  (running max in log2 units, denominator)
+  size_t part_acc;  // f32 [B*Hq*nchunks*D]
+  size_t total;
+  int nchunks;
+};
+AttnWs attn_ws_layout(const dsk_attn_args& a);
+hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st);
+
+}  // namespace dsk

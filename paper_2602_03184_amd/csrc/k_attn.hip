@@ -1,0 +1,217 @@
+// Sparse decode attention over the K/V rows of the selected slots (App. B.2 Steps 2-3):
+// a split-K flash-decode.  The gather is HBM-bound (512 B of K+V per token, ~2 flop/B), so
+// there is no MFMA here: a 256-byte bf16 row is spread over 16 lanes x 16 B, a wavefront
+// reads 4 token rows per load instruction and issues every load of a slot (K and V) before
+// it touches the data.  Each wavefront folds its slots into an online-softmax state
+// (m, l, acc); the 4 wavefronts of a workgroup merge through LDS into one partial per
+// (sequence, head, chunk of slots); a second small kernel merges the partials in chunk order.
+#include "dsk_common.hpp"
+#include "dsk_internal.hpp"
+
+namespace dsk {
+
+constexpr int kAttnThreads = 256;
+constexpr int kAttnWaves = kAttnThreads / DSK_WAVE;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct WaveState {
+  float m;        // running max of the logits, in log2 units (wave-uniform)
+  float l;        // this lane group's part of the denominator
+  float acc[8];   // this lane group's part of the numerator, channels 8c..8c+7
+};
+
+// Fold up to 4*NS token rows starting at `start` into the state.  nvalid >= 1 rows are real;
+// loads of the padded rows are redirected to the last real row and weighted zero.
+template <int NS>
+__device__ __forceinline__ void fold_rows(WaveState& st, const float (&qf)[8], const uint16_t* __restrict__ kbase,
+                                          const uint16_t* __restrict__ vbase, int64_t kst, int64_t vst,
+                                          int nvalid, int g, float scale_log2) {
+  uint4 kv[NS], vv[NS];
+#pragma unroll
+  for (int u = 0; u < NS; ++u) {
+    int r = 4 * u + g;
+    r = r < nvalid ? r : nvalid - 1;
+    kv[u] = *reinterpret_cast<const uint4*>(kbase + (int64_t)r * kst);
+  }
+#pragma unroll
+  for (int u = 0; u < NS; ++u) {
+    int r = 4 * u + g;
+    r = r < nvalid ? r : nvalid - 1;
+    vv[u] = *reinterpret_cast<const uint4*>(vbase + (int64_t)r * vst);
+  }
+  float z[NS];
+  float mloc = -__builtin_inff();
+#pragma unroll
+  for (int u = 0; u < NS; ++u) {
+    float f[8];
+    unpack8(kv[u], f);
+    float d = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) d = fmaf(qf[k], f[k], d);
+    d = group16_sum(d) * scale_log2;
+    z[u] = (4 * u + g < nvalid) ? d : -__builtin_inff();
+    mloc = fmaxf(mloc, z[u]);
+  }
+  mloc = fmaxf(mloc, shfl_xor_f(mloc, 16));
+  mloc = fmaxf(mloc, shfl_xor_f(mloc, 32));
+  const float m_new = fmaxf(st.m, mloc);           // finite: nvalid >= 1
+  const float alpha = exp2f(st.m - m_new);         // 0 on the first fold (st.m = -inf)
+  st.l *= alpha;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) st.acc[k] *= alpha;
+#pragma unroll
+  for (int u = 0; u < NS; ++u) {
+    const float p = exp2f(z[u] - m_new);           // 0 for padded rows
+    st.l += p;
+    float f[8];
+    unpack8(vv[u], f);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) st.acc[k] = fmaf(p, f[k], st.acc[k]);
+  }
+  st.m = m_new;
+}
+
+__global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+    int64_t kst, int64_t ksh, int64_t vst, int64_t vsh, int Hq, int G, int k, int b, int total_tokens,
+    const int32_t* __restrict__ sel_start, const int32_t* __restrict__ sel_len,
+    const int32_t* __restrict__ sel_count, float scale_log2, int nchunks,
+    float2* __restrict__ part_ml, float* __restrict__ part_acc) {
+  __shared__ float sm_m[kAttnWaves];
+  __shared__ float sm_l[kAttnWaves];
+  __shared__ float sm_acc[kAttnWaves][DSK_HEAD_DIM];
+
+  const int chunk = blockIdx.x;
+  const int h = blockIdx.y;
+  const int s = blockIdx.z;
+  const int64_t sh = (int64_t)s * Hq + h;
+  int count = sel_count[sh];
+  if (count > k) count = k;
+  const int slot0 = chunk * kAttnSlotsPerWg;
+  if (slot0 >= count) return;   // uniform over the workgroup; the merge kernel skips this chunk too
+
+  const int lane = threadIdx.x & (DSK_WAVE - 1);
+  const int wave = threadIdx.x / DSK_WAVE;
+  const int g = lane >> 4;
+  const int c = lane & 15;
+  const int hk = h / G;
+
+  float qf[8];
+  {
+    const uint4 qv = *reinterpret_cast<const uint4*>(q + sh * DSK_HEAD_DIM + c * 8);
+    unpack8(qv, qf);
+  }
+  const uint16_t* Kh = K + (int64_t)hk * ksh + c * 8;
+  const uint16_t* Vh = V + (int64_t)hk * vsh + c * 8;
+
+  WaveState st;
+  st.m = -__builtin_inff();
+  st.l = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) st.acc[i] = 0.0f;
+
+  for (int j = slot0 + wave; j < slot0 + kAttnSlotsPerWg && j < count; j += kAttnWaves) {
+    const int start = sel_start[sh * k + j];
+    int len = sel_len[sh * k + j];
+    if (len > b) len = b;
+    if (start < 0 || len <= 0 || start > total_tokens - len) continue;   // never read outside K/V
+    for (int r0 = 0; r0 < len; r0 += 32) {
+      const int nv = len - r0;
+      const uint16_t* kb = Kh + (int64_t)(start + r0) * kst;
+      const uint16_t* vb = Vh + (int64_t)(start + r0) * vst;
+      if (nv > 16) fold_rows<8>(st, qf, kb, vb, kst, vst, nv < 32 ? nv : 32, g, scale_log2);
+      else fold_rows<4>(st, qf, kb, vb, kst, vst, nv, g, scale_log2);
+    }
+  }
+
+  // lane groups -> wave
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    st.acc[i] += shfl_xor_f(st.acc[i], 16);
+    st.acc[i] += shfl_xor_f(st.acc[i], 32);
+  }
+  st.l += shfl_xor_f(st.l, 16);
+  st.l += shfl_xor_f(st.l, 32);
+  if (lane == 0) { sm_m[wave] = st.m; sm_l[wave] = st.l; }
+  if (g == 0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sm_acc[wave][c * 8 + i] = st.acc[i];
+  }
+  __syncthreads();
+
+  // waves -> workgroup partial, fixed order
+  if (threadIdx.x < DSK_HEAD_DIM) {
+    float M = sm_m[0];
+#pragma unroll
+    for (int w = 1; w < kAttnWaves; ++w) M = fmaxf(M, sm_m[w]);
+    float l = 0.0f, a = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kAttnWaves; ++w) {
+      const float f = sm_m[w] == -__builtin_inff() ? 0.0f : exp2f(sm_m[w] - M);   // idle wave
+      l = fmaf(sm_l[w], f, l);
+      a = fmaf(sm_acc[w][threadIdx.x], f, a);
+    }
+    const int64_t pi = sh * nchunks + chunk;
+    part_acc[pi * DSK_HEAD_DIM + threadIdx.x] = a;
+    if (threadIdx.x == 0) part_ml[pi] = make_float2(M, l);
+  }
+}
+
+__global__ __launch_bounds__(DSK_HEAD_DIM) void attn_merge_kernel(
+    const float2* __restrict__ part_ml, const float* __restrict__ part_acc,
+    const int32_t* __restrict__ sel_count, int k, int nchunks, float* __restrict__ out,
+    float* __restrict__ lse) {
+  const int64_t sh = blockIdx.x;
+  const int d = threadIdx.x;
+  int count = sel_count[sh];
+  if (count > k) count = k;
+  const int used = (count + kAttnSlotsPerWg - 1) / kAttnSlotsPerWg;
+  if (used <= 0) {
+    out[sh * DSK_HEAD_DIM + d] = 0.0f;
+    if (d == 0 && lse) lse[sh] = -__builtin_inff();
+    return;
+  }
+  const float2* ml = part_ml + sh * nchunks;
+  const float* acc = part_acc + sh * nchunks * DSK_HEAD_DIM;
+  float M = -__builtin_inff();
+  for (int ch = 0; ch < used; ++ch) M = fmaxf(M, ml[ch].x);
+  float l = 0.0f, a = 0.0f;
+  for (int ch = 0; ch < used; ++ch) {
+    const float2 v = ml[ch];
+    const float f = v.x == -__builtin_inff() ? 0.0f : exp2f(v.x - M);
+    l = fmaf(v.y, f, l);
+    a = fmaf(acc[(int64_t)ch * DSK_HEAD_DIM + d], f, a);
+  }
+  out[sh * DSK_HEAD_DIM + d] = l > 0.0f ? a / l : 0.0f;
+  if (d == 0 && lse) lse[sh] = l > 0.0f ? (M + log2f(l)) * kLn2 : -__builtin_inff();
+}
+
+AttnWs attn_ws_layout(const dsk_attn_args& a) {
+  AttnWs ws;
+  ws.nchunks = (a.k + kAttnSlotsPerWg - 1) / kAttnSlotsPerWg;
+  const size_t n = (size_t)a.B * a.Hq * ws.nchunks;
+  ws.part_ml = 0;
+  ws.part_acc = align_up(n * sizeof(float2));
+  ws.total = ws.part_acc + align_up(n * DSK_HEAD_DIM * sizeof(float));
+  return ws;
+}
+
+hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st) {
+  unsigned char* w = static_cast<unsigned char*>(a.workspace);
+  float2* part_ml = reinterpret_cast<float2*>(w + ws.part_ml);
+  float* part_acc = reinterpret_cast<float*>(w + ws.part_acc);
+  const float scale = a.scale != 0.0f ? a.scale : 0.08838834764831845f;   // 128^-1/2
+  const dim3 grid((unsigned)ws.nchunks, (unsigned)a.Hq, (unsigned)a.B);
+  attn_partial_kernel<<<grid, dim3(kAttnThreads), 0, st>>>(
+      static_cast<const uint16_t*>(a.q), static_cast<const uint16_t*>(a.K), static_cast<const uint16_t*>(a.V),
+      a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, a.Hq / a.Hkv, a.k, a.b,
+      a.total_tokens, a.sel_start, a.sel_len, a.sel_count, scale * kLog2e, ws.nchunks, part_ml, part_acc);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  attn_merge_kernel<<<dim3((unsigned)(a.B * a.Hq)), dim3(DSK_HEAD_DIM), 0, st>>>(
+      part_ml, part_acc, a.sel_count, a.k, ws.nchunks, a.out, a.lse);
+  return hipGetLastError();
+}
+
+}  // namespace dsk

@@ -1,0 +1,93 @@
+// V2F compression (Sec. 4.2, KVCache Compression): element-wise min and max of K (or V)
+// over the tokens of every variable-length block.  One wavefront per (head, block):
+// a 128-channel bf16 row is 256 B = 16 lanes x 16 B, so the 64 lanes cover 4 token rows
+// per load instruction; rows stream from HBM fully coalesced and each is read once.
+#include "dsk_common.hpp"
+#include "dsk_internal.hpp"
+
+namespace dsk {
+
+constexpr int kSumThreads = 256;
+constexpr int kSumWaves = kSumThreads / DSK_WAVE;
+constexpr int kSumUnroll = 8;  // 8 row-groups of 4 rows = 32 rows in flight per wave
+
+__global__ __launch_bounds__(kSumThreads) void summaries_kernel(
+    const uint16_t* __restrict__ X, int64_t stride_tok, int64_t stride_head, int Hkv,
+    const int32_t* __restrict__ block_start, const int32_t* __restrict__ cu_blocks, int B,
+    int cap, int total_tokens, uint16_t* __restrict__ out, int32_t* dev_status) {
+  const int lane = threadIdx.x & (DSK_WAVE - 1);
+  const int wave = threadIdx.x / DSK_WAVE;
+  const int g = lane >> 4;   // row group 0..3
+  const int c = lane & 15;   // 16-byte column 0..15
+  int nblk = cu_blocks[B];
+  if (nblk > cap) nblk = cap;
+  const int64_t items = (int64_t)Hkv * nblk;
+  const int64_t nwaves = (int64_t)gridDim.x * kSumWaves;
+  for (int64_t item = (int64_t)blockIdx.x * kSumWaves + wave; item < items; item += nwaves) {
+    const int h = (int)(item / nblk);
+    const int i = (int)(item - (int64_t)h * nblk);
+    const int s = block_start[i];
+    const int e = block_start[i + 1];
+    const int len = e - s;
+    uint16_t* o = out + ((int64_t)h * cap + i) * (2 * DSK_HEAD_DIM);
+    if (s < 0 || len <= 0 || e > total_tokens) {   // malformed table: defined output, flag it
+      if (lane < 32) reinterpret_cast<uint4*>(o)[lane] = make_uint4(0, 0, 0, 0);
+      if (lane == 0) set_status(dev_status, DSK_ERR_SHAPE);
+      continue;
+    }
+    const uint16_t* base = X + (int64_t)h * stride_head + (int64_t)s * stride_tok + c * 8;
+    float mn[8], mx[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { mn[k] = __builtin_inff(); mx[k] = -__builtin_inff(); }
+    for (int r0 = 0; r0 < len; r0 += 4 * kSumUnroll) {
+      uint4 v[kSumUnroll];
+#pragma unroll
+      for (int u = 0; u < kSumUnroll; ++u) {
+        int r = r0 + 4 * u + g;
+        r = r < len ? r : len - 1;   // a repeated row changes neither min nor max
+        v[u] = *reinterpret_cast<const uint4*>(base + (int64_t)r * stride_tok);
+      }
+#pragma unroll
+      for (int u = 0; u < kSumUnroll; ++u) {
+        float f[8];
+        unpack8(v[u], f);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { mn[k] = fminf(mn[k], f[k]); mx[k] = fmaxf(mx[k], f[k]); }
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      mn[k] = fminf(mn[k], shfl_xor_f(mn[k], 16)); mx[k] = fmaxf(mx[k], shfl_xor_f(mx[k], 16));
+      mn[k] = fminf(mn[k], shfl_xor_f(mn[k], 32)); mx[k] = fmaxf(mx[k], shfl_xor_f(mx[k], 32));
+    }
+    if (g == 0) {
+      reinterpret_cast<uint4*>(o)[c] = make_uint4(pack_bf16_exact(mn[0], mn[1]), pack_bf16_exact(mn[2], mn[3]),
+                                                  pack_bf16_exact(mn[4], mn[5]), pack_bf16_exact(mn[6], mn[7]));
+    } else if (g == 1) {
+      reinterpret_cast<uint4*>(o)[16 + c] = make_uint4(pack_bf16_exact(mx[0], mx[1]), pack_bf16_exact(mx[2], mx[3]),
+                                                       pack_bf16_exact(mx[4], mx[5]), pack_bf16_exact(mx[6], mx[7]));
+    }
+  }
+}
+
+hipError_t launch_summaries(const dsk_compress_args& a, hipStream_t st) {
+  const int64_t max_items = (int64_t)a.Hkv * a.max_blocks_total;
+  if (max_items <= 0) return hipSuccess;
+  int64_t wgs = (max_items + kSumWaves - 1) / kSumWaves;
+  const int64_t max_wgs = 256 * 8;   // 8 workgroups (32 waves) per CU keeps HBM requests deep
+  if (wgs > max_wgs) wgs = max_wgs;
+  summaries_kernel<<<dim3((unsigned)wgs), dim3(kSumThreads), 0, st>>>(
+      static_cast<const uint16_t*>(a.K), a.k_stride_tok, a.k_stride_head, a.Hkv, a.block_start,
+      a.cu_blocks, a.B, a.max_blocks_total, a.total_tokens, static_cast<uint16_t*>(a.ksum), a.dev_status);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  if (a.vsum != nullptr) {
+    summaries_kernel<<<dim3((unsigned)wgs), dim3(kSumThreads), 0, st>>>(
+        static_cast<const uint16_t*>(a.V), a.v_stride_tok, a.v_stride_head, a.Hkv, a.block_start,
+        a.cu_blocks, a.B, a.max_blocks_total, a.total_tokens, static_cast<uint16_t*>(a.vsum), a.dev_status);
+    err = hipGetLastError();
+  }
+  return err;
+}
+
+}  // namespace dsk

@@ -1,0 +1,161 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function
+include/dsk.h declares, the ctypes structs mirror the C structs, and argument validation
+rejects bad input before anything is launched."""
+import ctypes as C
+import os
+import re
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "dsk.h")
+
+
+@pytest.fixture(scope="module")
+def dsk():
+    import paper_2602_03184_amd as d
+    return d
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(dsk_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol(dsk):
+    names = _declared_functions()
+    assert {"dsk_compress", "dsk_select_topk", "dsk_sparse_decode_attn"} <= set(names)
+    lib = C.CDLL(dsk.binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert dsk.dsk_version() == 1
+    assert dsk.dsk_strerror(0) == "ok" and "capacity" in dsk.dsk_strerror(dsk.DSK_ERR_CAPACITY)
+    assert dsk.dsk_block_capacity(131072, 1, 16) == 8193
+    assert dsk.dsk_block_capacity(10, 0, 16) == -1
+
+
+def test_ctypes_structs_mirror_the_header(dsk, tmp_path):
+    prog = tmp_path / "sizes.c"
+    prog.write_text(r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "dsk.h"
+int main(void) {
+  printf("%zu %zu %zu ", sizeof(dsk_compress_args), sizeof(dsk_select_args), sizeof(dsk_attn_args));
+  printf("%zu %zu %zu ", offsetof(dsk_compress_args, qwin), offsetof(dsk_compress_args, C_per_seq), offsetof(dsk_compress_args, workspace_bytes));
+  printf("%zu %zu ", offsetof(dsk_select_args, budget), offsetof(dsk_select_args, workspace_bytes));
+  printf("%zu %zu %zu\n", offsetof(dsk_attn_args, total_tokens), offsetof(dsk_attn_args, scale), offsetof(dsk_attn_args, workspace_bytes));
+  return 0;
+}''')
+    exe = tmp_path / "sizes"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(prog), "-o", str(exe)])
+    got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    ca, sa, aa = dsk.dsk_compress_args, dsk.dsk_select_args, dsk.dsk_attn_args
+    want = [C.sizeof(ca), C.sizeof(sa), C.sizeof(aa), ca.qwin.offset, ca.C_per_seq.offset, ca.workspace_bytes.offset,
+            sa.budget.offset, sa.workspace_bytes.offset, aa.total_tokens.offset, aa.scale.offset,
+            aa.workspace_bytes.offset]
+    assert got == want
+
+
+def _valid_compress(dsk):
+    a = dsk.dsk_compress_args()
+    a.struct_size = C.sizeof(a)
+    a.stages = dsk.DSK_STAGE_SEGMENT
+    a.B, a.Hq, a.Hkv, a.D = 1, 4, 2, 128
+    a.total_tokens = a.max_seqlen = 1000
+    fake = 0x10000   # never dereferenced: validation fails first in every case below
+    a.cu_seqlens = fake
+    a.n_class, a.max_cand_total = 4, 10
+    a.cand_pos = a.cand_class = a.cand_cu = fake
+    a.class_weight_q = fake
+    a.C, a.delta, a.alpha_num, a.alpha_den, a.b = 24, 12, 5, 10, 16
+    a.max_blocks_total = 100
+    a.block_start = a.cu_blocks = a.slot_base = fake
+    return a
+
+
+def test_compress_validation_rejects_before_launch(dsk):
+    a = _valid_compress(dsk)
+    # valid so far except for the workspace -> WORKSPACE proves every earlier check passed
+    assert dsk.dsk_compress(a, 0, check=False) == dsk.DSK_ERR_WORKSPACE
+    assert dsk.dsk_compress_workspace_bytes(a) > 0
+    cases = [
+        ("struct_size", 8, dsk.DSK_ERR_VERSION), ("stages", 0, dsk.DSK_ERR_PARAM), ("stages", 64, dsk.DSK_ERR_PARAM),
+        ("B", 0, dsk.DSK_ERR_SHAPE), ("D", 64, dsk.DSK_ERR_SHAPE), ("Hkv", 3, dsk.DSK_ERR_SHAPE),
+        ("max_seqlen", 2000, dsk.DSK_ERR_SHAPE), ("cu_seqlens", None, dsk.DSK_ERR_NULL),
+        ("n_class", 0, dsk.DSK_ERR_PARAM), ("n_class", 65, dsk.DSK_ERR_PARAM), ("cand_cu", None, dsk.DSK_ERR_NULL),
+        ("cand_pos", None, dsk.DSK_ERR_NULL), ("class_weight_q", None, dsk.DSK_ERR_NULL),
+        ("delta", 24, dsk.DSK_ERR_PARAM), ("delta", -1, dsk.DSK_ERR_PARAM), ("C", 0, dsk.DSK_ERR_PARAM),
+        ("C", 8190, dsk.DSK_ERR_PARAM), ("alpha_num", 11, dsk.DSK_ERR_PARAM), ("alpha_den", 0, dsk.DSK_ERR_PARAM),
+        ("b", 0, dsk.DSK_ERR_PARAM), ("b", 2048, dsk.DSK_ERR_PARAM), ("max_blocks_total", 0, dsk.DSK_ERR_PARAM),
+        ("block_start", None, dsk.DSK_ERR_NULL), ("slot_base", None, dsk.DSK_ERR_NULL),
+    ]
+    for field, value, want in cases:
+        a = _valid_compress(dsk)
+        setattr(a, field, value)
+        assert dsk.dsk_compress(a, 0, check=False) == want, field
+    with pytest.raises(dsk.DskError):
+        dsk.dsk_compress(_valid_compress(dsk), 0)
+    # summaries stage: alignment and stride rules
+    for field, value, want in (("K", 0x10002, dsk.DSK_ERR_ALIGN), ("k_stride_tok", 132, dsk.DSK_ERR_ALIGN),
+                               ("k_stride_tok", 64, dsk.DSK_ERR_SHAPE), ("ksum", None, dsk.DSK_ERR_NULL),
+                               ("k_stride_head", 0, dsk.DSK_ERR_SHAPE)):
+        a2 = _valid_compress(dsk)
+        a2.stages = dsk.DSK_STAGE_SUMMARIES
+        a2.K, a2.ksum = 0x10000, 0x20000
+        a2.k_stride_tok, a2.k_stride_head = 128, 128000
+        setattr(a2, field, value)
+        assert dsk.dsk_compress(a2, 0, check=False) == want, field
+
+
+def test_select_and_attn_validation(dsk):
+    fake = 0x10000
+
+    def sel():
+        a = dsk.dsk_select_args()
+        a.struct_size = C.sizeof(a)
+        a.B, a.Hq, a.Hkv, a.D = 1, 4, 2, 128
+        a.max_blocks_total = 100
+        for f in ("cu_blocks", "block_start", "slot_base", "ksum", "q", "sel_slot", "sel_start", "sel_len", "sel_count"):
+            setattr(a, f, fake)
+        a.b, a.budget = 16, 64
+        return a
+    assert dsk.dsk_select_topk(sel(), 0, check=False) == dsk.DSK_ERR_WORKSPACE
+    assert dsk.dsk_select_workspace_bytes(sel()) >= 4 * 100 * 4
+    for field, value, want in (("struct_size", 1, dsk.DSK_ERR_VERSION), ("Hq", 5, dsk.DSK_ERR_SHAPE),
+                               ("budget", 15, dsk.DSK_ERR_PARAM), ("b", 0, dsk.DSK_ERR_PARAM),
+                               ("q", None, dsk.DSK_ERR_NULL), ("q", fake + 4, dsk.DSK_ERR_ALIGN),
+                               ("max_blocks_total", 0, dsk.DSK_ERR_SHAPE), ("sel_count", None, dsk.DSK_ERR_NULL)):
+        a = sel()
+        setattr(a, field, value)
+        assert dsk.dsk_select_topk(a, 0, check=False) == want, field
+
+    def att():
+        a = dsk.dsk_attn_args()
+        a.struct_size = C.sizeof(a)
+        a.B, a.Hq, a.Hkv, a.D = 1, 4, 2, 128
+        for f in ("q", "K", "V", "sel_start", "sel_len", "sel_count", "out"):
+            setattr(a, f, fake)
+        a.k_stride_tok = a.v_stride_tok = 128
+        a.k_stride_head = a.v_stride_head = 128 * 1000
+        a.total_tokens, a.k, a.b = 1000, 8, 16
+        return a
+    assert dsk.dsk_sparse_decode_attn(att(), 0, check=False) == dsk.DSK_ERR_WORKSPACE
+    assert dsk.dsk_attn_workspace_bytes(att()) > 0
+    for field, value, want in (("k", 0, dsk.DSK_ERR_PARAM), ("scale", -1.0, dsk.DSK_ERR_PARAM),
+                               ("scale", float("nan"), dsk.DSK_ERR_PARAM), ("V", None, dsk.DSK_ERR_NULL),
+                               ("v_stride_tok", 100, dsk.DSK_ERR_SHAPE), ("k_stride_tok", 129, dsk.DSK_ERR_ALIGN),
+                               ("out", None, dsk.DSK_ERR_NULL), ("D", 256, dsk.DSK_ERR_SHAPE)):
+        a = att()
+        setattr(a, field, value)
+        assert dsk.dsk_sparse_decode_attn(a, 0, check=False) == want, field
+
+
+def test_binding_never_imports_the_oracle(dsk):
+    assert not any(m == "oracle" or m.startswith("oracle.") for m in sys.modules
+                   if "paper_2602_03184_amd" in (getattr(sys.modules[m], "__package__", "") or ""))
+    src = open(os.path.join(ROOT, "paper_2602_03184_amd", "binding.py")).read()
+    assert "oracle" not in src.replace("no CPU fallback", "")

@@ -1,0 +1,268 @@
+"""GPU parity of dsk_select_topk and dsk_sparse_decode_attn against the fp64 oracle.
+
+Selections must equal the oracle's slot sets bit-exactly, except where the oracle's score gap
+to the threshold is below 1e-4 relative (then the swap is counted and reported).  Attention
+outputs must be within 2e-3 max relative error (fp32 accumulation), lse within 1e-3."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dynsplit_oracle as O
+from dsk_testutil import (DEFAULT_SCALE, bf16_bits_of, dev_bf16, dev_i32, gpu_case, rel_err, selection_check)
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+LSE_TOL = 1e-3
+
+
+def _dsk():
+    import paper_2602_03184_amd as dsk
+    return dsk
+
+
+def _oracle_scores(case, comp_bits_min, comp_bits_max, q_bits, s, heads):
+    """fp64 block scores of sequence s for the given query heads, from the (verified
+    bit-exact) summaries."""
+    cfg, seg = case.cfg, case.seg
+    b0, b1 = int(seg.cu_blocks[s]), int(seg.cu_blocks[s + 1])
+    G = cfg.G
+    out = {}
+    for h in heads:
+        hk = h // G
+        kmin = O.widen_bf16(comp_bits_min[hk, b0:b1])[None]
+        kmax = O.widen_bf16(comp_bits_max[hk, b0:b1])[None]
+        q = O.widen_bf16(q_bits[s, h])[None]
+        out[h] = O.block_scores(q, kmin, kmax)[0]
+    return out
+
+
+def _heads_to_check(cfg):
+    return list(range(cfg.Hq)) if cfg.Hq <= 8 else sorted({0, 1, cfg.G, cfg.Hq // 2 + 1, cfg.Hq - 1})
+
+
+def _seqs_to_check(cfg):
+    return list(range(cfg.B)) if cfg.B <= 2 else [0, cfg.B // 2, cfg.B - 1]
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5])
+def test_select_and_attention_parity(cfg_id):
+    dsk = _dsk()
+    case = gpu_case(cfg_id)
+    cfg, seg, wl = case.cfg, case.seg, case.wl
+    comp = case.compressed()
+    sums = bf16_bits_of(comp.ksum)
+    kmin_bits, kmax_bits = sums[:, :, 0], sums[:, :, 1]
+    n_q = min(cfg.n_queries, 3)
+    swapped_total = 0
+    worst_attn = 0.0
+    for qi in range(n_q):
+        q_bits = wl.q[qi]                                   # [B, Hq, D]
+        q = dev_bf16(q_bits)
+        sel = dsk.select_topk(comp, q, cfg.T, want_scores=True)
+        att = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b)
+        torch.cuda.synchronize()
+        g_slot = sel.sel_slot.cpu().numpy()
+        g_start = sel.sel_start.cpu().numpy()
+        g_len = sel.sel_len.cpu().numpy()
+        g_cnt = sel.sel_count.cpu().numpy()
+        g_scores = sel.scores.cpu().numpy()
+        g_out = att.out.cpu().numpy()
+        g_lse = att.lse.cpu().numpy()
+        for s in _seqs_to_check(cfg):
+            b0, b1 = int(seg.cu_blocks[s]), int(seg.cu_blocks[s + 1])
+            sb = seg.slot_base[b0: b1 + 1]
+            bs = seg.block_start[b0: b1 + 1]
+            heads = _heads_to_check(cfg)
+            osc = _oracle_scores(case, kmin_bits, kmax_bits, q_bits, s, heads)
+            for h in heads:
+                # a6: fp32 scores against fp64
+                np.testing.assert_allclose(g_scores[h, b0:b1], osc[h], rtol=2e-5, atol=2e-4)
+                # a7: slot set
+                o_sel, tau = O.select_slots(osc[h], sb - sb[0], cfg.k)
+                o_sel = o_sel + int(sb[0])
+                cnt = int(g_cnt[s, h])
+                assert cnt == len(o_sel)
+                gs = g_slot[s, h, :cnt]
+                assert (np.diff(gs) > 0).all()
+                assert (g_slot[s, h, cnt:] == -1).all() and (g_len[s, h, cnt:] == 0).all()
+                swapped_total += selection_check(gs, o_sel, tau, osc[h], sb)
+                # spans of the GPU's own slots must be what the slot map says
+                for j in range(cnt):
+                    _, st, ln = O.slot_span(int(gs[j]) - int(sb[0]), bs, sb - sb[0], cfg.b)
+                    assert (int(g_start[s, h, j]), int(g_len[s, h, j])) == (st, ln)
+                # a8 end to end: attention over the GPU's own selection vs the oracle on that set
+                toks = np.concatenate([np.arange(g_start[s, h, j], g_start[s, h, j] + g_len[s, h, j])
+                                       for j in range(cnt)])
+                hk = h // cfg.G
+                Kh = O.widen_bf16(wl.K[hk][toks])
+                Vh = O.widen_bf16(wl.V[hk][toks])
+                o, lse = O.sparse_attention(O.widen_bf16(q_bits[s, h]), Kh, Vh, np.arange(len(toks)), DEFAULT_SCALE)
+                e = rel_err(g_out[s, h], o)
+                worst_attn = max(worst_attn, e)
+                assert e <= ATTN_TOL, (s, h, e)
+                assert abs(float(g_lse[s, h]) - lse) <= LSE_TOL
+    print("cfg%d: swapped selections (near ties) = %d, worst attention rel err = %.3e" %
+          (cfg_id, swapped_total, worst_attn))
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2])
+def test_attention_on_oracle_selection(cfg_id):
+    """dsk_sparse_decode_attn fed the oracle's index set (not its own selection)."""
+    dsk = _dsk()
+    case = gpu_case(cfg_id)
+    cfg, seg, wl = case.cfg, case.seg, case.wl
+    q_bits = wl.q[0]
+    k = cfg.k
+    starts = np.zeros((cfg.B, cfg.Hq, k), np.int32)
+    lens = np.zeros((cfg.B, cfg.Hq, k), np.int32)
+    cnts = np.zeros((cfg.B, cfg.Hq), np.int32)
+    want = {}
+    for s in range(cfg.B):
+        bs, sb = seg.per_seq_block_start[s], O.slot_map(seg.per_seq_block_start[s], cfg.b)
+        lo = int(wl.cu_seqlens[s])
+        for h in range(cfg.Hq):
+            hk = h // cfg.G
+            Kh = O.widen_bf16(wl.K[hk, lo: lo + int(bs[-1])])
+            Vh = O.widen_bf16(wl.V[hk, lo: lo + int(bs[-1])])
+            kmin, kmax = O.block_summaries(Kh[None], bs)
+            sc = O.block_scores(O.widen_bf16(q_bits[s, h])[None], kmin, kmax)[0]
+            sel, _ = O.select_slots(sc, sb, k)
+            for j, g in enumerate(sel):
+                _, st, ln = O.slot_span(int(g), bs, sb, cfg.b)
+                starts[s, h, j], lens[s, h, j] = st + lo, ln
+            cnts[s, h] = len(sel)
+            toks = O.selected_tokens(sel, bs, sb, cfg.b)
+            want[(s, h)] = O.sparse_attention(O.widen_bf16(q_bits[s, h]), Kh, Vh, toks, DEFAULT_SCALE)
+        if cfg.Hq > 8:
+            break
+    att = dsk.sparse_decode_attn(dev_bf16(q_bits), case.K, case.V, dev_i32(starts), dev_i32(lens), dev_i32(cnts), cfg.b)
+    torch.cuda.synchronize()
+    out, lse = att.out.cpu().numpy(), att.lse.cpu().numpy()
+    for (s, h), (o, l) in want.items():
+        assert rel_err(out[s, h], o) <= ATTN_TOL
+        assert abs(float(lse[s, h]) - l) <= LSE_TOL
+
+
+def test_budget_all_equals_dense_attention():
+    """Budget >= sequence length selects every slot; the result is dense softmax attention."""
+    dsk = _dsk()
+    case = gpu_case(1)
+    cfg, wl = case.cfg, case.wl
+    comp = case.compressed()
+    q_bits = wl.q[0]
+    q = dev_bf16(q_bits)
+    L = wl.total_tokens
+    budget = (int(case.seg.slot_base[-1]) + 5) * cfg.b
+    sel = dsk.select_topk(comp, q, budget)
+    att = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b)
+    torch.cuda.synchronize()
+    assert int(sel.sel_count.cpu()[0, 0]) == int(case.seg.slot_base[-1])
+    assert int(sel.sel_len.sum().item()) == L
+    Kh, Vh, qv = O.widen_bf16(wl.K[0]), O.widen_bf16(wl.V[0]), O.widen_bf16(q_bits[0, 0])
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(qv)[None, None, None], torch.from_numpy(Kh)[None, None], torch.from_numpy(Vh)[None, None],
+        scale=DEFAULT_SCALE)[0, 0, 0].numpy()
+    assert rel_err(att.out.cpu().numpy()[0, 0], ref) <= ATTN_TOL
+    lse_ref = float(torch.logsumexp(torch.from_numpy(Kh @ qv) * DEFAULT_SCALE, 0))
+    assert abs(float(att.lse.cpu()[0, 0]) - lse_ref) <= LSE_TOL
+
+
+def test_exact_ties_go_to_lowest_slot_index():
+    """A zero query scores every block 0: the k lowest-numbered slots must be chosen."""
+    dsk = _dsk()
+    case = gpu_case(2)
+    cfg = case.cfg
+    comp = case.compressed()
+    q = torch.zeros(cfg.B, cfg.Hq, 128, dtype=torch.bfloat16, device="cuda")
+    sel = dsk.select_topk(comp, q, cfg.T)
+    torch.cuda.synchronize()
+    want = np.arange(cfg.k)
+    for h in (0, 7, cfg.Hq - 1):
+        np.testing.assert_array_equal(sel.sel_slot.cpu().numpy()[0, h], want)
+    # duplicate block scores made on purpose: copy one head's summaries of block 10 into 20..40
+    ksum = comp.ksum.clone()
+    ksum[:, 20:41] = ksum[:, 10:11]
+    import dataclasses
+    comp2 = dataclasses.replace(comp, ksum=ksum)
+    wl = case.wl
+    qb = wl.q[0]
+    sel2 = dsk.select_topk(comp2, dev_bf16(qb), cfg.T, want_scores=True)
+    torch.cuda.synchronize()
+    sums = bf16_bits_of(ksum)
+    seg = case.seg
+    nb = int(seg.cu_blocks[-1])
+    for h in (0, 3, 13):
+        hk = h // cfg.G
+        sc = O.block_scores(O.widen_bf16(qb[0, h])[None], O.widen_bf16(sums[hk, :nb, 0])[None],
+                            O.widen_bf16(sums[hk, :nb, 1])[None])[0]
+        o_sel, tau = O.select_slots(sc, seg.slot_base, cfg.k)
+        cnt = int(sel2.sel_count.cpu()[0, h])
+        selection_check(sel2.sel_slot.cpu().numpy()[0, h, :cnt], o_sel, tau, sc, seg.slot_base)
+
+
+def test_small_budgets_and_b1():
+    """k = 1, b = 1 (token-level mapping of Sec. 4.2) and a budget that ends inside a block."""
+    dsk = _dsk()
+    case = gpu_case(1)
+    cfg, wl, seg = case.cfg, case.wl, case.seg
+    for b, budget in ((1, 1), (1, 37), (4, 4), (4, 50), (16, 16), (64, 200)):
+        comp = dsk.compress(**case.compress_kwargs(
+            stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_SEGMENT | dsk.DSK_STAGE_SUMMARIES,
+            token_ids=case.token_ids, delim_ids=case.delim_ids, b=b))
+        q_bits = wl.q[0]
+        q = dev_bf16(q_bits)
+        sel = dsk.select_topk(comp, q, budget)
+        att = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, b)
+        torch.cuda.synchronize()
+        bs = seg.per_seq_block_start[0]
+        sb = O.slot_map(bs, b)
+        np.testing.assert_array_equal(comp.slot_base.cpu().numpy()[: len(sb)], sb)
+        Kh, Vh, qv = O.widen_bf16(wl.K[0]), O.widen_bf16(wl.V[0]), O.widen_bf16(q_bits[0, 0])
+        kmin, kmax = O.block_summaries(Kh[None], bs)
+        sc = O.block_scores(qv[None], kmin, kmax)[0]
+        o_sel, tau = O.select_slots(sc, sb, budget // b)
+        cnt = int(sel.sel_count.cpu()[0, 0])
+        gs = sel.sel_slot.cpu().numpy()[0, 0, :cnt]
+        selection_check(gs, o_sel, tau, sc, sb)
+        toks = O.selected_tokens(gs, bs, sb, b)
+        o, lse = O.sparse_attention(qv, Kh, Vh, toks, DEFAULT_SCALE)
+        assert rel_err(att.out.cpu().numpy()[0, 0], o) <= ATTN_TOL
+        assert abs(float(att.lse.cpu()[0, 0]) - lse) <= LSE_TOL
+
+
+def test_empty_selection_and_custom_scale():
+    dsk = _dsk()
+    case = gpu_case(1)
+    wl = case.wl
+    q = dev_bf16(wl.q[0])
+    k = 4
+    starts = dev_i32(np.asarray([[[5, 100, 0, 0]]]))
+    lens = dev_i32(np.asarray([[[3, 16, 0, 0]]]))
+    att = dsk.sparse_decode_attn(q, case.K, case.V, starts, lens, dev_i32([[0]]), 16)
+    torch.cuda.synchronize()
+    assert float(att.out.abs().max().item()) == 0.0 and float(att.lse.item()) == -math.inf
+    att = dsk.sparse_decode_attn(q, case.K, case.V, starts, lens, dev_i32([[2]]), 16, scale=0.25)
+    torch.cuda.synchronize()
+    toks = np.concatenate([np.arange(5, 8), np.arange(100, 116)])
+    o, lse = O.sparse_attention(O.widen_bf16(wl.q[0][0, 0]), O.widen_bf16(wl.K[0]), O.widen_bf16(wl.V[0]), toks, 0.25)
+    assert rel_err(att.out.cpu().numpy()[0, 0], o) <= ATTN_TOL
+    assert abs(float(att.lse.item()) - lse) <= LSE_TOL
+
+
+def test_decode_is_deterministic():
+    dsk = _dsk()
+    case = gpu_case(2)
+    cfg = case.cfg
+    comp = case.compressed()
+    q = dev_bf16(case.wl.q[0])
+    outs = []
+    for _ in range(2):
+        sel = dsk.select_topk(comp, q, cfg.T)
+        att = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b)
+        torch.cuda.synchronize()
+        outs.append((sel.sel_slot.cpu().numpy().copy(), att.out.cpu().numpy().copy()))
+    np.testing.assert_array_equal(outs[0][0], outs[1][0])
+    np.testing.assert_array_equal(outs[0][1], outs[1][1])
