@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the DynSplit-KV hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
+
+A step is one decode step of the whole per-token path -- dsk_select_topk (block scores +
+slot top-k) followed by dsk_sparse_decode_attn -- on the configuration named by
+the benchmark's metric (configs[2]: Llama-3-8B shape, 128K context, b=32, budget 4096),
+cycling over 32 distinct queries.  Inputs are resident in HBM before the timed region; the
+K timed steps are captured in one HIP graph so that host launch cost is not what is timed.
+The compression pass (dsk_compress) is timed separately and reported in the same line, as
+are the roofline of the dominant kernel and the CPU oracle timed on this machine's host cores.
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=320)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold", action="store_true", help="rotate over distinct cache instances (cold LLC)")
+    return ap.parse_args()
+
+
+def event_ms(fn, stream):
+    import torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    fn()
+    e1.record(stream)
+    e1.synchronize()
+    return e0.elapsed_time(e1)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported. Run with --gpus 1." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2602_03184_amd as dsk
+    from workloads import CONFIGS, make_workload
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = CONFIGS[args.config]
+    t0 = time.time()
+    wl = make_workload(args.config)
+    gen_s = time.time() - t0
+
+    def bf16(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    def i32(a):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+
+    K, V = bf16(wl.K), bf16(wl.V)
+    queries = [bf16(wl.q[i]) for i in range(cfg.n_queries)]
+    cu = i32(wl.cu_seqlens)
+    ckw = dict(cu_seqlens=cu, max_seqlen=int(wl.seqlens.max()), Hq=cfg.Hq, K=K, V=V,
+               stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_SEGMENT | dsk.DSK_STAGE_SUMMARIES,
+               token_ids=i32(wl.token_ids), delim_ids=i32(wl.delim_ids), n_class=cfg.n_class,
+               class_weight_q=torch.from_numpy(wl.class_weight_q).to(dev),
+               C_=int(wl.C.max()), delta=int(wl.delta.max()),
+               C_per_seq=i32(wl.C) if cfg.B > 1 else None, delta_per_seq=i32(wl.delta) if cfg.B > 1 else None,
+               min_chunk=int((wl.C - wl.delta).min()), alpha_num=cfg.a_num, alpha_den=cfg.a_den, b=cfg.b)
+    stream = torch.cuda.Stream()   # default priority
+    with torch.cuda.stream(stream):
+        comp = dsk.compress(**ckw)
+        stream.synchronize()
+        assert int(comp.dev_status.item()) == 0
+        nblk = int(comp.cu_blocks.cpu()[-1])
+        nslots = int(comp.slot_base.cpu()[nblk])
+
+        # ---- compression pass, timed by itself (same buffers re-used) -------------------------
+        cargs = comp.args
+        for _ in range(3):
+            dsk.dsk_compress(cargs, stream)
+        n_c = 10
+        compress_ms = event_ms(lambda: [dsk.dsk_compress(cargs, stream) for _ in range(n_c)], stream) / n_c
+        compress_bytes = wl.total_tokens * cfg.Hkv * 128 * 2 + nblk * cfg.Hkv * 512 + wl.total_tokens * 4
+
+        # ---- decode step: per-query argument structs, buffers shared --------------------------
+        nq = len(queries)
+        sels = [dsk.make_select_args(comp, queries[0], cfg.T)]
+        for i in range(1, nq):
+            sels.append(dsk.make_select_args(comp, queries[i], cfg.T, out=sels[0]))
+        atts = [dsk.make_attn_args(queries[0], K, V, sels[0].sel_start, sels[0].sel_len, sels[0].sel_count, cfg.b)]
+        for i in range(1, nq):
+            atts.append(dsk.make_attn_args(queries[i], K, V, sels[0].sel_start, sels[0].sel_len, sels[0].sel_count,
+                                           cfg.b, out=atts[0]))
+
+        def step(i):
+            dsk.dsk_select_topk(sels[i % nq].args, stream)
+            dsk.dsk_sparse_decode_attn(atts[i % nq].args, stream)
+
+        for i in range(args.warmup):
+            step(i)
+        stream.synchronize()
+
+        # algorithmic bytes of one step: every summary once + K/V rows of the selected tokens
+        sel_tokens = []
+        for i in range(nq):
+            step(i)
+            stream.synchronize()
+            sel_tokens.append(int(sels[0].sel_len.sum().item()))
+        mean_sel_tokens = float(np.mean(sel_tokens))
+        bytes_scores = nblk * cfg.Hkv * 512
+        bytes_attn = mean_sel_tokens * 512          # 256 B of K + 256 B of V per selected (head, token)
+        bytes_small = cfg.B * cfg.Hq * (128 * 2 + 128 * 4 + 3 * cfg.k * 4 * 2)
+        step_bytes = bytes_scores + bytes_attn + bytes_small
+
+        # ---- K steps in one graph --------------------------------------------------------------
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(args.steps):
+                step(i)
+        graph.replay()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t_ms = event_ms(graph.replay, stream)
+        torch.cuda.synchronize()
+        us_per_step = t_ms * 1e3 / args.steps
+
+        # eager launches, for reference (host launch cost included)
+        eager_ms = event_ms(lambda: [step(i) for i in range(args.steps)], stream)
+        eager_us = eager_ms * 1e3 / args.steps
+
+        # ---- dominant kernel: the attention gather, timed on its own stream region --------------
+        g_attn = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_attn, stream=stream):
+            for i in range(args.steps):
+                dsk.dsk_sparse_decode_attn(atts[i % nq].args, stream)
+        g_attn.replay()
+        stream.synchronize()
+        attn_us = event_ms(g_attn.replay, stream) * 1e3 / args.steps
+        g_sel = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_sel, stream=stream):
+            for i in range(args.steps):
+                dsk.dsk_select_topk(sels[i % nq].args, stream)
+        g_sel.replay()
+        stream.synchronize()
+        select_us = event_ms(g_sel.replay, stream) * 1e3 / args.steps
+    torch.cuda.synchronize()
+
+    attn_gbs = bytes_attn / (attn_us * 1e-6) / 1e9
+    step_gbs = step_bytes / (us_per_step * 1e-6) / 1e9
+    out = {
+        "metric": "decode attn us/step + achieved HBM GB/s at 128K ctx (Llama-3-8B shape)",
+        "value": round(us_per_step, 3),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(us_per_step / 1e3, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 in, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "context": int(wl.total_tokens), "Hq": cfg.Hq, "Hkv": cfg.Hkv, "b": cfg.b,
+                   "budget": cfg.T, "blocks": nblk, "slots": nslots, "queries": nq,
+                   "selection": "per query head", "timing": "HIP graph of %d steps" % args.steps},
+        "achieved_GBps": round(step_gbs, 1),
+        "step_bytes": int(step_bytes),
+        "eager_us_per_step": round(eager_us, 3),
+        "select_us": round(select_us, 3),
+        "attn_us": round(attn_us, 3),
+        "compress": {"us": round(compress_ms * 1e3, 2), "bytes": int(compress_bytes),
+                     "GBps": round(compress_bytes / (compress_ms * 1e-3) / 1e9, 1),
+                     "frac_of_hbm_peak": round(compress_bytes / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "stages": "candidates+segment+summaries(K)"},
+        "roofline": {"bound": "hbm", "kernel": "dsk_sparse_decode_attn (attn_partial_kernel + merge)",
+                     "achieved": round(attn_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(attn_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "bytes_per_launch": int(bytes_attn), "us_per_launch": round(attn_us, 3)},
+        "workload_gen_s": round(gen_s, 1),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, comp, nblk)
+    print(json.dumps(out))
+
+
+def cpu_baseline(wl, comp, nblk):
+    """The fp64 oracle, as it stands, timed on this machine's host cores on a bounded sample:
+    decode steps (scores + slot top-k + attention over the selection) for all query heads of
+    the first queries of the workload, on the GPU-produced (parity-tested) block table and
+    summaries.  BLAS/OpenMP pools are limited to one thread so the thread count is known."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+
+    from oracle import dynsplit_oracle as O
+    cfg = wl.cfg
+    bs = comp.block_start.cpu().numpy()[: nblk + 1].astype(np.int64)
+    sb = comp.slot_base.cpu().numpy()[: nblk + 1].astype(np.int64)
+    sums = comp.ksum[:, :nblk].contiguous().view(__import__("torch").int16).cpu().numpy().view(np.uint16)
+    scale = 1.0 / np.sqrt(128.0)
+    budget_s, n_done, t_spent = 12.0, 0, 0.0
+    with threadpool_limits(limits=1):
+        kmin = O.widen_bf16(sums[:, :, 0])
+        kmax = O.widen_bf16(sums[:, :, 1])
+        while n_done < cfg.n_queries and t_spent < budget_s:
+            qb = wl.q[n_done]
+            t0 = time.perf_counter()
+            for s in range(cfg.B):
+                b0, b1 = int(comp.cu_blocks.cpu()[s]), int(comp.cu_blocks.cpu()[s + 1])
+                qf = O.widen_bf16(qb[s])
+                sc = O.block_scores(qf, kmin[:, b0:b1], kmax[:, b0:b1])
+                for h in range(cfg.Hq):
+                    sel, _ = O.select_slots(sc[h], sb[b0: b1 + 1] - sb[b0], cfg.k)
+                    toks = O.selected_tokens(sel, bs[b0: b1 + 1], sb[b0: b1 + 1] - sb[b0], cfg.b)
+                    hk = h // cfg.G
+                    O.sparse_attention(qf[h], O.widen_bf16(wl.K[hk][toks]), O.widen_bf16(wl.V[hk][toks]),
+                                       np.arange(len(toks)), scale)
+            t_spent += time.perf_counter() - t0
+            n_done += 1
+    return {"value": round(t_spent / n_done * 1e6, 1), "unit": "us/step", "cores": 1, "kind": "oracle",
+            "sample": "%d full decode steps (scores + slot top-k + attention, all %d query heads) of %s"
+                      % (n_done, cfg.Hq, cfg.name)}
+
+
+if __name__ == "__main__":
+    main()
