@@ -141,9 +141,10 @@ typedef struct dsk_compress_args {
   int32_t alpha_num, alpha_den;/* alpha_sel = alpha_num/alpha_den in [0,1], alpha_den in 1..1000 */
   int32_t b;                   /* fixed mapped block (slot) length, 1..1024 */
   int32_t max_blocks_total;    /* capacity (in blocks) of the outputs below */
-  int32_t* block_start;        /* [dev] [max_blocks_total+1] */
+  int32_t* block_start;        /* [dev] [max_blocks_total+4] (entries 0..max_blocks_total used) */
   int32_t* cu_blocks;          /* [dev] [B+1] block range of each sequence */
-  int32_t* slot_base;          /* [dev] [max_blocks_total+1] */
+  int32_t* slot_base;          /* [dev] [max_blocks_total+4] (entries 0..max_blocks_total used;
+                                  dsk_select_topk reads it in 16-byte vectors) */
 
   /* summaries: [Hkv, max_blocks_total, 2, D] bf16; [.., 0, :] = min, [.., 1, :] = max */
   void* ksum;                  /* [dev] */
@@ -169,8 +170,8 @@ typedef struct dsk_select_args {
   int32_t B, Hq, Hkv, D;
   int32_t max_blocks_total;    /* capacity used when ksum / block tables were allocated */
   const int32_t* cu_blocks;    /* [dev] [B+1] */
-  const int32_t* block_start;  /* [dev] */
-  const int32_t* slot_base;    /* [dev] */
+  const int32_t* block_start;  /* [dev] both tables: 16-byte aligned and readable up to a multiple */
+  const int32_t* slot_base;    /* [dev] of 4 entries, i.e. allocate max_blocks_total + 4 ints */
   const void* ksum;            /* [dev] bf16 [Hkv, max_blocks_total, 2, D] */
   const void* q;               /* [dev] bf16 [B, Hq, D] */
   int32_t b;                   /* slot length used by dsk_compress */

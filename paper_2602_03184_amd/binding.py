@@ -281,8 +281,8 @@ def compress(*, cu_seqlens: torch.Tensor, max_seqlen: int, Hq: int, K: Optional[
             mc = min_chunk if min_chunk is not None else C_ - delta
             max_blocks_total = dsk_block_capacity(total_tokens, B, mc)
     if stages & DSK_STAGE_SEGMENT:
-        block_start = torch.empty(max_blocks_total + 1, **i32)
-        slot_base = torch.empty(max_blocks_total + 1, **i32)
+        block_start = torch.zeros(max_blocks_total + 4, **i32)  # both tables are read in 16-byte vectors
+        slot_base = torch.zeros(max_blocks_total + 4, **i32)   # read in 16-byte vectors by dsk_select_topk
         cu_blocks = torch.empty(B + 1, **i32)
     a.max_blocks_total = max_blocks_total
     a.block_start, a.cu_blocks, a.slot_base = _ptr(block_start), _ptr(cu_blocks), _ptr(slot_base)

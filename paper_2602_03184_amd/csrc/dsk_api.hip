@@ -109,11 +109,10 @@ static dsk_status validate_select(const dsk_select_args* a) {
   if (!a->cu_blocks || !a->block_start || !a->slot_base || !a->ksum || !a->q || !a->sel_slot || !a->sel_start ||
       !a->sel_len || !a->sel_count)
     return DSK_ERR_NULL;
-  if (!aligned16(a->ksum) || !aligned16(a->q)) return DSK_ERR_ALIGN;
-  if (a->scores == nullptr) {
-    if (a->workspace == nullptr || a->workspace_bytes < dsk_select_workspace_bytes(a)) return DSK_ERR_WORKSPACE;
-    if (!aligned256(a->workspace)) return DSK_ERR_ALIGN;
-  }
+  if (!aligned16(a->ksum) || !aligned16(a->q) || !aligned16(a->slot_base) || !aligned16(a->block_start))
+    return DSK_ERR_ALIGN;
+  if (a->workspace == nullptr || a->workspace_bytes < dsk_select_workspace_bytes(a)) return DSK_ERR_WORKSPACE;
+  if (!aligned256(a->workspace)) return DSK_ERR_ALIGN;
   return DSK_OK;
 }
 
@@ -174,7 +173,7 @@ size_t dsk_compress_workspace_bytes(const dsk_compress_args* a) {
 size_t dsk_select_workspace_bytes(const dsk_select_args* a) {
   if (a == nullptr || a->struct_size != sizeof(dsk_select_args)) return 0;
   if (a->Hq < 1 || a->max_blocks_total < 1) return 0;
-  return align_up((size_t)a->Hq * a->max_blocks_total * sizeof(float));
+  return align_up((size_t)a->Hq * select_score_stride(*a) * sizeof(float));
 }
 
 size_t dsk_attn_workspace_bytes(const dsk_attn_args* a) {
@@ -203,9 +202,10 @@ dsk_status dsk_select_topk(const dsk_select_args* a, void* stream) {
   const dsk_status v = validate_select(a);
   if (v != DSK_OK) return v;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  float* scores = a->scores ? a->scores : static_cast<float*>(a->workspace);
-  if (launch_scores(*a, scores, st) != hipSuccess) return DSK_ERR_LAUNCH;
-  if (launch_select(*a, scores, st) != hipSuccess) return DSK_ERR_LAUNCH;
+  float* scores = static_cast<float*>(a->workspace);
+  const int stride = select_score_stride(*a);
+  if (launch_scores(*a, scores, stride, st) != hipSuccess) return DSK_ERR_LAUNCH;
+  if (launch_select(*a, scores, stride, st) != hipSuccess) return DSK_ERR_LAUNCH;
   return DSK_OK;
 }
 

@@ -40,8 +40,10 @@ hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, hipS
 hipError_t launch_summaries(const dsk_compress_args& a, hipStream_t st);
 
 // ---- dsk_select_topk ----------------------------------------------------------------------
-hipError_t launch_scores(const dsk_select_args& a, float* scores, hipStream_t st);
-hipError_t launch_select(const dsk_select_args& a, const float* scores, hipStream_t st);
+// block scores live in the workspace as rows of `stride` = round_up(max_blocks_total, 4) floats
+inline int select_score_stride(const dsk_select_args& a) { return (a.max_blocks_total + 3) / 4 * 4; }
+hipError_t launch_scores(const dsk_select_args& a, float* scores, int stride, hipStream_t st);
+hipError_t launch_select(const dsk_select_args& a, const float* scores, int stride, hipStream_t st);
 
 // ---- dsk_sparse_decode_attn -----------------------------------------------------------------
 struct AttnWs {

@@ -4,7 +4,9 @@
 // reads 4 token rows per load instruction and issues every load of a slot (K and V) before
 // it touches the data.  Each wavefront folds its slots into an online-softmax state
 // (m, l, acc); the 4 wavefronts of a workgroup merge through LDS into one partial per
-// (sequence, head, chunk of slots); a second small kernel merges the partials in chunk order.
+// (sequence, head, chunk of slots); a second small kernel merges the partials in a fixed order
+// (a device-wide fence per workgroup, as a single-kernel merge needs, costs far more on this
+// part than the extra launch inside a stream or graph).
 #include "dsk_common.hpp"
 #include "dsk_internal.hpp"
 
@@ -72,12 +74,15 @@ __device__ __forceinline__ void fold_rows(WaveState& st, const float (&qf)[8], c
   st.m = m_new;
 }
 
-__global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
+// One workgroup per (chunk of kAttnSlotsPerWg slots, head, sequence); writes one partial, or the
+// final result when the head has a single chunk.
+__global__ __launch_bounds__(kAttnThreads) void attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     int64_t kst, int64_t ksh, int64_t vst, int64_t vsh, int Hq, int G, int k, int b, int total_tokens,
     const int32_t* __restrict__ sel_start, const int32_t* __restrict__ sel_len,
     const int32_t* __restrict__ sel_count, float scale_log2, int nchunks,
-    float2* __restrict__ part_ml, float* __restrict__ part_acc) {
+    float2* __restrict__ part_ml, float* __restrict__ part_acc, float* __restrict__ out,
+    float* __restrict__ lse) {
   __shared__ float sm_m[kAttnWaves];
   __shared__ float sm_l[kAttnWaves];
   __shared__ float sm_acc[kAttnWaves][DSK_HEAD_DIM];
@@ -86,17 +91,34 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
   const int h = blockIdx.y;
   const int s = blockIdx.z;
   const int64_t sh = (int64_t)s * Hq + h;
-  int count = sel_count[sh];
-  if (count > k) count = k;
-  const int slot0 = chunk * kAttnSlotsPerWg;
-  if (slot0 >= count) return;   // uniform over the workgroup; the merge kernel skips this chunk too
-
   const int lane = threadIdx.x & (DSK_WAVE - 1);
   const int wave = threadIdx.x / DSK_WAVE;
+  const int slot0 = chunk * kAttnSlotsPerWg;
+
+  // the wave's slots: slot0 + wave + kAttnWaves * r; their spans are fetched together with the count
+  constexpr int kSlotsPerWave = kAttnSlotsPerWg / kAttnWaves;
+  int count = sel_count[sh];
+  int st_[kSlotsPerWave], ln_[kSlotsPerWave];
+#pragma unroll
+  for (int r = 0; r < kSlotsPerWave; ++r) {
+    const int j = slot0 + wave + kAttnWaves * r;
+    st_[r] = j < k ? sel_start[sh * k + j] : 0;
+    ln_[r] = j < k ? sel_len[sh * k + j] : 0;
+  }
+  if (count > k) count = k;
+  if (count <= 0) {   // nothing selected: chunk 0 writes the defined empty result
+    if (chunk == 0 && threadIdx.x < DSK_HEAD_DIM) {
+      out[sh * DSK_HEAD_DIM + threadIdx.x] = 0.0f;
+      if (threadIdx.x == 0 && lse) lse[sh] = -__builtin_inff();
+    }
+    return;
+  }
+  if (slot0 >= count) return;   // uniform over the workgroup; not counted in `used` below
+  const int used = (count + kAttnSlotsPerWg - 1) / kAttnSlotsPerWg;
+
   const int g = lane >> 4;
   const int c = lane & 15;
   const int hk = h / G;
-
   float qf[8];
   {
     const uint4 qv = *reinterpret_cast<const uint4*>(q + sh * DSK_HEAD_DIM + c * 8);
@@ -111,11 +133,13 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
 #pragma unroll
   for (int i = 0; i < 8; ++i) st.acc[i] = 0.0f;
 
-  for (int j = slot0 + wave; j < slot0 + kAttnSlotsPerWg && j < count; j += kAttnWaves) {
-    const int start = sel_start[sh * k + j];
-    int len = sel_len[sh * k + j];
+#pragma unroll
+  for (int r = 0; r < kSlotsPerWave; ++r) {
+    const int j = slot0 + wave + kAttnWaves * r;
+    const int start = st_[r];
+    int len = ln_[r];
     if (len > b) len = b;
-    if (start < 0 || len <= 0 || start > total_tokens - len) continue;   // never read outside K/V
+    if (j >= count || start < 0 || len <= 0 || start > total_tokens - len) continue;   // never read outside K/V
     for (int r0 = 0; r0 < len; r0 += 32) {
       const int nv = len - r0;
       const uint16_t* kb = Kh + (int64_t)(start + r0) * kst;
@@ -141,50 +165,88 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
   __syncthreads();
 
   // waves -> workgroup partial, fixed order
-  if (threadIdx.x < DSK_HEAD_DIM) {
-    float M = sm_m[0];
+  const int d = threadIdx.x;
+  float M = 0.0f, l = 0.0f, a = 0.0f;
+  if (d < DSK_HEAD_DIM) {
+    M = sm_m[0];
 #pragma unroll
     for (int w = 1; w < kAttnWaves; ++w) M = fmaxf(M, sm_m[w]);
-    float l = 0.0f, a = 0.0f;
 #pragma unroll
     for (int w = 0; w < kAttnWaves; ++w) {
       const float f = sm_m[w] == -__builtin_inff() ? 0.0f : exp2f(sm_m[w] - M);   // idle wave
       l = fmaf(sm_l[w], f, l);
-      a = fmaf(sm_acc[w][threadIdx.x], f, a);
+      a = fmaf(sm_acc[w][d], f, a);
     }
-    const int64_t pi = sh * nchunks + chunk;
-    part_acc[pi * DSK_HEAD_DIM + threadIdx.x] = a;
-    if (threadIdx.x == 0) part_ml[pi] = make_float2(M, l);
+  }
+  if (used == 1) {   // the only chunk of this head: finish here
+    if (d < DSK_HEAD_DIM) {
+      out[sh * DSK_HEAD_DIM + d] = l > 0.0f ? a / l : 0.0f;
+      if (d == 0 && lse) lse[sh] = l > 0.0f ? (M + log2f(l)) * kLn2 : -__builtin_inff();
+    }
+    return;
+  }
+  const int64_t pbase = sh * nchunks;
+  if (d < DSK_HEAD_DIM) {
+    part_acc[(pbase + chunk) * DSK_HEAD_DIM + d] = a;
+    if (d == 0) part_ml[pbase + chunk] = make_float2(M, l);
   }
 }
 
-__global__ __launch_bounds__(DSK_HEAD_DIM) void attn_merge_kernel(
+// Merge of the partials of one (sequence, head) in a fixed order: 16 lane groups each fold the
+// chunks ch = group, group+16, ... (all loads of a round are independent), then one pass over
+// the 16 group states in LDS.  Heads with a single chunk were finished by attn_kernel.
+constexpr int kMergeThreads = 256;
+constexpr int kMergeGroups = kMergeThreads / 16;
+__global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
     const float2* __restrict__ part_ml, const float* __restrict__ part_acc,
     const int32_t* __restrict__ sel_count, int k, int nchunks, float* __restrict__ out,
     float* __restrict__ lse) {
+  __shared__ float sm_m[kMergeGroups];
+  __shared__ float sm_l[kMergeGroups];
+  __shared__ float sm_acc[kMergeGroups][DSK_HEAD_DIM];
   const int64_t sh = blockIdx.x;
-  const int d = threadIdx.x;
   int count = sel_count[sh];
   if (count > k) count = k;
   const int used = (count + kAttnSlotsPerWg - 1) / kAttnSlotsPerWg;
-  if (used <= 0) {
-    out[sh * DSK_HEAD_DIM + d] = 0.0f;
-    if (d == 0 && lse) lse[sh] = -__builtin_inff();
-    return;
-  }
+  if (used <= 1) return;   // empty or single-chunk heads are complete already
+  const int grp = threadIdx.x >> 4;
+  const int c = threadIdx.x & 15;
   const float2* ml = part_ml + sh * nchunks;
-  const float* acc = part_acc + sh * nchunks * DSK_HEAD_DIM;
-  float M = -__builtin_inff();
-  for (int ch = 0; ch < used; ++ch) M = fmaxf(M, ml[ch].x);
-  float l = 0.0f, a = 0.0f;
-  for (int ch = 0; ch < used; ++ch) {
+  const float* acc = part_acc + sh * nchunks * DSK_HEAD_DIM + c * 8;
+  float m = -__builtin_inff(), l = 0.0f, a[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = 0.0f;
+  for (int ch = grp; ch < used; ch += kMergeGroups) {
     const float2 v = ml[ch];
-    const float f = v.x == -__builtin_inff() ? 0.0f : exp2f(v.x - M);
-    l = fmaf(v.y, f, l);
-    a = fmaf(acc[(int64_t)ch * DSK_HEAD_DIM + d], f, a);
+    const float4 x0 = *reinterpret_cast<const float4*>(acc + (int64_t)ch * DSK_HEAD_DIM);
+    const float4 x1 = *reinterpret_cast<const float4*>(acc + (int64_t)ch * DSK_HEAD_DIM + 4);
+    if (v.x == -__builtin_inff()) continue;
+    const float mn = fmaxf(m, v.x);
+    const float fo = exp2f(m - mn), fn = exp2f(v.x - mn);   // m = -inf -> fo = 0
+    l = l * fo + v.y * fn;
+    a[0] = a[0] * fo + x0.x * fn; a[1] = a[1] * fo + x0.y * fn; a[2] = a[2] * fo + x0.z * fn; a[3] = a[3] * fo + x0.w * fn;
+    a[4] = a[4] * fo + x1.x * fn; a[5] = a[5] * fo + x1.y * fn; a[6] = a[6] * fo + x1.z * fn; a[7] = a[7] * fo + x1.w * fn;
+    m = mn;
   }
-  out[sh * DSK_HEAD_DIM + d] = l > 0.0f ? a / l : 0.0f;
-  if (d == 0 && lse) lse[sh] = l > 0.0f ? (M + log2f(l)) * kLn2 : -__builtin_inff();
+  if (c == 0) { sm_m[grp] = m; sm_l[grp] = l; }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) sm_acc[grp][c * 8 + i] = a[i];
+  __syncthreads();
+  const int d = threadIdx.x;
+  if (d < DSK_HEAD_DIM) {
+    float M = sm_m[0];
+#pragma unroll
+    for (int g2 = 1; g2 < kMergeGroups; ++g2) M = fmaxf(M, sm_m[g2]);
+    float L = 0.0f, A = 0.0f;
+#pragma unroll
+    for (int g2 = 0; g2 < kMergeGroups; ++g2) {
+      const float f = sm_m[g2] == -__builtin_inff() ? 0.0f : exp2f(sm_m[g2] - M);
+      L = fmaf(sm_l[g2], f, L);
+      A = fmaf(sm_acc[g2][d], f, A);
+    }
+    out[sh * DSK_HEAD_DIM + d] = L > 0.0f ? A / L : 0.0f;
+    if (d == 0 && lse) lse[sh] = L > 0.0f ? (M + log2f(L)) * kLn2 : -__builtin_inff();
+  }
 }
 
 AttnWs attn_ws_layout(const dsk_attn_args& a) {
@@ -203,13 +265,14 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   float* part_acc = reinterpret_cast<float*>(w + ws.part_acc);
   const float scale = a.scale != 0.0f ? a.scale : 0.08838834764831845f;   // 128^-1/2
   const dim3 grid((unsigned)ws.nchunks, (unsigned)a.Hq, (unsigned)a.B);
-  attn_partial_kernel<<<grid, dim3(kAttnThreads), 0, st>>>(
+  attn_kernel<<<grid, dim3(kAttnThreads), 0, st>>>(
       static_cast<const uint16_t*>(a.q), static_cast<const uint16_t*>(a.K), static_cast<const uint16_t*>(a.V),
       a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, a.Hq / a.Hkv, a.k, a.b,
-      a.total_tokens, a.sel_start, a.sel_len, a.sel_count, scale * kLog2e, ws.nchunks, part_ml, part_acc);
+      a.total_tokens, a.sel_start, a.sel_len, a.sel_count, scale * kLog2e, ws.nchunks, part_ml,
+      part_acc, a.out, a.lse);
   hipError_t err = hipGetLastError();
-  if (err != hipSuccess) return err;
-  attn_merge_kernel<<<dim3((unsigned)(a.B * a.Hq)), dim3(DSK_HEAD_DIM), 0, st>>>(
+  if (err != hipSuccess || ws.nchunks <= 1) return err;
+  attn_merge_kernel<<<dim3((unsigned)(a.B * a.Hq)), dim3(kMergeThreads), 0, st>>>(
       part_ml, part_acc, a.sel_count, a.k, ws.nchunks, a.out, a.lse);
   return hipGetLastError();
 }

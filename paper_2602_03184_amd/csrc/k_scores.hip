@@ -3,79 +3,155 @@
 // with q+ = max(q,0), q- = min(q,0): one dot product of length 2D against the 512-byte
 // (min,max) summary of the block.  Memory-bound: every summary is read once per step and
 // shared by the G query heads of its KV head.  A half-wavefront (32 lanes x 16 B) covers one
-// summary, so a wavefront scores two blocks per load.
+// summary; it takes 8 (4 for G = 8) consecutive blocks, issues all their loads first, and
+// reduces the blocks x heads partial sums over its 32 lanes with a transposing butterfly
+// (each exchange halves the values a lane still carries), so a lane ends up owning the
+// finished score of one (block, head) pair.
 #include "dsk_common.hpp"
 #include "dsk_internal.hpp"
 
 namespace dsk {
 
 constexpr int kScoreThreads = 256;
-constexpr int kScoreBlocksPerWg = 64;   // 4 waves x 2 half-waves x 8 blocks
+constexpr int kHalvesPerWg = kScoreThreads / 32;
+__host__ __device__ constexpr int score_blocks_per_half(int G) { return G >= 8 ? 4 : 8; }
 
+// Sum V (a power of two, <= 32) per-lane values over the 32 lanes of a half-wave.  While more
+// than one value is left, a step over lane bit M halves them: the lane keeps the upper half of
+// the value indices if its bit M is set (the lower half otherwise) and adds what its partner
+// (lane ^ M) carried for that half; afterwards plain exchanges finish the sum.  On return
+// v[0] is the finished sum of original value index `idx` (built MSB-first from the lane bits
+// of the halving steps).
+template <int N, int V, int M>
+__device__ __forceinline__ void half_wave_reduce(float (&v)[N], int lane, int& idx) {
+  if constexpr (M >= 1) {
+    if constexpr (V >= 2) {
+      const bool up = (lane & M) != 0;
+#pragma unroll
+      for (int x = 0; x < V / 2; ++x) {
+        const float send = up ? v[x] : v[x + V / 2];
+        const float keep = up ? v[x + V / 2] : v[x];
+        v[x] = keep + shfl_xor_f(send, M);
+      }
+      idx = idx * 2 + (up ? 1 : 0);
+      half_wave_reduce<N, V / 2, M / 2>(v, lane, idx);
+    } else {
+      v[0] += shfl_xor_f(v[0], M);
+      half_wave_reduce<N, 1, M / 2>(v, lane, idx);
+    }
+  }
+}
+
+// value index = block_in_group * G + g
 template <int G>
 __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
     const uint16_t* __restrict__ ksum, const uint16_t* __restrict__ q, const int32_t* __restrict__ cu_blocks,
-    int B, int Hq, int cap, float* __restrict__ scores) {
+    int B, int Hq, int cap, int stride, float* __restrict__ scores, float* __restrict__ user) {
+  constexpr int NB = score_blocks_per_half(G);
+  constexpr int V = NB * G;
+  static_assert(V <= 32 && (V & (V - 1)) == 0, "one finished value per lane");
   const int hk = blockIdx.y;
   int nblk = cu_blocks[B];
   if (nblk > cap) nblk = cap;
   const int half = threadIdx.x >> 5;          // 0..7 within the workgroup
   const int c = threadIdx.x & 31;             // 16-byte column of the summary
-  const int is_max = c >> 4;                  // lanes 0-15: kmin, 16-31: kmax
+  const bool is_max = c >= 16;                // lanes 0-15: kmin, 16-31: kmax
   const int d0 = (c & 15) * 8;
-  const int first = blockIdx.x * kScoreBlocksPerWg;
-  const uint16_t* kh = ksum + (int64_t)hk * cap * (2 * DSK_HEAD_DIM);
+  const int i0 = (blockIdx.x * kHalvesPerWg + half) * NB;   // first block of this half-wave
+  if (i0 >= nblk) return;                     // whole half-waves leave together
+  const uint16_t* kh = ksum + (int64_t)hk * cap * (2 * DSK_HEAD_DIM) + c * 8;
 
-  int cur_s = -1;
-  float qs[G][8];
-  for (int it = 0; it < kScoreBlocksPerWg / 8; ++it) {
-    const int i = first + it * 8 + half;      // all 32 lanes of a half-wave share i
-    if (i >= nblk) break;
-    // sequence of block i (blocks of a sequence are contiguous)
-    int s = cur_s < 0 ? 0 : cur_s;
-    while (s + 1 < B && cu_blocks[s + 1] <= i) ++s;
-    if (s != cur_s) {
-      cur_s = s;
+  uint4 kv[NB];
 #pragma unroll
+  for (int u = 0; u < NB; ++u) {
+    int i = i0 + u;
+    i = i < nblk ? i : nblk - 1;              // tail: re-read the last block, result dropped
+    kv[u] = *reinterpret_cast<const uint4*>(kh + (int64_t)i * (2 * DSK_HEAD_DIM));
+  }
+  // sequence of the group (blocks of a sequence are contiguous; a group rarely straddles two)
+  int s_first = 0;
+  while (s_first + 1 < B && cu_blocks[s_first + 1] <= i0) ++s_first;
+  const int ilast = (i0 + NB - 1 < nblk) ? i0 + NB - 1 : nblk - 1;
+  const bool one_seq = (s_first + 1 >= B) || (cu_blocks[s_first + 1] > ilast);
+  if (!one_seq) {
+    // slow path: per block, with its own sequence's query
+    int s = s_first;
+    for (int u = 0; u < NB && i0 + u < nblk; ++u) {
+      const int i = i0 + u;
+      while (s + 1 < B && cu_blocks[s + 1] <= i) ++s;
+      const uint4 kvu = *reinterpret_cast<const uint4*>(kh + (int64_t)i * (2 * DSK_HEAD_DIM));
+      float f[8];
+      unpack8(kvu, f);
       for (int g = 0; g < G; ++g) {
         const uint4 qv = *reinterpret_cast<const uint4*>(q + ((int64_t)s * Hq + hk * G + g) * DSK_HEAD_DIM + d0);
-        float f[8];
-        unpack8(qv, f);
+        float qf[8];
+        unpack8(qv, qf);
+        float acc = 0.0f;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) qs[g][k] = is_max ? fmaxf(f[k], 0.0f) : fminf(f[k], 0.0f);
+        for (int k = 0; k < 8; ++k) acc = fmaf(is_max ? fmaxf(qf[k], 0.0f) : fminf(qf[k], 0.0f), f[k], acc);
+        // same summation tree as the fast path: lane bits 16, 8, 4, 2, 1
+        acc += shfl_xor_f(acc, 16);
+        acc += shfl_xor_f(acc, 8);
+        acc += shfl_xor_f(acc, 4);
+        acc += shfl_xor_f(acc, 2);
+        acc += shfl_xor_f(acc, 1);
+        if (c == 0) {
+          scores[(int64_t)(hk * G + g) * stride + i] = acc;
+          if (user) user[(int64_t)(hk * G + g) * cap + i] = acc;
+        }
       }
     }
-    const uint4 kv = *reinterpret_cast<const uint4*>(kh + (int64_t)i * (2 * DSK_HEAD_DIM) + c * 8);
+    return;
+  }
+
+  float qs[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const uint4 qv = *reinterpret_cast<const uint4*>(q + ((int64_t)s_first * Hq + hk * G + g) * DSK_HEAD_DIM + d0);
     float f[8];
-    unpack8(kv, f);
+    unpack8(qv, f);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) qs[g][k] = is_max ? fmaxf(f[k], 0.0f) : fminf(f[k], 0.0f);
+  }
+  float v[V];
+#pragma unroll
+  for (int u = 0; u < NB; ++u) {
+    float f[8];
+    unpack8(kv[u], f);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       float acc = 0.0f;
 #pragma unroll
       for (int k = 0; k < 8; ++k) acc = fmaf(qs[g][k], f[k], acc);
-      acc = group16_sum(acc);
-      acc += shfl_xor_f(acc, 16);
-      if (c == 0) scores[(int64_t)(hk * G + g) * cap + i] = acc;
+      v[u * G + g] = acc;
     }
+  }
+  int idx = 0;
+  half_wave_reduce<V, V, 16>(v, c, idx);
+  const bool writer = (c & (32 / V - 1)) == 0;   // lanes differing only in non-halving bits hold copies
+  const int u = idx / G, g = idx % G;
+  if (writer && i0 + u < nblk) {
+    scores[(int64_t)(hk * G + g) * stride + i0 + u] = v[0];
+    if (user) user[(int64_t)(hk * G + g) * cap + i0 + u] = v[0];
   }
 }
 
-// any group width: q is re-read per block (it stays in the vector cache)
+// any group width: one block per half-wave step, q re-read per block (it stays in the vector cache)
 __global__ __launch_bounds__(kScoreThreads) void scores_kernel_anyg(
     const uint16_t* __restrict__ ksum, const uint16_t* __restrict__ q, const int32_t* __restrict__ cu_blocks,
-    int B, int Hq, int G, int cap, float* __restrict__ scores) {
+    int B, int Hq, int G, int cap, int stride, float* __restrict__ scores, float* __restrict__ user) {
   const int hk = blockIdx.y;
   int nblk = cu_blocks[B];
   if (nblk > cap) nblk = cap;
   const int half = threadIdx.x >> 5;
   const int c = threadIdx.x & 31;
-  const int is_max = c >> 4;
+  const bool is_max = c >= 16;
   const int d0 = (c & 15) * 8;
-  const int first = blockIdx.x * kScoreBlocksPerWg;
+  const int first = (blockIdx.x * kHalvesPerWg + half) * 8;
   const uint16_t* kh = ksum + (int64_t)hk * cap * (2 * DSK_HEAD_DIM);
   int s = 0;
-  for (int it = 0; it < kScoreBlocksPerWg / 8; ++it) {
-    const int i = first + it * 8 + half;
+  for (int it = 0; it < 8; ++it) {
+    const int i = first + it;
     if (i >= nblk) break;
     while (s + 1 < B && cu_blocks[s + 1] <= i) ++s;
     const uint4 kv = *reinterpret_cast<const uint4*>(kh + (int64_t)i * (2 * DSK_HEAD_DIM) + c * 8);
@@ -95,20 +171,21 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel_anyg(
   }
 }
 
-hipError_t launch_scores(const dsk_select_args& a, float* scores, hipStream_t st) {
+hipError_t launch_scores(const dsk_select_args& a, float* scores, int stride, hipStream_t st) {
   if (a.max_blocks_total <= 0) return hipSuccess;
   const int G = a.Hq / a.Hkv;
-  const dim3 grid((unsigned)((a.max_blocks_total + kScoreBlocksPerWg - 1) / kScoreBlocksPerWg), (unsigned)a.Hkv);
+  const int per_wg = kHalvesPerWg * score_blocks_per_half(G);
+  const dim3 grid((unsigned)((a.max_blocks_total + per_wg - 1) / per_wg), (unsigned)a.Hkv);
   const dim3 block(kScoreThreads);
   const uint16_t* ksum = static_cast<const uint16_t*>(a.ksum);
   const uint16_t* q = static_cast<const uint16_t*>(a.q);
   switch (G) {
-    case 1: scores_kernel<1><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, scores); break;
-    case 2: scores_kernel<2><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, scores); break;
-    case 4: scores_kernel<4><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, scores); break;
-    case 8: scores_kernel<8><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, scores); break;
+    case 1: scores_kernel<1><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, stride, scores, a.scores); break;
+    case 2: scores_kernel<2><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, stride, scores, a.scores); break;
+    case 4: scores_kernel<4><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, stride, scores, a.scores); break;
+    case 8: scores_kernel<8><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, stride, scores, a.scores); break;
     default:
-      scores_kernel_anyg<<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, G, a.max_blocks_total, scores);
+      scores_kernel_anyg<<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, G, a.max_blocks_total, stride, scores, a.scores);
   }
   return hipGetLastError();
 }

@@ -1,27 +1,57 @@
-// Slot top-k (Sec. 4.2, Block-to-Token Mapping; App. B.2 Step 1) per (sequence, query head).
+// Slot top-k (Sec. 4.2, Block-to-Token Mapping; App. B.2 Step 1): one workgroup per
+// (sequence, query head).
+//
 // Every fixed-length slot inherits the score of its semantic block, so the k best slots are
-// found on the block scores with each block weighted by its slot count: an MSB-first radix
-// select (4 passes of 8 bits over order-preserving keys, weighted LDS histograms) yields the
-// threshold score tau and how many slots of the tau-scored blocks are still needed; two
-// workgroup scans then resolve ties by lowest slot index and give every chosen slot its
-// position in the ascending output.
+// found on the block scores with each block weighted by its slot count.  Thread t owns the
+// kSelPerThread consecutive blocks [t*16, t*16+16) of the sequence: their keys (order-preserving
+// integer images of the scores) and slot counts live in registers, fetched with 16-byte loads
+// that are all in flight at once.
+//   1. key range and slot total (workgroup reduction);
+//   2. the bits shared by the smallest and the largest key are skipped, then an MSB-first radix
+//      select (8 bits per pass, slot-count-weighted LDS histogram) finds the threshold key tau
+//      and how many slots of the tau-scored blocks are still needed;
+//   3. one workgroup scan over per-thread sums (thread order = block order) resolves ties by
+//      lowest slot index and gives every chosen slot its position in the ascending output
+//      (block_start was fetched with the scores; the chosen blocks pass through an LDS work
+//      list so that all threads write slots in parallel).
+// Sequences with more blocks than the register tile holds take select_big, the same algorithm
+// reading keys from memory.
 #include "dsk_common.hpp"
 #include "dsk_internal.hpp"
 
 namespace dsk {
 
-constexpr int kSelThreads = 256;
+constexpr int kSelThreads = 512;
 constexpr int kSelWaves = kSelThreads / DSK_WAVE;
-constexpr int kSelLdsKeys = 6144;   // blocks of one sequence kept in LDS (48 KB); the rest is re-read from L2
+constexpr int kSelPerThread = 16;                       // blocks per thread
+constexpr int kSelTile = kSelThreads * kSelPerThread;   // 8192 aligned elements per workgroup
+constexpr int kSelVecs = kSelPerThread / 4;             // 16-byte vectors of scores per thread
+constexpr int kSelWork = 1024;                          // chosen blocks staged in LDS per emission round
+
+// does a sequence of n blocks fit the register tile whatever its alignment shift (0..3)?
+__host__ __device__ constexpr bool sel_fits_tile(int n) { return n + 3 <= kSelTile; }
 
 struct SelShared {
-  uint32_t keys[kSelLdsKeys];
-  uint32_t wts[kSelLdsKeys];
   uint32_t hist[256];
   int wave_tot[kSelWaves];
-  uint32_t digit;
-  int krem;
+  uint32_t red_min[kSelWaves], red_max[kSelWaves];
+  int red_sum[kSelWaves];
+  int wave_tot2[2 * kSelWaves];
+  int digit, krem;
+  int n_work;
+  int4 work[kSelWork + 1];             // (first token, end token, first slot, output offset); last = dump
+  int work_take[kSelWork + 1];
 };
+
+#ifdef DSK_SELECT_TIMING
+__device__ long long dsk_dbg[64 * 16];
+#define DSK_TS(slot) do { if (threadIdx.x == 0) dsk_dbg[(blockIdx.y * gridDim.x + blockIdx.x) % 64 * 16 + (slot)] = wall_clock64(); } while (0)
+extern "C" __attribute__((visibility("default"))) void dsk_debug_read(long long* host) {
+  (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(dsk_dbg), sizeof(long long) * 64 * 16);
+}
+#else
+#define DSK_TS(slot) do {} while (0)
+#endif
 
 // exclusive prefix sum of one int per thread over the workgroup, in thread order
 __device__ __forceinline__ int wg_excl_scan(int v, int* wave_tot, int& total) {
@@ -42,8 +72,203 @@ __device__ __forceinline__ int wg_excl_scan(int v, int* wave_tot, int& total) {
   return off + incl - v;
 }
 
+// the same for two ints per thread at once
+__device__ __forceinline__ void wg_excl_scan2(int a, int b, int* wave_tot2, int& a_excl, int& b_excl) {
+  const int lane = threadIdx.x & (DSK_WAVE - 1);
+  const int wave = threadIdx.x / DSK_WAVE;
+  const int ia = wave_incl_scan_i(a, lane);
+  const int ib = wave_incl_scan_i(b, lane);
+  __syncthreads();
+  if (lane == DSK_WAVE - 1) { wave_tot2[2 * wave] = ia; wave_tot2[2 * wave + 1] = ib; }
+  __syncthreads();
+  int oa = 0, ob = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    if (w < wave) { oa += wave_tot2[2 * w]; ob += wave_tot2[2 * w + 1]; }
+  }
+  a_excl = oa + ia - a;
+  b_excl = ob + ib - b;
+}
+
+// After the histogram of one pass is complete: wave 0 finds the digit holding the krem-th slot
+// counted from the top digit down; result broadcast through LDS.
+__device__ __forceinline__ void pick_digit(SelShared& sh, int krem, int& digit_out, int& krem_out) {
+  if (threadIdx.x < DSK_WAVE) {
+    const int lane = threadIdx.x;
+    int hv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) hv[u] = (int)sh.hist[255 - 4 * lane - u];
+    const int mine = hv[0] + hv[1] + hv[2] + hv[3];
+    int excl = wave_incl_scan_i(mine, lane) - mine;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (excl < krem && krem <= excl + hv[u]) {   // true for exactly one (lane, u)
+        sh.digit = 255 - 4 * lane - u;
+        sh.krem = krem - excl;
+      }
+      excl += hv[u];
+    }
+  }
+  __syncthreads();
+  digit_out = sh.digit;
+  krem_out = sh.krem;
+}
+
+__device__ __forceinline__ void write_padding(int count, int k, int64_t obase, int64_t sh_idx,
+                                              int32_t* sel_slot, int32_t* sel_start, int32_t* sel_len,
+                                              int32_t* sel_count) {
+  if (threadIdx.x == 0) sel_count[sh_idx] = count;
+  for (int o = count + threadIdx.x; o < k; o += blockDim.x) {
+    sel_slot[obase + o] = -1;
+    sel_start[obase + o] = 0;
+    sel_len[obase + o] = 0;
+  }
+}
+
+// Same algorithm for sequences whose blocks do not fit the register tile: keys and slot counts
+// are re-read from memory (L2) in every pass; thread t owns a contiguous range of blocks.
+__device__ __noinline__ void select_big(
+    SelShared& sh, const float* __restrict__ scores, int stride, const int32_t* __restrict__ cu_blocks,
+    const int32_t* __restrict__ block_start, const int32_t* __restrict__ slot_base, int cap, int Hq,
+    int b, int k, int32_t* __restrict__ sel_slot, int32_t* __restrict__ sel_start,
+    int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
+  const int h = blockIdx.x;
+  const int s = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int lane = tid & (DSK_WAVE - 1);
+  const int wave = tid / DSK_WAVE;
+  const int64_t sh_idx = (int64_t)s * Hq + h;
+  const int64_t obase = sh_idx * k;
+  int blk0 = s == 0 ? 0 : cu_blocks[s];
+  blk0 = blk0 < cap ? (blk0 > 0 ? blk0 : 0) : cap;       // same clamping as select_kernel
+  int blk1 = cu_blocks[s + 1];
+  if (blk1 > cap) blk1 = cap;
+  const int n = blk1 - blk0;
+  if (n <= 0 || sel_fits_tile(n)) return;                // not ours
+  const float* sc = scores + (int64_t)h * stride + blk0;
+  const int32_t* sb = slot_base + blk0;
+  const int32_t* bs = block_start + blk0;
+  const int per = (n + kSelThreads - 1) / kSelThreads;
+  const int i0 = tid * per < n ? tid * per : n;
+  const int i1 = i0 + per < n ? i0 + per : n;
+
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+  int nslots = 0;
+  for (int i = i0; i < i1; ++i) {
+    const uint32_t key = float_key(sc[i]);
+    const int wi = sb[i + 1] - sb[i];
+    kmin = key < kmin ? key : kmin;
+    kmax = key > kmax ? key : kmax;
+    nslots += wi > 0 ? wi : 0;
+  }
+#pragma unroll
+  for (int m = 1; m < DSK_WAVE; m <<= 1) {
+    const uint32_t o1 = (uint32_t)__shfl_xor((int)kmin, m, DSK_WAVE);
+    const uint32_t o2 = (uint32_t)__shfl_xor((int)kmax, m, DSK_WAVE);
+    kmin = o1 < kmin ? o1 : kmin;
+    kmax = o2 > kmax ? o2 : kmax;
+    nslots += __shfl_xor(nslots, m, DSK_WAVE);
+  }
+  if (lane == 0) { sh.red_min[wave] = kmin; sh.red_max[wave] = kmax; sh.red_sum[wave] = nslots; }
+  if (tid < 256) sh.hist[tid] = 0;
+  __syncthreads();
+  nslots = 0;
+#pragma unroll
+  for (int wv = 0; wv < kSelWaves; ++wv) {
+    kmin = sh.red_min[wv] < kmin ? sh.red_min[wv] : kmin;
+    kmax = sh.red_max[wv] > kmax ? sh.red_max[wv] : kmax;
+    nslots += sh.red_sum[wv];
+  }
+  const int count = nslots < k ? nslots : k;
+  write_padding(count, k, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
+  if (count <= 0) return;
+
+  const bool take_all = nslots <= k;
+  uint32_t tau = 0u;
+  int krem = 0;
+  if (!take_all) {
+    const uint32_t diff = kmin ^ kmax;
+    if (diff == 0) {
+      tau = kmax;
+      krem = k;
+    } else {
+      int rbits = 32 - __clz((int)diff);
+      uint32_t prefix = rbits >= 32 ? 0u : (kmax >> rbits) << rbits;
+      uint32_t mask = rbits >= 32 ? 0u : ~((1u << rbits) - 1u);
+      krem = k;
+      while (rbits > 0) {
+        const int dbits = rbits < 8 ? rbits : 8;
+        const int shift_d = rbits - dbits;
+        const uint32_t dmask = (1u << dbits) - 1u;
+        for (int i = tid; i < n; i += kSelThreads) {
+          const uint32_t key = float_key(sc[i]);
+          const int wi = sb[i + 1] - sb[i];
+          if (wi > 0 && (key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift_d) & dmask], (uint32_t)wi);
+        }
+        __syncthreads();
+        int digit, knew;
+        pick_digit(sh, krem, digit, knew);
+        krem = knew;
+        prefix |= (uint32_t)digit << shift_d;
+        mask |= dmask << shift_d;
+        rbits = shift_d;
+        if (tid < 256) sh.hist[tid] = 0;
+        __syncthreads();
+      }
+      tau = prefix;
+    }
+  }
+  auto take_of = [&](int i, int& tb) -> int {
+    const uint32_t key = float_key(sc[i]);
+    int wi = sb[i + 1] - sb[i];
+    wi = wi > 0 ? wi : 0;
+    if (take_all || key > tau) return wi;
+    if (key == tau) {
+      const int left = krem - tb;
+      tb += wi;
+      return left <= 0 ? 0 : (left < wi ? left : wi);
+    }
+    return 0;
+  };
+  int tie_before = 0;
+  if (!take_all) {
+    int tie_local = 0;
+    for (int i = i0; i < i1; ++i)
+      if (float_key(sc[i]) == tau) { const int wi = sb[i + 1] - sb[i]; tie_local += wi > 0 ? wi : 0; }
+    int total;
+    tie_before = wg_excl_scan(tie_local, sh.wave_tot, total);
+  }
+  int sel_local = 0;
+  {
+    int tb = tie_before;
+    for (int i = i0; i < i1; ++i) sel_local += take_of(i, tb);
+  }
+  int total_sel;
+  int off = wg_excl_scan(sel_local, sh.wave_tot, total_sel);
+  int tb = tie_before;
+  for (int i = i0; i < i1; ++i) {
+    const int take = take_of(i, tb);
+    if (take > 0) {
+      const int st0 = bs[i], be = bs[i + 1], g0 = sb[i];
+      for (int jj = 0; jj < take; ++jj) {
+        const int o = off + jj;
+        if (o < k) {
+          const int st = st0 + jj * b;
+          const int ln = be - st < b ? be - st : b;
+          sel_slot[obase + o] = g0 + jj;
+          sel_start[obase + o] = st;
+          sel_len[obase + o] = ln > 0 ? ln : 0;
+        }
+      }
+      off += take;
+    }
+  }
+}
+
+// scores: rows of `stride` floats (stride % 4 == 0, stride >= cap, base 16-byte aligned);
+// slot_base, block_start: 16-byte aligned, readable up to a multiple of 4 entries past cap.
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
-    const float* __restrict__ scores, const int32_t* __restrict__ cu_blocks,
+    const float* __restrict__ scores, int stride, const int32_t* __restrict__ cu_blocks,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ slot_base, int cap, int Hq,
     int b, int k, int32_t* __restrict__ sel_slot, int32_t* __restrict__ sel_start,
     int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
@@ -51,126 +276,210 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   const int h = blockIdx.x;
   const int s = blockIdx.y;
   const int tid = threadIdx.x;
-  const int64_t obase = ((int64_t)s * Hq + h) * k;
-  int blk0 = cu_blocks[s];
+  const int lane = tid & (DSK_WAVE - 1);
+  const int wave = tid / DSK_WAVE;
+  const int64_t sh_idx = (int64_t)s * Hq + h;
+  const int64_t obase = sh_idx * k;
+  DSK_TS(0);
+
+  // cu_blocks[0] is 0 by definition: sequence 0 can address its loads before anything arrives
+  const int blk0_raw = s == 0 ? 0 : cu_blocks[s];
+  const int blk0 = blk0_raw < cap ? (blk0_raw > 0 ? blk0_raw : 0) : cap;
+  const int shift = blk0 & 3;                         // same for scores rows (stride % 4 == 0)
+  const int v_first = (blk0 - shift) / 4 + tid * kSelVecs;   // thread t owns vectors [v_first, v_first + kSelVecs)
+  const int max_vec_sc = stride / 4 - 1;              // clamp to the buffers, mask by index later
+  const int max_vec_sb = cap / 4;
+  const float4* sc4 = reinterpret_cast<const float4*>(scores + (int64_t)h * stride);
+  const int4* sb4 = reinterpret_cast<const int4*>(slot_base);
+  const int4* bs4 = reinterpret_cast<const int4*>(block_start);
+  float4 fv[kSelVecs];
+  int4 iv[kSelVecs + 1], bv[kSelVecs + 1];
+#pragma unroll
+  for (int u = 0; u < kSelVecs; ++u) {
+    const int v = v_first + u;
+    issue_load16(fv[u], sc4 + (v < max_vec_sc ? v : max_vec_sc));
+  }
+#pragma unroll
+  for (int u = 0; u < kSelVecs + 1; ++u) {
+    const int v = v_first + u;
+    issue_load16(iv[u], sb4 + (v < max_vec_sb ? v : max_vec_sb));
+  }
+#pragma unroll
+  for (int u = 0; u < kSelVecs + 1; ++u) {
+    const int v = v_first + u;
+    issue_load16(bv[u], bs4 + (v < max_vec_sb ? v : max_vec_sb));
+  }
   int blk1 = cu_blocks[s + 1];
+  wait_issued_loads();                                // all vector loads were in flight together
   if (blk1 > cap) blk1 = cap;
-  if (blk0 > blk1) blk0 = blk1;
   const int n = blk1 - blk0;
-  const int nslots = n > 0 ? slot_base[blk1] - slot_base[blk0] : 0;
-  const int count = nslots < k ? nslots : k;
-  if (tid == 0) sel_count[(int64_t)s * Hq + h] = count;
-  for (int o = count + tid; o < k; o += kSelThreads) {   // padding
-    sel_slot[obase + o] = -1;
-    sel_start[obase + o] = 0;
-    sel_len[obase + o] = 0;
+  if (n <= 0) {
+    write_padding(0, k, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
+    return;
   }
-  if (count <= 0) return;
+  if (!sel_fits_tile(n)) {                            // too many blocks for the register tile
+    select_big(sh, scores, stride, cu_blocks, block_start, slot_base, cap, Hq, b, k, sel_slot, sel_start, sel_len,
+               sel_count);
+    return;
+  }
 
-  const float* sc = scores + (int64_t)h * cap + blk0;
-  const int32_t* sb = slot_base + blk0;
-  for (int i = tid; i < n && i < kSelLdsKeys; i += kSelThreads) {
-    sh.keys[i] = float_key(sc[i]);
-    sh.wts[i] = (uint32_t)(sb[i + 1] - sb[i]);
+  // registers: key[r], w[r] of block i = tid*32 + r - shift (w = 0 marks "no block")
+  uint32_t key[kSelPerThread];
+  int w[kSelPerThread];
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+  int nslots = 0;
+  {
+    const float* f = reinterpret_cast<const float*>(fv);
+    const int* x = reinterpret_cast<const int*>(iv);
+#pragma unroll
+    for (int r = 0; r < kSelPerThread; ++r) {
+      const int i = tid * kSelPerThread + r - shift;
+      const bool ok = i >= 0 && i < n;
+      key[r] = float_key(f[r]);
+      int wr = x[r + 1] - x[r];
+      wr = (ok && wr > 0) ? wr : 0;                   // malformed table: never count backwards
+      w[r] = wr;
+      kmin = (ok && key[r] < kmin) ? key[r] : kmin;
+      kmax = (ok && key[r] > kmax) ? key[r] : kmax;
+      nslots += wr;
+    }
   }
+  DSK_TS(1);
+  // 1. workgroup reductions
+#pragma unroll
+  for (int m = 1; m < DSK_WAVE; m <<= 1) {
+    const uint32_t o1 = (uint32_t)__shfl_xor((int)kmin, m, DSK_WAVE);
+    const uint32_t o2 = (uint32_t)__shfl_xor((int)kmax, m, DSK_WAVE);
+    kmin = o1 < kmin ? o1 : kmin;
+    kmax = o2 > kmax ? o2 : kmax;
+    nslots += __shfl_xor(nslots, m, DSK_WAVE);
+  }
+  if (lane == 0) { sh.red_min[wave] = kmin; sh.red_max[wave] = kmax; sh.red_sum[wave] = nslots; }
+  if (tid < 256) sh.hist[tid] = 0;
+  if (tid == 0) sh.n_work = 0;
   __syncthreads();
-  auto key_of = [&](int i) -> uint32_t { return i < kSelLdsKeys ? sh.keys[i] : float_key(sc[i]); };
-  auto wt_of = [&](int i) -> int { return i < kSelLdsKeys ? (int)sh.wts[i] : sb[i + 1] - sb[i]; };
+  nslots = 0;
+#pragma unroll
+  for (int wv = 0; wv < kSelWaves; ++wv) {
+    kmin = sh.red_min[wv] < kmin ? sh.red_min[wv] : kmin;
+    kmax = sh.red_max[wv] > kmax ? sh.red_max[wv] : kmax;
+    nslots += sh.red_sum[wv];
+  }
+  const int count = nslots < k ? nslots : k;
+  write_padding(count, k, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
+  if (count <= 0) return;
+  DSK_TS(2);
 
+  // 2. threshold
   const bool take_all = nslots <= k;
-  uint32_t tau = 0;       // key of the threshold score
-  int krem = 0;           // slots still needed from blocks whose key == tau
+  uint32_t tau = 0u;       // take_all: every block qualifies
+  int krem = 0;            // slots still needed from blocks whose key == tau
   if (!take_all) {
-    uint32_t prefix = 0, mask = 0;
-    krem = k;
-    for (int pass = 0; pass < 4; ++pass) {
-      const int shift = 24 - 8 * pass;
-      sh.hist[tid] = 0;
-      __syncthreads();
-      for (int i = tid; i < n; i += kSelThreads) {
-        const uint32_t key = key_of(i);
-        if ((key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255u], (uint32_t)wt_of(i));
+    const uint32_t diff = kmin ^ kmax;
+    if (diff == 0) {       // all scores equal: pure index-order tie
+      tau = kmax;
+      krem = k;
+    } else {
+      int rbits = 32 - __clz((int)diff);                 // low bits in which keys can differ
+      uint32_t prefix = rbits >= 32 ? 0u : (kmax >> rbits) << rbits;
+      uint32_t mask = rbits >= 32 ? 0u : ~((1u << rbits) - 1u);
+      krem = k;
+      while (rbits > 0) {                                // hist is zero on entry
+        const int dbits = rbits < 8 ? rbits : 8;
+        const int shift_d = rbits - dbits;
+        const uint32_t dmask = (1u << dbits) - 1u;
+#pragma unroll
+        for (int r = 0; r < kSelPerThread; ++r)
+          if (w[r] != 0 && (key[r] & mask) == prefix) atomicAdd(&sh.hist[(key[r] >> shift_d) & dmask], (uint32_t)w[r]);
+        __syncthreads();
+        int digit, knew;
+        pick_digit(sh, krem, digit, knew);
+        krem = knew;
+        prefix |= (uint32_t)digit << shift_d;
+        mask |= dmask << shift_d;
+        rbits = shift_d;
+        if (tid < 256) sh.hist[tid] = 0;                 // everyone has read digit / krem
+        __syncthreads();
       }
-      __syncthreads();
-      // thread t looks at digit 255-t: cumulative slot count from the top digit downwards
-      const int v = (int)sh.hist[255 - tid];
-      int total;
-      const int excl = wg_excl_scan(v, sh.wave_tot, total);
-      if (excl < krem && krem <= excl + v) {   // exactly one thread: the digit holding the k-th slot
-        sh.digit = (uint32_t)(255 - tid);
-        sh.krem = krem - excl;
-      }
-      __syncthreads();
-      prefix |= sh.digit << shift;
-      mask |= 255u << shift;
-      krem = sh.krem;
-      __syncthreads();
-    }
-    tau = prefix;
-  }
-
-  // contiguous range of blocks per thread keeps index order inside the scans
-  const int per = (n + kSelThreads - 1) / kSelThreads;
-  const int i0 = tid * per < n ? tid * per : n;
-  const int i1 = i0 + per < n ? i0 + per : n;
-
-  // scan 1: slots of tau-scored blocks before each thread's range (ties go to the lowest slots)
-  int tie_before = 0;
-  if (!take_all) {
-    int tie_local = 0;
-    for (int i = i0; i < i1; ++i) if (key_of(i) == tau) tie_local += wt_of(i);
-    int total;
-    tie_before = wg_excl_scan(tie_local, sh.wave_tot, total);
-  }
-  // scan 2: selected slots before each thread's range
-  int sel_local = 0;
-  {
-    int tb = tie_before;
-    for (int i = i0; i < i1; ++i) {
-      const uint32_t key = key_of(i);
-      const int w = wt_of(i);
-      int take;
-      if (take_all || key > tau) take = w;
-      else if (key == tau) { int left = krem - tb; take = left <= 0 ? 0 : (left < w ? left : w); tb += w; }
-      else take = 0;
-      sel_local += take;
+      tau = prefix;
     }
   }
-  int total_sel;
-  int off = wg_excl_scan(sel_local, sh.wave_tot, total_sel);
+  DSK_TS(3);
+
+  // 3. ties by lowest index, output positions (thread order = block order).  One scan of the
+  //    pair (slots of tau-scored blocks, slots of better blocks) per thread is enough: the slots
+  //    emitted before a thread are  better_before + min(tie_before, krem).
+  int tie_local = 0, gt_local = 0;
+#pragma unroll
+  for (int r = 0; r < kSelPerThread; ++r) {
+    const bool gt = take_all || key[r] > tau;
+    gt_local += gt ? w[r] : 0;
+    tie_local += (!gt && key[r] == tau) ? w[r] : 0;
+  }
+  int tie_before, gt_before;
+  wg_excl_scan2(tie_local, gt_local, sh.wave_tot2, tie_before, gt_before);
+  int off = gt_before + (tie_before < krem ? tie_before : krem);
+  DSK_TS(4);
+  // Chosen blocks go through an LDS work list (any order: every entry carries its output
+  // offset) so that their slots are written by all threads in parallel; block_start is already
+  // in registers.  Entries outside the current round's window land in a dump entry.
+  int n_mine = 0;
   {
     int tb = tie_before;
-    for (int i = i0; i < i1; ++i) {
-      const uint32_t key = key_of(i);
-      const int w = wt_of(i);
-      int take;
-      if (take_all || key > tau) take = w;
-      else if (key == tau) { int left = krem - tb; take = left <= 0 ? 0 : (left < w ? left : w); tb += w; }
-      else take = 0;
-      if (take > 0) {
-        const int bs = block_start[blk0 + i];
-        const int be = block_start[blk0 + i + 1];
-        const int g0 = sb[i];
-        for (int jj = 0; jj < take; ++jj) {
-          const int o = off + jj;
-          if (o < k) {
-            const int st = bs + jj * b;
-            const int ln = be - st < b ? be - st : b;
-            sel_slot[obase + o] = g0 + jj;
-            sel_start[obase + o] = st;
-            sel_len[obase + o] = ln > 0 ? ln : 0;
-          }
+#pragma unroll
+    for (int r = 0; r < kSelPerThread; ++r) {
+      const bool gt = take_all || key[r] > tau;
+      int take = gt ? w[r] : 0;
+      if (!gt && key[r] == tau) {
+        const int left = krem - tb;
+        take = left <= 0 ? 0 : (left < w[r] ? left : w[r]);
+        tb += w[r];
+      }
+      w[r] = take;                                       // from here on: slots taken from block r
+      n_mine += take > 0 ? 1 : 0;
+    }
+  }
+  const int e0 = n_mine > 0 ? atomicAdd(&sh.n_work, n_mine) : 0;   // one reservation per thread
+  __syncthreads();
+  const int n_work = sh.n_work;
+  const int* xs = reinterpret_cast<const int*>(iv);
+  const int* xb = reinterpret_cast<const int*>(bv);
+  for (int base = 0; base < n_work; base += kSelWork) {
+    int e = e0 - base, o = off;
+#pragma unroll
+    for (int r = 0; r < kSelPerThread; ++r) {
+      const bool on = w[r] > 0;
+      const int idx = (on && e >= 0 && e < kSelWork) ? e : kSelWork;
+      sh.work[idx] = make_int4(xb[r], xb[r + 1], xs[r], o);
+      sh.work_take[idx] = w[r];
+      e += on ? 1 : 0;
+      o += w[r];
+    }
+    __syncthreads();
+    const int n_round = n_work - base < kSelWork ? n_work - base : kSelWork;
+    for (int j = tid; j < n_round; j += kSelThreads) {
+      const int4 wk = sh.work[j];
+      const int take = sh.work_take[j];
+      for (int jj = 0; jj < take; ++jj) {
+        const int oo = wk.w + jj;
+        if (oo < k) {
+          const int st = wk.x + jj * b;
+          const int ln = wk.y - st < b ? wk.y - st : b;
+          sel_slot[obase + oo] = wk.z + jj;
+          sel_start[obase + oo] = st;
+          sel_len[obase + oo] = ln > 0 ? ln : 0;
         }
-        off += take;
       }
     }
+    __syncthreads();
   }
+  DSK_TS(5);
 }
 
-hipError_t launch_select(const dsk_select_args& a, const float* scores, hipStream_t st) {
+hipError_t launch_select(const dsk_select_args& a, const float* scores, int stride, hipStream_t st) {
   const int k = a.budget / a.b;
   const dim3 grid((unsigned)a.Hq, (unsigned)a.B);
-  select_kernel<<<grid, dim3(kSelThreads), 0, st>>>(scores, a.cu_blocks, a.block_start, a.slot_base,
+  select_kernel<<<grid, dim3(kSelThreads), 0, st>>>(scores, stride, a.cu_blocks, a.block_start, a.slot_base,
                                                     a.max_blocks_total, a.Hq, a.b, k, a.sel_slot, a.sel_start,
                                                     a.sel_len, a.sel_count);
   return hipGetLastError();

@@ -125,6 +125,9 @@ def test_select_and_attn_validation(dsk):
         return a
     assert dsk.dsk_select_topk(sel(), 0, check=False) == dsk.DSK_ERR_WORKSPACE
     assert dsk.dsk_select_workspace_bytes(sel()) >= 4 * 100 * 4
+    a = sel()
+    a.slot_base = fake + 8
+    assert dsk.dsk_select_topk(a, 0, check=False) == dsk.DSK_ERR_ALIGN
     for field, value, want in (("struct_size", 1, dsk.DSK_ERR_VERSION), ("Hq", 5, dsk.DSK_ERR_SHAPE),
                                ("budget", 15, dsk.DSK_ERR_PARAM), ("b", 0, dsk.DSK_ERR_PARAM),
                                ("q", None, dsk.DSK_ERR_NULL), ("q", fake + 4, dsk.DSK_ERR_ALIGN),

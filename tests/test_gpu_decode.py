@@ -266,3 +266,31 @@ def test_decode_is_deterministic():
         outs.append((sel.sel_slot.cpu().numpy().copy(), att.out.cpu().numpy().copy()))
     np.testing.assert_array_equal(outs[0][0], outs[1][0])
     np.testing.assert_array_equal(outs[0][1], outs[1][1])
+
+
+def test_sequences_with_more_blocks_than_the_register_tile():
+    """> 8189 blocks in one sequence: the memory-resident variant of the slot top-k."""
+    dsk = _dsk()
+    case = gpu_case(1, seqlens=[40000], C=4, delta=1, gap_means=[4], b=2, T=96, Hq=2, Hkv=1)
+    cfg, seg, wl = case.cfg, case.seg, case.wl
+    assert int(seg.cu_blocks[-1]) > 8192
+    comp = case.compressed()
+    nb = int(seg.cu_blocks[-1])
+    np.testing.assert_array_equal(comp.block_start.cpu().numpy()[: nb + 1], seg.block_start)
+    sums = bf16_bits_of(comp.ksum)
+    for qi, q_bits in enumerate([wl.q[0], np.zeros_like(wl.q[0])]):
+        q = dev_bf16(q_bits)
+        sel = dsk.select_topk(comp, q, cfg.T)
+        att = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b)
+        torch.cuda.synchronize()
+        for h in range(cfg.Hq):
+            sc = O.block_scores(O.widen_bf16(q_bits[0, h])[None], O.widen_bf16(sums[0, :nb, 0])[None],
+                                O.widen_bf16(sums[0, :nb, 1])[None])[0]
+            o_sel, tau = O.select_slots(sc, seg.slot_base, cfg.k)
+            cnt = int(sel.sel_count.cpu()[0, h])
+            gs = sel.sel_slot.cpu().numpy()[0, h, :cnt]
+            selection_check(gs, o_sel, tau, sc, seg.slot_base)
+            toks = O.selected_tokens(gs, seg.block_start, seg.slot_base, cfg.b)
+            o, lse = O.sparse_attention(O.widen_bf16(q_bits[0, h]), O.widen_bf16(wl.K[0]), O.widen_bf16(wl.V[0]),
+                                        toks, DEFAULT_SCALE)
+            assert rel_err(att.out.cpu().numpy()[0, h], o) <= ATTN_TOL

@@ -1,0 +1,112 @@
+"""GPU parity of the delimiter-importance stage of dsk_compress (Alg. 1 on one layer, sampled
+candidates, class weights in tenths) against the fp64 oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dynsplit_oracle as O
+from workloads import make_workload
+from dsk_testutil import dev_bf16, dev_i32, dev_u8
+
+pytestmark = pytest.mark.gpu
+
+SCORE_TOL = 2e-5      # fp32 MFMA accumulation + fp32 softmax vs fp64
+EDGE_TOL = 1e-3       # a weight may differ by one tenth only this close to a rounding edge
+
+
+def _run(cfg_id, **ov):
+    import paper_2602_03184_amd as dsk
+    wl = make_workload(cfg_id, with_kv=True, with_qwin=True, **ov)
+    cfg = wl.cfg
+    K = dev_bf16(wl.K)
+    prior = np.full((cfg.B, cfg.n_class), 3, np.uint8)
+    comp = dsk.compress(
+        cu_seqlens=dev_i32(wl.cu_seqlens), max_seqlen=int(wl.seqlens.max()), Hq=cfg.Hq, K=K, V=None,
+        stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_IMPORTANCE,
+        token_ids=dev_i32(wl.token_ids), delim_ids=dev_i32(wl.delim_ids), n_class=cfg.n_class,
+        M=cfg.M, W=cfg.W, R=cfg.R, alpha_imp=cfg.alpha_imp, qwin=dev_bf16(wl.qwin), class_weight_q=dev_u8(prior))
+    torch.cuda.synchronize()
+    assert int(comp.dev_status.item()) == 0
+    return wl, comp, prior
+
+
+def _check(wl, comp, prior, seqs=None):
+    cfg = wl.cfg
+    samp = comp.samp_pos.cpu().numpy()
+    score = comp.samp_score.cpu().numpy()
+    mean = comp.class_mean.cpu().numpy()
+    wq = comp.class_weight_q.cpu().numpy()
+    scale = 1.0 / math.sqrt(128.0)
+    worst = 0.0
+    for s in (range(cfg.B) if seqs is None else seqs):
+        lo, hi = int(wl.cu_seqlens[s]), int(wl.cu_seqlens[s + 1])
+        Kf = O.widen_bf16(wl.K[:, lo:hi])
+        pos, cls = O.extract_candidates(wl.token_ids[lo:hi], wl.delim_ids)
+        want_samp = O.sample_candidates(pos, cls, cfg.n_class, cfg.M, cfg.R, cfg.W, hi - lo)
+        np.testing.assert_array_equal(samp[s], np.where(want_samp >= 0, want_samp + lo, -1))
+        s_or = np.zeros((cfg.n_class, cfg.M))
+        for c in range(cfg.n_class):
+            for m in range(cfg.M):
+                t = int(want_samp[c, m])
+                if t < 0:
+                    assert math.isnan(score[s, c, m])
+                    continue
+                qw = O.widen_bf16(wl.qwin[s, c * cfg.M + m])          # [W, Hq, D]
+                s_or[c, m] = O.delimiter_importance(qw, Kf, t, cfg.R, cfg.alpha_imp, scale)
+                err = abs(float(score[s, c, m]) - s_or[c, m])
+                worst = max(worst, err)
+                assert err <= SCORE_TOL, (s, c, m, t, float(score[s, c, m]), s_or[c, m])
+        wq_or, mean_or, edge = O.class_weights(s_or, want_samp, cfg.alpha_imp, prior[s])
+        for c in range(cfg.n_class):
+            if math.isnan(mean_or[c]):
+                assert math.isnan(mean[s, c]) and wq[s, c] == prior[s, c]
+                continue
+            assert abs(float(mean[s, c]) - mean_or[c]) <= SCORE_TOL
+            if edge[c] > EDGE_TOL:
+                assert int(wq[s, c]) == int(wq_or[c]), (s, c, mean_or[c])
+            else:
+                assert abs(int(wq[s, c]) - int(wq_or[c])) <= 1
+    return worst
+
+
+def test_importance_single_head_small():
+    wl, comp, prior = _run(1)
+    print("cfg1 worst |s_gpu - s_oracle| = %.2e" % _check(wl, comp, prior))
+
+
+def test_importance_gqa4_llama_shape():
+    wl, comp, prior = _run(2, seqlens=[12288])
+    print("cfg2 worst = %.2e" % _check(wl, comp, prior))
+
+
+def test_importance_gqa8_two_row_tiles_and_odd_window():
+    wl, comp, prior = _run(2, seqlens=[6000], Hkv=4, W=5, R=100, M=3, alpha_imp=0.5)
+    print("G=8 worst = %.2e" % _check(wl, comp, prior))
+
+
+def test_importance_mha_ragged_batch():
+    wl, comp, prior = _run(5, B=3, seqlens=[3000, 150, 5000], Hq=6, Hkv=6, M=4)
+    print("MHA ragged worst = %.2e" % _check(wl, comp, prior))
+
+
+def test_importance_feeds_segmentation_in_one_call():
+    """All four stages in one dsk_compress call: weights estimated on the GPU drive DD-Select."""
+    import paper_2602_03184_amd as dsk
+    wl = make_workload(2, with_kv=True, with_qwin=True, seqlens=[8192])
+    cfg = wl.cfg
+    prior = np.full((1, cfg.n_class), 3, np.uint8)
+    comp = dsk.compress(
+        cu_seqlens=dev_i32(wl.cu_seqlens), max_seqlen=8192, Hq=cfg.Hq, K=dev_bf16(wl.K), V=None,
+        stages=dsk.DSK_STAGE_ALL, token_ids=dev_i32(wl.token_ids), delim_ids=dev_i32(wl.delim_ids),
+        n_class=cfg.n_class, M=cfg.M, W=cfg.W, R=cfg.R, alpha_imp=cfg.alpha_imp, qwin=dev_bf16(wl.qwin),
+        class_weight_q=dev_u8(prior), C_=30, delta=15, alpha_num=5, alpha_den=10, b=16)
+    torch.cuda.synchronize()
+    assert int(comp.dev_status.item()) == 0
+    wq = comp.class_weight_q.cpu().numpy()[0]
+    pos, cls = O.extract_candidates(wl.token_ids, wl.delim_ids)
+    bs = O.dd_select(8192, pos, cls, wq, 30, 15, 5, 10)     # oracle segmentation with the GPU's weights
+    nb = len(bs) - 1
+    assert int(comp.cu_blocks.cpu()[1]) == nb
+    np.testing.assert_array_equal(comp.block_start.cpu().numpy()[: nb + 1], bs)
