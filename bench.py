@@ -32,7 +32,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cold", action="store_true", help="rotate over distinct cache instances (cold LLC)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (reference dispatch for rocprofv3 "
+                         "--pmc FETCH_SIZE / WRITE_SIZE scaling)")
     return ap.parse_args()
 
 
@@ -83,6 +85,13 @@ def main():
                C_per_seq=i32(wl.C) if cfg.B > 1 else None, delta_per_seq=i32(wl.delta) if cfg.B > 1 else None,
                min_chunk=int((wl.C - wl.delta).min()), alpha_num=cfg.a_num, alpha_den=cfg.a_den, b=cfg.b)
     stream = torch.cuda.Stream()   # default priority
+    if args.calib_copy_mib > 0:
+        src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)               # reads and writes exactly calib_copy_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
     with torch.cuda.stream(stream):
         comp = dsk.compress(**ckw)
         stream.synchronize()
@@ -100,9 +109,10 @@ def main():
 
         # ---- decode step: per-query argument structs, buffers shared --------------------------
         nq = len(queries)
-        sels = [dsk.make_select_args(comp, queries[0], cfg.T)]
+        # the block count was read back once after compression: it sizes the score launch
+        sels = [dsk.make_select_args(comp, queries[0], cfg.T, max_blocks_used=nblk)]
         for i in range(1, nq):
-            sels.append(dsk.make_select_args(comp, queries[i], cfg.T, out=sels[0]))
+            sels.append(dsk.make_select_args(comp, queries[i], cfg.T, out=sels[0], max_blocks_used=nblk))
         atts = [dsk.make_attn_args(queries[0], K, V, sels[0].sel_start, sels[0].sel_len, sels[0].sel_count, cfg.b)]
         for i in range(1, nq):
             atts.append(dsk.make_attn_args(queries[i], K, V, sels[0].sel_start, sels[0].sel_len, sels[0].sel_count,

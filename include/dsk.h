@@ -169,6 +169,10 @@ typedef struct dsk_select_args {
   uint32_t struct_size;
   int32_t B, Hq, Hkv, D;
   int32_t max_blocks_total;    /* capacity used when ksum / block tables were allocated */
+  int32_t max_blocks_used;     /* [host] optional tighter upper bound on cu_blocks[B], e.g. the value
+                                  read back once after dsk_compress; 0 = max_blocks_total.  Only
+                                  sizes the launch and bounds speculative reads; the device value
+                                  still decides what is scored. */
   const int32_t* cu_blocks;    /* [dev] [B+1] */
   const int32_t* block_start;  /* [dev] both tables: 16-byte aligned and readable up to a multiple */
   const int32_t* slot_base;    /* [dev] of 4 entries, i.e. allocate max_blocks_total + 4 ints */

@@ -66,7 +66,7 @@ class dsk_select_args(C.Structure):
     _fields_ = [
         ("struct_size", C.c_uint32),
         ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
-        ("max_blocks_total", C.c_int32),
+        ("max_blocks_total", C.c_int32), ("max_blocks_used", C.c_int32),
         ("cu_blocks", _p), ("block_start", _p), ("slot_base", _p),
         ("ksum", _p), ("q", _p),
         ("b", C.c_int32), ("budget", C.c_int32),
@@ -319,8 +319,9 @@ class Selection:
 
 
 def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_scores: bool = False,
-                     out: Optional[Selection] = None) -> Selection:
-    """Fill dsk_select_args for query q (bf16 [B, Hq, D]); buffers are reused from `out`."""
+                     out: Optional[Selection] = None, max_blocks_used: int = 0) -> Selection:
+    """Fill dsk_select_args for query q (bf16 [B, Hq, D]); buffers are reused from `out`.
+    `max_blocks_used`: optional host-known bound on the total block count (0 = capacity)."""
     dev = q.device
     B, Hq = comp.B, comp.Hq
     assert q.shape == (B, Hq, DSK_HEAD_DIM) and q.dtype == torch.bfloat16 and q.is_contiguous()
@@ -330,6 +331,7 @@ def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_sco
     a.struct_size = C.sizeof(dsk_select_args)
     a.B, a.Hq, a.Hkv, a.D = B, Hq, comp.Hkv, DSK_HEAD_DIM
     a.max_blocks_total = comp.max_blocks_total
+    a.max_blocks_used = max_blocks_used
     a.cu_blocks, a.block_start, a.slot_base = _ptr(comp.cu_blocks), _ptr(comp.block_start), _ptr(comp.slot_base)
     a.ksum, a.q = _ptr(comp.ksum), _ptr(q)
     a.b, a.budget = comp.b, budget
@@ -350,8 +352,8 @@ def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_sco
 
 
 def select_topk(comp: Compressed, q: torch.Tensor, budget: int, *, want_scores: bool = False, stream=None,
-                check: bool = True) -> Selection:
-    sel = make_select_args(comp, q, budget, want_scores=want_scores)
+                check: bool = True, max_blocks_used: int = 0) -> Selection:
+    sel = make_select_args(comp, q, budget, want_scores=want_scores, max_blocks_used=max_blocks_used)
     dsk_select_topk(sel.args, stream, check=check)
     return sel
 

@@ -28,16 +28,16 @@ __device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
   f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
 }
 
-// ---- explicitly issued 16-byte global loads ---------------------------------------------
-// The compiler sinks ordinary loads towards their first use, which turns a batch of
-// independent loads into a chain of memory round trips in latency-bound kernels.  These are
-// issued exactly where written; none of them may be read before wait_issued_loads().
+// ---- keeping a batch of independent loads in flight together -------------------------------
+// The compiler sinks loads towards their first use, which turns a batch of independent loads
+// into a chain of memory round trips in latency-bound kernels.  pin_loaded(x) is an empty asm
+// that takes x in and out and clobbers "memory": no load written before it in the source can be
+// moved below it, so every load of the batch is issued before the first pin, and the compiler
+// (which still tracks these ordinary loads) places its own s_waitcnt in front of each pin.
 template <typename T>
-__device__ __forceinline__ void issue_load16(T& dst, const void* p) {
-  static_assert(sizeof(T) == 16, "16-byte vector");
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
+__device__ __forceinline__ void pin_loaded(T& v) {
+  asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w)::"memory");
 }
-__device__ __forceinline__ void wait_issued_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // ---- wavefront (64 lanes) helpers ------------------------------------------------------
 __device__ __forceinline__ float shfl_xor_f(float v, int mask) { return __shfl_xor(v, mask, DSK_WAVE); }

@@ -13,7 +13,6 @@ namespace dsk {
 constexpr int kSegTile = 1024;        // positions per DD-Select tile
 constexpr int kMaxChunkSpan = 8192;   // limit on C + delta
 constexpr int kCandTile = 1024;       // tokens per candidate-extraction tile
-constexpr int kAttnSlotsPerWg = 8;    // slots one attention workgroup folds into one partial
 constexpr int kMaxSamplesPerClass = 64;
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
@@ -51,6 +50,7 @@ struct AttnWs {
   size_t part_acc;  // f32 [B*Hq*nchunks*D]
   size_t total;
   int nchunks;
+  int slots_per_wg;  // slots one attention workgroup folds into one partial (8, or 16 for b <= 16)
 };
 AttnWs attn_ws_layout(const dsk_attn_args& a);
 hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st);

@@ -1,12 +1,13 @@
 // Sparse decode attention over the K/V rows of the selected slots (App. B.2 Steps 2-3):
 // a split-K flash-decode.  The gather is HBM-bound (512 B of K+V per token, ~2 flop/B), so
-// there is no MFMA here: a 256-byte bf16 row is spread over 16 lanes x 16 B, a wavefront
-// reads 4 token rows per load instruction and issues every load of a slot (K and V) before
-// it touches the data.  Each wavefront folds its slots into an online-softmax state
-// (m, l, acc); the 4 wavefronts of a workgroup merge through LDS into one partial per
+// there is no MFMA here: a 256-byte bf16 row is spread over 16 lanes x 16 B and a wavefront
+// reads 4 token rows per load instruction.  A wavefront owns SPW slots of at most 4*NS rows and
+// issues every K and V load of all of them (32 x 16 B per lane, 32 KB per wavefront) before it
+// touches any data, then folds them in issue order into an online-softmax state (m, l, acc)
+// as the loads land.  The 4 wavefronts of a workgroup merge through LDS into one partial per
 // (sequence, head, chunk of slots); a second small kernel merges the partials in a fixed order
-// (a device-wide fence per workgroup, as a single-kernel merge needs, costs far more on this
-// part than the extra launch inside a stream or graph).
+// (a single-kernel merge was measured slower: both a device-wide fence per workgroup and
+// write-through partials with an arrival counter cost more than the extra launch).
 #include "dsk_common.hpp"
 #include "dsk_internal.hpp"
 
@@ -16,6 +17,11 @@ constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = kAttnThreads / DSK_WAVE;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kMergeThreads = 256;
+constexpr int kMergeGroups = kMergeThreads / 16;
+
+// slots per workgroup for a slot length bound b: 32 vector loads per lane in flight either way
+__host__ __device__ constexpr int attn_slots_per_wg(int b) { return b <= 16 ? 16 : 8; }
 
 struct WaveState {
   float m;        // running max of the logits, in log2 units (wave-uniform)
@@ -23,25 +29,11 @@ struct WaveState {
   float acc[8];   // this lane group's part of the numerator, channels 8c..8c+7
 };
 
-// Fold up to 4*NS token rows starting at `start` into the state.  nvalid >= 1 rows are real;
-// loads of the padded rows are redirected to the last real row and weighted zero.
+// Fold 4*NS already-loaded token rows (K rows kv, V rows vv; row 4u+g in kv[u] of lane group g)
+// into the state.  Rows >= nvalid are padding (their loads were redirected to a real row).
 template <int NS>
-__device__ __forceinline__ void fold_rows(WaveState& st, const float (&qf)[8], const uint16_t* __restrict__ kbase,
-                                          const uint16_t* __restrict__ vbase, int64_t kst, int64_t vst,
-                                          int nvalid, int g, float scale_log2) {
-  uint4 kv[NS], vv[NS];
-#pragma unroll
-  for (int u = 0; u < NS; ++u) {
-    int r = 4 * u + g;
-    r = r < nvalid ? r : nvalid - 1;
-    kv[u] = *reinterpret_cast<const uint4*>(kbase + (int64_t)r * kst);
-  }
-#pragma unroll
-  for (int u = 0; u < NS; ++u) {
-    int r = 4 * u + g;
-    r = r < nvalid ? r : nvalid - 1;
-    vv[u] = *reinterpret_cast<const uint4*>(vbase + (int64_t)r * vst);
-  }
+__device__ __forceinline__ void fold_loaded(WaveState& st, const float (&qf)[8], const uint4 (&kv)[NS],
+                                            const uint4 (&vv)[NS], int nvalid, int g, float scale_log2) {
   float z[NS];
   float mloc = -__builtin_inff();
 #pragma unroll
@@ -74,8 +66,48 @@ __device__ __forceinline__ void fold_rows(WaveState& st, const float (&qf)[8], c
   st.m = m_new;
 }
 
-// One workgroup per (chunk of kAttnSlotsPerWg slots, head, sequence); writes one partial, or the
-// final result when the head has a single chunk.
+// ordinary (compiler-scheduled) loads; used for slots longer than 32 rows
+template <int NS>
+__device__ __forceinline__ void fold_rows(WaveState& st, const float (&qf)[8], const uint16_t* __restrict__ kbase,
+                                          const uint16_t* __restrict__ vbase, int64_t kst, int64_t vst,
+                                          int nvalid, int g, float scale_log2) {
+  uint4 kv[NS], vv[NS];
+#pragma unroll
+  for (int u = 0; u < NS; ++u) {
+    int r = 4 * u + g;
+    r = r < nvalid ? r : nvalid - 1;
+    kv[u] = *reinterpret_cast<const uint4*>(kbase + (int64_t)r * kst);
+  }
+#pragma unroll
+  for (int u = 0; u < NS; ++u) {
+    int r = 4 * u + g;
+    r = r < nvalid ? r : nvalid - 1;
+    vv[u] = *reinterpret_cast<const uint4*>(vbase + (int64_t)r * vst);
+  }
+  fold_loaded<NS>(st, qf, kv, vv, nvalid, g, scale_log2);
+}
+
+// compile-time loop over the slots of a wave: wait for slot S's K and V, fold, recurse
+template <int NS, int SPW, int S>
+struct FoldSlots {
+  static __device__ __forceinline__ void run(WaveState& st, const float (&qf)[8], uint4 (&kd)[SPW][NS],
+                                             uint4 (&vd)[SPW][NS], const int (&nv)[SPW], int g,
+                                             float scale_log2) {
+    // loads were issued slot by slot, K rows then V rows; pinning slot S here keeps the loads of
+    // the later slots in flight while this one is folded
+#pragma unroll
+    for (int u = 0; u < NS; ++u) pin_loaded(kd[S][u]);
+#pragma unroll
+    for (int u = 0; u < NS; ++u) pin_loaded(vd[S][u]);
+    if (nv[S] > 0) fold_loaded<NS>(st, qf, kd[S], vd[S], nv[S], g, scale_log2);
+    if constexpr (S + 1 < SPW) FoldSlots<NS, SPW, S + 1>::run(st, qf, kd, vd, nv, g, scale_log2);
+  }
+};
+
+// One workgroup per (chunk of kAttnWaves*SPW slots, head, sequence); writes one partial, or the
+// final result when the head has a single chunk.  NS = 0 selects the generic path for slots
+// longer than 32 rows (2 slots per wave, rows folded 32 at a time).
+template <int NS, int SPW>
 __global__ __launch_bounds__(kAttnThreads) void attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     int64_t kst, int64_t ksh, int64_t vst, int64_t vsh, int Hq, int G, int k, int b, int total_tokens,
@@ -86,6 +118,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(
   __shared__ float sm_m[kAttnWaves];
   __shared__ float sm_l[kAttnWaves];
   __shared__ float sm_acc[kAttnWaves][DSK_HEAD_DIM];
+  constexpr int kSlotsPerWg = kAttnWaves * SPW;
 
   const int chunk = blockIdx.x;
   const int h = blockIdx.y;
@@ -93,14 +126,13 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(
   const int64_t sh = (int64_t)s * Hq + h;
   const int lane = threadIdx.x & (DSK_WAVE - 1);
   const int wave = threadIdx.x / DSK_WAVE;
-  const int slot0 = chunk * kAttnSlotsPerWg;
+  const int slot0 = chunk * kSlotsPerWg;
 
   // the wave's slots: slot0 + wave + kAttnWaves * r; their spans are fetched together with the count
-  constexpr int kSlotsPerWave = kAttnSlotsPerWg / kAttnWaves;
   int count = sel_count[sh];
-  int st_[kSlotsPerWave], ln_[kSlotsPerWave];
+  int st_[SPW], ln_[SPW];
 #pragma unroll
-  for (int r = 0; r < kSlotsPerWave; ++r) {
+  for (int r = 0; r < SPW; ++r) {
     const int j = slot0 + wave + kAttnWaves * r;
     st_[r] = j < k ? sel_start[sh * k + j] : 0;
     ln_[r] = j < k ? sel_len[sh * k + j] : 0;
@@ -114,7 +146,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(
     return;
   }
   if (slot0 >= count) return;   // uniform over the workgroup; not counted in `used` below
-  const int used = (count + kAttnSlotsPerWg - 1) / kAttnSlotsPerWg;
+  const int used = (count + kSlotsPerWg - 1) / kSlotsPerWg;
 
   const int g = lane >> 4;
   const int c = lane & 15;
@@ -133,19 +165,49 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(
 #pragma unroll
   for (int i = 0; i < 8; ++i) st.acc[i] = 0.0f;
 
+  if constexpr (NS > 0) {
+    // every slot has at most 4*NS rows: all K/V loads of the wave's SPW slots go out now
+    uint4 kd[SPW][NS], vd[SPW][NS];
+    int nv[SPW];
 #pragma unroll
-  for (int r = 0; r < kSlotsPerWave; ++r) {
-    const int j = slot0 + wave + kAttnWaves * r;
-    const int start = st_[r];
-    int len = ln_[r];
-    if (len > b) len = b;
-    if (j >= count || start < 0 || len <= 0 || start > total_tokens - len) continue;   // never read outside K/V
-    for (int r0 = 0; r0 < len; r0 += 32) {
-      const int nv = len - r0;
-      const uint16_t* kb = Kh + (int64_t)(start + r0) * kst;
-      const uint16_t* vb = Vh + (int64_t)(start + r0) * vst;
-      if (nv > 16) fold_rows<8>(st, qf, kb, vb, kst, vst, nv < 32 ? nv : 32, g, scale_log2);
-      else fold_rows<4>(st, qf, kb, vb, kst, vst, nv, g, scale_log2);
+    for (int r = 0; r < SPW; ++r) {
+      const int j = slot0 + wave + kAttnWaves * r;
+      int start = st_[r];
+      int len = ln_[r] < b ? ln_[r] : b;
+      len = len < 4 * NS ? len : 4 * NS;
+      const bool ok = j < count && start >= 0 && len > 0 && start <= total_tokens - len;   // never read outside K/V
+      nv[r] = ok ? len : 0;
+      start = ok ? start : 0;            // a skipped slot reads row 0 (harmless) so that the loads
+      len = ok ? len : 1;                // below stay unconditional
+#pragma unroll
+      for (int u = 0; u < NS; ++u) {
+        int row = 4 * u + g;
+        row = row < len ? row : len - 1;
+        kd[r][u] = *reinterpret_cast<const uint4*>(Kh + (int64_t)(start + row) * kst);
+      }
+#pragma unroll
+      for (int u = 0; u < NS; ++u) {
+        int row = 4 * u + g;
+        row = row < len ? row : len - 1;
+        vd[r][u] = *reinterpret_cast<const uint4*>(Vh + (int64_t)(start + row) * vst);
+      }
+    }
+    FoldSlots<NS, SPW, 0>::run(st, qf, kd, vd, nv, g, scale_log2);
+  } else {
+#pragma unroll
+    for (int r = 0; r < SPW; ++r) {
+      const int j = slot0 + wave + kAttnWaves * r;
+      const int start = st_[r];
+      int len = ln_[r];
+      if (len > b) len = b;
+      if (j >= count || start < 0 || len <= 0 || start > total_tokens - len) continue;   // never read outside K/V
+      for (int r0 = 0; r0 < len; r0 += 32) {
+        const int nvr = len - r0;
+        const uint16_t* kb = Kh + (int64_t)(start + r0) * kst;
+        const uint16_t* vb = Vh + (int64_t)(start + r0) * vst;
+        if (nvr > 16) fold_rows<8>(st, qf, kb, vb, kst, vst, nvr < 32 ? nvr : 32, g, scale_log2);
+        else fold_rows<4>(st, qf, kb, vb, kst, vst, nvr, g, scale_log2);
+      }
     }
   }
 
@@ -166,40 +228,33 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(
 
   // waves -> workgroup partial, fixed order
   const int d = threadIdx.x;
-  float M = 0.0f, l = 0.0f, a = 0.0f;
-  if (d < DSK_HEAD_DIM) {
-    M = sm_m[0];
+  if (d >= DSK_HEAD_DIM) return;
+  float M = sm_m[0];
 #pragma unroll
-    for (int w = 1; w < kAttnWaves; ++w) M = fmaxf(M, sm_m[w]);
+  for (int w = 1; w < kAttnWaves; ++w) M = fmaxf(M, sm_m[w]);
+  float l = 0.0f, a = 0.0f;
 #pragma unroll
-    for (int w = 0; w < kAttnWaves; ++w) {
-      const float f = sm_m[w] == -__builtin_inff() ? 0.0f : exp2f(sm_m[w] - M);   // idle wave
-      l = fmaf(sm_l[w], f, l);
-      a = fmaf(sm_acc[w][d], f, a);
-    }
+  for (int w = 0; w < kAttnWaves; ++w) {
+    const float f = sm_m[w] == -__builtin_inff() ? 0.0f : exp2f(sm_m[w] - M);   // idle wave
+    l = fmaf(sm_l[w], f, l);
+    a = fmaf(sm_acc[w][d], f, a);
   }
   if (used == 1) {   // the only chunk of this head: finish here
-    if (d < DSK_HEAD_DIM) {
-      out[sh * DSK_HEAD_DIM + d] = l > 0.0f ? a / l : 0.0f;
-      if (d == 0 && lse) lse[sh] = l > 0.0f ? (M + log2f(l)) * kLn2 : -__builtin_inff();
-    }
+    out[sh * DSK_HEAD_DIM + d] = l > 0.0f ? a / l : 0.0f;
+    if (d == 0 && lse) lse[sh] = l > 0.0f ? (M + log2f(l)) * kLn2 : -__builtin_inff();
     return;
   }
   const int64_t pbase = sh * nchunks;
-  if (d < DSK_HEAD_DIM) {
-    part_acc[(pbase + chunk) * DSK_HEAD_DIM + d] = a;
-    if (d == 0) part_ml[pbase + chunk] = make_float2(M, l);
-  }
+  part_acc[(pbase + chunk) * DSK_HEAD_DIM + d] = a;
+  if (d == 0) part_ml[pbase + chunk] = make_float2(M, l);
 }
 
 // Merge of the partials of one (sequence, head) in a fixed order: 16 lane groups each fold the
 // chunks ch = group, group+16, ... (all loads of a round are independent), then one pass over
 // the 16 group states in LDS.  Heads with a single chunk were finished by attn_kernel.
-constexpr int kMergeThreads = 256;
-constexpr int kMergeGroups = kMergeThreads / 16;
 __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
     const float2* __restrict__ part_ml, const float* __restrict__ part_acc,
-    const int32_t* __restrict__ sel_count, int k, int nchunks, float* __restrict__ out,
+    const int32_t* __restrict__ sel_count, int k, int nchunks, int slots_per_wg, float* __restrict__ out,
     float* __restrict__ lse) {
   __shared__ float sm_m[kMergeGroups];
   __shared__ float sm_l[kMergeGroups];
@@ -207,7 +262,7 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
   const int64_t sh = blockIdx.x;
   int count = sel_count[sh];
   if (count > k) count = k;
-  const int used = (count + kAttnSlotsPerWg - 1) / kAttnSlotsPerWg;
+  const int used = (count + slots_per_wg - 1) / slots_per_wg;
   if (used <= 1) return;   // empty or single-chunk heads are complete already
   const int grp = threadIdx.x >> 4;
   const int c = threadIdx.x & 15;
@@ -251,7 +306,8 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
 
 AttnWs attn_ws_layout(const dsk_attn_args& a) {
   AttnWs ws;
-  ws.nchunks = (a.k + kAttnSlotsPerWg - 1) / kAttnSlotsPerWg;
+  ws.slots_per_wg = attn_slots_per_wg(a.b);
+  ws.nchunks = (a.k + ws.slots_per_wg - 1) / ws.slots_per_wg;
   const size_t n = (size_t)a.B * a.Hq * ws.nchunks;
   ws.part_ml = 0;
   ws.part_acc = align_up(n * sizeof(float2));
@@ -265,15 +321,22 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   float* part_acc = reinterpret_cast<float*>(w + ws.part_acc);
   const float scale = a.scale != 0.0f ? a.scale : 0.08838834764831845f;   // 128^-1/2
   const dim3 grid((unsigned)ws.nchunks, (unsigned)a.Hq, (unsigned)a.B);
-  attn_kernel<<<grid, dim3(kAttnThreads), 0, st>>>(
-      static_cast<const uint16_t*>(a.q), static_cast<const uint16_t*>(a.K), static_cast<const uint16_t*>(a.V),
-      a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, a.Hq / a.Hkv, a.k, a.b,
-      a.total_tokens, a.sel_start, a.sel_len, a.sel_count, scale * kLog2e, ws.nchunks, part_ml,
-      part_acc, a.out, a.lse);
+  const dim3 block(kAttnThreads);
+  const uint16_t* q = static_cast<const uint16_t*>(a.q);
+  const uint16_t* K = static_cast<const uint16_t*>(a.K);
+  const uint16_t* V = static_cast<const uint16_t*>(a.V);
+#define DSK_ATTN_ARGS                                                                                          \
+  q, K, V, a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, a.Hq / a.Hkv, a.k, a.b,     \
+      a.total_tokens, a.sel_start, a.sel_len, a.sel_count, scale * kLog2e, ws.nchunks, part_ml, part_acc, a.out, \
+      a.lse
+  if (a.b <= 16) attn_kernel<4, 4><<<grid, block, 0, st>>>(DSK_ATTN_ARGS);        // 16 slots per workgroup
+  else if (a.b <= 32) attn_kernel<8, 2><<<grid, block, 0, st>>>(DSK_ATTN_ARGS);   // 8 slots per workgroup
+  else attn_kernel<0, 2><<<grid, block, 0, st>>>(DSK_ATTN_ARGS);
+#undef DSK_ATTN_ARGS
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || ws.nchunks <= 1) return err;
   attn_merge_kernel<<<dim3((unsigned)(a.B * a.Hq)), dim3(kMergeThreads), 0, st>>>(
-      part_ml, part_acc, a.sel_count, a.k, ws.nchunks, a.out, a.lse);
+      part_ml, part_acc, a.sel_count, a.k, ws.nchunks, ws.slots_per_wg, a.out, a.lse);
   return hipGetLastError();
 }
 

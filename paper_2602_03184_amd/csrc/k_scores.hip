@@ -46,28 +46,32 @@ __device__ __forceinline__ void half_wave_reduce(float (&v)[N], int lane, int& i
 template <int G>
 __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
     const uint16_t* __restrict__ ksum, const uint16_t* __restrict__ q, const int32_t* __restrict__ cu_blocks,
-    int B, int Hq, int cap, int stride, float* __restrict__ scores, float* __restrict__ user) {
+    int B, int Hq, int cap, int bound, int stride, float* __restrict__ scores, float* __restrict__ user) {
   constexpr int NB = score_blocks_per_half(G);
   constexpr int V = NB * G;
   static_assert(V <= 32 && (V & (V - 1)) == 0, "one finished value per lane");
   const int hk = blockIdx.y;
-  int nblk = cu_blocks[B];
-  if (nblk > cap) nblk = cap;
   const int half = threadIdx.x >> 5;          // 0..7 within the workgroup
   const int c = threadIdx.x & 31;             // 16-byte column of the summary
   const bool is_max = c >= 16;                // lanes 0-15: kmin, 16-31: kmax
   const int d0 = (c & 15) * 8;
   const int i0 = (blockIdx.x * kHalvesPerWg + half) * NB;   // first block of this half-wave
-  if (i0 >= nblk) return;                     // whole half-waves leave together
   const uint16_t* kh = ksum + (int64_t)hk * cap * (2 * DSK_HEAD_DIM) + c * 8;
 
+  // `bound` (<= cap) is the host's upper bound on the block count: the loads are addressed
+  // without waiting for the device's count, all NB of them in flight together
   uint4 kv[NB];
 #pragma unroll
   for (int u = 0; u < NB; ++u) {
     int i = i0 + u;
-    i = i < nblk ? i : nblk - 1;              // tail: re-read the last block, result dropped
+    i = i < bound ? i : bound - 1;            // past the end: re-read the last record, result dropped
     kv[u] = *reinterpret_cast<const uint4*>(kh + (int64_t)i * (2 * DSK_HEAD_DIM));
   }
+  int nblk = cu_blocks[B];
+#pragma unroll
+  for (int u = 0; u < NB; ++u) pin_loaded(kv[u]);
+  if (nblk > bound) nblk = bound;
+  if (i0 >= nblk) return;                     // whole half-waves leave together
   // sequence of the group (blocks of a sequence are contiguous; a group rarely straddles two)
   int s_first = 0;
   while (s_first + 1 < B && cu_blocks[s_first + 1] <= i0) ++s_first;
@@ -175,15 +179,16 @@ hipError_t launch_scores(const dsk_select_args& a, float* scores, int stride, hi
   if (a.max_blocks_total <= 0) return hipSuccess;
   const int G = a.Hq / a.Hkv;
   const int per_wg = kHalvesPerWg * score_blocks_per_half(G);
-  const dim3 grid((unsigned)((a.max_blocks_total + per_wg - 1) / per_wg), (unsigned)a.Hkv);
+  const int bound = a.max_blocks_used > 0 ? a.max_blocks_used : a.max_blocks_total;
+  const dim3 grid((unsigned)((bound + per_wg - 1) / per_wg), (unsigned)a.Hkv);
   const dim3 block(kScoreThreads);
   const uint16_t* ksum = static_cast<const uint16_t*>(a.ksum);
   const uint16_t* q = static_cast<const uint16_t*>(a.q);
   switch (G) {
-    case 1: scores_kernel<1><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, stride, scores, a.scores); break;
-    case 2: scores_kernel<2><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, stride, scores, a.scores); break;
-    case 4: scores_kernel<4><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, stride, scores, a.scores); break;
-    case 8: scores_kernel<8><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, stride, scores, a.scores); break;
+    case 1: scores_kernel<1><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, bound, stride, scores, a.scores); break;
+    case 2: scores_kernel<2><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, bound, stride, scores, a.scores); break;
+    case 4: scores_kernel<4><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, bound, stride, scores, a.scores); break;
+    case 8: scores_kernel<8><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, bound, stride, scores, a.scores); break;
     default:
       scores_kernel_anyg<<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, G, a.max_blocks_total, stride, scores, a.scores);
   }

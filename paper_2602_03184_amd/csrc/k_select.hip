@@ -297,20 +297,25 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 #pragma unroll
   for (int u = 0; u < kSelVecs; ++u) {
     const int v = v_first + u;
-    issue_load16(fv[u], sc4 + (v < max_vec_sc ? v : max_vec_sc));
+    fv[u] = sc4[v < max_vec_sc ? v : max_vec_sc];
   }
 #pragma unroll
   for (int u = 0; u < kSelVecs + 1; ++u) {
     const int v = v_first + u;
-    issue_load16(iv[u], sb4 + (v < max_vec_sb ? v : max_vec_sb));
+    iv[u] = sb4[v < max_vec_sb ? v : max_vec_sb];
   }
 #pragma unroll
   for (int u = 0; u < kSelVecs + 1; ++u) {
     const int v = v_first + u;
-    issue_load16(bv[u], bs4 + (v < max_vec_sb ? v : max_vec_sb));
+    bv[u] = bs4[v < max_vec_sb ? v : max_vec_sb];
   }
   int blk1 = cu_blocks[s + 1];
-  wait_issued_loads();                                // all vector loads were in flight together
+#pragma unroll
+  for (int u = 0; u < kSelVecs; ++u) pin_loaded(fv[u]);              // all vector loads in flight together
+#pragma unroll
+  for (int u = 0; u < kSelVecs + 1; ++u) pin_loaded(iv[u]);
+#pragma unroll
+  for (int u = 0; u < kSelVecs + 1; ++u) pin_loaded(bv[u]);
   if (blk1 > cap) blk1 = cap;
   const int n = blk1 - blk0;
   if (n <= 0) {
