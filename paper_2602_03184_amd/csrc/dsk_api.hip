@@ -22,7 +22,6 @@ CompressWs compress_ws_layout(const dsk_compress_args& a) {
   ws.n_cand_tiles = (a.total_tokens + kCandTile - 1) / kCandTile;
   const size_t n_tiles = (size_t)a.B * ws.tiles_per_seq;
   size_t off = 0;
-  ws.marker = off;     off += align_up((size_t)a.total_tokens + 1 + 16);
   ws.tile_map = off;   off += align_up(n_tiles * ws.map_row * sizeof(uint2));
   ws.tile_info = off;  off += align_up(n_tiles * sizeof(int4));
   ws.seq_info = off;   off += align_up((size_t)a.B * sizeof(int4));
@@ -193,7 +192,7 @@ dsk_status dsk_compress(const dsk_compress_args* a, void* stream) {
   if (a->stages & DSK_STAGE_IMPORTANCE)
     if (launch_importance(*a, ws, st) != hipSuccess) return DSK_ERR_LAUNCH;
   if (a->stages & DSK_STAGE_SEGMENT)
-    if (launch_segment(*a, ws, st) != hipSuccess) return DSK_ERR_LAUNCH;
+    if (launch_segment(*a, ws, (a->stages & DSK_STAGE_CANDIDATES) != 0, st) != hipSuccess) return DSK_ERR_LAUNCH;
   if (a->stages & DSK_STAGE_SUMMARIES)
     if (launch_summaries(*a, st) != hipSuccess) return DSK_ERR_LAUNCH;
   return DSK_OK;

@@ -10,7 +10,7 @@
 
 namespace dsk {
 
-constexpr int kSegTile = 1024;        // positions per DD-Select tile
+constexpr int kSegTile = 2048;        // positions per DD-Select tile
 constexpr int kMaxChunkSpan = 8192;   // limit on C + delta
 constexpr int kCandTile = 1024;       // tokens per candidate-extraction tile
 constexpr int kMaxSamplesPerClass = 64;
@@ -19,7 +19,6 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
 // ---- dsk_compress workspace ---------------------------------------------------------------
 struct CompressWs {
-  size_t marker;      // u8  [total_tokens + 1]      boundary -> weight tenths, 255 = none
   size_t tile_map;    // uint2 [n_tiles * map_row]   entry offset -> (exit offset | blocks<<16, slots)
   size_t tile_info;   // int4 [n_tiles]              entry position, block offset, slot offset
   size_t seq_info;    // int4 [B]                    blocks, slots, block base, slot base
@@ -35,7 +34,8 @@ CompressWs compress_ws_layout(const dsk_compress_args& a);
 
 hipError_t launch_candidates(const dsk_compress_args& a, const CompressWs& ws, hipStream_t st);
 hipError_t launch_importance(const dsk_compress_args& a, const CompressWs& ws, hipStream_t st);
-hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, hipStream_t st);
+// have_cls_at: the dense class bytes in the workspace were just written by launch_candidates
+hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, bool have_cls_at, hipStream_t st);
 hipError_t launch_summaries(const dsk_compress_args& a, hipStream_t st);
 
 // ---- dsk_select_topk ----------------------------------------------------------------------

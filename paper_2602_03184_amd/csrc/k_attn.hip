@@ -1,10 +1,9 @@
 // Sparse decode attention over the K/V rows of the selected slots (App. B.2 Steps 2-3):
 // a split-K flash-decode.  The gather is HBM-bound (512 B of K+V per token, ~2 flop/B), so
 // there is no MFMA here: a 256-byte bf16 row is spread over 16 lanes x 16 B and a wavefront
-// reads 4 token rows per load instruction.  A wavefront owns SPW slots of at most 4*NS rows and
-// issues every K and V load of all of them (32 x 16 B per lane, 32 KB per wavefront) before it
-// touches any data, then folds them in issue order into an online-softmax state (m, l, acc)
-// as the loads land.  The 4 wavefronts of a workgroup merge through LDS into one partial per
+// reads 4 token rows per load instruction.  A wavefront owns SPW slots of at most 4*NS rows; it
+// issues every K and V load of a slot (16 x 16 B per lane, 16 KB per wavefront for 32 rows)
+// before it touches the data, then folds the slot into an online-softmax state (m, l, acc).  The 4 wavefronts of a workgroup merge through LDS into one partial per
 // (sequence, head, chunk of slots); a second small kernel merges the partials in a fixed order
 // (a single-kernel merge was measured slower: both a device-wide fence per workgroup and
 // write-through partials with an arrival counter cost more than the extra launch).
@@ -13,14 +12,12 @@
 
 namespace dsk {
 
-constexpr int kAttnThreads = 256;
-constexpr int kAttnWaves = kAttnThreads / DSK_WAVE;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kMergeThreads = 256;
 constexpr int kMergeGroups = kMergeThreads / 16;
 
-// slots per workgroup for a slot length bound b: 32 vector loads per lane in flight either way
+// slots per workgroup for a slot length bound b
 __host__ __device__ constexpr int attn_slots_per_wg(int b) { return b <= 16 ? 16 : 8; }
 
 struct WaveState {
@@ -104,17 +101,18 @@ struct FoldSlots {
   }
 };
 
-// One workgroup per (chunk of kAttnWaves*SPW slots, head, sequence); writes one partial, or the
+// One workgroup of WAVES wavefronts per (chunk of WAVES*SPW slots, head, sequence); writes one partial, or the
 // final result when the head has a single chunk.  NS = 0 selects the generic path for slots
 // longer than 32 rows (2 slots per wave, rows folded 32 at a time).
-template <int NS, int SPW>
-__global__ __launch_bounds__(kAttnThreads) void attn_kernel(
+template <int NS, int SPW, int WAVES, bool STAGED = false>
+__global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     int64_t kst, int64_t ksh, int64_t vst, int64_t vsh, int Hq, int G, int k, int b, int total_tokens,
     const int32_t* __restrict__ sel_start, const int32_t* __restrict__ sel_len,
     const int32_t* __restrict__ sel_count, float scale_log2, int nchunks,
     float2* __restrict__ part_ml, float* __restrict__ part_acc, float* __restrict__ out,
     float* __restrict__ lse) {
+  constexpr int kAttnWaves = WAVES;
   __shared__ float sm_m[kAttnWaves];
   __shared__ float sm_l[kAttnWaves];
   __shared__ float sm_acc[kAttnWaves][DSK_HEAD_DIM];
@@ -191,8 +189,15 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(
         row = row < len ? row : len - 1;
         vd[r][u] = *reinterpret_cast<const uint4*>(Vh + (int64_t)(start + row) * vst);
       }
+      if constexpr (STAGED) {
+#pragma unroll
+        for (int u = 0; u < NS; ++u) pin_loaded(kd[r][u]);
+#pragma unroll
+        for (int u = 0; u < NS; ++u) pin_loaded(vd[r][u]);
+        if (nv[r] > 0) fold_loaded<NS>(st, qf, kd[r], vd[r], nv[r], g, scale_log2);
+      }
     }
-    FoldSlots<NS, SPW, 0>::run(st, qf, kd, vd, nv, g, scale_log2);
+    if constexpr (!STAGED) FoldSlots<NS, SPW, 0>::run(st, qf, kd, vd, nv, g, scale_log2);
   } else {
 #pragma unroll
     for (int r = 0; r < SPW; ++r) {
@@ -321,7 +326,7 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   float* part_acc = reinterpret_cast<float*>(w + ws.part_acc);
   const float scale = a.scale != 0.0f ? a.scale : 0.08838834764831845f;   // 128^-1/2
   const dim3 grid((unsigned)ws.nchunks, (unsigned)a.Hq, (unsigned)a.B);
-  const dim3 block(kAttnThreads);
+
   const uint16_t* q = static_cast<const uint16_t*>(a.q);
   const uint16_t* K = static_cast<const uint16_t*>(a.K);
   const uint16_t* V = static_cast<const uint16_t*>(a.V);
@@ -329,9 +334,11 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   q, K, V, a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, a.Hq / a.Hkv, a.k, a.b,     \
       a.total_tokens, a.sel_start, a.sel_len, a.sel_count, scale * kLog2e, ws.nchunks, part_ml, part_acc, a.out, \
       a.lse
-  if (a.b <= 16) attn_kernel<4, 4><<<grid, block, 0, st>>>(DSK_ATTN_ARGS);        // 16 slots per workgroup
-  else if (a.b <= 32) attn_kernel<8, 2><<<grid, block, 0, st>>>(DSK_ATTN_ARGS);   // 8 slots per workgroup
-  else attn_kernel<0, 2><<<grid, block, 0, st>>>(DSK_ATTN_ARGS);
+  // Measured on config 3 (b = 32): one slot (16 KB) in flight per wavefront, the next slot issued
+  // after the fold (STAGED), 9.9 us; both slots issued up front 10.9 us; 8 wavefronts x 1 slot 10.3 us.
+  if (a.b <= 16) attn_kernel<4, 4, 4, true><<<grid, dim3(256), 0, st>>>(DSK_ATTN_ARGS);       // 16 slots per workgroup
+  else if (a.b <= 32) attn_kernel<8, 2, 4, true><<<grid, dim3(256), 0, st>>>(DSK_ATTN_ARGS);  // 8 slots per workgroup
+  else attn_kernel<0, 2, 4><<<grid, dim3(256), 0, st>>>(DSK_ATTN_ARGS);
 #undef DSK_ATTN_ARGS
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || ws.nchunks <= 1) return err;
