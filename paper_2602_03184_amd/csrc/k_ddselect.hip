@@ -22,6 +22,16 @@
 
 namespace dsk {
 
+#ifdef DSK_SEG_TIMING
+__device__ long long dsk_dbg2[64 * 16];
+#define SEG_TS(slot) do { if (MODE == 0 && threadIdx.x == 0) dsk_dbg2[(blockIdx.x % 64) * 16 + (slot)] = wall_clock64(); } while (0)
+extern "C" __attribute__((visibility("default"))) void dsk_debug_read2(long long* host) {
+  (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(dsk_dbg2), sizeof(long long) * 64 * 16);
+}
+#else
+#define SEG_TS(slot) do {} while (0)
+#endif
+
 constexpr int kSegThreads = 256;
 constexpr int kSegPerThread = kSegTile / kSegThreads;   // consecutive positions owned by a thread
 constexpr int kSegWaves = kSegThreads / DSK_WAVE;
@@ -93,15 +103,14 @@ __global__ __launch_bounds__(256) void seg_scatter_kernel(
 // ---- tile kernel -----------------------------------------------------------------------------
 // dynamic LDS layout (bytes):
 //   best  u64 [kSegTile]                      votes; dead after the successor table is built,
-//   pos/cb/cs u16 [2][kSegTile] each          ... so the pointer-jumping arrays overlay it
-//   nxt   u16 [kSegTile]   successor - position
+//   jpb u32 [2][kSegTile], jcs u16 [2][kSegTile]   ... so the pointer-jumping arrays overlay it
 //   ns    u16 [kSegTile]   slots of the chunk starting here
 //   mark  u8  [kSegTile]   (emit mode) reachable from the tile's entry
 //   wq    u8  [64]         class -> weight tenths of this sequence
 //   red   i32 [2*kSegWaves + 2]
 __host__ __device__ constexpr size_t seg_tile_lds_bytes() {
   return (size_t)kSegTile * 12      // jump arrays (the vote array, 8 bytes per position, overlays them)
-         + (size_t)kSegTile * 4     // nxt, ns
+         + (size_t)kSegTile * 2     // ns
          + (size_t)kSegTile         // mark
          + 64 + 64;                 // wq, red
 }
@@ -115,11 +124,9 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
   extern __shared__ __align__(16) unsigned char smem[];
   // jump arrays (12 * kSegTile bytes) share storage with the vote array (8 * kSegTile bytes)
   unsigned long long* best = reinterpret_cast<unsigned long long*>(smem);
-  uint16_t* jpos = reinterpret_cast<uint16_t*>(smem);            // [2][kSegTile] position - p0, or exit
-  uint16_t* jcb = jpos + 2 * kSegTile;                            // [2][kSegTile] blocks laid down
-  uint16_t* jcs = jcb + 2 * kSegTile;                             // [2][kSegTile] slots laid down
-  uint16_t* nxt = jcs + 2 * kSegTile;
-  uint16_t* ns = nxt + kSegTile;
+  uint32_t* jpb = reinterpret_cast<uint32_t*>(smem);             // [2][kSegTile] (position - p0 or exit) | blocks << 16
+  uint16_t* jcs = reinterpret_cast<uint16_t*>(jpb + 2 * kSegTile);   // [2][kSegTile] slots laid down
+  uint16_t* ns = jcs + 2 * kSegTile;                              // [kSegTile] slots of the chunk starting here
   uint8_t* mark = reinterpret_cast<uint8_t*>(ns + kSegTile);
   uint8_t* wq = mark + kSegTile;
   int* red = reinterpret_cast<int*>(wq + 64);
@@ -127,6 +134,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
   const int s = blockIdx.y;
   const int j = blockIdx.x;
   const int tid = threadIdx.x;
+  SEG_TS(0);
   const int seq0 = p.cu_seqlens[s];
   const int L = p.cu_seqlens[s + 1] - seq0;
   if (!seq_ok(p, seq0, L)) {
@@ -154,37 +162,68 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
   }
   for (int i = tid; i < kSegTile; i += kSegThreads) { best[i] = 0ull; mark[i] = 0; }
   __syncthreads();
+  SEG_TS(1);
 
   // votes: boundary e (offered by a delimiter at e-1) can end a chunk that starts at q with
   // s_e = q + C in [e - delta, e + delta] and s_e < L.  key = score << 16 | (0xFFFF - (e - q)):
-  // highest score wins, then the smallest e; 0 = no vote.
+  // highest score wins, then the smallest e; 0 = no vote.  The boundaries in reach are scanned
+  // kVoteChunk at a time (normally once); the delimiters found are first compacted into an LDS
+  // list so that the vote loops run on threads that all have one (a dense scan would leave 1
+  // lane in 30 busy).
   {
+    constexpr int kVoteChunk = 2 * kSegTile;                                        // 16 class bytes per thread
+    constexpr int kPerThread = kVoteChunk / kSegThreads;
+    uint16_t* clist = reinterpret_cast<uint16_t*>(smem + (size_t)kSegTile * 8);     // free until the jump arrays are built
+    int* n_list = red;
     const int e_lo = p0 + C - delta > 1 ? p0 + C - delta : 1;
     int e_hi = p1 - 1 + C + delta;
     if (e_hi > L) e_hi = L;
-    for (int e = e_lo + tid; e <= e_hi; e += kSegThreads) {
-      const int cls = cls_at[seq0 + e - 1];
-      if (cls == 255) continue;
-      const int w = cls < 64 ? wq[cls] : 0;
-      int q_lo = e - C - delta, q_hi = e - C + delta;
-      if (q_lo < p0) q_lo = p0;
-      if (q_hi > p1 - 1) q_hi = p1 - 1;
-      if (q_hi > L - C - 1) q_hi = L - C - 1;      // s_e = q + C must stay below L
-      for (int q = q_lo; q <= q_hi; ++q) {
-        const int s_e = q + C;
-        const int dist = e > s_e ? e - s_e : s_e - e;
-        const unsigned long long sc = (unsigned long long)(p.a_num * w * dd + (p.a_den - p.a_num) * 10 * (dd - dist));
-        const unsigned long long key = ((sc + 1ull) << 16) | (unsigned long long)(0xFFFF - (e - q));
-        atomicMax(&best[q - p0], key);
+    for (int e0 = e_lo; e0 <= e_hi; e0 += kVoteChunk) {
+      uint8_t cb_[kPerThread];
+#pragma unroll
+      for (int r = 0; r < kPerThread; ++r) {       // independent byte loads: one round trip
+        int e = e0 + r * kSegThreads + tid;
+        e = e <= e_hi ? e : e_hi;
+        cb_[r] = cls_at[seq0 + e - 1];
       }
+      if (tid == 0) *n_list = 0;
+      __syncthreads();
+#pragma unroll
+      for (int r = 0; r < kPerThread; ++r) {
+        const int eo = r * kSegThreads + tid;        // e - e0 < 4096: 12 bits, weight 0..10: 4 bits
+        if (e0 + eo <= e_hi && cb_[r] != 255) {
+          const int w = cb_[r] < 64 ? wq[cb_[r]] : 0;
+          clist[atomicAdd(n_list, 1)] = (uint16_t)((eo << 4) | w);   // at most kVoteChunk entries = 8 KB
+        }
+      }
+      __syncthreads();
+      const int n = *n_list;
+      for (int ci = tid; ci < n; ci += kSegThreads) {
+        const int ent = clist[ci];
+        const int e = e0 + (ent >> 4);
+        const int w = ent & 15;
+        int q_lo = e - C - delta, q_hi = e - C + delta;
+        if (q_lo < p0) q_lo = p0;
+        if (q_hi > p1 - 1) q_hi = p1 - 1;
+        if (q_hi > L - C - 1) q_hi = L - C - 1;      // s_e = q + C must stay below L
+        for (int q = q_lo; q <= q_hi; ++q) {
+          const int s_e = q + C;
+          const int dist = e > s_e ? e - s_e : s_e - e;
+          const unsigned long long sc = (unsigned long long)(p.a_num * w * dd + (p.a_den - p.a_num) * 10 * (dd - dist));
+          const unsigned long long key = ((sc + 1ull) << 16) | (unsigned long long)(0xFFFF - (e - q));
+          atomicMax(&best[q - p0], key);
+        }
+      }
+      __syncthreads();
     }
   }
-  __syncthreads();
-  // successor table (registers first: `best` is about to be overlaid)
+  SEG_TS(2);
+  // successor table (registers first: `best` is about to be overlaid).  Lane-interleaved
+  // ownership (i = r*256 + tid) keeps these LDS accesses free of bank conflicts.
   int my_len[kSegPerThread];
 #pragma unroll
   for (int r = 0; r < kSegPerThread; ++r) {
-    const int i = tid * kSegPerThread + r;
+    const int i = r * kSegThreads + tid;
     const int q = p0 + i;
     int len = 0;
     if (i < tlen) {
@@ -200,64 +239,85 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
   __syncthreads();
 #pragma unroll
   for (int r = 0; r < kSegPerThread; ++r) {
-    const int i = tid * kSegPerThread + r;
+    const int i = r * kSegThreads + tid;
     const int len = my_len[r];
     const int nslot = (len + p.b - 1) / p.b;
-    nxt[i] = (uint16_t)len;
     ns[i] = (uint16_t)nslot;
-    // level-0 jump: one chunk
-    jpos[i] = (uint16_t)(i + len);          // >= tlen means "left the tile" (i + len <= tlen + C + delta)
-    jcb[i] = (uint16_t)(i < tlen ? 1 : 0);
+    // level-0 jump: one chunk.  position >= tlen means "left the tile" (i + len <= tlen + C + delta)
+    jpb[i] = (uint32_t)(i + len) | ((i < tlen ? 1u : 0u) << 16);
     jcs[i] = (uint16_t)nslot;
   }
   if (MODE == 1 && tid == 0 && info.x >= p0 && info.x < p1) mark[info.x - p0] = 1;
   __syncthreads();
 
+  SEG_TS(3);
   // pointer jumping: level r holds 2^r chunks per hop; positions that left the tile are fixed points
   int cur = 0;
+  int* any_active = red + 2 * kSegWaves;   // two flags, used alternately
+  if (tid == 0) { any_active[0] = 0; any_active[1] = 0; }
+  __syncthreads();
   for (int round = 0; round < 16; ++round) {
     int active = 0;
-    uint16_t* ps = jpos + cur * kSegTile; uint16_t* pd = jpos + (cur ^ 1) * kSegTile;
-    uint16_t* bs_ = jcb + cur * kSegTile; uint16_t* bd = jcb + (cur ^ 1) * kSegTile;
-    uint16_t* ss = jcs + cur * kSegTile;  uint16_t* sd = jcs + (cur ^ 1) * kSegTile;
+    const uint32_t* ps = jpb + cur * kSegTile; uint32_t* pd = jpb + (cur ^ 1) * kSegTile;
+    const uint16_t* ss = jcs + cur * kSegTile; uint16_t* sd = jcs + (cur ^ 1) * kSegTile;
 #pragma unroll
     for (int r = 0; r < kSegPerThread; ++r) {
-      const int i = tid * kSegPerThread + r;
-      const int t = ps[i];
-      int np = t, nb = bs_[i], nsl = ss[i];
+      const int i = r * kSegThreads + tid;
+      const uint32_t v = ps[i];
+      const int t = (int)(v & 0xFFFFu);
+      uint32_t nv = v;
+      int nsl = ss[i];
       if (i < tlen && t < tlen) {
         if (MODE == 1 && mark[i]) mark[t] = 1;   // reachable set doubles with the hop length
-        np = ps[t];
-        nb += bs_[t];
+        const uint32_t v2 = ps[t];
+        nv = (v2 & 0xFFFFu) | ((v & 0xFFFF0000u) + (v2 & 0xFFFF0000u));
         nsl += ss[t];
         active = 1;
       }
-      pd[i] = (uint16_t)np; bd[i] = (uint16_t)nb; sd[i] = (uint16_t)nsl;
+      pd[i] = nv;
+      sd[i] = (uint16_t)nsl;
     }
     cur ^= 1;
-    if (!__syncthreads_or(active)) break;
+    if (active) any_active[round & 1] = 1;          // benign race: everyone writes the same value
+    if (tid == 0) any_active[(round + 1) & 1] = 0;  // not read again before the next barrier
+    __syncthreads();
+    if (!any_active[round & 1]) break;
   }
-  const uint16_t* fpos = jpos + cur * kSegTile;
-  const uint16_t* fcb = jcb + cur * kSegTile;
+  SEG_TS(4);
+  const uint32_t* fpb = jpb + cur * kSegTile;
   const uint16_t* fcs = jcs + cur * kSegTile;
 
   if (MODE == 0) {
     uint2* row = tile_map + (int64_t)tile * p.map_row;
     for (int ent = tid; ent < p.map_row; ent += kSegThreads) {
       uint2 rv = make_uint2(0u, 0u);
-      if (ent < tlen) rv = make_uint2((uint32_t)(fpos[ent] - tlen) | ((uint32_t)fcb[ent] << 16), (uint32_t)fcs[ent]);
+      if (ent < tlen) {
+        const uint32_t v = fpb[ent];
+        rv = make_uint2(((v & 0xFFFFu) - (uint32_t)tlen) | (v & 0xFFFF0000u), (uint32_t)fcs[ent]);
+      }
       row[ent] = rv;
     }
+    SEG_TS(5);
     return;
   }
 
-  // emit: rank the marked positions of the tile (thread order = position order)
+  // emit: rank the marked positions of the tile; here a thread owns 8 consecutive positions
+  // (thread order = position order), read as one 8-byte and one 16-byte vector
+  static_assert(kSegPerThread == 8, "vector reads below");
+  const uint2 mk8 = *reinterpret_cast<const uint2*>(mark + tid * 8);
+  const uint4 ns8 = *reinterpret_cast<const uint4*>(ns + tid * 8);
+  int mk[8], nsv[8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const uint32_t mw = r < 4 ? mk8.x : mk8.y;
+    mk[r] = (tid * 8 + r < tlen) ? (int)((mw >> (8 * (r & 3))) & 255u) : 0;
+    const uint32_t nw = r < 2 ? ns8.x : (r < 4 ? ns8.y : (r < 6 ? ns8.z : ns8.w));
+    nsv[r] = (int)((nw >> (16 * (r & 1))) & 0xFFFFu);
+  }
   int nb_local = 0, ns_local = 0;
 #pragma unroll
-  for (int r = 0; r < kSegPerThread; ++r) {
-    const int i = tid * kSegPerThread + r;
-    if (i < tlen && mark[i]) { ++nb_local; ns_local += ns[i]; }
-  }
+  for (int r = 0; r < 8; ++r)
+    if (mk[r]) { ++nb_local; ns_local += nsv[r]; }
   const int lane = tid & (DSK_WAVE - 1), wave = tid / DSK_WAVE;
   const int ib = wave_incl_scan_i(nb_local, lane);
   const int is = wave_incl_scan_i(ns_local, lane);
@@ -270,18 +330,16 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
   int gb = sq.z + info.y + ob + ib - nb_local;
   int gs = sq.w + info.z + os + is - ns_local;
 #pragma unroll
-  for (int r = 0; r < kSegPerThread; ++r) {
-    const int i = tid * kSegPerThread + r;
-    if (i < tlen && mark[i]) {
+  for (int r = 0; r < 8; ++r) {
+    if (mk[r]) {
       if (gb < p.cap) {
-        block_start[gb] = seq0 + p0 + i;
+        block_start[gb] = seq0 + p0 + tid * 8 + r;
         slot_base[gb] = gs;
       }
       ++gb;
-      gs += ns[i];
+      gs += nsv[r];
     }
   }
-  (void)fpos; (void)fcb; (void)fcs;
 }
 
 // ---- chain ----------------------------------------------------------------------------------
