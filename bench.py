@@ -24,6 +24,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM traffic of the dominant kernel per launch, from `rocprofv3 --pmc FETCH_SIZE` and
+# `--pmc WRITE_SIZE` runs of this file (summaries under profiles/), each scaled by what the same
+# counter reads for the plain 256 MiB device copy of --calib-copy-mib (FETCH_SIZE reads half the
+# copied bytes on this part -> x2; WRITE_SIZE reads them exactly -> x1).  Keyed by workload.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg3_llama3_8b_128k": {"attn_kernel": int(20420.9 * 1024 * 2.000 + 272.0 * 1024 * 1.000)},
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -154,7 +162,17 @@ def main():
         eager_ms = event_ms(lambda: [step(i) for i in range(args.steps)], stream)
         eager_us = eager_ms * 1e3 / args.steps
 
-        # ---- dominant kernel: the attention gather, timed on its own stream region --------------
+        # ---- dominant kernel: the attention gather (attn_kernel) alone, HIP events on its stream ---
+        gathers = [dsk.make_attn_args(queries[i], K, V, sels[0].sel_start, sels[0].sel_len, sels[0].sel_count,
+                                      cfg.b, out=atts[0], flags=dsk.DSK_ATTN_PARTIALS_ONLY) for i in range(nq)]
+        g_gather = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_gather, stream=stream):
+            for i in range(args.steps):
+                dsk.dsk_sparse_decode_attn(gathers[i % nq].args, stream)
+        g_gather.replay()
+        stream.synchronize()
+        gather_us = event_ms(g_gather.replay, stream) * 1e3 / args.steps
+        # the whole attention call (gather + merge of the partials) and the whole selection call
         g_attn = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g_attn, stream=stream):
             for i in range(args.steps):
@@ -171,7 +189,8 @@ def main():
         select_us = event_ms(g_sel.replay, stream) * 1e3 / args.steps
     torch.cuda.synchronize()
 
-    attn_gbs = bytes_attn / (attn_us * 1e-6) / 1e9
+    attn_gbs = bytes_attn / (gather_us * 1e-6) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("attn_kernel")
     step_gbs = step_bytes / (us_per_step * 1e-6) / 1e9
     out = {
         "metric": "decode attn us/step + achieved HBM GB/s at 128K ctx (Llama-3-8B shape)",
@@ -198,10 +217,13 @@ def main():
                      "GBps": round(compress_bytes / (compress_ms * 1e-3) / 1e9, 1),
                      "frac_of_hbm_peak": round(compress_bytes / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                      "stages": "candidates+segment+summaries(K)"},
-        "roofline": {"bound": "hbm", "kernel": "dsk_sparse_decode_attn (attn_partial_kernel + merge)",
+        "roofline": {"bound": "hbm", "kernel": "attn_kernel (K/V gather + online softmax of dsk_sparse_decode_attn)",
                      "achieved": round(attn_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(attn_gbs / HBM_PEAK_GBS, 4), "traffic": None,
-                     "bytes_per_launch": int(bytes_attn), "us_per_launch": round(attn_us, 3)},
+                     "frac": round(attn_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "bytes_per_launch": int(bytes_attn), "us_per_launch": round(gather_us, 3),
+                     "attn_call_us": round(attn_us, 3),
+                     "attn_call_frac": round(bytes_attn / (attn_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                     "step_frac": round(step_gbs / HBM_PEAK_GBS, 4)},
         "workload_gen_s": round(gen_s, 1),
     }
     if not args.no_cpu_baseline:

@@ -196,6 +196,12 @@ typedef struct dsk_select_args {
  * fp32 accumulation, split over slots with an online-softmax merge in a fixed order.
  * A (sequence, head) with no selected token gets out = 0 and lse = -inf.
  * ---------------------------------------------------------------------------------------- */
+/* dsk_attn_args.flags: stop after the per-chunk partials (running max in log2 units, denominator,
+ * unnormalised numerator) and leave them in the workspace -- for a caller that merges partials
+ * itself, e.g. across devices that each hold part of a sequence.  out / lse are then final only
+ * for heads whose selection fits one chunk. */
+#define DSK_ATTN_PARTIALS_ONLY 1u
+
 typedef struct dsk_attn_args {
   uint32_t struct_size;
   int32_t B, Hq, Hkv, D;
@@ -210,6 +216,7 @@ typedef struct dsk_attn_args {
   const int32_t* sel_len;      /* [dev] [B, Hq, k] */
   const int32_t* sel_count;    /* [dev] [B, Hq] */
   float scale;                 /* 0 -> D^-1/2 */
+  uint32_t flags;              /* DSK_ATTN_* bits */
   float* out;                  /* [dev] f32 [B, Hq, D] */
   float* lse;                  /* [dev] f32 [B, Hq], natural log; may be NULL */
   void* workspace;             /* [dev] */

@@ -32,6 +32,7 @@ DSK_STAGE_CANDIDATES, DSK_STAGE_IMPORTANCE, DSK_STAGE_SEGMENT, DSK_STAGE_SUMMARI
 DSK_STAGE_ALL = 15
 DSK_HEAD_DIM = 128
 DSK_MAX_CLASSES = 64
+DSK_ATTN_PARTIALS_ONLY = 1
 
 _p = C.c_void_p
 
@@ -85,7 +86,7 @@ class dsk_attn_args(C.Structure):
         ("v_stride_tok", C.c_int64), ("v_stride_head", C.c_int64),
         ("total_tokens", C.c_int32), ("k", C.c_int32), ("b", C.c_int32),
         ("sel_start", _p), ("sel_len", _p), ("sel_count", _p),
-        ("scale", C.c_float),
+        ("scale", C.c_float), ("flags", C.c_uint32),
         ("out", _p), ("lse", _p),
         ("workspace", _p), ("workspace_bytes", C.c_size_t),
     ]
@@ -368,7 +369,7 @@ class AttnOut:
 
 def make_attn_args(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, sel_start: torch.Tensor,
                    sel_len: torch.Tensor, sel_count: torch.Tensor, b: int, *, scale: float = 0.0,
-                   out: Optional[AttnOut] = None) -> AttnOut:
+                   out: Optional[AttnOut] = None, flags: int = 0) -> AttnOut:
     dev = q.device
     B, Hq, D = q.shape
     assert D == DSK_HEAD_DIM and q.dtype == torch.bfloat16 and q.is_contiguous()
@@ -382,6 +383,7 @@ def make_attn_args(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, sel_start:
     a.total_tokens, a.k, a.b = K.shape[1], k, b
     a.sel_start, a.sel_len, a.sel_count = _ptr(sel_start), _ptr(sel_len), _ptr(sel_count)
     a.scale = scale
+    a.flags = flags
     if out is None:
         o = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
         lse = torch.empty(B, Hq, dtype=torch.float32, device=dev)

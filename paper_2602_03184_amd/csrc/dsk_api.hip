@@ -122,7 +122,7 @@ static dsk_status validate_attn(const dsk_attn_args* a) {
   if (!geometry_ok(a->B, a->Hq, a->Hkv, a->D)) return DSK_ERR_SHAPE;
   if (a->total_tokens < 0) return DSK_ERR_SHAPE;
   if (a->k < 1 || a->b < 1 || a->b > 1024) return DSK_ERR_PARAM;
-  if (!(a->scale >= 0.0f)) return DSK_ERR_PARAM;
+  if (!(a->scale >= 0.0f) || (a->flags & ~(uint32_t)DSK_ATTN_PARTIALS_ONLY)) return DSK_ERR_PARAM;
   if (!a->q || !a->K || !a->V || !a->sel_start || !a->sel_len || !a->sel_count || !a->out) return DSK_ERR_NULL;
   if (a->k_stride_tok < DSK_HEAD_DIM || a->v_stride_tok < DSK_HEAD_DIM || a->k_stride_head < 0 ||
       a->v_stride_head < 0)

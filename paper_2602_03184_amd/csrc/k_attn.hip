@@ -341,7 +341,7 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   else attn_kernel<0, 2, 4><<<grid, dim3(256), 0, st>>>(DSK_ATTN_ARGS);
 #undef DSK_ATTN_ARGS
   hipError_t err = hipGetLastError();
-  if (err != hipSuccess || ws.nchunks <= 1) return err;
+  if (err != hipSuccess || ws.nchunks <= 1 || (a.flags & DSK_ATTN_PARTIALS_ONLY)) return err;
   attn_merge_kernel<<<dim3((unsigned)(a.B * a.Hq)), dim3(kMergeThreads), 0, st>>>(
       part_ml, part_acc, a.sel_count, a.k, ws.nchunks, ws.slots_per_wg, a.out, a.lse);
   return hipGetLastError();

@@ -149,7 +149,8 @@ def test_select_and_attn_validation(dsk):
     assert dsk.dsk_sparse_decode_attn(att(), 0, check=False) == dsk.DSK_ERR_WORKSPACE
     assert dsk.dsk_attn_workspace_bytes(att()) > 0
     for field, value, want in (("k", 0, dsk.DSK_ERR_PARAM), ("scale", -1.0, dsk.DSK_ERR_PARAM),
-                               ("scale", float("nan"), dsk.DSK_ERR_PARAM), ("V", None, dsk.DSK_ERR_NULL),
+                               ("scale", float("nan"), dsk.DSK_ERR_PARAM), ("flags", 2, dsk.DSK_ERR_PARAM),
+                               ("V", None, dsk.DSK_ERR_NULL),
                                ("v_stride_tok", 100, dsk.DSK_ERR_SHAPE), ("k_stride_tok", 129, dsk.DSK_ERR_ALIGN),
                                ("out", None, dsk.DSK_ERR_NULL), ("D", 256, dsk.DSK_ERR_SHAPE)):
         a = att()
