@@ -4,8 +4,8 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
 
 A step is one decode step of the whole per-token path -- dsk_select_topk (block scores +
-slot top-k) followed by dsk_sparse_decode_attn -- on the configuration named by
-the benchmark's metric (configs[2]: Llama-3-8B shape, 128K context, b=32, budget 4096),
+slot top-k) followed by dsk_sparse_decode_attn -- on the configuration the headline metric is
+quoted on (Llama-3-8B layer shape, 128K context, b=32, budget 4096),
 cycling over 32 distinct queries.  Inputs are resident in HBM before the timed region; the
 K timed steps are captured in one HIP graph so that host launch cost is not what is timed.
 The compression pass (dsk_compress) is timed separately and reported in the same line, as

@@ -265,21 +265,35 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
   __shared__ float sm_l[kMergeGroups];
   __shared__ float sm_acc[kMergeGroups][DSK_HEAD_DIM];
   const int64_t sh = blockIdx.x;
-  int count = sel_count[sh];
-  if (count > k) count = k;
-  const int used = (count + slots_per_wg - 1) / slots_per_wg;
-  if (used <= 1) return;   // empty or single-chunk heads are complete already
   const int grp = threadIdx.x >> 4;
   const int c = threadIdx.x & 15;
   const float2* ml = part_ml + sh * nchunks;
   const float* acc = part_acc + sh * nchunks * DSK_HEAD_DIM + c * 8;
+  // first round of partials is fetched together with the count (the workspace always holds
+  // nchunks entries per head; stale ones are discarded below by index)
+  float2 v0 = make_float2(0.0f, 0.0f);
+  float4 x00 = make_float4(0.f, 0.f, 0.f, 0.f), x01 = x00;
+  if (grp < nchunks) {
+    v0 = ml[grp];
+    x00 = *reinterpret_cast<const float4*>(acc + (int64_t)grp * DSK_HEAD_DIM);
+    x01 = *reinterpret_cast<const float4*>(acc + (int64_t)grp * DSK_HEAD_DIM + 4);
+  }
+  int count = sel_count[sh];
+  if (count > k) count = k;
+  const int used = (count + slots_per_wg - 1) / slots_per_wg;
+  if (used <= 1) return;   // empty or single-chunk heads are complete already
   float m = -__builtin_inff(), l = 0.0f, a[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) a[i] = 0.0f;
   for (int ch = grp; ch < used; ch += kMergeGroups) {
-    const float2 v = ml[ch];
-    const float4 x0 = *reinterpret_cast<const float4*>(acc + (int64_t)ch * DSK_HEAD_DIM);
-    const float4 x1 = *reinterpret_cast<const float4*>(acc + (int64_t)ch * DSK_HEAD_DIM + 4);
+    float2 v;
+    float4 x0, x1;
+    if (ch == grp) { v = v0; x0 = x00; x1 = x01; }
+    else {
+      v = ml[ch];
+      x0 = *reinterpret_cast<const float4*>(acc + (int64_t)ch * DSK_HEAD_DIM);
+      x1 = *reinterpret_cast<const float4*>(acc + (int64_t)ch * DSK_HEAD_DIM + 4);
+    }
     if (v.x == -__builtin_inff()) continue;
     const float mn = fmaxf(m, v.x);
     const float fo = exp2f(m - mn), fn = exp2f(v.x - mn);   // m = -inf -> fo = 0

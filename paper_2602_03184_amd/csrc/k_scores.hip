@@ -68,6 +68,11 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
     kv[u] = *reinterpret_cast<const uint4*>(kh + (int64_t)i * (2 * DSK_HEAD_DIM));
   }
   int nblk = cu_blocks[B];
+  // queries of sequence 0 go out with the summaries (the only sequence when B == 1)
+  uint4 q0[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+    q0[g] = *reinterpret_cast<const uint4*>(q + ((int64_t)(hk * G + g)) * DSK_HEAD_DIM + d0);
 #pragma unroll
   for (int u = 0; u < NB; ++u) pin_loaded(kv[u]);
   if (nblk > bound) nblk = bound;
@@ -111,7 +116,8 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
   float qs[G][8];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    const uint4 qv = *reinterpret_cast<const uint4*>(q + ((int64_t)s_first * Hq + hk * G + g) * DSK_HEAD_DIM + d0);
+    uint4 qv = q0[g];
+    if (s_first != 0) qv = *reinterpret_cast<const uint4*>(q + ((int64_t)s_first * Hq + hk * G + g) * DSK_HEAD_DIM + d0);
     float f[8];
     unpack8(qv, f);
 #pragma unroll
