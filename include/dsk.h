@@ -107,7 +107,7 @@ typedef struct dsk_compress_args {
   /* KV cache, bf16; element strides; dim stride is 1.  V may be NULL when vsum is NULL. */
   const void* K;               /* [dev] K[h*k_stride_head + t*k_stride_tok + d] */
   const void* V;               /* [dev] */
-  int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head; /* multiples of 8 */
+  int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head; /* multiples of 8; token strides <= 2^24 */
 
   /* candidates */
   const int32_t* token_ids;    /* [dev] [total_tokens]            (stage CANDIDATES in) */

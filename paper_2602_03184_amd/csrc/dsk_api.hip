@@ -86,10 +86,12 @@ static dsk_status validate_compress(const dsk_compress_args* a) {
         a->k_stride_head < 0)
       return a->k_stride_tok < DSK_HEAD_DIM || a->k_stride_head < 0 ? DSK_ERR_SHAPE : DSK_ERR_ALIGN;
     if (a->Hkv > 1 && a->k_stride_head == 0) return DSK_ERR_SHAPE;
+    if (a->k_stride_tok > kMaxTokenStride) return DSK_ERR_SHAPE;
   }
   if (st_sum && a->vsum != nullptr) {
     if (!aligned16(a->V) || a->v_stride_tok % 8 || a->v_stride_head % 8) return DSK_ERR_ALIGN;
-    if (a->v_stride_tok < DSK_HEAD_DIM || a->v_stride_head < 0) return DSK_ERR_SHAPE;
+    if (a->v_stride_tok < DSK_HEAD_DIM || a->v_stride_head < 0 || a->v_stride_tok > kMaxTokenStride)
+      return DSK_ERR_SHAPE;
   }
   const CompressWs ws = compress_ws_layout(*a);
   if (st_cand || st_imp || st_seg) {

@@ -12,6 +12,7 @@ namespace dsk {
 
 constexpr int kSegTile = 2048;        // positions per DD-Select tile
 constexpr int kMaxChunkSpan = 8192;   // limit on C + delta
+constexpr int64_t kMaxTokenStride = 1 << 24;  // elements; keeps 32 rows of lane offsets in 32 bits
 constexpr int kCandTile = 1024;       // tokens per candidate-extraction tile
 constexpr int kMaxSamplesPerClass = 64;
 

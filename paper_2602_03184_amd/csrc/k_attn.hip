@@ -44,8 +44,7 @@ __device__ __forceinline__ void fold_loaded(WaveState& st, const float (&qf)[8],
     z[u] = (4 * u + g < nvalid) ? d : -__builtin_inff();
     mloc = fmaxf(mloc, z[u]);
   }
-  mloc = fmaxf(mloc, shfl_xor_f(mloc, 16));
-  mloc = fmaxf(mloc, shfl_xor_f(mloc, 32));
+  mloc = fmaxf(fmaxf(rows4_f(mloc, 0), rows4_f(mloc, 1)), fmaxf(rows4_f(mloc, 2), rows4_f(mloc, 3)));
   const float m_new = fmaxf(st.m, mloc);           // finite: nvalid >= 1
   const float alpha = exp2f(st.m - m_new);         // 0 on the first fold (st.m = -inf)
   st.l *= alpha;

@@ -81,17 +81,28 @@ __global__ __launch_bounds__(kCandThreads) void cand_scan_kernel(
     if (carry > max_cand) set_status(dev_status, DSK_ERR_CAPACITY);
   }
   __syncthreads();
-  for (int s = threadIdx.x; s <= B; s += kCandThreads) {
+  // candidate range of every sequence: exclusive count at its first token.  One wavefront per
+  // boundary; the partial tile in front of it is counted with all loads in flight.
+  const int lane = threadIdx.x & (DSK_WAVE - 1);
+  const int wave = threadIdx.x / DSK_WAVE;
+  for (int s = wave; s <= B; s += kCandWaves) {
     const int p = cu_seqlens[s];
     int c;
     if (p >= total_tokens || p < 0) {
       c = p < 0 ? 0 : carry;
     } else {
       const int tile = p / kCandTile;
-      c = tile_count[tile];
-      for (int t = tile * kCandTile; t < p; ++t) c += (cls_at[t] != 255);
+      const int t0 = tile * kCandTile;
+      int part = 0;
+#pragma unroll
+      for (int u = 0; u < kCandTile / DSK_WAVE; ++u) {
+        const int t = t0 + u * DSK_WAVE + lane;
+        const uint8_t cl = cls_at[t < p ? t : t0];           // t0 <= p < total_tokens: in bounds
+        part += (t < p && cl != 255) ? 1 : 0;
+      }
+      c = tile_count[tile] + wave_sum_i(part);
     }
-    cand_cu[s] = c;
+    if (lane == 0) cand_cu[s] = c;
   }
 }
 

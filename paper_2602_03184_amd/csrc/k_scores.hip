@@ -68,6 +68,7 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
     kv[u] = *reinterpret_cast<const uint4*>(kh + (int64_t)i * (2 * DSK_HEAD_DIM));
   }
   int nblk = cu_blocks[B];
+  int start_first = cu_blocks[1 + c < B ? 1 + c : B];      // sequence starts 1..32, fetched with the count
   // queries of sequence 0 go out with the summaries (the only sequence when B == 1)
   uint4 q0[G];
 #pragma unroll
@@ -77,11 +78,21 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
   for (int u = 0; u < NB; ++u) pin_loaded(kv[u]);
   if (nblk > bound) nblk = bound;
   if (i0 >= nblk) return;                     // whole half-waves leave together
-  // sequence of the group (blocks of a sequence are contiguous; a group rarely straddles two)
-  int s_first = 0;
-  while (s_first + 1 < B && cu_blocks[s_first + 1] <= i0) ++s_first;
+  // sequence of the group (blocks of a sequence are contiguous; a group rarely straddles two):
+  // number of sequence starts at or before i0, counted by the 32 lanes of the half-wave at once
   const int ilast = (i0 + NB - 1 < nblk) ? i0 + NB - 1 : nblk - 1;
-  const bool one_seq = (s_first + 1 >= B) || (cu_blocks[s_first + 1] > ilast);
+  int s_first = 0, s_last = 0;
+  for (int sb = 1; sb < B; sb += 32) {
+    const int sidx = sb + c;
+    int start = sb == 1 ? start_first : cu_blocks[sidx < B ? sidx : B];
+    if (sidx >= B) start = 0x7FFFFFFF;
+    const unsigned long long le_first = __ballot(start <= i0);
+    const unsigned long long le_last = __ballot(start <= ilast);
+    const int sh_ = (threadIdx.x & 32);                    // this half-wave's 32 bits of the ballot
+    s_first += __popcll((le_first >> sh_) & 0xFFFFFFFFull);
+    s_last += __popcll((le_last >> sh_) & 0xFFFFFFFFull);
+  }
+  const bool one_seq = s_first == s_last;
   if (!one_seq) {
     // slow path: per block, with its own sequence's query
     int s = s_first;

@@ -161,14 +161,9 @@ __device__ __noinline__ void select_big(
     kmax = key > kmax ? key : kmax;
     nslots += wi > 0 ? wi : 0;
   }
-#pragma unroll
-  for (int m = 1; m < DSK_WAVE; m <<= 1) {
-    const uint32_t o1 = (uint32_t)__shfl_xor((int)kmin, m, DSK_WAVE);
-    const uint32_t o2 = (uint32_t)__shfl_xor((int)kmax, m, DSK_WAVE);
-    kmin = o1 < kmin ? o1 : kmin;
-    kmax = o2 > kmax ? o2 : kmax;
-    nslots += __shfl_xor(nslots, m, DSK_WAVE);
-  }
+  kmin = wave_min_u(kmin);
+  kmax = wave_max_u(kmax);
+  nslots = wave_sum_i(nslots);
   if (lane == 0) { sh.red_min[wave] = kmin; sh.red_max[wave] = kmax; sh.red_sum[wave] = nslots; }
   if (tid < 256) sh.hist[tid] = 0;
   __syncthreads();
@@ -351,14 +346,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   }
   DSK_TS(1);
   // 1. workgroup reductions
-#pragma unroll
-  for (int m = 1; m < DSK_WAVE; m <<= 1) {
-    const uint32_t o1 = (uint32_t)__shfl_xor((int)kmin, m, DSK_WAVE);
-    const uint32_t o2 = (uint32_t)__shfl_xor((int)kmax, m, DSK_WAVE);
-    kmin = o1 < kmin ? o1 : kmin;
-    kmax = o2 > kmax ? o2 : kmax;
-    nslots += __shfl_xor(nslots, m, DSK_WAVE);
-  }
+  kmin = wave_min_u(kmin);
+  kmax = wave_max_u(kmax);
+  nslots = wave_sum_i(nslots);
   if (lane == 0) { sh.red_min[wave] = kmin; sh.red_max[wave] = kmax; sh.red_sum[wave] = nslots; }
   if (tid < 256) sh.hist[tid] = 0;
   if (tid == 0) sh.n_work = 0;

@@ -9,64 +9,89 @@ namespace dsk {
 
 constexpr int kSumThreads = 256;
 constexpr int kSumWaves = kSumThreads / DSK_WAVE;
-constexpr int kSumUnroll = 8;  // 8 row-groups of 4 rows = 32 rows in flight per wave
+#ifndef DSK_SUM_UNROLL
+#define DSK_SUM_UNROLL 8
+#endif
+constexpr int kSumUnroll = DSK_SUM_UNROLL;  // row-groups of 4 rows in flight per wave
+#ifdef DSK_SUM_WPE
+#define DSK_SUM_OCC __attribute__((amdgpu_waves_per_eu(DSK_SUM_WPE, DSK_SUM_WPE)))
+#else
+#define DSK_SUM_OCC
+#endif
 
-__global__ __launch_bounds__(kSumThreads) void summaries_kernel(
+// 8 waves per SIMD (32 per CU) so that one launch keeps every wave of the grid resident
+__global__ __launch_bounds__(kSumThreads) DSK_SUM_OCC void summaries_kernel(
     const uint16_t* __restrict__ X, int64_t stride_tok, int64_t stride_head, int Hkv,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ cu_blocks, int B,
     int cap, int total_tokens, uint16_t* __restrict__ out, int32_t* dev_status) {
   const int lane = threadIdx.x & (DSK_WAVE - 1);
-  const int wave = threadIdx.x / DSK_WAVE;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DSK_WAVE);   // wave-uniform: scalar registers
   const int g = lane >> 4;   // row group 0..3
   const int c = lane & 15;   // 16-byte column 0..15
   int nblk = cu_blocks[B];
   if (nblk > cap) nblk = cap;
   const int64_t items = (int64_t)Hkv * nblk;
   const int64_t nwaves = (int64_t)gridDim.x * kSumWaves;
-  for (int64_t item = (int64_t)blockIdx.x * kSumWaves + wave; item < items; item += nwaves) {
-    const int h = (int)(item / nblk);
-    const int i = (int)(item - (int64_t)h * nblk);
-    const int s = block_start[i];
-    const int e = block_start[i + 1];
+  int64_t item = (int64_t)blockIdx.x * kSumWaves + wave;
+  if (item >= items) return;
+  int h = (int)(item / nblk);
+  int i = (int)(item - (int64_t)h * nblk);
+  int s = __builtin_amdgcn_readfirstlane(block_start[i]);
+  int e = __builtin_amdgcn_readfirstlane(block_start[i + 1]);
+  const unsigned ustride = (unsigned)stride_tok;
+  for (;;) {
+    // the bounds of this wave's next item travel with the rows of the current one
+    const int64_t nitem = item + nwaves;
+    const int64_t pitem = nitem < items ? nitem : item;
+    const int nh = (int)(pitem / nblk);
+    const int ni = (int)(pitem - (int64_t)nh * nblk);
+    const int ns = __builtin_amdgcn_readfirstlane(block_start[ni]);
+    const int ne = __builtin_amdgcn_readfirstlane(block_start[ni + 1]);
     const int len = e - s;
     uint16_t* o = out + ((int64_t)h * cap + i) * (2 * DSK_HEAD_DIM);
     if (s < 0 || len <= 0 || e > total_tokens) {   // malformed table: defined output, flag it
       if (lane < 32) reinterpret_cast<uint4*>(o)[lane] = make_uint4(0, 0, 0, 0);
       if (lane == 0) set_status(dev_status, DSK_ERR_SHAPE);
-      continue;
-    }
-    const uint16_t* base = X + (int64_t)h * stride_head + (int64_t)s * stride_tok + c * 8;
-    float mn[8], mx[8];
+    } else {
+      const uint16_t* base = X + (int64_t)h * stride_head + (int64_t)s * stride_tok;   // uniform
+      float mn[8], mx[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) { mn[k] = __builtin_inff(); mx[k] = -__builtin_inff(); }
-    for (int r0 = 0; r0 < len; r0 += 4 * kSumUnroll) {
-      uint4 v[kSumUnroll];
+      for (int k = 0; k < 8; ++k) { mn[k] = __builtin_inff(); mx[k] = -__builtin_inff(); }
+      for (int r0 = 0; r0 < len; r0 += 4 * kSumUnroll) {
+        // scalar 64-bit base of this row batch + 32-bit lane offsets (stride_tok <= 2^24, host-checked)
+        const char* rb = reinterpret_cast<const char*>(base + (int64_t)r0 * stride_tok);
+        const int last = len - 1 - r0;
+        uint4 v[kSumUnroll];
 #pragma unroll
-      for (int u = 0; u < kSumUnroll; ++u) {
-        int r = r0 + 4 * u + g;
-        r = r < len ? r : len - 1;   // a repeated row changes neither min nor max
-        v[u] = *reinterpret_cast<const uint4*>(base + (int64_t)r * stride_tok);
+        for (int u = 0; u < kSumUnroll; ++u) {
+          int r = 4 * u + g;
+          r = r < last ? r : last;     // a repeated row changes neither min nor max
+          const unsigned byte_off = ((unsigned)r * ustride + (unsigned)(c * 8)) * 2u;
+          v[u] = *reinterpret_cast<const uint4*>(rb + byte_off);
+        }
+#pragma unroll
+        for (int u = 0; u < kSumUnroll; ++u) {
+          float f[8];
+          unpack8(v[u], f);
+#pragma unroll
+          for (int k = 0; k < 8; ++k) { mn[k] = fminf(mn[k], f[k]); mx[k] = fmaxf(mx[k], f[k]); }
+        }
       }
 #pragma unroll
-      for (int u = 0; u < kSumUnroll; ++u) {
-        float f[8];
-        unpack8(v[u], f);
-#pragma unroll
-        for (int k = 0; k < 8; ++k) { mn[k] = fminf(mn[k], f[k]); mx[k] = fmaxf(mx[k], f[k]); }
+      for (int k = 0; k < 8; ++k) {
+        mn[k] = fminf(mn[k], shfl_xor_f(mn[k], 16)); mx[k] = fmaxf(mx[k], shfl_xor_f(mx[k], 16));
+        mn[k] = fminf(mn[k], shfl_xor_f(mn[k], 32)); mx[k] = fmaxf(mx[k], shfl_xor_f(mx[k], 32));
+      }
+      if (g == 0) {
+        reinterpret_cast<uint4*>(o)[c] = make_uint4(pack_bf16_exact(mn[0], mn[1]), pack_bf16_exact(mn[2], mn[3]),
+                                                    pack_bf16_exact(mn[4], mn[5]), pack_bf16_exact(mn[6], mn[7]));
+      } else if (g == 1) {
+        reinterpret_cast<uint4*>(o)[16 + c] = make_uint4(pack_bf16_exact(mx[0], mx[1]), pack_bf16_exact(mx[2], mx[3]),
+                                                         pack_bf16_exact(mx[4], mx[5]), pack_bf16_exact(mx[6], mx[7]));
       }
     }
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      mn[k] = fminf(mn[k], shfl_xor_f(mn[k], 16)); mx[k] = fmaxf(mx[k], shfl_xor_f(mx[k], 16));
-      mn[k] = fminf(mn[k], shfl_xor_f(mn[k], 32)); mx[k] = fmaxf(mx[k], shfl_xor_f(mx[k], 32));
-    }
-    if (g == 0) {
-      reinterpret_cast<uint4*>(o)[c] = make_uint4(pack_bf16_exact(mn[0], mn[1]), pack_bf16_exact(mn[2], mn[3]),
-                                                  pack_bf16_exact(mn[4], mn[5]), pack_bf16_exact(mn[6], mn[7]));
-    } else if (g == 1) {
-      reinterpret_cast<uint4*>(o)[16 + c] = make_uint4(pack_bf16_exact(mx[0], mx[1]), pack_bf16_exact(mx[2], mx[3]),
-                                                       pack_bf16_exact(mx[4], mx[5]), pack_bf16_exact(mx[6], mx[7]));
-    }
+    if (nitem >= items) break;
+    item = nitem; h = nh; i = ni; s = ns; e = ne;
   }
 }
 
