@@ -58,8 +58,12 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
   const int i0 = (blockIdx.x * kHalvesPerWg + half) * NB;   // first block of this half-wave
   const uint16_t* kh = ksum + (int64_t)hk * cap * (2 * DSK_HEAD_DIM) + c * 8;
 
-  // `bound` (<= cap) is the host's upper bound on the block count: the loads are addressed
-  // without waiting for the device's count, all NB of them in flight together
+  // Sequence starts 1..32 and the block count go out first: loads return in order, so their
+  // values can be used while the summaries issued behind them are still in flight.
+  const int start_first = cu_blocks[1 + c < B ? 1 + c : B];
+  int nblk = cu_blocks[B];
+  // `bound` (<= cap) is the host's upper bound on the block count: the summary loads are
+  // addressed without waiting for the device's count, all NB of them in flight together
   uint4 kv[NB];
 #pragma unroll
   for (int u = 0; u < NB; ++u) {
@@ -67,93 +71,92 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
     i = i < bound ? i : bound - 1;            // past the end: re-read the last record, result dropped
     kv[u] = *reinterpret_cast<const uint4*>(kh + (int64_t)i * (2 * DSK_HEAD_DIM));
   }
-  int nblk = cu_blocks[B];
-  int start_first = cu_blocks[1 + c < B ? 1 + c : B];      // sequence starts 1..32, fetched with the count
-  // queries of sequence 0 go out with the summaries (the only sequence when B == 1)
-  uint4 q0[G];
+  if (nblk > bound) nblk = bound;
+  // sequence of the group (blocks of a sequence are contiguous; a group rarely straddles two):
+  // number of sequence starts at or before its first / last block, counted by the 32 lanes of
+  // the half-wave at once
+  const int ilast = (i0 + NB - 1 < nblk) ? i0 + NB - 1 : nblk - 1;
+  const int half_shift = threadIdx.x & 32;    // this half-wave's 32 bits of a ballot
+  int s_first, s_last;
+  {
+    const bool have = 1 + c < B;
+    s_first = __popcll((__ballot(have && start_first <= i0) >> half_shift) & 0xFFFFFFFFull);
+    s_last = __popcll((__ballot(have && start_first <= ilast) >> half_shift) & 0xFFFFFFFFull);
+  }
+  // queries of that sequence (exact when B <= 33; corrected below otherwise)
+  uint4 qv[G];
 #pragma unroll
   for (int g = 0; g < G; ++g)
-    q0[g] = *reinterpret_cast<const uint4*>(q + ((int64_t)(hk * G + g)) * DSK_HEAD_DIM + d0);
+    qv[g] = *reinterpret_cast<const uint4*>(q + ((int64_t)s_first * Hq + hk * G + g) * DSK_HEAD_DIM + d0);
 #pragma unroll
   for (int u = 0; u < NB; ++u) pin_loaded(kv[u]);
-  if (nblk > bound) nblk = bound;
-  if (i0 >= nblk) return;                     // whole half-waves leave together
-  // sequence of the group (blocks of a sequence are contiguous; a group rarely straddles two):
-  // number of sequence starts at or before i0, counted by the 32 lanes of the half-wave at once
-  const int ilast = (i0 + NB - 1 < nblk) ? i0 + NB - 1 : nblk - 1;
-  int s_first = 0, s_last = 0;
-  for (int sb = 1; sb < B; sb += 32) {
-    const int sidx = sb + c;
-    int start = sb == 1 ? start_first : cu_blocks[sidx < B ? sidx : B];
-    if (sidx >= B) start = 0x7FFFFFFF;
-    const unsigned long long le_first = __ballot(start <= i0);
-    const unsigned long long le_last = __ballot(start <= ilast);
-    const int sh_ = (threadIdx.x & 32);                    // this half-wave's 32 bits of the ballot
-    s_first += __popcll((le_first >> sh_) & 0xFFFFFFFFull);
-    s_last += __popcll((le_last >> sh_) & 0xFFFFFFFFull);
-  }
-  const bool one_seq = s_first == s_last;
-  if (!one_seq) {
-    // slow path: per block, with its own sequence's query
-    int s = s_first;
-    for (int u = 0; u < NB && i0 + u < nblk; ++u) {
-      const int i = i0 + u;
-      while (s + 1 < B && cu_blocks[s + 1] <= i) ++s;
-      const uint4 kvu = *reinterpret_cast<const uint4*>(kh + (int64_t)i * (2 * DSK_HEAD_DIM));
-      float f[8];
-      unpack8(kvu, f);
-      for (int g = 0; g < G; ++g) {
-        const uint4 qv = *reinterpret_cast<const uint4*>(q + ((int64_t)s * Hq + hk * G + g) * DSK_HEAD_DIM + d0);
-        float qf[8];
-        unpack8(qv, qf);
-        float acc = 0.0f;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) acc = fmaf(is_max ? fmaxf(qf[k], 0.0f) : fminf(qf[k], 0.0f), f[k], acc);
-        // same summation tree as the fast path: lane bits 16, 8, 4, 2, 1
-        acc += shfl_xor_f(acc, 16);
-        acc += shfl_xor_f(acc, 8);
-        acc += shfl_xor_f(acc, 4);
-        acc += shfl_xor_f(acc, 2);
-        acc += shfl_xor_f(acc, 1);
-        if (c == 0) {
-          scores[(int64_t)(hk * G + g) * stride + i] = acc;
-          if (user) user[(int64_t)(hk * G + g) * cap + i] = acc;
+  for (int g = 0; g < G; ++g) pin_loaded(qv[g]);
+  if (i0 >= nblk) return;                     // whole half-waves leave together
+  if (B > 33) {                               // more sequence starts than one ballot covers
+    const int s_before = s_first;
+    for (int sb = 33; sb < B; sb += 32) {
+      const int sidx = sb + c;
+      const int start = cu_blocks[sidx < B ? sidx : B];
+      const bool have = sidx < B;
+      s_first += __popcll((__ballot(have && start <= i0) >> half_shift) & 0xFFFFFFFFull);
+      s_last += __popcll((__ballot(have && start <= ilast) >> half_shift) & 0xFFFFFFFFull);
+    }
+    if (s_first != s_before) {
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+        qv[g] = *reinterpret_cast<const uint4*>(q + ((int64_t)s_first * Hq + hk * G + g) * DSK_HEAD_DIM + d0);
+    }
+  }
+  // One pass per sequence the group touches (nearly always one): the group's summaries stay in
+  // registers, only the queries change, and a pass writes the blocks of its own sequence.  The
+  // summation tree is the same in every pass, so a block's score does not depend on the batch
+  // it was computed in.
+  int s = s_first;
+  int cur = i0;                                // first block not yet written
+  for (;;) {
+    int seg_end = ilast + 1;
+    if (s != s_last) {                         // the sequence ends inside the group
+      seg_end = cu_blocks[s + 1];
+      seg_end = seg_end < ilast + 1 ? seg_end : ilast + 1;
+    }
+    if (seg_end > cur) {
+      float qs[G][8];
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float f[8];
+        unpack8(qv[g], f);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) qs[g][k] = is_max ? fmaxf(f[k], 0.0f) : fminf(f[k], 0.0f);
+      }
+      float v[V];
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        float f[8];
+        unpack8(kv[u], f);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float acc = 0.0f;
+#pragma unroll
+          for (int k = 0; k < 8; ++k) acc = fmaf(qs[g][k], f[k], acc);
+          v[u * G + g] = acc;
         }
       }
+      int idx = 0;
+      half_wave_reduce<V, V, 16>(v, c, idx);
+      const bool writer = (c & (32 / V - 1)) == 0;   // lanes differing only in non-halving bits hold copies
+      const int u = idx / G, g = idx % G;
+      if (writer && i0 + u >= cur && i0 + u < seg_end) {
+        scores[(int64_t)(hk * G + g) * stride + i0 + u] = v[0];
+        if (user) user[(int64_t)(hk * G + g) * cap + i0 + u] = v[0];
+      }
+      cur = seg_end;
     }
-    return;
-  }
-
-  float qs[G][8];
+    if (s == s_last) break;
+    ++s;
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    uint4 qv = q0[g];
-    if (s_first != 0) qv = *reinterpret_cast<const uint4*>(q + ((int64_t)s_first * Hq + hk * G + g) * DSK_HEAD_DIM + d0);
-    float f[8];
-    unpack8(qv, f);
-#pragma unroll
-    for (int k = 0; k < 8; ++k) qs[g][k] = is_max ? fmaxf(f[k], 0.0f) : fminf(f[k], 0.0f);
-  }
-  float v[V];
-#pragma unroll
-  for (int u = 0; u < NB; ++u) {
-    float f[8];
-    unpack8(kv[u], f);
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float acc = 0.0f;
-#pragma unroll
-      for (int k = 0; k < 8; ++k) acc = fmaf(qs[g][k], f[k], acc);
-      v[u * G + g] = acc;
-    }
-  }
-  int idx = 0;
-  half_wave_reduce<V, V, 16>(v, c, idx);
-  const bool writer = (c & (32 / V - 1)) == 0;   // lanes differing only in non-halving bits hold copies
-  const int u = idx / G, g = idx % G;
-  if (writer && i0 + u < nblk) {
-    scores[(int64_t)(hk * G + g) * stride + i0 + u] = v[0];
-    if (user) user[(int64_t)(hk * G + g) * cap + i0 + u] = v[0];
+    for (int g = 0; g < G; ++g)
+      qv[g] = *reinterpret_cast<const uint4*>(q + ((int64_t)s * Hq + hk * G + g) * DSK_HEAD_DIM + d0);
   }
 }
 
