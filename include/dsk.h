@@ -239,6 +239,23 @@ size_t dsk_compress_workspace_bytes(const dsk_compress_args* args);
 size_t dsk_select_workspace_bytes(const dsk_select_args* args);
 size_t dsk_attn_workspace_bytes(const dsk_attn_args* args);
 
+/* Where dsk_sparse_decode_attn leaves its split-K partials in args->workspace (what a caller
+ * that sets DSK_ATTN_PARTIALS_ONLY reads).  Chunk c of (sequence s, head h) covers the selected
+ * slots [c*slots_per_chunk, (c+1)*slots_per_chunk) and is valid for
+ * c < ceil(min(sel_count[s,h], k) / slots_per_chunk).  With p = (s*Hq + h)*nchunks + c:
+ *   (m, l)  = ((const float*)(workspace + ml_offset))[2p], [2p+1]   running max of the logits in
+ *             log2 units (logit * log2(e)), and sum of 2^(logit2 - m)
+ *   acc[d]  = ((const float*)(workspace + acc_offset))[p*D + d]      sum of 2^(logit2 - m) * V[d]
+ * The merged result is out = sum_c acc_c 2^(m_c - M) / sum_c l_c 2^(m_c - M), M = max_c m_c, and
+ * lse = ln(2) * M + ln(sum_c l_c 2^(m_c - M)) (App. B.2 Step 3, online-softmax split).
+ * When nchunks == 1 no partials are written: out / lse are final.  Returns DSK_ERR_SHAPE /
+ * DSK_ERR_NULL / DSK_ERR_VERSION on unusable arguments (only geometry fields are read). */
+typedef struct dsk_attn_partials {
+  size_t ml_offset, acc_offset;    /* bytes from args->workspace */
+  int32_t nchunks, slots_per_chunk;
+} dsk_attn_partials;
+dsk_status dsk_attn_partials_layout(const dsk_attn_args* args, dsk_attn_partials* layout);
+
 dsk_status dsk_compress(const dsk_compress_args* args, void* stream);
 dsk_status dsk_select_topk(const dsk_select_args* args, void* stream);
 dsk_status dsk_sparse_decode_attn(const dsk_attn_args* args, void* stream);

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libdsk.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
-        "libdsk.so is not built (%s). Run `python -m paper_2602_03184_amd.build` first; "
+        "libdsk.so is not built (%s). Run `python paper_2602_03184_amd/build.py` first; "
         "the DynSplit-KV path has no fallback implementation." % LIB_PATH)
 _lib = C.CDLL(LIB_PATH)
 
@@ -92,6 +92,13 @@ class dsk_attn_args(C.Structure):
     ]
 
 
+class dsk_attn_partials(C.Structure):
+    _fields_ = [
+        ("ml_offset", C.c_size_t), ("acc_offset", C.c_size_t),
+        ("nchunks", C.c_int32), ("slots_per_chunk", C.c_int32),
+    ]
+
+
 _lib.dsk_version.restype = C.c_uint32
 _lib.dsk_version.argtypes = []
 _lib.dsk_strerror.restype = C.c_char_p
@@ -102,6 +109,8 @@ for _name, _cls in (("compress", dsk_compress_args), ("select", dsk_select_args)
     _f = getattr(_lib, "dsk_%s_workspace_bytes" % _name)
     _f.restype = C.c_size_t
     _f.argtypes = [C.POINTER(_cls)]
+_lib.dsk_attn_partials_layout.restype = C.c_int32
+_lib.dsk_attn_partials_layout.argtypes = [C.POINTER(dsk_attn_args), C.POINTER(dsk_attn_partials)]
 _lib.dsk_compress.restype = C.c_int32
 _lib.dsk_compress.argtypes = [C.POINTER(dsk_compress_args), _p]
 _lib.dsk_select_topk.restype = C.c_int32
@@ -139,6 +148,14 @@ def dsk_select_workspace_bytes(args: dsk_select_args) -> int:
 
 def dsk_attn_workspace_bytes(args: dsk_attn_args) -> int:
     return int(_lib.dsk_attn_workspace_bytes(C.byref(args)))
+
+
+def dsk_attn_partials_layout(args: dsk_attn_args) -> dsk_attn_partials:
+    lay = dsk_attn_partials()
+    status = int(_lib.dsk_attn_partials_layout(C.byref(args), C.byref(lay)))
+    if status != DSK_OK:
+        raise DskError(status, "dsk_attn_partials_layout")
+    return lay
 
 
 def _stream_handle(stream) -> Optional[int]:

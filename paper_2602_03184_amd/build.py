@@ -1,6 +1,6 @@
 """Builds libdsk.so (the HIP kernels + C ABI) in-tree for gfx950 with hipcc.
 
-    python -m paper_2602_03184_amd.build
+    python paper_2602_03184_amd/build.py
 
 Objects go to paper_2602_03184_amd/_build/, the library to paper_2602_03184_amd/libdsk.so.
 """

@@ -184,6 +184,18 @@ size_t dsk_attn_workspace_bytes(const dsk_attn_args* a) {
   return attn_ws_layout(*a).total;
 }
 
+dsk_status dsk_attn_partials_layout(const dsk_attn_args* a, dsk_attn_partials* out) {
+  if (a == nullptr || out == nullptr) return DSK_ERR_NULL;
+  if (a->struct_size != sizeof(dsk_attn_args)) return DSK_ERR_VERSION;
+  if (a->B < 1 || a->Hq < 1 || a->k < 1 || a->b < 1) return DSK_ERR_SHAPE;
+  const AttnWs ws = attn_ws_layout(*a);
+  out->ml_offset = ws.part_ml;
+  out->acc_offset = ws.part_acc;
+  out->nchunks = ws.nchunks;
+  out->slots_per_chunk = ws.slots_per_wg;
+  return DSK_OK;
+}
+
 dsk_status dsk_compress(const dsk_compress_args* a, void* stream) {
   const dsk_status v = validate_compress(a);
   if (v != DSK_OK) return v;

@@ -47,21 +47,20 @@ def _seqs_to_check(cfg):
     return list(range(cfg.B)) if cfg.B <= 2 else [0, cfg.B // 2, cfg.B - 1]
 
 
-@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5])
-def test_select_and_attention_parity(cfg_id):
+def _check_decode(case, n_q, seqs, heads, label, **select_kw):
+    """Scores, slot sets, spans and attention of the GPU path against the oracle for the given
+    sequences and query heads."""
     dsk = _dsk()
-    case = gpu_case(cfg_id)
     cfg, seg, wl = case.cfg, case.seg, case.wl
     comp = case.compressed()
     sums = bf16_bits_of(comp.ksum)
     kmin_bits, kmax_bits = sums[:, :, 0], sums[:, :, 1]
-    n_q = min(cfg.n_queries, 3)
     swapped_total = 0
     worst_attn = 0.0
     for qi in range(n_q):
         q_bits = wl.q[qi]                                   # [B, Hq, D]
         q = dev_bf16(q_bits)
-        sel = dsk.select_topk(comp, q, cfg.T, want_scores=True)
+        sel = dsk.select_topk(comp, q, cfg.T, want_scores=True, **select_kw)
         att = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b)
         torch.cuda.synchronize()
         g_slot = sel.sel_slot.cpu().numpy()
@@ -71,11 +70,14 @@ def test_select_and_attention_parity(cfg_id):
         g_scores = sel.scores.cpu().numpy()
         g_out = att.out.cpu().numpy()
         g_lse = att.lse.cpu().numpy()
-        for s in _seqs_to_check(cfg):
+        for s in seqs:
             b0, b1 = int(seg.cu_blocks[s]), int(seg.cu_blocks[s + 1])
             sb = seg.slot_base[b0: b1 + 1]
             bs = seg.block_start[b0: b1 + 1]
-            heads = _heads_to_check(cfg)
+            if b1 == b0:                                    # empty sequence: defined empty result
+                assert (g_cnt[s] == 0).all() and (g_slot[s] == -1).all()
+                assert (g_out[s] == 0).all() and np.isneginf(g_lse[s]).all()
+                continue
             osc = _oracle_scores(case, kmin_bits, kmax_bits, q_bits, s, heads)
             for h in heads:
                 # a6: fp32 scores against fp64
@@ -104,8 +106,49 @@ def test_select_and_attention_parity(cfg_id):
                 worst_attn = max(worst_attn, e)
                 assert e <= ATTN_TOL, (s, h, e)
                 assert abs(float(g_lse[s, h]) - lse) <= LSE_TOL
-    print("cfg%d: swapped selections (near ties) = %d, worst attention rel err = %.3e" %
-          (cfg_id, swapped_total, worst_attn))
+    print("%s: swapped selections (near ties) = %d, worst attention rel err = %.3e" %
+          (label, swapped_total, worst_attn))
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5])
+def test_select_and_attention_parity(cfg_id):
+    case = gpu_case(cfg_id)
+    cfg = case.cfg
+    _check_decode(case, min(cfg.n_queries, 3), _seqs_to_check(cfg), _heads_to_check(cfg), "cfg%d" % cfg_id)
+
+
+def test_many_short_sequences_share_score_groups():
+    """40 ragged sequences of a few blocks each (two of them empty, one of a single token): the
+    groups of consecutive blocks that the score kernel handles together straddle up to several
+    sequences, and there are more sequence starts than one wavefront ballot covers."""
+    rng = np.random.default_rng(7)
+    seqlens = [int(x) for x in rng.integers(20, 400, size=40)]
+    seqlens[5] = 0
+    seqlens[6] = 0
+    seqlens[17] = 1
+    seqlens[39] = 3000
+    case = gpu_case(5, B=40, seqlens=seqlens, T=128, n_queries=2)
+    _check_decode(case, 2, list(range(40)), [0, 3, 4, 17, 31], "40 short sequences")
+
+
+def test_block_count_hint_does_not_change_results():
+    """max_blocks_used (a host-side upper bound that only sizes the score launch) must leave every
+    output bit-identical, whether exact, loose or absent."""
+    dsk = _dsk()
+    case = gpu_case(5)
+    cfg = case.cfg
+    comp = case.compressed()
+    nblk = int(comp.cu_blocks.cpu()[-1])
+    q = dev_bf16(case.wl.q[0])
+    ref = dsk.select_topk(comp, q, cfg.T, want_scores=True)
+    torch.cuda.synchronize()
+    for hint in (nblk, nblk + 1000):
+        got = dsk.select_topk(comp, q, cfg.T, want_scores=True, max_blocks_used=hint)
+        torch.cuda.synchronize()
+        for name in ("sel_slot", "sel_start", "sel_len", "sel_count"):
+            assert torch.equal(getattr(ref, name), getattr(got, name)), (hint, name)
+        assert torch.equal(ref.scores[:, :nblk], got.scores[:, :nblk])
+    _check_decode(case, 1, [0, cfg.B - 1], [0, cfg.Hq - 1], "cfg5 with block-count hint", max_blocks_used=nblk)
 
 
 @pytest.mark.parametrize("cfg_id", [1, 2])
@@ -294,3 +337,45 @@ def test_sequences_with_more_blocks_than_the_register_tile():
             o, lse = O.sparse_attention(O.widen_bf16(q_bits[0, h]), O.widen_bf16(wl.K[0]), O.widen_bf16(wl.V[0]),
                                         toks, DEFAULT_SCALE)
             assert rel_err(att.out.cpu().numpy()[0, h], o) <= ATTN_TOL
+
+
+def test_partials_only_leaves_mergeable_partials():
+    """With DSK_ATTN_PARTIALS_ONLY the call stops after the per-chunk partials; merging them on
+    the host by the documented formula must reproduce the library's own merged output (and
+    hence the oracle's), and the layout query must describe where they are."""
+    dsk = _dsk()
+    case = gpu_case(2)
+    cfg, wl = case.cfg, case.wl
+    comp = case.compressed()
+    q = dev_bf16(wl.q[0])
+    sel = dsk.select_topk(comp, q, cfg.T)
+    full = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b)
+    torch.cuda.synchronize()
+    part = dsk.make_attn_args(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b,
+                              flags=dsk.DSK_ATTN_PARTIALS_ONLY)
+    part.out.fill_(7.0)
+    dsk.dsk_sparse_decode_attn(part.args)
+    torch.cuda.synchronize()
+    lay = dsk.dsk_attn_partials_layout(part.args)
+    assert lay.nchunks == -(-cfg.k // lay.slots_per_chunk) and lay.nchunks > 1
+    assert float(part.out.min().item()) == 7.0            # untouched: every head needs a merge here
+    ws = part.keep[-1]                                    # the workspace tensor made by the binding
+    assert ws.data_ptr() == int(part.args.workspace)
+    raw = ws.view(torch.uint8).cpu().numpy()[:int(part.args.workspace_bytes)]
+    n = cfg.B * cfg.Hq * lay.nchunks
+    ml = raw[lay.ml_offset: lay.ml_offset + n * 8].view(np.float32).reshape(cfg.B, cfg.Hq, lay.nchunks, 2)
+    acc = raw[lay.acc_offset: lay.acc_offset + n * 128 * 4].view(np.float32).reshape(cfg.B, cfg.Hq, lay.nchunks, 128)
+    cnt = sel.sel_count.cpu().numpy()
+    want_out = full.out.cpu().numpy()
+    want_lse = full.lse.cpu().numpy()
+    for s in range(cfg.B):
+        for h in range(cfg.Hq):
+            used = -(-min(int(cnt[s, h]), cfg.k) // lay.slots_per_chunk)
+            m = ml[s, h, :used, 0].astype(np.float64)
+            l = ml[s, h, :used, 1].astype(np.float64)
+            M = m.max()
+            wgt = np.exp2(m - M)
+            den = float((l * wgt).sum())
+            out = (acc[s, h, :used].astype(np.float64) * wgt[:, None]).sum(axis=0) / den
+            assert rel_err(want_out[s, h], out) <= 1e-5
+            assert abs(float(want_lse[s, h]) - (math.log(2.0) * M + math.log(den))) <= 1e-4

@@ -48,6 +48,12 @@ def test_sample_candidates_first_M_in_range():
     np.testing.assert_array_equal(samp, [[10, 20], [95, -1], [-1, -1]])
     samp = O.sample_candidates(pos, cls, n_class=3, M=2, R=8, W=5, L=100)   # t <= 94
     np.testing.assert_array_equal(samp[1], [-1, -1])
+    # both edges are inclusive: t = R has a full retained region {1..R} behind it and a
+    # non-empty discarded region {0}; t = L-1-W has its last window query at position L-1
+    pos = np.asarray([7, 8, 95, 96])
+    cls = np.asarray([0, 0, 0, 0])
+    samp = O.sample_candidates(pos, cls, n_class=1, M=4, R=8, W=4, L=100)
+    np.testing.assert_array_equal(samp, [[8, 95, -1, -1]])
 
 
 # ---------------------------------------------------------------- Alg. 1
