@@ -40,6 +40,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold-instances", type=int, default=16,
+                    help="copies of the cache (K, V, summaries) the cold-cache measurement rotates over; 0 = skip")
+    ap.add_argument("--stream-read-mib", type=int, default=2048,
+                    help="size of the buffer the streaming-read reference reads; 0 = skip")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (reference dispatch for rocprofv3 "
                          "--pmc FETCH_SIZE / WRITE_SIZE scaling)")
@@ -187,6 +191,71 @@ def main():
         g_sel.replay()
         stream.synchronize()
         select_us = event_ms(g_sel.replay, stream) * 1e3 / args.steps
+
+        # ---- streaming-read reference: what a plain coalesced read reaches on this device ------
+        stream_read_gbs = None
+        if args.stream_read_mib > 0:
+            big = torch.empty(args.stream_read_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+            sink = torch.zeros(1, dtype=torch.int32, device=dev)
+            stream.wait_stream(torch.cuda.current_stream())
+            for _ in range(2):
+                dsk.dsk_stream_read_probe(big, stream, sink)
+            reps = 10
+            ms = event_ms(lambda: [dsk.dsk_stream_read_probe(big, stream, sink) for _ in range(reps)], stream) / reps
+            stream_read_gbs = big.numel() / (ms * 1e-3) / 1e9
+            del big
+            torch.cuda.empty_cache()
+
+        # ---- cold caches: rotate over N copies of (K, V, summaries) so that no step finds the data
+        #      of an earlier one in L2 or the memory-side cache; block tables are shared ----------
+        cold = None
+        if args.cold_instances > 1:
+            n_inst = args.cold_instances
+            Ks = [K] + [K.clone() for _ in range(n_inst - 1)]
+            Vs = [V] + [V.clone() for _ in range(n_inst - 1)]
+            ksums = [comp.ksum] + [comp.ksum.clone() for _ in range(n_inst - 1)]
+            torch.cuda.synchronize()
+            csel, catt, cgat = [], [], []
+            n_cold = max(nq, n_inst)
+            for i in range(n_cold):
+                inst = i % n_inst
+                sa = dsk.make_select_args(comp, queries[i % nq], cfg.T, out=sels[0], max_blocks_used=nblk)
+                sa.args.ksum = ksums[inst].data_ptr()
+                csel.append(sa)
+                catt.append(dsk.make_attn_args(queries[i % nq], Ks[inst], Vs[inst], sels[0].sel_start, sels[0].sel_len,
+                                               sels[0].sel_count, cfg.b, out=atts[0]))
+                cgat.append(dsk.make_attn_args(queries[i % nq], Ks[inst], Vs[inst], sels[0].sel_start, sels[0].sel_len,
+                                               sels[0].sel_count, cfg.b, out=atts[0], flags=dsk.DSK_ATTN_PARTIALS_ONLY))
+
+            def cold_step(i):
+                dsk.dsk_select_topk(csel[i % n_cold].args, stream)
+                dsk.dsk_sparse_decode_attn(catt[i % n_cold].args, stream)
+
+            g_cold = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_cold, stream=stream):
+                for i in range(args.steps):
+                    cold_step(i)
+            g_cold.replay()
+            stream.synchronize()
+            cold_us = event_ms(g_cold.replay, stream) * 1e3 / args.steps
+            # gather alone, cold: each launch follows the selection of its own step's query, so run
+            # select (untimed share subtracted) is not possible inside one graph; time gather-only
+            # launches on the rotating copies with the last selection instead
+            g_cg = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_cg, stream=stream):
+                for i in range(args.steps):
+                    dsk.dsk_sparse_decode_attn(cgat[i % n_cold].args, stream)
+            g_cg.replay()
+            stream.synchronize()
+            cold_gather_us = event_ms(g_cg.replay, stream) * 1e3 / args.steps
+            last_sel_bytes = float(sels[0].sel_len.sum().item()) * 512
+            cold = {"instances": n_inst, "cache_bytes_per_instance": int(2 * K.numel() * 2 + comp.ksum.numel() * 2),
+                    "us_per_step": round(cold_us, 3),
+                    "gather_us": round(cold_gather_us, 3),
+                    "gather_GBps": round(last_sel_bytes / (cold_gather_us * 1e-6) / 1e9, 1),
+                    "gather_frac": round(last_sel_bytes / (cold_gather_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+            del Ks, Vs, ksums, csel, catt, cgat, g_cold, g_cg
+            torch.cuda.empty_cache()
     torch.cuda.synchronize()
 
     attn_gbs = bytes_attn / (gather_us * 1e-6) / 1e9
@@ -226,6 +295,13 @@ def main():
                      "step_frac": round(step_gbs / HBM_PEAK_GBS, 4)},
         "workload_gen_s": round(gen_s, 1),
     }
+    if stream_read_gbs is not None:
+        out["stream_read"] = {"GBps": round(stream_read_gbs, 1), "mib": args.stream_read_mib,
+                              "gather_frac_of_stream_read": round(attn_gbs / stream_read_gbs, 4),
+                              "compress_frac_of_stream_read":
+                                  round(compress_bytes / (compress_ms * 1e-3) / 1e9 / stream_read_gbs, 4)}
+    if cold is not None:
+        out["cold"] = cold
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, comp, nblk)
     print(json.dumps(out))

@@ -256,6 +256,14 @@ typedef struct dsk_attn_partials {
 } dsk_attn_partials;
 dsk_status dsk_attn_partials_layout(const dsk_attn_args* args, dsk_attn_partials* layout);
 
+/* Measurement aid, no part of the method: reads the `bytes` (rounded down to a multiple of 16)
+ * at device pointer `buf` (16-byte aligned) exactly once with coalesced 16-byte loads on
+ * `stream`.  Timed by the caller, it gives the streaming-read rate of the device, the practical
+ * ceiling next to which the HBM-bound kernels here are reported.  `sink` is a device word (or
+ * NULL) that the kernel may write; nothing else is modified.  Errors: DSK_ERR_NULL (buf),
+ * DSK_ERR_ALIGN, DSK_ERR_LAUNCH. */
+dsk_status dsk_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
+
 dsk_status dsk_compress(const dsk_compress_args* args, void* stream);
 dsk_status dsk_select_topk(const dsk_select_args* args, void* stream);
 dsk_status dsk_sparse_decode_attn(const dsk_attn_args* args, void* stream);

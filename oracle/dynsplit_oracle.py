@@ -266,3 +266,24 @@ def sparse_attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, tokens: np.nda
     den = p.sum()
     o = (p[:, None] * V[tokens]).sum(axis=0) / den
     return o, float(m + math.log(den))
+
+
+# ----------------------------------------------------------------------------
+# Full attention over the whole cache (the full-KV baseline of Sec. 5, GPU
+# Inference analysis, Figure 8) -- the definition, written out
+# ----------------------------------------------------------------------------
+def dense_attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float) -> Tuple[np.ndarray, float]:
+    """One head, one decode query: A_t = exp(q.K_t * scale) / sum_u exp(q.K_u * scale) over
+    every token t of the sequence, o = sum_t A_t V_t, lse = log sum_t exp(q.K_t * scale).
+    q[D], K[L,D], V[L,D]; L >= 1."""
+    L = K.shape[0]
+    z = np.empty(L, dtype=np.float64)
+    for t in range(L):
+        z[t] = float(np.dot(q, K[t])) * scale
+    zmax = float(z.max())
+    w = np.exp(z - zmax)
+    den = float(w.sum())
+    o = np.zeros(V.shape[1], dtype=np.float64)
+    for t in range(L):
+        o += (w[t] / den) * V[t]
+    return o, zmax + math.log(den)

@@ -111,6 +111,8 @@ for _name, _cls in (("compress", dsk_compress_args), ("select", dsk_select_args)
     _f.argtypes = [C.POINTER(_cls)]
 _lib.dsk_attn_partials_layout.restype = C.c_int32
 _lib.dsk_attn_partials_layout.argtypes = [C.POINTER(dsk_attn_args), C.POINTER(dsk_attn_partials)]
+_lib.dsk_stream_read_probe.restype = C.c_int32
+_lib.dsk_stream_read_probe.argtypes = [_p, C.c_size_t, _p, _p]
 _lib.dsk_compress.restype = C.c_int32
 _lib.dsk_compress.argtypes = [C.POINTER(dsk_compress_args), _p]
 _lib.dsk_select_topk.restype = C.c_int32
@@ -148,6 +150,14 @@ def dsk_select_workspace_bytes(args: dsk_select_args) -> int:
 
 def dsk_attn_workspace_bytes(args: dsk_attn_args) -> int:
     return int(_lib.dsk_attn_workspace_bytes(C.byref(args)))
+
+
+def dsk_stream_read_probe(buf: torch.Tensor, stream=None, sink: Optional[torch.Tensor] = None) -> None:
+    """Enqueue one streaming read of the whole tensor (a measurement aid; see include/dsk.h)."""
+    status = int(_lib.dsk_stream_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink),
+                                            _stream_handle(stream)))
+    if status != DSK_OK:
+        raise DskError(status, "dsk_stream_read_probe")
 
 
 def dsk_attn_partials_layout(args: dsk_attn_args) -> dsk_attn_partials:

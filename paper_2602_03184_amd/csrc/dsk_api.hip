@@ -184,6 +184,14 @@ size_t dsk_attn_workspace_bytes(const dsk_attn_args* a) {
   return attn_ws_layout(*a).total;
 }
 
+dsk_status dsk_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (buf == nullptr) return DSK_ERR_NULL;
+  if (!aligned16(buf) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return DSK_ERR_ALIGN;
+  if (launch_stream_read(buf, bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream)) != hipSuccess)
+    return DSK_ERR_LAUNCH;
+  return DSK_OK;
+}
+
 dsk_status dsk_attn_partials_layout(const dsk_attn_args* a, dsk_attn_partials* out) {
   if (a == nullptr || out == nullptr) return DSK_ERR_NULL;
   if (a->struct_size != sizeof(dsk_attn_args)) return DSK_ERR_VERSION;

@@ -55,5 +55,6 @@ struct AttnWs {
 };
 AttnWs attn_ws_layout(const dsk_attn_args& a);
 hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st);
+hipError_t launch_stream_read(const void* buf, size_t bytes, uint32_t* sink, hipStream_t st);
 
 }  // namespace dsk

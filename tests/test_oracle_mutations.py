@@ -65,6 +65,11 @@ MUTANTS = [
     ("attention_scale_dropped", "z = (K[tokens] @ q) * scale", "z = (K[tokens] @ q)"),
     ("attention_values_are_keys", "o = (p[:, None] * V[tokens]).sum(axis=0) / den", "o = (p[:, None] * K[tokens]).sum(axis=0) / den"),
     ("attention_not_normalised", "o = (p[:, None] * V[tokens]).sum(axis=0) / den", "o = (p[:, None] * V[tokens]).sum(axis=0)"),
+    ("dense_scale_dropped", "z[t] = float(np.dot(q, K[t])) * scale", "z[t] = float(np.dot(q, K[t]))"),
+    ("dense_values_are_keys", "o += (w[t] / den) * V[t]", "o += (w[t] / den) * K[t]"),
+    ("dense_not_normalised", "o += (w[t] / den) * V[t]", "o += w[t] * V[t]"),
+    ("dense_lse_forgets_max", "return o, zmax + math.log(den)", "return o, math.log(den)"),
+    ("dense_skips_last_token", "for t in range(L):\n        o +=", "for t in range(L - 1):\n        o +="),
     ("lse_forgets_max", "return o, float(m + math.log(den))", "return o, float(math.log(den))"),
 ]
 

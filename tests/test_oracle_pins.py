@@ -404,6 +404,36 @@ def test_attention_budget_all_equals_dense_sdpa():
     assert lse == pytest.approx(float(torch.logsumexp(torch.from_numpy(K @ q) * scale, 0)), abs=1e-12)
 
 
+def test_dense_attention_is_sdpa_and_its_closed_forms():
+    r = rng(21)
+    L, D = 193, 16
+    q, K, V = r.standard_normal(D), r.standard_normal((L, D)), r.standard_normal((L, D))
+    scale = 0.37
+    o, lse = O.dense_attention(q, K, V, scale)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[None, None, None], torch.from_numpy(K)[None, None],
+        torch.from_numpy(V)[None, None], scale=scale)[0, 0, 0].numpy()
+    np.testing.assert_allclose(o, ref, atol=1e-12)
+    assert lse == pytest.approx(float(torch.logsumexp(torch.from_numpy(K @ q) * scale, 0)), abs=1e-12)
+    # the sparse path with every token selected is the same function
+    o2, lse2 = O.sparse_attention(q, K, V, np.arange(L), scale)
+    np.testing.assert_allclose(o, o2, atol=1e-13)
+    assert lse == pytest.approx(lse2, abs=1e-12)
+    # one token: its V row; identical keys: the mean of V, lse = z + log L
+    o, lse = O.dense_attention(q, K[:1], V[:1], scale)
+    np.testing.assert_allclose(o, V[0], atol=1e-15)
+    assert lse == pytest.approx(float(K[0] @ q) * scale)
+    Kc = np.tile(K[3], (L, 1))
+    o, lse = O.dense_attention(q, Kc, V, scale)
+    np.testing.assert_allclose(o, V.mean(axis=0), atol=1e-13)
+    assert lse == pytest.approx(float(K[3] @ q) * scale + math.log(L))
+    # one key far ahead of the rest: the output is that token's V row
+    Kp = K.copy()
+    Kp[77] = 200.0 * q / (q @ q) / scale + 0.0        # logit 200 above a field of O(1) logits
+    o, _ = O.dense_attention(q, Kp, V, scale)
+    np.testing.assert_allclose(o, V[77], atol=1e-12)
+
+
 def test_attention_special_cases():
     r = rng(13)
     L, D = 50, 8
