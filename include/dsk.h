@@ -223,6 +223,34 @@ typedef struct dsk_attn_args {
   size_t workspace_bytes;
 } dsk_attn_args;
 
+/* ------------------------------------------------------------------------------------------
+ * dsk_dense_decode_attn -- full attention of one decode query per (sequence, head) over the
+ * WHOLE cache: out = softmax(q K^T scale) V over every token of the sequence.  This is the
+ * full-KV baseline the method is compared with (Sec. 5, GPU Inference analysis, Figure 8), on
+ * the same device and the same K/V layout, so that a decode step of the sparse path can be set
+ * against it.  The heads of a GQA group share one pass over their K/V rows (every K/V byte is
+ * read once per call when Hq/Hkv is 1, 2 or 4; twice for 8; other ratios read it Hq/Hkv times).
+ * bf16 inputs, fp32 accumulation, split over tokens with an online-softmax merge in a fixed
+ * order.  A sequence of length 0 gets out = 0 and lse = -inf.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct dsk_dense_attn_args {
+  uint32_t struct_size;
+  int32_t B, Hq, Hkv, D;
+  const void* q;               /* [dev] bf16 [B, Hq, D] */
+  const void* K;               /* [dev] bf16, strides as in dsk_compress_args */
+  const void* V;               /* [dev] */
+  int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;
+  int32_t total_tokens;        /* [host] tokens per head in K/V; cu_seqlens[B] must not exceed it */
+  int32_t max_seqlen;          /* [host] upper bound of the sequence lengths (sizes the split) */
+  const int32_t* cu_seqlens;   /* [dev] [B+1] */
+  float scale;                 /* 0 -> D^-1/2 */
+  uint32_t flags;              /* must be 0 */
+  float* out;                  /* [dev] f32 [B, Hq, D] */
+  float* lse;                  /* [dev] f32 [B, Hq], natural log; may be NULL */
+  void* workspace;             /* [dev] 256-byte aligned */
+  size_t workspace_bytes;
+} dsk_dense_attn_args;
+
 /* Library / ABI version (DSK_ABI_VERSION of the build). */
 uint32_t dsk_version(void);
 
@@ -238,6 +266,7 @@ int64_t dsk_block_capacity(int32_t total_tokens, int32_t B, int32_t min_chunk);
 size_t dsk_compress_workspace_bytes(const dsk_compress_args* args);
 size_t dsk_select_workspace_bytes(const dsk_select_args* args);
 size_t dsk_attn_workspace_bytes(const dsk_attn_args* args);
+size_t dsk_dense_attn_workspace_bytes(const dsk_dense_attn_args* args);
 
 /* Where dsk_sparse_decode_attn leaves its split-K partials in args->workspace (what a caller
  * that sets DSK_ATTN_PARTIALS_ONLY reads).  Chunk c of (sequence s, head h) covers the selected
@@ -267,6 +296,7 @@ dsk_status dsk_stream_read_probe(const void* buf, size_t bytes, void* sink, void
 dsk_status dsk_compress(const dsk_compress_args* args, void* stream);
 dsk_status dsk_select_topk(const dsk_select_args* args, void* stream);
 dsk_status dsk_sparse_decode_attn(const dsk_attn_args* args, void* stream);
+dsk_status dsk_dense_decode_attn(const dsk_dense_attn_args* args, void* stream);
 
 #ifdef __cplusplus
 }

@@ -92,6 +92,21 @@ class dsk_attn_args(C.Structure):
     ]
 
 
+class dsk_dense_attn_args(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+        ("q", _p), ("K", _p), ("V", _p),
+        ("k_stride_tok", C.c_int64), ("k_stride_head", C.c_int64),
+        ("v_stride_tok", C.c_int64), ("v_stride_head", C.c_int64),
+        ("total_tokens", C.c_int32), ("max_seqlen", C.c_int32),
+        ("cu_seqlens", _p),
+        ("scale", C.c_float), ("flags", C.c_uint32),
+        ("out", _p), ("lse", _p),
+        ("workspace", _p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
 class dsk_attn_partials(C.Structure):
     _fields_ = [
         ("ml_offset", C.c_size_t), ("acc_offset", C.c_size_t),
@@ -105,12 +120,15 @@ _lib.dsk_strerror.restype = C.c_char_p
 _lib.dsk_strerror.argtypes = [C.c_int32]
 _lib.dsk_block_capacity.restype = C.c_int64
 _lib.dsk_block_capacity.argtypes = [C.c_int32, C.c_int32, C.c_int32]
-for _name, _cls in (("compress", dsk_compress_args), ("select", dsk_select_args), ("attn", dsk_attn_args)):
+for _name, _cls in (("compress", dsk_compress_args), ("select", dsk_select_args), ("attn", dsk_attn_args),
+                    ("dense_attn", dsk_dense_attn_args)):
     _f = getattr(_lib, "dsk_%s_workspace_bytes" % _name)
     _f.restype = C.c_size_t
     _f.argtypes = [C.POINTER(_cls)]
 _lib.dsk_attn_partials_layout.restype = C.c_int32
 _lib.dsk_attn_partials_layout.argtypes = [C.POINTER(dsk_attn_args), C.POINTER(dsk_attn_partials)]
+_lib.dsk_dense_decode_attn.restype = C.c_int32
+_lib.dsk_dense_decode_attn.argtypes = [C.POINTER(dsk_dense_attn_args), _p]
 _lib.dsk_stream_read_probe.restype = C.c_int32
 _lib.dsk_stream_read_probe.argtypes = [_p, C.c_size_t, _p, _p]
 _lib.dsk_compress.restype = C.c_int32
@@ -150,6 +168,17 @@ def dsk_select_workspace_bytes(args: dsk_select_args) -> int:
 
 def dsk_attn_workspace_bytes(args: dsk_attn_args) -> int:
     return int(_lib.dsk_attn_workspace_bytes(C.byref(args)))
+
+
+def dsk_dense_attn_workspace_bytes(args: dsk_dense_attn_args) -> int:
+    return int(_lib.dsk_dense_attn_workspace_bytes(C.byref(args)))
+
+
+def dsk_dense_decode_attn(args: dsk_dense_attn_args, stream=None, check: bool = True) -> int:
+    st = int(_lib.dsk_dense_decode_attn(C.byref(args), _stream_handle(stream)))
+    if check and st != DSK_OK:
+        raise DskError(st, "dsk_dense_decode_attn")
+    return st
 
 
 def dsk_stream_read_probe(buf: torch.Tensor, stream=None, sink: Optional[torch.Tensor] = None) -> None:
@@ -427,3 +456,37 @@ def sparse_decode_attn(q, K, V, sel_start, sel_len, sel_count, b, *, scale: floa
     r = make_attn_args(q, K, V, sel_start, sel_len, sel_count, b, scale=scale)
     dsk_sparse_decode_attn(r.args, stream, check=check)
     return r
+
+
+def make_dense_attn_args(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, cu_seqlens: torch.Tensor,
+                         max_seqlen: int, *, scale: float = 0.0, out: Optional[AttnOut] = None) -> AttnOut:
+    dev = q.device
+    B, Hq, D = q.shape
+    assert D == DSK_HEAD_DIM and q.dtype == torch.bfloat16 and q.is_contiguous()
+    assert cu_seqlens.dtype == torch.int32 and cu_seqlens.numel() == B + 1
+    a = dsk_dense_attn_args()
+    a.struct_size = C.sizeof(dsk_dense_attn_args)
+    a.B, a.Hq, a.Hkv, a.D = B, Hq, K.shape[0], D
+    a.q, a.K, a.V = _ptr(q), _ptr(K), _ptr(V)
+    a.k_stride_tok, a.k_stride_head = _kv_strides(K)
+    a.v_stride_tok, a.v_stride_head = _kv_strides(V)
+    a.total_tokens, a.max_seqlen = K.shape[1], max_seqlen
+    a.cu_seqlens = _ptr(cu_seqlens)
+    a.scale = scale
+    a.flags = 0
+    if out is None:
+        o = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
+        lse = torch.empty(B, Hq, dtype=torch.float32, device=dev)
+        ws = _ws(dsk_dense_attn_workspace_bytes(a), dev)
+    else:
+        o, lse, ws = out.out, out.lse, out.keep[-1]
+    a.out, a.lse = _ptr(o), _ptr(lse)
+    a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
+    return AttnOut(out=o, lse=lse, args=a, keep=(q, K, V, cu_seqlens, ws))
+
+
+def dense_decode_attn(q, K, V, cu_seqlens, max_seqlen, *, scale: float = 0.0, stream=None,
+                      check: bool = True) -> AttnOut:
+    att = make_dense_attn_args(q, K, V, cu_seqlens, max_seqlen, scale=scale)
+    dsk_dense_decode_attn(att.args, stream, check=check)
+    return att

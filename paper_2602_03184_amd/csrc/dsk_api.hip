@@ -137,6 +137,24 @@ static dsk_status validate_attn(const dsk_attn_args* a) {
   return DSK_OK;
 }
 
+static dsk_status validate_dense(const dsk_dense_attn_args* a) {
+  if (a == nullptr) return DSK_ERR_NULL;
+  if (a->struct_size != sizeof(dsk_dense_attn_args)) return DSK_ERR_VERSION;
+  if (!geometry_ok(a->B, a->Hq, a->Hkv, a->D)) return DSK_ERR_SHAPE;
+  if (a->total_tokens < 0 || a->max_seqlen < 1) return DSK_ERR_SHAPE;
+  if (!(a->scale >= 0.0f) || a->flags != 0) return DSK_ERR_PARAM;
+  if (!a->q || !a->K || !a->V || !a->cu_seqlens || !a->out) return DSK_ERR_NULL;
+  if (a->k_stride_tok < DSK_HEAD_DIM || a->v_stride_tok < DSK_HEAD_DIM || a->k_stride_head < 0 ||
+      a->v_stride_head < 0)
+    return DSK_ERR_SHAPE;
+  if (!aligned16(a->q) || !aligned16(a->K) || !aligned16(a->V) || a->k_stride_tok % 8 || a->k_stride_head % 8 ||
+      a->v_stride_tok % 8 || a->v_stride_head % 8)
+    return DSK_ERR_ALIGN;
+  if (a->workspace == nullptr || a->workspace_bytes < dsk_dense_attn_workspace_bytes(a)) return DSK_ERR_WORKSPACE;
+  if (!aligned256(a->workspace)) return DSK_ERR_ALIGN;
+  return DSK_OK;
+}
+
 }  // namespace dsk
 
 using namespace dsk;
@@ -182,6 +200,20 @@ size_t dsk_attn_workspace_bytes(const dsk_attn_args* a) {
   if (a == nullptr || a->struct_size != sizeof(dsk_attn_args)) return 0;
   if (a->B < 1 || a->Hq < 1 || a->k < 1) return 0;
   return attn_ws_layout(*a).total;
+}
+
+size_t dsk_dense_attn_workspace_bytes(const dsk_dense_attn_args* a) {
+  if (a == nullptr || a->struct_size != sizeof(dsk_dense_attn_args)) return 0;
+  if (!geometry_ok(a->B, a->Hq, a->Hkv, a->D) || a->max_seqlen < 1) return 0;
+  return dense_ws_layout(*a).total;
+}
+
+dsk_status dsk_dense_decode_attn(const dsk_dense_attn_args* a, void* stream) {
+  const dsk_status v = validate_dense(a);
+  if (v != DSK_OK) return v;
+  const DenseWs ws = dense_ws_layout(*a);
+  if (launch_dense_attn(*a, ws, static_cast<hipStream_t>(stream)) != hipSuccess) return DSK_ERR_LAUNCH;
+  return DSK_OK;
 }
 
 dsk_status dsk_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {

@@ -55,6 +55,25 @@ struct AttnWs {
 };
 AttnWs attn_ws_layout(const dsk_attn_args& a);
 hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st);
+// Fixed-order merge of nchunks partials per (sequence, head); chunk c is valid for
+// c < ceil(min(count, k) / per_chunk) where count = counts[s*Hq+h], or the length of sequence s
+// when cu_seqlens is given.
+hipError_t launch_attn_merge(const float2* part_ml, const float* part_acc, const int32_t* counts,
+                             const int32_t* cu_seqlens, int B, int Hq, int k, int nchunks, int per_chunk, float* out,
+                             float* lse, hipStream_t st);
+
+// ---- dsk_dense_decode_attn workspace ---------------------------------------------------------
+struct DenseWs {
+  size_t part_ml;        // float2 [B*Hq*nsplit]
+  size_t part_acc;       // f32 [B*Hq*nsplit*D]
+  size_t total;
+  int nsplit;            // token ranges per sequence
+  int tokens_per_split;  // multiple of 128
+  int group_tile;        // query heads of a GQA group folded per pass over K/V (1, 2 or 4)
+};
+DenseWs dense_ws_layout(const dsk_dense_attn_args& a);
+hipError_t launch_dense_attn(const dsk_dense_attn_args& a, const DenseWs& ws, hipStream_t st);
+
 hipError_t launch_stream_read(const void* buf, size_t bytes, uint32_t* sink, hipStream_t st);
 
 }  // namespace dsk

@@ -7,60 +7,17 @@
 // (sequence, head, chunk of slots); a second small kernel merges the partials in a fixed order
 // (a single-kernel merge was measured slower: both a device-wide fence per workgroup and
 // write-through partials with an arrival counter cost more than the extra launch).
+#include "dsk_attn_fold.hpp"
 #include "dsk_common.hpp"
 #include "dsk_internal.hpp"
 
 namespace dsk {
 
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kMergeThreads = 256;
 constexpr int kMergeGroups = kMergeThreads / 16;
 
 // slots per workgroup for a slot length bound b
 __host__ __device__ constexpr int attn_slots_per_wg(int b) { return b <= 16 ? 16 : 8; }
-
-struct WaveState {
-  float m;        // running max of the logits, in log2 units (wave-uniform)
-  float l;        // this lane group's part of the denominator
-  float acc[8];   // this lane group's part of the numerator, channels 8c..8c+7
-};
-
-// Fold 4*NS already-loaded token rows (K rows kv, V rows vv; row 4u+g in kv[u] of lane group g)
-// into the state.  Rows >= nvalid are padding (their loads were redirected to a real row).
-template <int NS>
-__device__ __forceinline__ void fold_loaded(WaveState& st, const float (&qf)[8], const uint4 (&kv)[NS],
-                                            const uint4 (&vv)[NS], int nvalid, int g, float scale_log2) {
-  float z[NS];
-  float mloc = -__builtin_inff();
-#pragma unroll
-  for (int u = 0; u < NS; ++u) {
-    float f[8];
-    unpack8(kv[u], f);
-    float d = 0.0f;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) d = fmaf(qf[k], f[k], d);
-    d = group16_sum(d) * scale_log2;
-    z[u] = (4 * u + g < nvalid) ? d : -__builtin_inff();
-    mloc = fmaxf(mloc, z[u]);
-  }
-  mloc = fmaxf(fmaxf(rows4_f(mloc, 0), rows4_f(mloc, 1)), fmaxf(rows4_f(mloc, 2), rows4_f(mloc, 3)));
-  const float m_new = fmaxf(st.m, mloc);           // finite: nvalid >= 1
-  const float alpha = exp2f(st.m - m_new);         // 0 on the first fold (st.m = -inf)
-  st.l *= alpha;
-#pragma unroll
-  for (int k = 0; k < 8; ++k) st.acc[k] *= alpha;
-#pragma unroll
-  for (int u = 0; u < NS; ++u) {
-    const float p = exp2f(z[u] - m_new);           // 0 for padded rows
-    st.l += p;
-    float f[8];
-    unpack8(vv[u], f);
-#pragma unroll
-    for (int k = 0; k < 8; ++k) st.acc[k] = fmaf(p, f[k], st.acc[k]);
-  }
-  st.m = m_new;
-}
 
 // ordinary (compiler-scheduled) loads; used for slots longer than 32 rows
 template <int NS>
@@ -258,8 +215,8 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
 // the 16 group states in LDS.  Heads with a single chunk were finished by attn_kernel.
 __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
     const float2* __restrict__ part_ml, const float* __restrict__ part_acc,
-    const int32_t* __restrict__ sel_count, int k, int nchunks, int slots_per_wg, float* __restrict__ out,
-    float* __restrict__ lse) {
+    const int32_t* __restrict__ sel_count, const int32_t* __restrict__ cu_seqlens, int Hq, int k, int nchunks,
+    int slots_per_wg, float* __restrict__ out, float* __restrict__ lse) {
   __shared__ float sm_m[kMergeGroups];
   __shared__ float sm_l[kMergeGroups];
   __shared__ float sm_acc[kMergeGroups][DSK_HEAD_DIM];
@@ -277,7 +234,14 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
     x00 = *reinterpret_cast<const float4*>(acc + (int64_t)grp * DSK_HEAD_DIM);
     x01 = *reinterpret_cast<const float4*>(acc + (int64_t)grp * DSK_HEAD_DIM + 4);
   }
-  int count = sel_count[sh];
+  // units folded per head: selected slots, or (full attention) the tokens of the sequence
+  int count;
+  if (cu_seqlens != nullptr) {
+    const int s = (int)(sh / Hq);
+    count = cu_seqlens[s + 1] - cu_seqlens[s];
+  } else {
+    count = sel_count[sh];
+  }
   if (count > k) count = k;
   const int used = (count + slots_per_wg - 1) / slots_per_wg;
   if (used <= 1) return;   // empty or single-chunk heads are complete already
@@ -355,8 +319,15 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
 #undef DSK_ATTN_ARGS
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || ws.nchunks <= 1 || (a.flags & DSK_ATTN_PARTIALS_ONLY)) return err;
-  attn_merge_kernel<<<dim3((unsigned)(a.B * a.Hq)), dim3(kMergeThreads), 0, st>>>(
-      part_ml, part_acc, a.sel_count, a.k, ws.nchunks, ws.slots_per_wg, a.out, a.lse);
+  return launch_attn_merge(part_ml, part_acc, a.sel_count, nullptr, a.B, a.Hq, a.k, ws.nchunks, ws.slots_per_wg, a.out,
+                           a.lse, st);
+}
+
+hipError_t launch_attn_merge(const float2* part_ml, const float* part_acc, const int32_t* counts,
+                             const int32_t* cu_seqlens, int B, int Hq, int k, int nchunks, int per_chunk, float* out,
+                             float* lse, hipStream_t st) {
+  attn_merge_kernel<<<dim3((unsigned)(B * Hq)), dim3(kMergeThreads), 0, st>>>(
+      part_ml, part_acc, counts, cu_seqlens, Hq, k, nchunks, per_chunk, out, lse);
   return hipGetLastError();
 }
 

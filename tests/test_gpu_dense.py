@@ -1,0 +1,106 @@
+"""GPU parity of dsk_dense_decode_attn (full attention over the whole cache, the full-KV
+baseline of Sec. 5) against the oracle's written-out definition: max relative error of the
+output <= 2e-3 (fp32 accumulation of bf16 inputs), lse within 1e-3."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dynsplit_oracle as O
+from dsk_testutil import DEFAULT_SCALE, dev_bf16, dev_i32, gpu_case, rel_err
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3
+LSE_TOL = 1e-3
+
+
+def _dsk():
+    import paper_2602_03184_amd as dsk
+    return dsk
+
+
+def _check(case, q_bits, seqs, heads, scale=0.0):
+    dsk = _dsk()
+    wl, cfg = case.wl, case.cfg
+    att = dsk.dense_decode_attn(dev_bf16(q_bits), case.K, case.V, case.cu_seqlens, case.max_seqlen, scale=scale)
+    torch.cuda.synchronize()
+    out, lse = att.out.cpu().numpy(), att.lse.cpu().numpy()
+    sc = DEFAULT_SCALE if scale == 0.0 else scale
+    worst = 0.0
+    for s in seqs:
+        lo, hi = int(wl.cu_seqlens[s]), int(wl.cu_seqlens[s + 1])
+        if hi == lo:
+            assert (out[s] == 0).all() and np.isneginf(lse[s]).all()
+            continue
+        for h in heads:
+            hk = h // cfg.G
+            o, l = O.dense_attention(O.widen_bf16(q_bits[s, h]), O.widen_bf16(wl.K[hk, lo:hi]),
+                                     O.widen_bf16(wl.V[hk, lo:hi]), sc)
+            e = rel_err(out[s, h], o)
+            worst = max(worst, e)
+            assert e <= ATTN_TOL, (s, h, e)
+            assert abs(float(lse[s, h]) - l) <= LSE_TOL, (s, h)
+    return worst
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2])
+def test_dense_attention_parity_all_heads(cfg_id):
+    case = gpu_case(cfg_id)
+    cfg = case.cfg
+    worst = _check(case, case.wl.q[0], range(cfg.B), range(cfg.Hq))
+    print("cfg%d dense attention: worst rel err %.3e" % (cfg_id, worst))
+
+
+@pytest.mark.parametrize("cfg_id", [3, 4, 5])
+def test_dense_attention_parity_full_size_sampled_heads(cfg_id):
+    case = gpu_case(cfg_id)
+    cfg = case.cfg
+    heads = sorted({0, cfg.G, cfg.Hq - 1})
+    seqs = [0] if cfg.B == 1 else [0, cfg.B - 1]
+    worst = _check(case, case.wl.q[0], seqs, heads)
+    print("cfg%d dense attention (sampled heads): worst rel err %.3e" % (cfg_id, worst))
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (8, 4), (8, 2), (8, 1), (6, 2), (5, 1)])
+def test_dense_attention_group_widths_and_ragged_lengths(Hq, Hkv):
+    """Group widths 1, 2, 4, 8 and two that no group tile divides; sequence lengths around the
+    128-row step of a workgroup and the 32-row tile of a wavefront, one empty, one of one token."""
+    seqlens = [0, 1, 31, 32, 33, 127, 128, 129, 700, 2049]
+    case = gpu_case(5, B=len(seqlens), seqlens=seqlens, Hq=Hq, Hkv=Hkv, n_queries=1)
+    _check(case, case.wl.q[0], range(len(seqlens)), range(Hq))
+    _check(case, case.wl.q[0], [4, 8], [0, Hq - 1], scale=0.21)
+
+
+def test_dense_equals_sparse_with_everything_selected():
+    """Same query, budget covering every slot: the sparse path and the dense baseline must agree
+    to fp32 rounding (they fold the same rows in different groupings)."""
+    dsk = _dsk()
+    case = gpu_case(1)
+    cfg, wl = case.cfg, case.wl
+    comp = case.compressed()
+    q = dev_bf16(wl.q[0])
+    nslots = int(comp.slot_base.cpu()[int(comp.cu_blocks.cpu()[-1])])
+    sel = dsk.select_topk(comp, q, nslots * cfg.b)
+    sp = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b)
+    de = dsk.dense_decode_attn(q, case.K, case.V, case.cu_seqlens, case.max_seqlen)
+    torch.cuda.synchronize()
+    assert rel_err(sp.out.cpu().numpy(), de.out.cpu().numpy().astype(np.float64)) <= 1e-5
+    assert float((sp.lse - de.lse).abs().max().item()) <= 1e-5
+
+
+def test_dense_is_deterministic_and_validates():
+    dsk = _dsk()
+    case = gpu_case(2)
+    q = dev_bf16(case.wl.q[0])
+    a = dsk.dense_decode_attn(q, case.K, case.V, case.cu_seqlens, case.max_seqlen)
+    b = dsk.dense_decode_attn(q, case.K, case.V, case.cu_seqlens, case.max_seqlen)
+    torch.cuda.synchronize()
+    assert torch.equal(a.out, b.out) and torch.equal(a.lse, b.lse)
+    args = dsk.make_dense_attn_args(q, case.K, case.V, case.cu_seqlens, case.max_seqlen).args
+    args.max_seqlen = 0
+    assert dsk.dsk_dense_decode_attn(args, check=False) == dsk.DSK_ERR_SHAPE
+    args.max_seqlen = case.max_seqlen
+    args.workspace_bytes = 16
+    assert dsk.dsk_dense_decode_attn(args, check=False) == dsk.DSK_ERR_WORKSPACE
