@@ -192,6 +192,20 @@ def main():
         stream.synchronize()
         select_us = event_ms(g_sel.replay, stream) * 1e3 / args.steps
 
+        # ---- full attention over the whole cache on the same device (the full-KV baseline) --------
+        dense = dsk.make_dense_attn_args(queries[0], K, V, cu, int(wl.seqlens.max()))
+        dense_args = [dense] + [dsk.make_dense_attn_args(queries[i], K, V, cu, int(wl.seqlens.max()), out=dense)
+                                for i in range(1, nq)]
+        n_dense = max(8, min(args.steps, 64))
+        g_dense = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_dense, stream=stream):
+            for i in range(n_dense):
+                dsk.dsk_dense_decode_attn(dense_args[i % nq].args, stream)
+        g_dense.replay()
+        stream.synchronize()
+        dense_us = event_ms(g_dense.replay, stream) * 1e3 / n_dense
+        dense_bytes = 2 * wl.total_tokens * cfg.Hkv * 128 * 2
+
         # ---- streaming-read reference: what a plain coalesced read reaches on this device ------
         stream_read_gbs = None
         if args.stream_read_mib > 0:
@@ -295,6 +309,11 @@ def main():
                      "step_frac": round(step_gbs / HBM_PEAK_GBS, 4)},
         "workload_gen_s": round(gen_s, 1),
     }
+    out["dense_baseline"] = {"us": round(dense_us, 2), "bytes": int(dense_bytes),
+                             "GBps": round(dense_bytes / (dense_us * 1e-6) / 1e9, 1),
+                             "frac_of_hbm_peak": round(dense_bytes / (dense_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                             "speedup_of_sparse_step": round(dense_us / us_per_step, 2),
+                             "what": "dsk_dense_decode_attn, full attention over the whole cache, same queries"}
     if stream_read_gbs is not None:
         out["stream_read"] = {"GBps": round(stream_read_gbs, 1), "mib": args.stream_read_mib,
                               "gather_frac_of_stream_read": round(attn_gbs / stream_read_gbs, 4),

@@ -21,7 +21,7 @@ __host__ __device__ constexpr int attn_slots_per_wg(int b) { return b <= 16 ? 16
 
 // ordinary (compiler-scheduled) loads; used for slots longer than 32 rows
 template <int NS>
-__device__ __forceinline__ void fold_rows(WaveState& st, const float (&qf)[8], const uint16_t* __restrict__ kbase,
+__device__ __forceinline__ void fold_rows(WaveState& st, const QRow& qf, const uint16_t* __restrict__ kbase,
                                           const uint16_t* __restrict__ vbase, int64_t kst, int64_t vst,
                                           int nvalid, int g, float scale_log2) {
   uint4 kv[NS], vv[NS];
@@ -43,7 +43,7 @@ __device__ __forceinline__ void fold_rows(WaveState& st, const float (&qf)[8], c
 // compile-time loop over the slots of a wave: wait for slot S's K and V, fold, recurse
 template <int NS, int SPW, int S>
 struct FoldSlots {
-  static __device__ __forceinline__ void run(WaveState& st, const float (&qf)[8], uint4 (&kd)[SPW][NS],
+  static __device__ __forceinline__ void run(WaveState& st, const QRow& qf, uint4 (&kd)[SPW][NS],
                                              uint4 (&vd)[SPW][NS], const int (&nv)[SPW], int g,
                                              float scale_log2) {
     // loads were issued slot by slot, K rows then V rows; pinning slot S here keeps the loads of
@@ -105,11 +105,7 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
   const int g = lane >> 4;
   const int c = lane & 15;
   const int hk = h / G;
-  float qf[8];
-  {
-    const uint4 qv = *reinterpret_cast<const uint4*>(q + sh * DSK_HEAD_DIM + c * 8);
-    unpack8(qv, qf);
-  }
+  const QRow qf = make_qrow(*reinterpret_cast<const uint4*>(q + sh * DSK_HEAD_DIM + c * 8));
   const uint16_t* Kh = K + (int64_t)hk * ksh + c * 8;
   const uint16_t* Vh = V + (int64_t)hk * vsh + c * 8;
 

@@ -12,10 +12,9 @@ namespace dsk {
 
 constexpr int kDenseWaves = 4;
 constexpr int kDenseThreads = kDenseWaves * DSK_WAVE;
-constexpr int kDenseTile = 32;                            // rows a wavefront loads at once
-constexpr int kDenseStep = kDenseWaves * kDenseTile;      // rows per workgroup iteration
+constexpr int kDenseStep = kDenseWaves * 32;              // token ranges are multiples of this
 
-template <int GT>
+template <int GT, int NS>
 __global__ __launch_bounds__(kDenseThreads) void dense_attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     int64_t kst, int64_t ksh, int64_t vst, int64_t vsh, int Hq, int G, int total_tokens,
@@ -55,13 +54,13 @@ __global__ __launch_bounds__(kDenseThreads) void dense_attn_kernel(
   const int t1 = t0 + tokens_per_split < L ? t0 + tokens_per_split : L;
   const int used = (L + tokens_per_split - 1) / tokens_per_split;
 
-  float qf[GT][8];
+  QRow qf[GT];
   WaveState st[GT];
 #pragma unroll
   for (int j = 0; j < GT; ++j) {
     const int gq = g0 + (j < ng ? j : 0);                      // absent heads shadow head g0, never written
     const uint4 qv = *reinterpret_cast<const uint4*>(q + ((int64_t)s * Hq + hk * G + gq) * DSK_HEAD_DIM + c * 8);
-    unpack8(qv, qf[j]);
+    qf[j] = make_qrow(qv);
     st[j].m = -__builtin_inff();
     st[j].l = 0.0f;
 #pragma unroll
@@ -70,23 +69,24 @@ __global__ __launch_bounds__(kDenseThreads) void dense_attn_kernel(
   const uint16_t* Kh = K + (int64_t)hk * ksh + (int64_t)seq0 * kst + c * 8;
   const uint16_t* Vh = V + (int64_t)hk * vsh + (int64_t)seq0 * vst + c * 8;
 
-  for (int r0 = t0 + wave * kDenseTile; r0 < t1; r0 += kDenseStep) {
-    const int nvalid = t1 - r0 < kDenseTile ? t1 - r0 : kDenseTile;
-    uint4 kv[8], vv[8];
+  constexpr int kTile = 4 * NS;                                // rows a wavefront loads at once
+  for (int r0 = t0 + wave * kTile; r0 < t1; r0 += kDenseWaves * kTile) {
+    const int nvalid = t1 - r0 < kTile ? t1 - r0 : kTile;
+    uint4 kv[NS], vv[NS];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < NS; ++u) {
       int r = 4 * u + grp;
       r = r < nvalid ? r : nvalid - 1;                         // padding rows re-read a real row
       kv[u] = *reinterpret_cast<const uint4*>(Kh + (int64_t)(r0 + r) * kst);
     }
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < NS; ++u) {
       int r = 4 * u + grp;
       r = r < nvalid ? r : nvalid - 1;
       vv[u] = *reinterpret_cast<const uint4*>(Vh + (int64_t)(r0 + r) * vst);
     }
 #pragma unroll
-    for (int j = 0; j < GT; ++j) fold_loaded<8>(st[j], qf[j], kv, vv, nvalid, grp, scale_log2);
+    for (int j = 0; j < GT; ++j) fold_loaded<NS>(st[j], qf[j], kv, vv, nvalid, grp, scale_log2);
   }
 
   // per head: lane groups -> wave -> workgroup partial, fixed order
@@ -166,9 +166,11 @@ hipError_t launch_dense_attn(const dsk_dense_attn_args& a, const DenseWs& ws, hi
 #define DSK_DENSE_ARGS                                                                                        \
   q, K, V, a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, G, a.total_tokens,         \
       a.cu_seqlens, ws.tokens_per_split, ws.nsplit, scale * kLog2e, part_ml, part_acc, a.out, a.lse
-  if (ws.group_tile == 4) dense_attn_kernel<4><<<grid, dim3(kDenseThreads), 0, st>>>(DSK_DENSE_ARGS);
-  else if (ws.group_tile == 2) dense_attn_kernel<2><<<grid, dim3(kDenseThreads), 0, st>>>(DSK_DENSE_ARGS);
-  else dense_attn_kernel<1><<<grid, dim3(kDenseThreads), 0, st>>>(DSK_DENSE_ARGS);
+  // 32-row tiles: 16- and 8-row tiles raise occupancy but were measured slower (the per-tile
+  // rescale of four heads' states is vector-ALU work the kernel has little room for)
+  if (ws.group_tile == 4) dense_attn_kernel<4, 8><<<grid, dim3(kDenseThreads), 0, st>>>(DSK_DENSE_ARGS);
+  else if (ws.group_tile == 2) dense_attn_kernel<2, 8><<<grid, dim3(kDenseThreads), 0, st>>>(DSK_DENSE_ARGS);
+  else dense_attn_kernel<1, 8><<<grid, dim3(kDenseThreads), 0, st>>>(DSK_DENSE_ARGS);
 #undef DSK_DENSE_ARGS
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || ws.nsplit <= 1) return err;
