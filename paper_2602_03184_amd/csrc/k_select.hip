@@ -39,8 +39,8 @@ struct SelShared {
   int wave_tot2[2 * kSelWaves];
   int digit, krem;
   int n_work;
-  int4 work[kSelWork + 1];             // (first token, end token, first slot, output offset); last = dump
-  int work_take[kSelWork + 1];
+  int4 work[kSelWork];                 // (first token, end token, first slot, output offset)
+  int work_take[kSelWork];
 };
 
 #ifdef DSK_SELECT_TIMING
@@ -417,7 +417,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   DSK_TS(4);
   // Chosen blocks go through an LDS work list (any order: every entry carries its output
   // offset) so that their slots are written by all threads in parallel; block_start is already
-  // in registers.  Entries outside the current round's window land in a dump entry.
+  // in registers.  Entries outside the current round's window are skipped.
   int n_mine = 0;
   {
     int tb = tie_before;
@@ -434,19 +434,20 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
       n_mine += take > 0 ? 1 : 0;
     }
   }
+  const int* xs = reinterpret_cast<const int*>(iv);
+  const int* xb = reinterpret_cast<const int*>(bv);
   const int e0 = n_mine > 0 ? atomicAdd(&sh.n_work, n_mine) : 0;   // one reservation per thread
   __syncthreads();
   const int n_work = sh.n_work;
-  const int* xs = reinterpret_cast<const int*>(iv);
-  const int* xb = reinterpret_cast<const int*>(bv);
   for (int base = 0; base < n_work; base += kSelWork) {
     int e = e0 - base, o = off;
 #pragma unroll
     for (int r = 0; r < kSelPerThread; ++r) {
       const bool on = w[r] > 0;
-      const int idx = (on && e >= 0 && e < kSelWork) ? e : kSelWork;
-      sh.work[idx] = make_int4(xb[r], xb[r + 1], xs[r], o);
-      sh.work_take[idx] = w[r];
+      if (on && e >= 0 && e < kSelWork) {                  // few lanes per step: masked LDS writes
+        sh.work[e] = make_int4(xb[r], xb[r + 1], xs[r], o);
+        sh.work_take[e] = w[r];
+      }
       e += on ? 1 : 0;
       o += w[r];
     }

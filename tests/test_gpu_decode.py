@@ -246,12 +246,15 @@ def test_exact_ties_go_to_lowest_slot_index():
         selection_check(sel2.sel_slot.cpu().numpy()[0, h, :cnt], o_sel, tau, sc, seg.slot_base)
 
 
-def test_small_budgets_and_b1():
-    """k = 1, b = 1 (token-level mapping of Sec. 4.2) and a budget that ends inside a block."""
+def test_small_and_large_budgets_and_b1():
+    """k = 1, b = 1 (token-level mapping of Sec. 4.2), budgets that end inside a block, and
+    budgets large enough for the staged emission of the selection kernel."""
     dsk = _dsk()
     case = gpu_case(1)
     cfg, wl, seg = case.cfg, case.wl, case.seg
-    for b, budget in ((1, 1), (1, 37), (4, 4), (4, 50), (16, 16), (64, 200)):
+    # the last three select more than 512 slots per head: emission staged through the work list,
+    # with b = 1 in more than one round of it
+    for b, budget in ((1, 1), (1, 37), (4, 4), (4, 50), (16, 16), (64, 200), (1, 513), (1, 2600), (4, 4000)):
         comp = dsk.compress(**case.compress_kwargs(
             stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_SEGMENT | dsk.DSK_STAGE_SUMMARIES,
             token_ids=case.token_ids, delim_ids=case.delim_ids, b=b))
