@@ -23,13 +23,12 @@ namespace dsk {
 
 constexpr int kSelThreads = 512;
 constexpr int kSelWaves = kSelThreads / DSK_WAVE;
-constexpr int kSelPerThread = 16;                       // blocks per thread
-constexpr int kSelTile = kSelThreads * kSelPerThread;   // 8192 aligned elements per workgroup
-constexpr int kSelVecs = kSelPerThread / 4;             // 16-byte vectors of scores per thread
+constexpr int kSelMaxPerThread = 16;                    // blocks per thread: 4, 8 or 16 (register tile of 2048, 4096 or 8192)
 constexpr int kSelWork = 1024;                          // chosen blocks staged in LDS per emission round
 
-// does a sequence of n blocks fit the register tile whatever its alignment shift (0..3)?
-__host__ __device__ constexpr bool sel_fits_tile(int n) { return n + 3 <= kSelTile; }
+// does a sequence of n blocks fit a register tile of `per_thread` blocks per thread whatever
+// its alignment shift (0..3)?
+__host__ __device__ constexpr bool sel_fits_tile(int n, int per_thread) { return n + 3 <= kSelThreads * per_thread; }
 
 struct SelShared {
   uint32_t hist[256];
@@ -130,7 +129,7 @@ __device__ __forceinline__ void write_padding(int count, int k, int64_t obase, i
 __device__ __noinline__ void select_big(
     SelShared& sh, const float* __restrict__ scores, int stride, const int32_t* __restrict__ cu_blocks,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ slot_base, int cap, int Hq,
-    int b, int k, int32_t* __restrict__ sel_slot, int32_t* __restrict__ sel_start,
+    int b, int k, int per_thread, int32_t* __restrict__ sel_slot, int32_t* __restrict__ sel_start,
     int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
   const int h = blockIdx.x;
   const int s = blockIdx.y;
@@ -144,7 +143,7 @@ __device__ __noinline__ void select_big(
   int blk1 = cu_blocks[s + 1];
   if (blk1 > cap) blk1 = cap;
   const int n = blk1 - blk0;
-  if (n <= 0 || sel_fits_tile(n)) return;                // not ours
+  if (n <= 0 || sel_fits_tile(n, per_thread)) return;    // not ours
   const float* sc = scores + (int64_t)h * stride + blk0;
   const int32_t* sb = slot_base + blk0;
   const int32_t* bs = block_start + blk0;
@@ -262,11 +261,15 @@ __device__ __noinline__ void select_big(
 
 // scores: rows of `stride` floats (stride % 4 == 0, stride >= cap, base 16-byte aligned);
 // slot_base, block_start: 16-byte aligned, readable up to a multiple of 4 entries past cap.
+template <int PT>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const float* __restrict__ scores, int stride, const int32_t* __restrict__ cu_blocks,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ slot_base, int cap, int Hq,
     int b, int k, int32_t* __restrict__ sel_slot, int32_t* __restrict__ sel_start,
     int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
+  static_assert(PT == 4 || PT == 8 || PT == 16, "register tile");
+  constexpr int kSelPerThread = PT;
+  constexpr int kSelVecs = PT / 4;
   __shared__ SelShared sh;
   const int h = blockIdx.x;
   const int s = blockIdx.y;
@@ -317,9 +320,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     write_padding(0, k, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
     return;
   }
-  if (!sel_fits_tile(n)) {                            // too many blocks for the register tile
-    select_big(sh, scores, stride, cu_blocks, block_start, slot_base, cap, Hq, b, k, sel_slot, sel_start, sel_len,
-               sel_count);
+  if (!sel_fits_tile(n, PT)) {                            // too many blocks for the register tile
+    select_big(sh, scores, stride, cu_blocks, block_start, slot_base, cap, Hq, b, k, PT, sel_slot, sel_start,
+               sel_len, sel_count);
     return;
   }
 
@@ -475,9 +478,16 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 hipError_t launch_select(const dsk_select_args& a, const float* scores, int stride, hipStream_t st) {
   const int k = a.budget / a.b;
   const dim3 grid((unsigned)a.Hq, (unsigned)a.B);
-  select_kernel<<<grid, dim3(kSelThreads), 0, st>>>(scores, stride, a.cu_blocks, a.block_start, a.slot_base,
-                                                    a.max_blocks_total, a.Hq, a.b, k, a.sel_slot, a.sel_start,
-                                                    a.sel_len, a.sel_count);
+  // a sequence has at most `bound` blocks: the smallest register tile that holds them all does
+  // the least per-thread work (larger sequences than the tile still work, through select_big)
+  const int bound = a.max_blocks_used > 0 ? a.max_blocks_used : a.max_blocks_total;
+#define DSK_SEL_ARGS                                                                                          \
+  scores, stride, a.cu_blocks, a.block_start, a.slot_base, a.max_blocks_total, a.Hq, a.b, k, a.sel_slot, a.sel_start, \
+      a.sel_len, a.sel_count
+  if (sel_fits_tile(bound, 4)) select_kernel<4><<<grid, dim3(kSelThreads), 0, st>>>(DSK_SEL_ARGS);
+  else if (sel_fits_tile(bound, 8)) select_kernel<8><<<grid, dim3(kSelThreads), 0, st>>>(DSK_SEL_ARGS);
+  else select_kernel<kSelMaxPerThread><<<grid, dim3(kSelThreads), 0, st>>>(DSK_SEL_ARGS);
+#undef DSK_SEL_ARGS
   return hipGetLastError();
 }
 
