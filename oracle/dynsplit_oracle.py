@@ -287,3 +287,40 @@ def dense_attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float) -
     for t in range(L):
         o += (w[t] / den) * V[t]
     return o, zmax + math.log(den)
+
+
+# ----------------------------------------------------------------------------
+# Incremental update during decoding (Sec. 4.1): chunks already computed are
+# kept; only the most recent segmentation ranges are recomputed
+# ----------------------------------------------------------------------------
+def first_open_block(block_start: Sequence[int], L_old: int, C: int, delta: int) -> int:
+    """Index of the first chunk whose end was decided without seeing its whole search range.
+
+    The end of the chunk that starts at s is chosen among boundaries up to s + C + delta; with
+    only L_old tokens present that choice is final exactly when s + C + delta <= L_old.  Chunk
+    starts ascend, so every chunk before the returned index is final, and -- the procedure
+    running left to right -- stays as it is however many tokens follow."""
+    nblk = len(block_start) - 1
+    for i in range(nblk):
+        if int(block_start[i]) + C + delta > L_old:
+            return i
+    return nblk
+
+
+def dd_select_append(block_start_old: Sequence[int], L_new: int, cand_pos: Sequence[int],
+                     cand_class: Sequence[int], wq: Sequence[int], C: int, delta: int, a_num: int,
+                     a_den: int) -> Tuple[np.ndarray, int]:
+    """Chunk boundaries of the sequence grown to L_new tokens, from the boundaries computed
+    when it had L_old = block_start_old[-1] tokens: the final chunks are kept, the procedure of
+    Sec. 4.1 is re-run from the start of the first open chunk.  cand_pos / cand_class describe
+    the grown sequence.  Returns (block_start_new, index of the first recomputed chunk)."""
+    L_old = int(block_start_old[-1])
+    assert L_new >= L_old
+    i0 = first_open_block(block_start_old, L_old, C, delta)
+    s0 = int(block_start_old[i0]) if i0 < len(block_start_old) - 1 else L_old
+    keep = [int(x) for x in block_start_old[:i0]]
+    # the tail is an ordinary DD-Select run on the suffix that starts at s0
+    tail_pos = [int(t) - s0 for t in cand_pos if int(t) >= s0]
+    tail_cls = [int(c) for t, c in zip(cand_pos, cand_class) if int(t) >= s0]
+    tail = dd_select(L_new - s0, tail_pos, tail_cls, wq, C, delta, a_num, a_den)
+    return np.asarray(keep + [int(x) + s0 for x in tail], dtype=np.int64), i0

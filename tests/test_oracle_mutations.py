@@ -70,6 +70,12 @@ MUTANTS = [
     ("dense_not_normalised", "o += (w[t] / den) * V[t]", "o += w[t] * V[t]"),
     ("dense_lse_forgets_max", "return o, zmax + math.log(den)", "return o, math.log(den)"),
     ("dense_skips_last_token", "for t in range(L):\n        o +=", "for t in range(L - 1):\n        o +="),
+    ("append_ignores_search_range", "if int(block_start[i]) + C + delta > L_old:", "if int(block_start[i]) + C > L_old:"),
+    ("append_finality_edge", "if int(block_start[i]) + C + delta > L_old:", "if int(block_start[i]) + C + delta >= L_old:"),
+    ("append_restarts_one_chunk_late", "s0 = int(block_start_old[i0]) if i0 < len(block_start_old) - 1 else L_old",
+     "s0 = int(block_start_old[min(i0 + 1, len(block_start_old) - 1)])"),
+    ("append_keeps_one_chunk_too_many", "keep = [int(x) for x in block_start_old[:i0]]",
+     "keep = [int(x) for x in block_start_old[:i0 + 1]]"),
     ("lse_forgets_max", "return o, float(m + math.log(den))", "return o, float(math.log(den))"),
 ]
 

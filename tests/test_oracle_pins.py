@@ -390,6 +390,59 @@ def test_select_slots_general_b_and_budget_all():
     assert list(toks) == [0, 1, 2, 3, 4, 16, 17, 18, 19]
 
 
+# ---------------------------------------------------------------- incremental update
+def _random_stream(r, L, n_class=4):
+    isd = r.random(L) < r.choice([0.02, 0.1, 0.5])
+    pos = np.nonzero(isd)[0]
+    return pos, r.integers(0, n_class, size=len(pos))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_append_equals_segmentation_from_scratch(seed):
+    """Sec. 4.1, incremental update: keeping the final chunks and re-running the procedure from
+    the first open one must give exactly the chunks of a run over the grown sequence."""
+    r = rng(300 + seed)
+    for _ in range(40):
+        L = int(r.integers(1, 300))
+        C = int(r.integers(1, 40))
+        delta = int(r.integers(0, C))
+        a_num = int(r.integers(0, 11))
+        wq = r.integers(0, 11, size=4)
+        pos, cls = _random_stream(r, L)
+        full = O.dd_select(L, pos, cls, wq, C, delta, a_num, 10)
+        L0 = int(r.integers(1, L + 1))
+        m = pos < L0
+        old = O.dd_select(L0, pos[m], cls[m], wq, C, delta, a_num, 10)
+        new, i0 = O.dd_select_append(old, L, pos, cls, wq, C, delta, a_num, 10)
+        np.testing.assert_array_equal(new, full)
+        np.testing.assert_array_equal(new[:i0], old[:i0])          # kept chunks are untouched
+
+
+def test_append_one_token_at_a_time_tracks_the_full_run():
+    r = rng(321)
+    L, C, delta = 260, 12, 5
+    pos, cls = _random_stream(r, L)
+    wq = r.integers(3, 11, size=4)
+    cur = O.dd_select(1, pos[pos < 1], cls[pos < 1], wq, C, delta, 4, 10)
+    recomputed = []
+    for n in range(2, L + 1):
+        m = pos < n
+        cur, i0 = O.dd_select_append(cur, n, pos[m], cls[m], wq, C, delta, 4, 10)
+        np.testing.assert_array_equal(cur, O.dd_select(n, pos[m], cls[m], wq, C, delta, 4, 10))
+        recomputed.append(len(cur) - 1 - i0)
+    # "only the most recent segmentation ranges are recomputed": the open chunks start within
+    # C + delta of the end, and every chunk has at least C - delta tokens
+    assert max(recomputed) <= (C + delta) // (C - delta) + 2
+
+
+def test_first_open_block_by_hand():
+    # C = 8, delta = 2: the chunk that starts at s was decided on boundaries up to s + 10
+    assert O.first_open_block([0, 10, 20], 20, 8, 2) == 2        # 0+10 <= 20, 10+10 <= 20: all final
+    assert O.first_open_block([0, 10, 19], 19, 8, 2) == 1        # 10+10 > 19: chunk 1 may still change
+    assert O.first_open_block([0, 7], 7, 8, 2) == 0              # the only chunk is the open last one
+    assert O.first_open_block([0, 9, 17, 26, 31], 31, 8, 2) == 3  # 10, 19, 27 <= 31 final; 26+10 = 36 > 31 open
+
+
 # ---------------------------------------------------------------- attention
 def test_attention_budget_all_equals_dense_sdpa():
     r = rng(12)
