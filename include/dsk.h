@@ -251,6 +251,47 @@ typedef struct dsk_dense_attn_args {
   size_t workspace_bytes;
 } dsk_dense_attn_args;
 
+/* ------------------------------------------------------------------------------------------
+ * dsk_append_tokens -- incremental update during decoding (Sec. 4.1): the chunks already
+ * computed are kept and only the most recent segmentation ranges are recomputed.
+ *
+ * One sequence per call, in the single-sequence layout of dsk_compress (block_start[0] == 0,
+ * cu_blocks == {0, nblk}); a batch is updated with one call per sequence on that sequence's own
+ * tables.  The sequence has grown from len_old to len_new tokens; token_ids and the K (V) rows
+ * of the new tokens are already in place.  The end of the chunk that starts at s was chosen
+ * among boundaries up to s + C + delta, so it is final iff s + C + delta <= len_old; the
+ * procedure of stage SEGMENT is re-run from the start of the first chunk that is not final (with
+ * the delimiter classes taken from token_ids / delim_ids and the weights from class_weight_q),
+ * and block_start, slot_base, cu_blocks[1] and the summaries of the recomputed chunks are
+ * rewritten.  The result equals a dsk_compress of the len_new tokens from scratch, bit for bit.
+ * Data-dependent errors through *dev_status: DSK_ERR_SHAPE if the table on the device does not
+ * end at len_old, DSK_ERR_CAPACITY if the chunks do not fit max_blocks_total (the table is
+ * then truncated).  C, delta, alpha and b must be the values the table was built with.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct dsk_append_args {
+  uint32_t struct_size;
+  int32_t Hkv, D;
+  int32_t len_old, len_new;    /* [host] len_new >= len_old >= 0 */
+  const void* K;               /* [dev] bf16, rows 0..len_new-1 valid; strides as in dsk_compress_args */
+  const void* V;               /* [dev] may be NULL when vsum is NULL */
+  int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;
+  const int32_t* token_ids;    /* [dev] [len_new] */
+  const int32_t* delim_ids;    /* [dev] [n_class] */
+  int32_t n_class;
+  const uint8_t* class_weight_q; /* [dev] [n_class] tenths */
+  int32_t C, delta, alpha_num, alpha_den, b;
+  int32_t max_blocks_total;    /* capacity of the tables below */
+  int32_t* block_start;        /* [dev] in/out [max_blocks_total + 4] */
+  int32_t* cu_blocks;          /* [dev] in/out [2] */
+  int32_t* slot_base;          /* [dev] in/out [max_blocks_total + 4] */
+  void* ksum;                  /* [dev] in/out bf16 [Hkv, max_blocks_total, 2, D] */
+  void* vsum;                  /* [dev] in/out or NULL */
+  int32_t* first_recomputed;   /* [dev] optional out: index of the first rewritten chunk */
+  int32_t* dev_status;         /* [dev] optional */
+  void* workspace;             /* [dev] 256-byte aligned, dsk_append_workspace_bytes() */
+  size_t workspace_bytes;
+} dsk_append_args;
+
 /* Library / ABI version (DSK_ABI_VERSION of the build). */
 uint32_t dsk_version(void);
 
@@ -267,6 +308,7 @@ size_t dsk_compress_workspace_bytes(const dsk_compress_args* args);
 size_t dsk_select_workspace_bytes(const dsk_select_args* args);
 size_t dsk_attn_workspace_bytes(const dsk_attn_args* args);
 size_t dsk_dense_attn_workspace_bytes(const dsk_dense_attn_args* args);
+size_t dsk_append_workspace_bytes(const dsk_append_args* args);
 
 /* Where dsk_sparse_decode_attn leaves its split-K partials in args->workspace (what a caller
  * that sets DSK_ATTN_PARTIALS_ONLY reads).  Chunk c of (sequence s, head h) covers the selected
@@ -297,6 +339,7 @@ dsk_status dsk_compress(const dsk_compress_args* args, void* stream);
 dsk_status dsk_select_topk(const dsk_select_args* args, void* stream);
 dsk_status dsk_sparse_decode_attn(const dsk_attn_args* args, void* stream);
 dsk_status dsk_dense_decode_attn(const dsk_dense_attn_args* args, void* stream);
+dsk_status dsk_append_tokens(const dsk_append_args* args, void* stream);
 
 #ifdef __cplusplus
 }

@@ -107,6 +107,26 @@ class dsk_dense_attn_args(C.Structure):
     ]
 
 
+class dsk_append_args(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("Hkv", C.c_int32), ("D", C.c_int32),
+        ("len_old", C.c_int32), ("len_new", C.c_int32),
+        ("K", _p), ("V", _p),
+        ("k_stride_tok", C.c_int64), ("k_stride_head", C.c_int64),
+        ("v_stride_tok", C.c_int64), ("v_stride_head", C.c_int64),
+        ("token_ids", _p), ("delim_ids", _p), ("n_class", C.c_int32),
+        ("class_weight_q", _p),
+        ("C", C.c_int32), ("delta", C.c_int32), ("alpha_num", C.c_int32), ("alpha_den", C.c_int32),
+        ("b", C.c_int32),
+        ("max_blocks_total", C.c_int32),
+        ("block_start", _p), ("cu_blocks", _p), ("slot_base", _p),
+        ("ksum", _p), ("vsum", _p),
+        ("first_recomputed", _p), ("dev_status", _p),
+        ("workspace", _p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
 class dsk_attn_partials(C.Structure):
     _fields_ = [
         ("ml_offset", C.c_size_t), ("acc_offset", C.c_size_t),
@@ -121,7 +141,7 @@ _lib.dsk_strerror.argtypes = [C.c_int32]
 _lib.dsk_block_capacity.restype = C.c_int64
 _lib.dsk_block_capacity.argtypes = [C.c_int32, C.c_int32, C.c_int32]
 for _name, _cls in (("compress", dsk_compress_args), ("select", dsk_select_args), ("attn", dsk_attn_args),
-                    ("dense_attn", dsk_dense_attn_args)):
+                    ("dense_attn", dsk_dense_attn_args), ("append", dsk_append_args)):
     _f = getattr(_lib, "dsk_%s_workspace_bytes" % _name)
     _f.restype = C.c_size_t
     _f.argtypes = [C.POINTER(_cls)]
@@ -129,6 +149,8 @@ _lib.dsk_attn_partials_layout.restype = C.c_int32
 _lib.dsk_attn_partials_layout.argtypes = [C.POINTER(dsk_attn_args), C.POINTER(dsk_attn_partials)]
 _lib.dsk_dense_decode_attn.restype = C.c_int32
 _lib.dsk_dense_decode_attn.argtypes = [C.POINTER(dsk_dense_attn_args), _p]
+_lib.dsk_append_tokens.restype = C.c_int32
+_lib.dsk_append_tokens.argtypes = [C.POINTER(dsk_append_args), _p]
 _lib.dsk_stream_read_probe.restype = C.c_int32
 _lib.dsk_stream_read_probe.argtypes = [_p, C.c_size_t, _p, _p]
 _lib.dsk_compress.restype = C.c_int32
@@ -178,6 +200,17 @@ def dsk_dense_decode_attn(args: dsk_dense_attn_args, stream=None, check: bool = 
     st = int(_lib.dsk_dense_decode_attn(C.byref(args), _stream_handle(stream)))
     if check and st != DSK_OK:
         raise DskError(st, "dsk_dense_decode_attn")
+    return st
+
+
+def dsk_append_workspace_bytes(args: dsk_append_args) -> int:
+    return int(_lib.dsk_append_workspace_bytes(C.byref(args)))
+
+
+def dsk_append_tokens(args: dsk_append_args, stream=None, check: bool = True) -> int:
+    st = int(_lib.dsk_append_tokens(C.byref(args), _stream_handle(stream)))
+    if check and st != DSK_OK:
+        raise DskError(st, "dsk_append_tokens")
     return st
 
 
@@ -490,3 +523,45 @@ def dense_decode_attn(q, K, V, cu_seqlens, max_seqlen, *, scale: float = 0.0, st
     att = make_dense_attn_args(q, K, V, cu_seqlens, max_seqlen, scale=scale)
     dsk_dense_decode_attn(att.args, stream, check=check)
     return att
+
+
+@dataclass
+class Appender:
+    """Argument struct of dsk_append_tokens bound to the tables of one single-sequence
+    Compressed; set len_old / len_new and call step()."""
+    args: dsk_append_args
+    first_recomputed: torch.Tensor
+    keep: tuple
+
+    def step(self, len_old: int, len_new: int, stream=None, check: bool = True) -> int:
+        self.args.len_old, self.args.len_new = len_old, len_new
+        return dsk_append_tokens(self.args, stream, check=check)
+
+
+def make_appender(comp: Compressed, K: torch.Tensor, V: Optional[torch.Tensor], token_ids: torch.Tensor,
+                  delim_ids: torch.Tensor, class_weight_q: torch.Tensor, *, C_: int, delta: int,
+                  alpha_num: int, alpha_den: int, b: int) -> Appender:
+    """comp must come from a B = 1 compress; its block_start / slot_base / cu_blocks / ksum (and
+    vsum) are updated in place by every step()."""
+    dev = K.device
+    assert comp.cu_blocks.numel() == 2, "one sequence per appender"
+    a = dsk_append_args()
+    a.struct_size = C.sizeof(dsk_append_args)
+    a.Hkv, a.D = K.shape[0], DSK_HEAD_DIM
+    a.K = _ptr(K)
+    a.k_stride_tok, a.k_stride_head = _kv_strides(K)
+    if comp.vsum is not None:
+        a.V = _ptr(V)
+        a.v_stride_tok, a.v_stride_head = _kv_strides(V)
+    a.token_ids, a.delim_ids, a.n_class = _ptr(token_ids), _ptr(delim_ids), delim_ids.numel()
+    a.class_weight_q = _ptr(class_weight_q)
+    a.C, a.delta, a.alpha_num, a.alpha_den, a.b = C_, delta, alpha_num, alpha_den, b
+    a.max_blocks_total = comp.args.max_blocks_total
+    a.block_start, a.cu_blocks, a.slot_base = _ptr(comp.block_start), _ptr(comp.cu_blocks), _ptr(comp.slot_base)
+    a.ksum, a.vsum = _ptr(comp.ksum), _ptr(comp.vsum)
+    first = torch.zeros(1, dtype=torch.int32, device=dev)
+    a.first_recomputed = _ptr(first)
+    a.dev_status = _ptr(comp.dev_status)
+    ws = _ws(dsk_append_workspace_bytes(a), dev)
+    a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
+    return Appender(args=a, first_recomputed=first, keep=(comp, K, V, token_ids, delim_ids, class_weight_q, ws))

@@ -137,6 +137,34 @@ static dsk_status validate_attn(const dsk_attn_args* a) {
   return DSK_OK;
 }
 
+static dsk_status validate_append(const dsk_append_args* a) {
+  if (a == nullptr) return DSK_ERR_NULL;
+  if (a->struct_size != sizeof(dsk_append_args)) return DSK_ERR_VERSION;
+  if (a->Hkv < 1 || a->D != DSK_HEAD_DIM) return DSK_ERR_SHAPE;
+  if (a->len_old < 0 || a->len_new < a->len_old) return DSK_ERR_SHAPE;
+  if (a->n_class < 1 || a->n_class > DSK_MAX_CLASSES) return DSK_ERR_PARAM;
+  if (a->C < 1 || a->delta < 0 || a->delta >= a->C || a->C + a->delta > kMaxChunkSpan) return DSK_ERR_PARAM;
+  if (a->alpha_den < 1 || a->alpha_den > 1000 || a->alpha_num < 0 || a->alpha_num > a->alpha_den)
+    return DSK_ERR_PARAM;
+  if (a->b < 1 || a->b > 1024 || a->max_blocks_total < 1) return DSK_ERR_PARAM;
+  if (!a->K || !a->token_ids || !a->delim_ids || !a->class_weight_q || !a->block_start || !a->cu_blocks ||
+      !a->slot_base || !a->ksum)
+    return DSK_ERR_NULL;
+  if (a->vsum != nullptr && a->V == nullptr) return DSK_ERR_NULL;
+  if (a->k_stride_tok < DSK_HEAD_DIM || a->k_stride_head < 0 || a->k_stride_tok > kMaxTokenStride ||
+      (a->Hkv > 1 && a->k_stride_head == 0))
+    return DSK_ERR_SHAPE;
+  if (!aligned16(a->K) || !aligned16(a->ksum) || a->k_stride_tok % 8 || a->k_stride_head % 8) return DSK_ERR_ALIGN;
+  if (a->vsum != nullptr) {
+    if (a->v_stride_tok < DSK_HEAD_DIM || a->v_stride_head < 0 || a->v_stride_tok > kMaxTokenStride)
+      return DSK_ERR_SHAPE;
+    if (!aligned16(a->V) || !aligned16(a->vsum) || a->v_stride_tok % 8 || a->v_stride_head % 8) return DSK_ERR_ALIGN;
+  }
+  if (a->workspace == nullptr || a->workspace_bytes < dsk_append_workspace_bytes(a)) return DSK_ERR_WORKSPACE;
+  if (!aligned256(a->workspace)) return DSK_ERR_ALIGN;
+  return DSK_OK;
+}
+
 static dsk_status validate_dense(const dsk_dense_attn_args* a) {
   if (a == nullptr) return DSK_ERR_NULL;
   if (a->struct_size != sizeof(dsk_dense_attn_args)) return DSK_ERR_VERSION;
@@ -213,6 +241,18 @@ dsk_status dsk_dense_decode_attn(const dsk_dense_attn_args* a, void* stream) {
   if (v != DSK_OK) return v;
   const DenseWs ws = dense_ws_layout(*a);
   if (launch_dense_attn(*a, ws, static_cast<hipStream_t>(stream)) != hipSuccess) return DSK_ERR_LAUNCH;
+  return DSK_OK;
+}
+
+size_t dsk_append_workspace_bytes(const dsk_append_args* a) {
+  if (a == nullptr || a->struct_size != sizeof(dsk_append_args)) return 0;
+  return 256;
+}
+
+dsk_status dsk_append_tokens(const dsk_append_args* a, void* stream) {
+  const dsk_status v = validate_append(a);
+  if (v != DSK_OK) return v;
+  if (launch_append(*a, static_cast<hipStream_t>(stream)) != hipSuccess) return DSK_ERR_LAUNCH;
   return DSK_OK;
 }
 

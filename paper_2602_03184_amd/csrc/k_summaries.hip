@@ -23,19 +23,32 @@ constexpr int kSumUnroll = DSK_SUM_UNROLL;  // row-groups of 4 rows in flight pe
 __global__ __launch_bounds__(kSumThreads) DSK_SUM_OCC void summaries_kernel(
     const uint16_t* __restrict__ X, int64_t stride_tok, int64_t stride_head, int Hkv,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ cu_blocks, int B,
-    int cap, int total_tokens, uint16_t* __restrict__ out, int32_t* dev_status) {
+    const int32_t* __restrict__ blk_range, int cap, int total_tokens, uint16_t* __restrict__ out,
+    int32_t* dev_status) {
   const int lane = threadIdx.x & (DSK_WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DSK_WAVE);   // wave-uniform: scalar registers
   const int g = lane >> 4;   // row group 0..3
   const int c = lane & 15;   // 16-byte column 0..15
-  int nblk = cu_blocks[B];
-  if (nblk > cap) nblk = cap;
+  // blocks [i_lo, i_lo + nblk): the whole table, or the range an incremental update rewrote
+  int i_lo = 0;
+  int nblk = 0;
+  if (blk_range != nullptr) {
+    i_lo = blk_range[0];
+    int i_hi = blk_range[1];
+    if (i_hi > cap) i_hi = cap;
+    if (i_lo < 0) i_lo = 0;
+    nblk = i_hi - i_lo;
+  } else {
+    nblk = cu_blocks[B];
+    if (nblk > cap) nblk = cap;
+  }
+  if (nblk <= 0) return;
   const int64_t items = (int64_t)Hkv * nblk;
   const int64_t nwaves = (int64_t)gridDim.x * kSumWaves;
   int64_t item = (int64_t)blockIdx.x * kSumWaves + wave;
   if (item >= items) return;
   int h = (int)(item / nblk);
-  int i = (int)(item - (int64_t)h * nblk);
+  int i = i_lo + (int)(item - (int64_t)h * nblk);
   int s = __builtin_amdgcn_readfirstlane(block_start[i]);
   int e = __builtin_amdgcn_readfirstlane(block_start[i + 1]);
   const unsigned ustride = (unsigned)stride_tok;
@@ -44,7 +57,7 @@ __global__ __launch_bounds__(kSumThreads) DSK_SUM_OCC void summaries_kernel(
     const int64_t nitem = item + nwaves;
     const int64_t pitem = nitem < items ? nitem : item;
     const int nh = (int)(pitem / nblk);
-    const int ni = (int)(pitem - (int64_t)nh * nblk);
+    const int ni = i_lo + (int)(pitem - (int64_t)nh * nblk);
     const int ns = __builtin_amdgcn_readfirstlane(block_start[ni]);
     const int ne = __builtin_amdgcn_readfirstlane(block_start[ni + 1]);
     const int len = e - s;
@@ -103,16 +116,29 @@ hipError_t launch_summaries(const dsk_compress_args& a, hipStream_t st) {
   if (wgs > max_wgs) wgs = max_wgs;
   summaries_kernel<<<dim3((unsigned)wgs), dim3(kSumThreads), 0, st>>>(
       static_cast<const uint16_t*>(a.K), a.k_stride_tok, a.k_stride_head, a.Hkv, a.block_start,
-      a.cu_blocks, a.B, a.max_blocks_total, a.total_tokens, static_cast<uint16_t*>(a.ksum), a.dev_status);
+      a.cu_blocks, a.B, nullptr, a.max_blocks_total, a.total_tokens, static_cast<uint16_t*>(a.ksum), a.dev_status);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   if (a.vsum != nullptr) {
     summaries_kernel<<<dim3((unsigned)wgs), dim3(kSumThreads), 0, st>>>(
         static_cast<const uint16_t*>(a.V), a.v_stride_tok, a.v_stride_head, a.Hkv, a.block_start,
-        a.cu_blocks, a.B, a.max_blocks_total, a.total_tokens, static_cast<uint16_t*>(a.vsum), a.dev_status);
+        a.cu_blocks, a.B, nullptr, a.max_blocks_total, a.total_tokens, static_cast<uint16_t*>(a.vsum), a.dev_status);
     err = hipGetLastError();
   }
   return err;
+}
+
+hipError_t launch_summaries_range(const void* X, int64_t stride_tok, int64_t stride_head, int Hkv,
+                                  const int32_t* block_start, const int32_t* blk_range, int max_blocks_in_range,
+                                  int cap, int total_tokens, void* out, int32_t* dev_status, hipStream_t st) {
+  const int64_t max_items = (int64_t)Hkv * max_blocks_in_range;
+  if (max_items <= 0) return hipSuccess;
+  int64_t wgs = (max_items + kSumWaves - 1) / kSumWaves;
+  if (wgs > 256 * 8) wgs = 256 * 8;
+  summaries_kernel<<<dim3((unsigned)wgs), dim3(kSumThreads), 0, st>>>(
+      static_cast<const uint16_t*>(X), stride_tok, stride_head, Hkv, block_start, nullptr, 0, blk_range, cap,
+      total_tokens, static_cast<uint16_t*>(out), dev_status);
+  return hipGetLastError();
 }
 
 }  // namespace dsk

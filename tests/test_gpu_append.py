@@ -1,0 +1,187 @@
+"""GPU parity of dsk_append_tokens (Sec. 4.1, incremental update during decoding): after every
+append the block table, the slot map and the summaries must equal, bit for bit, what the oracle
+computes from scratch on the grown sequence, and the index of the first rewritten chunk must be
+the oracle's."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dynsplit_oracle as O
+from dsk_testutil import bf16_bits_of, canon_zero, dev_bf16, dev_i32, dev_u8, gpu_case, oracle_summaries
+
+pytestmark = pytest.mark.gpu
+
+
+def _dsk():
+    import paper_2602_03184_amd as dsk
+    return dsk
+
+
+class _Seq:
+    """One sequence on the device with room to grow, its oracle-side candidates, and a
+    compression of its first L0 tokens."""
+
+    def __init__(self, K_bits, V_bits, token_ids, delim_ids, wq, L0, C, delta, a_num, a_den, b, want_vsum=False,
+                 max_blocks_total=None, Hq=None):
+        dsk = _dsk()
+        self.dsk = dsk
+        self.K_bits, self.V_bits = K_bits, V_bits
+        self.tok, self.delim, self.wq = np.asarray(token_ids), np.asarray(delim_ids), np.asarray(wq)
+        self.C, self.delta, self.a_num, self.a_den, self.b = C, delta, a_num, a_den, b
+        self.L_cap = K_bits.shape[1]
+        self.K, self.V = dev_bf16(K_bits), dev_bf16(V_bits)
+        self.d_tok, self.d_delim, self.d_wq = dev_i32(self.tok), dev_i32(self.delim), dev_u8(self.wq[None])
+        self.pos, self.cls = O.extract_candidates(self.tok, self.delim)
+        cap = dsk.dsk_block_capacity(self.L_cap, 1, C - delta) if max_blocks_total is None else max_blocks_total
+        L_first = max(L0, 1)          # an empty start is made from a one-token table emptied below
+        self.comp = dsk.compress(
+            cu_seqlens=dev_i32([0, L_first]), max_seqlen=L_first, Hq=Hq or K_bits.shape[0], K=self.K, V=self.V,
+            stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_SEGMENT | dsk.DSK_STAGE_SUMMARIES,
+            token_ids=self.d_tok, delim_ids=self.d_delim, n_class=len(self.delim), class_weight_q=self.d_wq,
+            C_=C, delta=delta, alpha_num=a_num, alpha_den=a_den, b=b, total_tokens=L_first,
+            max_cand_total=self.L_cap, max_blocks_total=cap, want_vsum=want_vsum)
+        if L0 == 0:
+            torch.cuda.synchronize()
+            self.comp.cu_blocks.zero_()
+            self.comp.block_start[:4].zero_()
+            self.comp.slot_base[:4].zero_()
+        self.app = dsk.make_appender(self.comp, self.K, self.V, self.d_tok, self.d_delim, self.d_wq, C_=C,
+                                     delta=delta, alpha_num=a_num, alpha_den=a_den, b=b)
+        self.L = L0
+        torch.cuda.synchronize()
+        assert int(self.comp.dev_status.item()) == 0
+        self.ora = self.oracle_table(L0) if L0 > 0 else np.zeros(1, dtype=np.int64)
+
+    def oracle_table(self, n):
+        m = self.pos < n
+        return O.dd_select(n, self.pos[m], self.cls[m], self.wq, self.C, self.delta, self.a_num, self.a_den)
+
+    def append(self, n_new, check_status=True):
+        L_new = self.L + n_new
+        m = self.pos < L_new
+        want, i0 = O.dd_select_append(self.ora, L_new, self.pos[m], self.cls[m], self.wq, self.C, self.delta,
+                                      self.a_num, self.a_den)
+        self.app.step(self.L, L_new)
+        torch.cuda.synchronize()
+        if check_status:
+            assert int(self.comp.dev_status.item()) == 0
+        self.L, self.ora = L_new, want
+        return want, i0
+
+    def check_tables(self, want, i0):
+        nblk = len(want) - 1
+        assert int(self.comp.cu_blocks.cpu()[1]) == nblk
+        np.testing.assert_array_equal(self.comp.block_start.cpu().numpy()[: nblk + 1], want)
+        np.testing.assert_array_equal(self.comp.slot_base.cpu().numpy()[: nblk + 1], O.slot_map(want, self.b))
+        assert int(self.app.first_recomputed.item()) == i0
+
+    def check_summaries(self, want, vsum=False):
+        nblk = len(want) - 1
+        got = bf16_bits_of(self.comp.vsum if vsum else self.comp.ksum)[:, :nblk]
+        mn, mx = oracle_summaries((self.V_bits if vsum else self.K_bits)[:, : self.L], want)
+        np.testing.assert_array_equal(canon_zero(got[:, :, 0]), canon_zero(mn))
+        np.testing.assert_array_equal(canon_zero(got[:, :, 1]), canon_zero(mx))
+
+
+def test_decode_loop_one_token_at_a_time_then_bursts():
+    case = gpu_case(1)
+    wl, cfg = case.wl, case.cfg
+    seq = _Seq(wl.K, wl.V, wl.token_ids, wl.delim_ids, wl.class_weight_q[0], 1000, int(wl.C[0]), int(wl.delta[0]),
+               cfg.a_num, cfg.a_den, cfg.b)
+    for step in range(300):
+        want, i0 = seq.append(1)
+        seq.check_tables(want, i0)
+        if step % 60 == 59:
+            seq.check_summaries(want)
+    for burst in (7, 64, 500, 0, 1):
+        want, i0 = seq.append(burst)
+        seq.check_tables(want, i0)
+        seq.check_summaries(want)
+    # the grown table is the table of a compression from scratch
+    np.testing.assert_array_equal(want, seq.oracle_table(seq.L))
+
+
+def test_append_with_gqa_heads_and_v_summaries_then_decode():
+    dsk = _dsk()
+    case = gpu_case(2, seqlens=[6000])
+    wl, cfg = case.wl, case.cfg
+    seq = _Seq(wl.K, wl.V, wl.token_ids, wl.delim_ids, wl.class_weight_q[0], 3000, int(wl.C[0]), int(wl.delta[0]),
+               cfg.a_num, cfg.a_den, cfg.b, want_vsum=True, Hq=cfg.Hq)
+    r = np.random.default_rng(5)
+    while seq.L < 5900:
+        want, i0 = seq.append(int(r.integers(1, 90)))
+        seq.check_tables(want, i0)
+    seq.check_summaries(want)
+    seq.check_summaries(want, vsum=True)
+    # selection and attention on the grown cache = those on a cache compressed from scratch
+    scratch = dsk.compress(
+        cu_seqlens=dev_i32([0, seq.L]), max_seqlen=seq.L, Hq=cfg.Hq, K=seq.K, V=seq.V,
+        stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_SEGMENT | dsk.DSK_STAGE_SUMMARIES,
+        token_ids=seq.d_tok, delim_ids=seq.d_delim, n_class=cfg.n_class, class_weight_q=seq.d_wq,
+        C_=seq.C, delta=seq.delta, alpha_num=cfg.a_num, alpha_den=cfg.a_den, b=cfg.b, total_tokens=seq.L)
+    q = dev_bf16(wl.q[0])
+    a = dsk.select_topk(seq.comp, q, cfg.T)
+    b_ = dsk.select_topk(scratch, q, cfg.T)
+    torch.cuda.synchronize()
+    for name in ("sel_slot", "sel_start", "sel_len", "sel_count"):
+        assert torch.equal(getattr(a, name), getattr(b_, name)), name
+    oa = dsk.sparse_decode_attn(q, seq.K, seq.V, a.sel_start, a.sel_len, a.sel_count, cfg.b)
+    ob = dsk.sparse_decode_attn(q, seq.K, seq.V, b_.sel_start, b_.sel_len, b_.sel_count, cfg.b)
+    torch.cuda.synchronize()
+    assert torch.equal(oa.out, ob.out)
+
+
+@pytest.mark.parametrize("C,delta,a_num,everywhere", [(100, 99, 10, True), (8, 0, 5, False), (1, 0, 5, False),
+                                                      (14, 7, 5, False), (40, 39, 0, True)])
+def test_append_edge_parameters(C, delta, a_num, everywhere):
+    """C - delta = 1 with delimiters everywhere and alpha = 1 gives one-token chunks, i.e. more
+    open chunks than one wavefront counts at a time; delta = 0 and C = 1 have no search range;
+    alpha = 0 ignores the weights."""
+    case = gpu_case(1)
+    wl, cfg = case.wl, case.cfg
+    L_cap = 1500
+    tok = wl.token_ids[:L_cap].copy()
+    wq = wl.class_weight_q[0].copy()
+    if everywhere:
+        tok[:] = wl.delim_ids[3]
+        wq[:] = 7
+    seq = _Seq(wl.K[:, :L_cap], wl.V[:, :L_cap], tok, wl.delim_ids, wq, 400, C, delta, a_num, 10, 4)
+    for n_new in (1, 1, 1, 2, 3, 1, 50, 1, 1, 300, 1, 199, 1):
+        want, i0 = seq.append(n_new)
+        seq.check_tables(want, i0)
+    seq.check_summaries(want)
+    if everywhere and delta == C - 1 and a_num == 10:
+        assert len(want) - 1 == seq.L - C + 1             # one-token chunks, then the last chunk of C tokens
+
+
+def test_append_from_an_empty_sequence():
+    case = gpu_case(1)
+    wl, cfg = case.wl, case.cfg
+    seq = _Seq(wl.K[:, :600], wl.V[:, :600], wl.token_ids[:600], wl.delim_ids, wl.class_weight_q[0], 0, 24, 12,
+               5, 10, 16)
+    for n_new in (1, 1, 10, 24, 100, 400):
+        want, i0 = seq.append(n_new)
+        seq.check_tables(want, i0)
+    seq.check_summaries(want)
+
+
+def test_append_reports_capacity_and_table_mismatch():
+    dsk = _dsk()
+    case = gpu_case(1)
+    wl, cfg = case.wl, case.cfg
+    seq = _Seq(wl.K[:, :2000], wl.V[:, :2000], wl.token_ids[:2000], wl.delim_ids, wl.class_weight_q[0], 500, 24,
+               12, 5, 10, 16, max_blocks_total=30)
+    seq.append(1500, check_status=False)                  # ~83 chunks do not fit 30
+    assert int(seq.comp.dev_status.item()) == dsk.DSK_ERR_CAPACITY
+    assert int(seq.comp.cu_blocks.cpu()[1]) == 30
+    seq.comp.dev_status.zero_()
+    seq.app.step(1234, 1300, check=True)                  # the table does not end at 1234
+    torch.cuda.synchronize()
+    assert int(seq.comp.dev_status.item()) == dsk.DSK_ERR_SHAPE
+    # host-side validation
+    seq.app.args.len_new = 10
+    seq.app.args.len_old = 20
+    assert dsk.dsk_append_tokens(seq.app.args, check=False) == dsk.DSK_ERR_SHAPE
+    seq.app.args.len_old, seq.app.args.len_new = 0, 10
+    seq.app.args.delta = seq.app.args.C
+    assert dsk.dsk_append_tokens(seq.app.args, check=False) == dsk.DSK_ERR_PARAM
