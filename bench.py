@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # counter reads for the plain 256 MiB device copy of --calib-copy-mib (FETCH_SIZE reads half the
 # copied bytes on this part -> x2; WRITE_SIZE reads them exactly -> x1).  Keyed by workload.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg3_llama3_8b_128k": {"attn_kernel": int(20420.9 * 1024 * 2.000 + 272.0 * 1024 * 1.000)},
+    "cfg3_llama3_8b_128k": {"attn_kernel": int(20411.2 * 1024 * 2.000 + 272.0 * 1024 * 1.000)},
 }
 
 
@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--append-steps", type=int, default=256,
+                    help="steps of the decode loop that appends one token per step before selecting; 0 = skip")
     ap.add_argument("--cold-instances", type=int, default=16,
                     help="copies of the cache (K, V, summaries) the cold-cache measurement rotates over; 0 = skip")
     ap.add_argument("--stream-read-mib", type=int, default=2048,
@@ -270,6 +272,49 @@ def main():
                     "gather_frac": round(last_sel_bytes / (cold_gather_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
             del Ks, Vs, ksums, csel, catt, cgat, g_cold, g_cg
             torch.cuda.empty_cache()
+
+        # ---- decode loop with the incremental update: the cache of the first L - n tokens is
+        #      compressed, then every step appends one token (dsk_append_tokens), selects and attends.
+        #      Single-sequence workloads only (the update takes one sequence per call). ---------------
+        loop = None
+        if cfg.B == 1 and args.append_steps > 0:
+            n_app = min(args.append_steps, wl.total_tokens // 2)
+            L0 = wl.total_tokens - n_app
+            lkw = dict(ckw)
+            lkw.update(cu_seqlens=i32([0, L0]), max_seqlen=L0, total_tokens=L0, max_cand_total=wl.total_tokens,
+                       max_blocks_total=dsk.dsk_block_capacity(wl.total_tokens, 1, int((wl.C - wl.delta).min())),
+                       C_per_seq=None, delta_per_seq=None)
+            lcomp = dsk.compress(**lkw)
+            stream.synchronize()
+            wq_dev = lkw["class_weight_q"]
+            appenders = []
+            for i in range(n_app):
+                ap = dsk.make_appender(lcomp, K, V, lkw["token_ids"], lkw["delim_ids"], wq_dev, C_=int(wl.C[0]),
+                                       delta=int(wl.delta[0]), alpha_num=cfg.a_num, alpha_den=cfg.a_den, b=cfg.b)
+                ap.args.len_old, ap.args.len_new = L0 + i, L0 + i + 1
+                appenders.append(ap)
+            hint = nblk + 8                                  # the grown table ends at the full table's size
+            lsel = [dsk.make_select_args(lcomp, queries[0], cfg.T, max_blocks_used=hint)]
+            for i in range(1, nq):
+                lsel.append(dsk.make_select_args(lcomp, queries[i], cfg.T, out=lsel[0], max_blocks_used=hint))
+            latt = [dsk.make_attn_args(queries[0], K, V, lsel[0].sel_start, lsel[0].sel_len, lsel[0].sel_count, cfg.b)]
+            for i in range(1, nq):
+                latt.append(dsk.make_attn_args(queries[i], K, V, lsel[0].sel_start, lsel[0].sel_len,
+                                               lsel[0].sel_count, cfg.b, out=latt[0]))
+            g_loop = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_loop, stream=stream):   # capture runs nothing: the table stays at L0
+                for i in range(n_app):
+                    dsk.dsk_append_tokens(appenders[i].args, stream)
+                    dsk.dsk_select_topk(lsel[i % nq].args, stream)
+                    dsk.dsk_sparse_decode_attn(latt[i % nq].args, stream)
+            loop_us = event_ms(g_loop.replay, stream) * 1e3 / n_app      # one replay: L0 -> L
+            stream.synchronize()
+            ok = int(lcomp.dev_status.item()) == 0 and int(lcomp.cu_blocks.cpu()[1]) == nblk and \
+                torch.equal(lcomp.block_start[: nblk + 1], comp.block_start[: nblk + 1]) and \
+                torch.equal(lcomp.ksum[:, :nblk], comp.ksum[:, :nblk])
+            loop = {"steps": n_app, "us_per_step": round(loop_us, 3),
+                    "append_us": round(loop_us - us_per_step, 3),
+                    "grown_table_equals_full_compress": bool(ok)}
     torch.cuda.synchronize()
 
     attn_gbs = bytes_attn / (gather_us * 1e-6) / 1e9
@@ -321,6 +366,8 @@ def main():
                                   round(compress_bytes / (compress_ms * 1e-3) / 1e9 / stream_read_gbs, 4)}
     if cold is not None:
         out["cold"] = cold
+    if loop is not None:
+        out["decode_loop_with_append"] = loop
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, comp, nblk)
     print(json.dumps(out))
