@@ -324,3 +324,35 @@ def dd_select_append(block_start_old: Sequence[int], L_new: int, cand_pos: Seque
     tail_cls = [int(c) for t, c in zip(cand_pos, cand_class) if int(t) >= s0]
     tail = dd_select(L_new - s0, tail_pos, tail_cls, wq, C, delta, a_num, a_den)
     return np.asarray(keep + [int(x) + s0 for x in tail], dtype=np.int64), i0
+
+
+# ----------------------------------------------------------------------------
+# Mean-pooling summaries (App. A.2, additional ablation: min/max compression
+# replaced by mean pooling, everything else unchanged)
+# ----------------------------------------------------------------------------
+def block_means(X: np.ndarray, block_start: np.ndarray) -> np.ndarray:
+    """Per-channel arithmetic mean over the tokens of every block.  X[h, t, d] -> mean[h, i, d]."""
+    H, _, D = X.shape
+    nblk = len(block_start) - 1
+    out = np.empty((H, nblk, D), dtype=np.float64)
+    for h in range(H):
+        for i in range(nblk):
+            s, e = int(block_start[i]), int(block_start[i + 1])
+            acc = np.zeros(D, dtype=np.float64)
+            for t in range(s, e):
+                acc += X[h, t]
+            out[h, i] = acc / (e - s)
+    return out
+
+
+def block_scores_mean(q: np.ndarray, kmean: np.ndarray) -> np.ndarray:
+    """score[hq, i] = q[hq] . kmean[hk, i], hk = hq // G: the query-compressed-vector product
+    (Sec. 4.2) when the compressed vector is the block's mean key."""
+    Hq = q.shape[0]
+    Hkv, nblk, _ = kmean.shape
+    G = Hq // Hkv
+    s = np.empty((Hq, nblk), dtype=np.float64)
+    for h in range(Hq):
+        for i in range(nblk):
+            s[h, i] = float(np.dot(q[h], kmean[h // G, i]))
+    return s

@@ -76,6 +76,10 @@ MUTANTS = [
      "s0 = int(block_start_old[min(i0 + 1, len(block_start_old) - 1)])"),
     ("append_keeps_one_chunk_too_many", "keep = [int(x) for x in block_start_old[:i0]]",
      "keep = [int(x) for x in block_start_old[:i0 + 1]]"),
+    ("mean_divides_by_len_plus_one", "out[h, i] = acc / (e - s)", "out[h, i] = acc / (e - s + 1)"),
+    ("mean_is_a_sum", "out[h, i] = acc / (e - s)", "out[h, i] = acc"),
+    ("mean_skips_first_token", "for t in range(s, e):\n                acc += X[h, t]", "for t in range(s + 1, e):\n                acc += X[h, t]"),
+    ("mean_score_gqa_mapping", "s[h, i] = float(np.dot(q[h], kmean[h // G, i]))", "s[h, i] = float(np.dot(q[h], kmean[h % Hkv, i]))"),
     ("lse_forgets_max", "return o, float(m + math.log(den))", "return o, float(math.log(den))"),
 ]
 

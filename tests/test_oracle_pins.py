@@ -390,6 +390,32 @@ def test_select_slots_general_b_and_budget_all():
     assert list(toks) == [0, 1, 2, 3, 4, 16, 17, 18, 19]
 
 
+# ---------------------------------------------------------------- mean pooling (App. A.2)
+def test_block_means_and_their_scores():
+    r = rng(40)
+    H, L, D = 3, 97, 8
+    X = r.standard_normal((H, L, D))
+    bs = np.asarray([0, 1, 9, 10, 40, 41, 97])
+    m = O.block_means(X, bs)
+    for h in range(H):
+        ref = np.add.reduceat(X[h], bs[:-1], axis=0) / np.diff(bs)[:, None]
+        np.testing.assert_allclose(m[h], ref, rtol=0, atol=1e-14)
+    np.testing.assert_array_equal(m[:, 0], X[:, 0])                     # one-token block: the token
+    np.testing.assert_allclose(O.block_means(np.ones((1, 12, 4)) * 2.5, np.asarray([0, 5, 12])), 2.5)
+    # scores: a plain dot product per (query head, block), GQA head h reads KV head h // G
+    q = r.standard_normal((6, D))
+    s = O.block_scores_mean(q, m)
+    ref = np.einsum("hgd,hid->hgi", q.reshape(3, 2, D), m).reshape(6, -1)
+    np.testing.assert_allclose(s, ref, atol=1e-13)
+    # the (min,max) score of a degenerate box [m, m] is the same dot product: what lets a
+    # mean summary stored in both rows go through the unchanged score path
+    np.testing.assert_allclose(O.block_scores(q, m, m), s, atol=1e-13)
+    # linearity pins the mean itself: q . mean(K_block) = mean_t (q . K_t)
+    tok = np.einsum("hd,htd->ht", q[::2], X)                             # heads 0, 2, 4 -> KV heads 0, 1, 2
+    for i in range(len(bs) - 1):
+        np.testing.assert_allclose(s[::2, i], tok[:, bs[i]: bs[i + 1]].mean(axis=1), atol=1e-13)
+
+
 # ---------------------------------------------------------------- incremental update
 def _random_stream(r, L, n_class=4):
     isd = r.random(L) < r.choice([0.02, 0.1, 0.5])
