@@ -58,6 +58,8 @@ typedef enum dsk_status {
 
 /* Stages of dsk_compress (bit mask).  A stage that is not run takes its inputs from the
  * buffers the earlier stage would have written. */
+enum { DSK_SUMMARY_MINMAX = 0, DSK_SUMMARY_MEAN = 1 };
+
 enum {
   DSK_STAGE_CANDIDATES = 1, /* token_ids + delim_ids -> cand_pos/cand_class/cand_cu (+ samp_pos) */
   DSK_STAGE_IMPORTANCE = 2, /* samp_pos + qwin + K -> class_weight_q (Alg. 1) */
@@ -92,6 +94,10 @@ enum {
  *   possibly shorter.
  * Stage SUMMARIES (Sec. 4.2, KVCache Compression): element-wise minimum and maximum of K
  *   (and of V when vsum != NULL) over the tokens of every block, exact in bf16.
+ *   summary_mode DSK_SUMMARY_MEAN (the mean-pooling variant of App. A.2, everything else
+ *   unchanged): the per-channel mean instead -- fp32 sum in a fixed order, divided by the
+ *   block length, rounded to nearest-even bf16 -- written to both rows of the record, so that
+ *   the score of dsk_select_topk, sum_d max(q_d*m_d, q_d*m_d), is the dot product q.m.
  * ---------------------------------------------------------------------------------------- */
 typedef struct dsk_compress_args {
   uint32_t struct_size;        /* sizeof(dsk_compress_args) */
@@ -146,9 +152,11 @@ typedef struct dsk_compress_args {
   int32_t* slot_base;          /* [dev] [max_blocks_total+4] (entries 0..max_blocks_total used;
                                   dsk_select_topk reads it in 16-byte vectors) */
 
-  /* summaries: [Hkv, max_blocks_total, 2, D] bf16; [.., 0, :] = min, [.., 1, :] = max */
+  /* summaries: [Hkv, max_blocks_total, 2, D] bf16; [.., 0, :] = min, [.., 1, :] = max
+     (DSK_SUMMARY_MEAN: both rows hold the mean) */
   void* ksum;                  /* [dev] */
   void* vsum;                  /* [dev] or NULL */
+  int32_t summary_mode;        /* DSK_SUMMARY_MINMAX (0) or DSK_SUMMARY_MEAN */
 
   int32_t* dev_status;         /* [dev] optional; must be zeroed by the caller */
   void* workspace;             /* [dev] */
@@ -286,6 +294,7 @@ typedef struct dsk_append_args {
   int32_t* slot_base;          /* [dev] in/out [max_blocks_total + 4] */
   void* ksum;                  /* [dev] in/out bf16 [Hkv, max_blocks_total, 2, D] */
   void* vsum;                  /* [dev] in/out or NULL */
+  int32_t summary_mode;        /* as in dsk_compress_args */
   int32_t* first_recomputed;   /* [dev] optional out: index of the first rewritten chunk */
   int32_t* dev_status;         /* [dev] optional */
   void* workspace;             /* [dev] 256-byte aligned, dsk_append_workspace_bytes() */

@@ -33,6 +33,7 @@ DSK_STAGE_ALL = 15
 DSK_HEAD_DIM = 128
 DSK_MAX_CLASSES = 64
 DSK_ATTN_PARTIALS_ONLY = 1
+DSK_SUMMARY_MINMAX, DSK_SUMMARY_MEAN = 0, 1
 
 _p = C.c_void_p
 
@@ -58,6 +59,7 @@ class dsk_compress_args(C.Structure):
         ("b", C.c_int32), ("max_blocks_total", C.c_int32),
         ("block_start", _p), ("cu_blocks", _p), ("slot_base", _p),
         ("ksum", _p), ("vsum", _p),
+        ("summary_mode", C.c_int32),
         ("dev_status", _p),
         ("workspace", _p), ("workspace_bytes", C.c_size_t),
     ]
@@ -122,6 +124,7 @@ class dsk_append_args(C.Structure):
         ("max_blocks_total", C.c_int32),
         ("block_start", _p), ("cu_blocks", _p), ("slot_base", _p),
         ("ksum", _p), ("vsum", _p),
+        ("summary_mode", C.c_int32),
         ("first_recomputed", _p), ("dev_status", _p),
         ("workspace", _p), ("workspace_bytes", C.c_size_t),
     ]
@@ -317,7 +320,7 @@ def compress(*, cu_seqlens: torch.Tensor, max_seqlen: int, Hq: int, K: Optional[
              max_blocks_total: Optional[int] = None, block_start: Optional[torch.Tensor] = None,
              cu_blocks: Optional[torch.Tensor] = None, slot_base: Optional[torch.Tensor] = None,
              want_vsum: bool = False, Hkv: Optional[int] = None, total_tokens: Optional[int] = None,
-             stream=None, check: bool = True) -> Compressed:
+             summary_mode: int = DSK_SUMMARY_MINMAX, stream=None, check: bool = True) -> Compressed:
     """Allocate outputs / workspace with torch, fill dsk_compress_args and call dsk_compress.
 
     `total_tokens` defaults to the token extent of K (or of token_ids).  Buffers a skipped
@@ -382,6 +385,7 @@ def compress(*, cu_seqlens: torch.Tensor, max_seqlen: int, Hq: int, K: Optional[
         if want_vsum:
             vsum = torch.empty_like(ksum)
     a.ksum, a.vsum = _ptr(ksum), _ptr(vsum)
+    a.summary_mode = summary_mode
     dev_status = torch.zeros(1, **i32)
     a.dev_status = _ptr(dev_status)
     ws = _ws(dsk_compress_workspace_bytes(a), dev)
@@ -559,6 +563,7 @@ def make_appender(comp: Compressed, K: torch.Tensor, V: Optional[torch.Tensor], 
     a.max_blocks_total = comp.args.max_blocks_total
     a.block_start, a.cu_blocks, a.slot_base = _ptr(comp.block_start), _ptr(comp.cu_blocks), _ptr(comp.slot_base)
     a.ksum, a.vsum = _ptr(comp.ksum), _ptr(comp.vsum)
+    a.summary_mode = comp.args.summary_mode
     first = torch.zeros(1, dtype=torch.int32, device=dev)
     a.first_recomputed = _ptr(first)
     a.dev_status = _ptr(comp.dev_status)

@@ -77,6 +77,7 @@ static dsk_status validate_compress(const dsk_compress_args* a) {
   }
   if (st_seg && a->slot_base == nullptr) return DSK_ERR_NULL;
   if (st_sum) {
+    if (a->summary_mode != DSK_SUMMARY_MINMAX && a->summary_mode != DSK_SUMMARY_MEAN) return DSK_ERR_PARAM;
     if (a->K == nullptr || a->ksum == nullptr) return DSK_ERR_NULL;
     if (a->vsum != nullptr && a->V == nullptr) return DSK_ERR_NULL;
     if (!aligned16(a->ksum) || (a->vsum && !aligned16(a->vsum))) return DSK_ERR_ALIGN;
@@ -147,6 +148,7 @@ static dsk_status validate_append(const dsk_append_args* a) {
   if (a->alpha_den < 1 || a->alpha_den > 1000 || a->alpha_num < 0 || a->alpha_num > a->alpha_den)
     return DSK_ERR_PARAM;
   if (a->b < 1 || a->b > 1024 || a->max_blocks_total < 1) return DSK_ERR_PARAM;
+  if (a->summary_mode != DSK_SUMMARY_MINMAX && a->summary_mode != DSK_SUMMARY_MEAN) return DSK_ERR_PARAM;
   if (!a->K || !a->token_ids || !a->delim_ids || !a->class_weight_q || !a->block_start || !a->cu_blocks ||
       !a->slot_base || !a->ksum)
     return DSK_ERR_NULL;

@@ -20,6 +20,13 @@ __device__ __forceinline__ uint32_t pack_bf16_exact(float lo, float hi) {
   return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xFFFF0000u);
 }
 
+// nearest bf16 value (ties to even) of a finite float, returned as a float
+__device__ __forceinline__ float bf16_round_rne(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return __uint_as_float(u & 0xFFFF0000u);
+}
+
 // 8 bf16 values (one 16-byte vector) widened to fp32
 __device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
   f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x);

@@ -77,7 +77,8 @@ hipError_t launch_dense_attn(const dsk_dense_attn_args& a, const DenseWs& ws, hi
 // summaries of the blocks [blk_range[0], blk_range[1]) only (device-resident range)
 hipError_t launch_summaries_range(const void* X, int64_t stride_tok, int64_t stride_head, int Hkv,
                                   const int32_t* block_start, const int32_t* blk_range, int max_blocks_in_range,
-                                  int cap, int total_tokens, void* out, int32_t* dev_status, hipStream_t st);
+                                  int cap, int total_tokens, int summary_mode, void* out, int32_t* dev_status,
+                                  hipStream_t st);
 // incremental update: workspace = int32 {first recomputed block, new block count}
 hipError_t launch_append(const dsk_append_args& a, hipStream_t st);
 

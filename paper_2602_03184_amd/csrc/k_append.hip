@@ -110,10 +110,10 @@ hipError_t launch_append(const dsk_append_args& a, hipStream_t st) {
   int64_t max_changed = span / (a.C - a.delta) + 2;
   if (max_changed > a.max_blocks_total) max_changed = a.max_blocks_total;
   err = launch_summaries_range(a.K, a.k_stride_tok, a.k_stride_head, a.Hkv, a.block_start, range, (int)max_changed,
-                               a.max_blocks_total, a.len_new, a.ksum, a.dev_status, st);
+                               a.max_blocks_total, a.len_new, a.summary_mode, a.ksum, a.dev_status, st);
   if (err != hipSuccess || a.vsum == nullptr) return err;
   return launch_summaries_range(a.V, a.v_stride_tok, a.v_stride_head, a.Hkv, a.block_start, range, (int)max_changed,
-                                a.max_blocks_total, a.len_new, a.vsum, a.dev_status, st);
+                                a.max_blocks_total, a.len_new, a.summary_mode, a.vsum, a.dev_status, st);
 }
 
 }  // namespace dsk

@@ -20,6 +20,7 @@ constexpr int kSumUnroll = DSK_SUM_UNROLL;  // row-groups of 4 rows in flight pe
 #endif
 
 // 8 waves per SIMD (32 per CU) so that one launch keeps every wave of the grid resident
+template <bool MEAN>
 __global__ __launch_bounds__(kSumThreads) DSK_SUM_OCC void summaries_kernel(
     const uint16_t* __restrict__ X, int64_t stride_tok, int64_t stride_head, int Hkv,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ cu_blocks, int B,
@@ -67,9 +68,10 @@ __global__ __launch_bounds__(kSumThreads) DSK_SUM_OCC void summaries_kernel(
       if (lane == 0) set_status(dev_status, DSK_ERR_SHAPE);
     } else {
       const uint16_t* base = X + (int64_t)h * stride_head + (int64_t)s * stride_tok;   // uniform
+      // MEAN: mn[] holds this lane's running sums instead
       float mn[8], mx[8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) { mn[k] = __builtin_inff(); mx[k] = -__builtin_inff(); }
+      for (int k = 0; k < 8; ++k) { mn[k] = MEAN ? 0.0f : __builtin_inff(); mx[k] = -__builtin_inff(); }
       for (int r0 = 0; r0 < len; r0 += 4 * kSumUnroll) {
         // scalar 64-bit base of this row batch + 32-bit lane offsets (stride_tok <= 2^24, host-checked)
         const char* rb = reinterpret_cast<const char*>(base + (int64_t)r0 * stride_tok);
@@ -86,14 +88,33 @@ __global__ __launch_bounds__(kSumThreads) DSK_SUM_OCC void summaries_kernel(
         for (int u = 0; u < kSumUnroll; ++u) {
           float f[8];
           unpack8(v[u], f);
+          if constexpr (MEAN) {
+            const bool real = 4 * u + g <= last;         // a repeated row must not be added again
 #pragma unroll
-          for (int k = 0; k < 8; ++k) { mn[k] = fminf(mn[k], f[k]); mx[k] = fmaxf(mx[k], f[k]); }
+            for (int k = 0; k < 8; ++k) mn[k] += real ? f[k] : 0.0f;
+          } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { mn[k] = fminf(mn[k], f[k]); mx[k] = fmaxf(mx[k], f[k]); }
+          }
         }
       }
+      if constexpr (MEAN) {
+        // fixed order: rows of a lane group in token order, then (g0 + g1) + (g2 + g3); the mean
+        // rounded to nearest-even bf16 goes into both rows of the record
+        const float inv_den = (float)len;
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        mn[k] = fminf(mn[k], shfl_xor_f(mn[k], 16)); mx[k] = fmaxf(mx[k], shfl_xor_f(mx[k], 16));
-        mn[k] = fminf(mn[k], shfl_xor_f(mn[k], 32)); mx[k] = fmaxf(mx[k], shfl_xor_f(mx[k], 32));
+        for (int k = 0; k < 8; ++k) {
+          mn[k] += shfl_xor_f(mn[k], 16);
+          mn[k] += shfl_xor_f(mn[k], 32);
+          mn[k] = bf16_round_rne(mn[k] / inv_den);
+          mx[k] = mn[k];
+        }
+      } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          mn[k] = fminf(mn[k], shfl_xor_f(mn[k], 16)); mx[k] = fmaxf(mx[k], shfl_xor_f(mx[k], 16));
+          mn[k] = fminf(mn[k], shfl_xor_f(mn[k], 32)); mx[k] = fmaxf(mx[k], shfl_xor_f(mx[k], 32));
+        }
       }
       if (g == 0) {
         reinterpret_cast<uint4*>(o)[c] = make_uint4(pack_bf16_exact(mn[0], mn[1]), pack_bf16_exact(mn[2], mn[3]),
@@ -108,19 +129,20 @@ __global__ __launch_bounds__(kSumThreads) DSK_SUM_OCC void summaries_kernel(
   }
 }
 
-hipError_t launch_summaries(const dsk_compress_args& a, hipStream_t st) {
+template <bool MEAN>
+static hipError_t launch_summaries_impl(const dsk_compress_args& a, hipStream_t st) {
   const int64_t max_items = (int64_t)a.Hkv * a.max_blocks_total;
   if (max_items <= 0) return hipSuccess;
   int64_t wgs = (max_items + kSumWaves - 1) / kSumWaves;
   const int64_t max_wgs = 256 * 8;   // 8 workgroups (32 waves) per CU keeps HBM requests deep
   if (wgs > max_wgs) wgs = max_wgs;
-  summaries_kernel<<<dim3((unsigned)wgs), dim3(kSumThreads), 0, st>>>(
+  summaries_kernel<MEAN><<<dim3((unsigned)wgs), dim3(kSumThreads), 0, st>>>(
       static_cast<const uint16_t*>(a.K), a.k_stride_tok, a.k_stride_head, a.Hkv, a.block_start,
       a.cu_blocks, a.B, nullptr, a.max_blocks_total, a.total_tokens, static_cast<uint16_t*>(a.ksum), a.dev_status);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   if (a.vsum != nullptr) {
-    summaries_kernel<<<dim3((unsigned)wgs), dim3(kSumThreads), 0, st>>>(
+    summaries_kernel<MEAN><<<dim3((unsigned)wgs), dim3(kSumThreads), 0, st>>>(
         static_cast<const uint16_t*>(a.V), a.v_stride_tok, a.v_stride_head, a.Hkv, a.block_start,
         a.cu_blocks, a.B, nullptr, a.max_blocks_total, a.total_tokens, static_cast<uint16_t*>(a.vsum), a.dev_status);
     err = hipGetLastError();
@@ -128,16 +150,26 @@ hipError_t launch_summaries(const dsk_compress_args& a, hipStream_t st) {
   return err;
 }
 
+hipError_t launch_summaries(const dsk_compress_args& a, hipStream_t st) {
+  return a.summary_mode == DSK_SUMMARY_MEAN ? launch_summaries_impl<true>(a, st) : launch_summaries_impl<false>(a, st);
+}
+
 hipError_t launch_summaries_range(const void* X, int64_t stride_tok, int64_t stride_head, int Hkv,
                                   const int32_t* block_start, const int32_t* blk_range, int max_blocks_in_range,
-                                  int cap, int total_tokens, void* out, int32_t* dev_status, hipStream_t st) {
+                                  int cap, int total_tokens, int summary_mode, void* out, int32_t* dev_status,
+                                  hipStream_t st) {
   const int64_t max_items = (int64_t)Hkv * max_blocks_in_range;
   if (max_items <= 0) return hipSuccess;
   int64_t wgs = (max_items + kSumWaves - 1) / kSumWaves;
   if (wgs > 256 * 8) wgs = 256 * 8;
-  summaries_kernel<<<dim3((unsigned)wgs), dim3(kSumThreads), 0, st>>>(
-      static_cast<const uint16_t*>(X), stride_tok, stride_head, Hkv, block_start, nullptr, 0, blk_range, cap,
-      total_tokens, static_cast<uint16_t*>(out), dev_status);
+  if (summary_mode == DSK_SUMMARY_MEAN)
+    summaries_kernel<true><<<dim3((unsigned)wgs), dim3(kSumThreads), 0, st>>>(
+        static_cast<const uint16_t*>(X), stride_tok, stride_head, Hkv, block_start, nullptr, 0, blk_range, cap,
+        total_tokens, static_cast<uint16_t*>(out), dev_status);
+  else
+    summaries_kernel<false><<<dim3((unsigned)wgs), dim3(kSumThreads), 0, st>>>(
+        static_cast<const uint16_t*>(X), stride_tok, stride_head, Hkv, block_start, nullptr, 0, blk_range, cap,
+        total_tokens, static_cast<uint16_t*>(out), dev_status);
   return hipGetLastError();
 }
 

@@ -88,6 +88,28 @@ def oracle_summaries(Xbits: np.ndarray, block_start: np.ndarray, heads=None):
     return np.stack(mins), np.stack(maxs)
 
 
+def oracle_means_bf16(Xbits: np.ndarray, block_start: np.ndarray, heads=None) -> np.ndarray:
+    """fp64 block means of the oracle, as floats (not yet rounded to bf16), [len(heads), nblk, D]."""
+    heads = range(Xbits.shape[0]) if heads is None else heads
+    return np.stack([O.block_means(O.widen_bf16(Xbits[h])[None], block_start)[0] for h in heads])
+
+
+def assert_bf16_of(got_bits: np.ndarray, exact: np.ndarray, max_off_frac: float = 2e-3) -> float:
+    """got_bits must be the bf16 rounding (nearest even) of `exact`, except that an fp32-accumulated
+    mean may land on the neighbouring bf16 value when the exact mean sits next to a rounding
+    midpoint: every element within one bf16 step, and only a small fraction off at all."""
+    from workloads import f32_to_bf16_bits
+    want_bits = f32_to_bf16_bits(exact.astype(np.float32))
+    got = O.widen_bf16(got_bits)
+    want = O.widen_bf16(want_bits)
+    off = canon_zero(got_bits) != canon_zero(want_bits)
+    step = np.maximum(np.abs(want), np.abs(got)) * 2.0 ** -7 + 1e-38      # one bf16 step is at most this
+    assert (np.abs(got - want)[off] <= step[off]).all(), "a mean is more than one bf16 step from the oracle"
+    frac = float(off.mean())
+    assert frac <= max_off_frac, "fraction of means off by one bf16 step: %.2e" % frac
+    return frac
+
+
 def selection_check(gpu_slots: np.ndarray, ora_slots: np.ndarray, tau: float, block_score: np.ndarray,
                     slot_base: np.ndarray, rel: float = 1e-4) -> int:
     """Bit-exact set equality, except that a slot may differ when its block's oracle score is
@@ -119,6 +141,7 @@ class GpuCase:
 
     def __init__(self, cfg_id: int, **overrides):
         from workloads import make_workload
+        self.summary_mode = overrides.pop("summary_mode", 0)     # 0 = (min,max), 1 = mean pooling
         self.wl = make_workload(cfg_id, with_kv=True, with_qwin=False, **overrides)
         wl = self.wl
         self.cfg = wl.cfg
@@ -142,7 +165,7 @@ class GpuCase:
                  C_per_seq=self.C_per_seq if cfg.B > 1 else None,
                  delta_per_seq=self.delta_per_seq if cfg.B > 1 else None,
                  min_chunk=int((wl.C - wl.delta).min()),
-                 alpha_num=cfg.a_num, alpha_den=cfg.a_den, b=cfg.b)
+                 alpha_num=cfg.a_num, alpha_den=cfg.a_den, b=cfg.b, summary_mode=self.summary_mode)
         d.update(kw)
         return d
 

@@ -49,7 +49,8 @@ int main(void) {
   printf("%zu %zu ", offsetof(dsk_select_args, budget), offsetof(dsk_select_args, workspace_bytes));
   printf("%zu %zu %zu ", offsetof(dsk_attn_args, total_tokens), offsetof(dsk_attn_args, scale), offsetof(dsk_attn_args, workspace_bytes));
   printf("%zu %zu %zu %zu ", sizeof(dsk_dense_attn_args), offsetof(dsk_dense_attn_args, cu_seqlens), offsetof(dsk_dense_attn_args, scale), offsetof(dsk_dense_attn_args, workspace_bytes));
-  printf("%zu %zu\n", sizeof(dsk_attn_partials), offsetof(dsk_attn_partials, nchunks));
+  printf("%zu %zu ", sizeof(dsk_attn_partials), offsetof(dsk_attn_partials, nchunks));
+  printf("%zu %zu %zu %zu\n", offsetof(dsk_compress_args, summary_mode), sizeof(dsk_append_args), offsetof(dsk_append_args, summary_mode), offsetof(dsk_append_args, workspace_bytes));
   return 0;
 }''')
     exe = tmp_path / "sizes"
@@ -62,6 +63,8 @@ int main(void) {
     da, pa = dsk.dsk_dense_attn_args, dsk.dsk_attn_partials
     want += [C.sizeof(da), da.cu_seqlens.offset, da.scale.offset, da.workspace_bytes.offset, C.sizeof(pa),
              pa.nchunks.offset]
+    ap = dsk.dsk_append_args
+    want += [ca.summary_mode.offset, C.sizeof(ap), ap.summary_mode.offset, ap.workspace_bytes.offset]
     assert got == want
 
 

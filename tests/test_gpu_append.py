@@ -22,7 +22,7 @@ class _Seq:
     compression of its first L0 tokens."""
 
     def __init__(self, K_bits, V_bits, token_ids, delim_ids, wq, L0, C, delta, a_num, a_den, b, want_vsum=False,
-                 max_blocks_total=None, Hq=None):
+                 max_blocks_total=None, Hq=None, summary_mode=0):
         dsk = _dsk()
         self.dsk = dsk
         self.K_bits, self.V_bits = K_bits, V_bits
@@ -39,7 +39,7 @@ class _Seq:
             stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_SEGMENT | dsk.DSK_STAGE_SUMMARIES,
             token_ids=self.d_tok, delim_ids=self.d_delim, n_class=len(self.delim), class_weight_q=self.d_wq,
             C_=C, delta=delta, alpha_num=a_num, alpha_den=a_den, b=b, total_tokens=L_first,
-            max_cand_total=self.L_cap, max_blocks_total=cap, want_vsum=want_vsum)
+            max_cand_total=self.L_cap, max_blocks_total=cap, want_vsum=want_vsum, summary_mode=summary_mode)
         if L0 == 0:
             torch.cuda.synchronize()
             self.comp.cu_blocks.zero_()
