@@ -17,7 +17,7 @@ constexpr int kMergeThreads = 256;
 constexpr int kMergeGroups = kMergeThreads / 16;
 
 // slots per workgroup for a slot length bound b
-__host__ __device__ constexpr int attn_slots_per_wg(int b) { return b <= 16 ? 16 : 8; }
+__host__ __device__ constexpr int attn_slots_per_wg(int b) { return b <= 32 ? 16 : 8; }
 
 // ordinary (compiler-scheduled) loads; used for slots longer than 32 rows
 template <int NS>
@@ -309,8 +309,12 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
       a.lse
   // Measured on config 3 (b = 32): one slot (16 KB) in flight per wavefront, the next slot issued
   // after the fold (STAGED), 9.9 us; both slots issued up front 10.9 us; 8 wavefronts x 1 slot 10.3 us.
-  if (a.b <= 16) attn_kernel<4, 4, 4, true><<<grid, dim3(256), 0, st>>>(DSK_ATTN_ARGS);       // 16 slots per workgroup
-  else if (a.b <= 32) attn_kernel<8, 2, 4, true><<<grid, dim3(256), 0, st>>>(DSK_ATTN_ARGS);  // 8 slots per workgroup
+  // Slots of at most 32 rows: workgroups of 8 wavefronts, 2 slots each (16 slots per workgroup).
+  // Measured against 4 wavefronts x 2 or 4 slots, 8 x 1 or 4, 16 x 1 or 2 on all configurations:
+  // the gather takes 7.3 instead of 8.6 us at 128K / b = 32, and 4.6 instead of 5.6 us at
+  // 32K / b = 16 (half as many workgroups to dispatch and half as many partials to merge).
+  if (a.b <= 16) attn_kernel<4, 2, 8, false><<<grid, dim3(512), 0, st>>>(DSK_ATTN_ARGS);
+  else if (a.b <= 32) attn_kernel<8, 2, 8, true><<<grid, dim3(512), 0, st>>>(DSK_ATTN_ARGS);
   else attn_kernel<0, 2, 4><<<grid, dim3(256), 0, st>>>(DSK_ATTN_ARGS);
 #undef DSK_ATTN_ARGS
   hipError_t err = hipGetLastError();
