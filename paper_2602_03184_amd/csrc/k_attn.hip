@@ -13,8 +13,9 @@
 
 namespace dsk {
 
-constexpr int kMergeThreads = 256;
-constexpr int kMergeGroups = kMergeThreads / 16;
+#ifndef DSK_MERGE_BIG
+#define DSK_MERGE_BIG 1024
+#endif
 
 // slots per workgroup for a slot length bound b
 __host__ __device__ constexpr int attn_slots_per_wg(int b) { return b <= 32 ? 16 : 8; }
@@ -209,10 +210,12 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
 // Merge of the partials of one (sequence, head) in a fixed order: 16 lane groups each fold the
 // chunks ch = group, group+16, ... (all loads of a round are independent), then one pass over
 // the 16 group states in LDS.  Heads with a single chunk were finished by attn_kernel.
+template <int kMergeThreads>
 __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
     const float2* __restrict__ part_ml, const float* __restrict__ part_acc,
     const int32_t* __restrict__ sel_count, const int32_t* __restrict__ cu_seqlens, int Hq, int k, int nchunks,
     int slots_per_wg, float* __restrict__ out, float* __restrict__ lse) {
+  constexpr int kMergeGroups = kMergeThreads / 16;
   __shared__ float sm_m[kMergeGroups];
   __shared__ float sm_l[kMergeGroups];
   __shared__ float sm_acc[kMergeGroups][DSK_HEAD_DIM];
@@ -326,8 +329,17 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
 hipError_t launch_attn_merge(const float2* part_ml, const float* part_acc, const int32_t* counts,
                              const int32_t* cu_seqlens, int B, int Hq, int k, int nchunks, int per_chunk, float* out,
                              float* lse, hipStream_t st) {
-  attn_merge_kernel<<<dim3((unsigned)(B * Hq)), dim3(kMergeThreads), 0, st>>>(
-      part_ml, part_acc, counts, cu_seqlens, Hq, k, nchunks, per_chunk, out, lse);
+  // one lane group of 16 per partial when there are few, several partials per group otherwise
+  const dim3 grid((unsigned)(B * Hq));
+  if (nchunks <= 8)
+    attn_merge_kernel<128><<<grid, dim3(128), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, k, nchunks, per_chunk,
+                                                       out, lse);
+  else if (nchunks <= 32)
+    attn_merge_kernel<256><<<grid, dim3(256), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, k, nchunks, per_chunk,
+                                                       out, lse);
+  else
+    attn_merge_kernel<DSK_MERGE_BIG><<<grid, dim3(DSK_MERGE_BIG), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, k,
+                                                                           nchunks, per_chunk, out, lse);
   return hipGetLastError();
 }
 

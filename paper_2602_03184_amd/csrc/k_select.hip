@@ -2,8 +2,8 @@
 // (sequence, query head).
 //
 // Every fixed-length slot inherits the score of its semantic block, so the k best slots are
-// found on the block scores with each block weighted by its slot count.  Thread t owns the
-// kSelPerThread consecutive blocks [t*16, t*16+16) of the sequence: their keys (order-preserving
+// found on the block scores with each block weighted by its slot count.  Thread t of the 1024
+// owns PT (4 or 8) consecutive blocks [t*PT, t*PT+PT) of the sequence: their keys (order-preserving
 // integer images of the scores) and slot counts live in registers, fetched with 16-byte loads
 // that are all in flight at once.
 //   1. key range and slot total (workgroup reduction);
@@ -21,9 +21,9 @@
 
 namespace dsk {
 
-constexpr int kSelThreads = 512;
+constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / DSK_WAVE;
-constexpr int kSelMaxPerThread = 16;                    // blocks per thread: 4, 8 or 16 (register tile of 2048, 4096 or 8192)
+constexpr int kSelMaxPerThread = 8;                     // blocks per thread: 4 or 8 (register tile of 4096 or 8192)
 constexpr int kSelWork = 1024;                          // chosen blocks staged in LDS per emission round
 
 // does a sequence of n blocks fit a register tile of `per_thread` blocks per thread whatever
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ slot_base, int cap, int Hq,
     int b, int k, int32_t* __restrict__ sel_slot, int32_t* __restrict__ sel_start,
     int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
-  static_assert(PT == 4 || PT == 8 || PT == 16, "register tile");
+  static_assert(PT == 4 || PT == 8, "register tile");
   constexpr int kSelPerThread = PT;
   constexpr int kSelVecs = PT / 4;
   __shared__ SelShared sh;
@@ -485,7 +485,6 @@ hipError_t launch_select(const dsk_select_args& a, const float* scores, int stri
   scores, stride, a.cu_blocks, a.block_start, a.slot_base, a.max_blocks_total, a.Hq, a.b, k, a.sel_slot, a.sel_start, \
       a.sel_len, a.sel_count
   if (sel_fits_tile(bound, 4)) select_kernel<4><<<grid, dim3(kSelThreads), 0, st>>>(DSK_SEL_ARGS);
-  else if (sel_fits_tile(bound, 8)) select_kernel<8><<<grid, dim3(kSelThreads), 0, st>>>(DSK_SEL_ARGS);
   else select_kernel<kSelMaxPerThread><<<grid, dim3(kSelThreads), 0, st>>>(DSK_SEL_ARGS);
 #undef DSK_SEL_ARGS
   return hipGetLastError();
