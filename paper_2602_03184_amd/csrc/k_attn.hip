@@ -3,8 +3,10 @@
 // there is no MFMA here: a 256-byte bf16 row is spread over 16 lanes x 16 B and a wavefront
 // reads 4 token rows per load instruction.  A wavefront owns SPW slots of at most 4*NS rows; it
 // issues every K and V load of a slot (16 x 16 B per lane, 16 KB per wavefront for 32 rows)
-// before it touches the data, then folds the slot into an online-softmax state (m, l, acc).  The 4 wavefronts of a workgroup merge through LDS into one partial per
-// (sequence, head, chunk of slots); a second small kernel merges the partials in a fixed order
+// before it touches the data, then folds the slot into an online-softmax state (m, l, acc).
+// The wavefronts of a workgroup (8 for slots of up to 32 rows, 2 slots each) merge through LDS
+// into one partial per (sequence, head, chunk of 16 slots); a second small kernel merges the
+// partials in a fixed order
 // (a single-kernel merge was measured slower: both a device-wide fence per workgroup and
 // write-through partials with an arrival counter cost more than the extra launch).
 #include "dsk_attn_fold.hpp"
