@@ -2,8 +2,8 @@
 // (sequence, query head).
 //
 // Every fixed-length slot inherits the score of its semantic block, so the k best slots are
-// found on the block scores with each block weighted by its slot count.  Thread t of the 1024
-// owns PT (4 or 8) consecutive blocks [t*PT, t*PT+PT) of the sequence: their keys (order-preserving
+// found on the block scores with each block weighted by its slot count.  Thread t of the 256,
+// 512 or 1024 (by the host's bound on the block count) owns PT (4 or 8) consecutive blocks [t*PT, t*PT+PT) of the sequence: their keys (order-preserving
 // integer images of the scores) and slot counts live in registers, fetched with 16-byte loads
 // that are all in flight at once.
 //   1. key range and slot total (workgroup reduction);
@@ -21,21 +21,23 @@
 
 namespace dsk {
 
-constexpr int kSelThreads = 1024;
-constexpr int kSelWaves = kSelThreads / DSK_WAVE;
+constexpr int kSelMaxThreads = 1024;                    // workgroups of 256, 512 or 1024 threads by block count
+constexpr int kSelMaxWaves = kSelMaxThreads / DSK_WAVE;
 constexpr int kSelMaxPerThread = 8;                     // blocks per thread: 4 or 8 (register tile of 4096 or 8192)
 constexpr int kSelWork = 1024;                          // chosen blocks staged in LDS per emission round
 
 // does a sequence of n blocks fit a register tile of `per_thread` blocks per thread whatever
 // its alignment shift (0..3)?
-__host__ __device__ constexpr bool sel_fits_tile(int n, int per_thread) { return n + 3 <= kSelThreads * per_thread; }
+__host__ __device__ constexpr bool sel_fits_tile(int n, int per_thread, int threads) {
+  return n + 3 <= threads * per_thread;
+}
 
 struct SelShared {
   uint32_t hist[256];
-  int wave_tot[kSelWaves];
-  uint32_t red_min[kSelWaves], red_max[kSelWaves];
-  int red_sum[kSelWaves];
-  int wave_tot2[2 * kSelWaves];
+  int wave_tot[kSelMaxWaves];
+  uint32_t red_min[kSelMaxWaves], red_max[kSelMaxWaves];
+  int red_sum[kSelMaxWaves];
+  int wave_tot2[2 * kSelMaxWaves];
   int digit, krem;
   int n_work;
   int4 work[kSelWork];                 // (first token, end token, first slot, output offset)
@@ -53,6 +55,7 @@ extern "C" __attribute__((visibility("default"))) void dsk_debug_read(long long*
 #endif
 
 // exclusive prefix sum of one int per thread over the workgroup, in thread order
+template <int NW>
 __device__ __forceinline__ int wg_excl_scan(int v, int* wave_tot, int& total) {
   const int lane = threadIdx.x & (DSK_WAVE - 1);
   const int wave = threadIdx.x / DSK_WAVE;
@@ -63,7 +66,7 @@ __device__ __forceinline__ int wg_excl_scan(int v, int* wave_tot, int& total) {
   int off = 0;
   total = 0;
 #pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) {
+  for (int w = 0; w < NW; ++w) {
     const int t = wave_tot[w];
     if (w < wave) off += t;
     total += t;
@@ -72,6 +75,7 @@ __device__ __forceinline__ int wg_excl_scan(int v, int* wave_tot, int& total) {
 }
 
 // the same for two ints per thread at once
+template <int NW>
 __device__ __forceinline__ void wg_excl_scan2(int a, int b, int* wave_tot2, int& a_excl, int& b_excl) {
   const int lane = threadIdx.x & (DSK_WAVE - 1);
   const int wave = threadIdx.x / DSK_WAVE;
@@ -82,7 +86,7 @@ __device__ __forceinline__ void wg_excl_scan2(int a, int b, int* wave_tot2, int&
   __syncthreads();
   int oa = 0, ob = 0;
 #pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) {
+  for (int w = 0; w < NW; ++w) {
     if (w < wave) { oa += wave_tot2[2 * w]; ob += wave_tot2[2 * w + 1]; }
   }
   a_excl = oa + ia - a;
@@ -126,6 +130,7 @@ __device__ __forceinline__ void write_padding(int count, int k, int64_t obase, i
 
 // Same algorithm for sequences whose blocks do not fit the register tile: keys and slot counts
 // are re-read from memory (L2) in every pass; thread t owns a contiguous range of blocks.
+template <int THREADS>
 __device__ __noinline__ void select_big(
     SelShared& sh, const float* __restrict__ scores, int stride, const int32_t* __restrict__ cu_blocks,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ slot_base, int cap, int Hq,
@@ -143,11 +148,12 @@ __device__ __noinline__ void select_big(
   int blk1 = cu_blocks[s + 1];
   if (blk1 > cap) blk1 = cap;
   const int n = blk1 - blk0;
-  if (n <= 0 || sel_fits_tile(n, per_thread)) return;    // not ours
+  constexpr int NW = THREADS / DSK_WAVE;
+  if (n <= 0 || sel_fits_tile(n, per_thread, THREADS)) return;    // not ours
   const float* sc = scores + (int64_t)h * stride + blk0;
   const int32_t* sb = slot_base + blk0;
   const int32_t* bs = block_start + blk0;
-  const int per = (n + kSelThreads - 1) / kSelThreads;
+  const int per = (n + THREADS - 1) / THREADS;
   const int i0 = tid * per < n ? tid * per : n;
   const int i1 = i0 + per < n ? i0 + per : n;
 
@@ -168,7 +174,7 @@ __device__ __noinline__ void select_big(
   __syncthreads();
   nslots = 0;
 #pragma unroll
-  for (int wv = 0; wv < kSelWaves; ++wv) {
+  for (int wv = 0; wv < NW; ++wv) {
     kmin = sh.red_min[wv] < kmin ? sh.red_min[wv] : kmin;
     kmax = sh.red_max[wv] > kmax ? sh.red_max[wv] : kmax;
     nslots += sh.red_sum[wv];
@@ -194,7 +200,7 @@ __device__ __noinline__ void select_big(
         const int dbits = rbits < 8 ? rbits : 8;
         const int shift_d = rbits - dbits;
         const uint32_t dmask = (1u << dbits) - 1u;
-        for (int i = tid; i < n; i += kSelThreads) {
+        for (int i = tid; i < n; i += THREADS) {
           const uint32_t key = float_key(sc[i]);
           const int wi = sb[i + 1] - sb[i];
           if (wi > 0 && (key & mask) == prefix) atomicAdd(&sh.hist[(key >> shift_d) & dmask], (uint32_t)wi);
@@ -230,7 +236,7 @@ __device__ __noinline__ void select_big(
     for (int i = i0; i < i1; ++i)
       if (float_key(sc[i]) == tau) { const int wi = sb[i + 1] - sb[i]; tie_local += wi > 0 ? wi : 0; }
     int total;
-    tie_before = wg_excl_scan(tie_local, sh.wave_tot, total);
+    tie_before = wg_excl_scan<NW>(tie_local, sh.wave_tot, total);
   }
   int sel_local = 0;
   {
@@ -238,7 +244,7 @@ __device__ __noinline__ void select_big(
     for (int i = i0; i < i1; ++i) sel_local += take_of(i, tb);
   }
   int total_sel;
-  int off = wg_excl_scan(sel_local, sh.wave_tot, total_sel);
+  int off = wg_excl_scan<NW>(sel_local, sh.wave_tot, total_sel);
   int tb = tie_before;
   for (int i = i0; i < i1; ++i) {
     const int take = take_of(i, tb);
@@ -261,13 +267,14 @@ __device__ __noinline__ void select_big(
 
 // scores: rows of `stride` floats (stride % 4 == 0, stride >= cap, base 16-byte aligned);
 // slot_base, block_start: 16-byte aligned, readable up to a multiple of 4 entries past cap.
-template <int PT>
-__global__ __launch_bounds__(kSelThreads) void select_kernel(
+template <int PT, int THREADS>
+__global__ __launch_bounds__(THREADS) void select_kernel(
     const float* __restrict__ scores, int stride, const int32_t* __restrict__ cu_blocks,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ slot_base, int cap, int Hq,
     int b, int k, int32_t* __restrict__ sel_slot, int32_t* __restrict__ sel_start,
     int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
   static_assert(PT == 4 || PT == 8, "register tile");
+  constexpr int NW = THREADS / DSK_WAVE;
   constexpr int kSelPerThread = PT;
   constexpr int kSelVecs = PT / 4;
   __shared__ SelShared sh;
@@ -320,8 +327,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     write_padding(0, k, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
     return;
   }
-  if (!sel_fits_tile(n, PT)) {                            // too many blocks for the register tile
-    select_big(sh, scores, stride, cu_blocks, block_start, slot_base, cap, Hq, b, k, PT, sel_slot, sel_start,
+  if (!sel_fits_tile(n, PT, THREADS)) {                            // too many blocks for the register tile
+    select_big<THREADS>(sh, scores, stride, cu_blocks, block_start, slot_base, cap, Hq, b, k, PT, sel_slot, sel_start,
                sel_len, sel_count);
     return;
   }
@@ -358,7 +365,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   __syncthreads();
   nslots = 0;
 #pragma unroll
-  for (int wv = 0; wv < kSelWaves; ++wv) {
+  for (int wv = 0; wv < NW; ++wv) {
     kmin = sh.red_min[wv] < kmin ? sh.red_min[wv] : kmin;
     kmax = sh.red_max[wv] > kmax ? sh.red_max[wv] : kmax;
     nslots += sh.red_sum[wv];
@@ -415,7 +422,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     tie_local += (!gt && key[r] == tau) ? w[r] : 0;
   }
   int tie_before, gt_before;
-  wg_excl_scan2(tie_local, gt_local, sh.wave_tot2, tie_before, gt_before);
+  wg_excl_scan2<NW>(tie_local, gt_local, sh.wave_tot2, tie_before, gt_before);
   int off = gt_before + (tie_before < krem ? tie_before : krem);
   DSK_TS(4);
   // Chosen blocks go through an LDS work list (any order: every entry carries its output
@@ -456,7 +463,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     }
     __syncthreads();
     const int n_round = n_work - base < kSelWork ? n_work - base : kSelWork;
-    for (int j = tid; j < n_round; j += kSelThreads) {
+    for (int j = tid; j < n_round; j += THREADS) {
       const int4 wk = sh.work[j];
       const int take = sh.work_take[j];
       for (int jj = 0; jj < take; ++jj) {
@@ -484,8 +491,10 @@ hipError_t launch_select(const dsk_select_args& a, const float* scores, int stri
 #define DSK_SEL_ARGS                                                                                          \
   scores, stride, a.cu_blocks, a.block_start, a.slot_base, a.max_blocks_total, a.Hq, a.b, k, a.sel_slot, a.sel_start, \
       a.sel_len, a.sel_count
-  if (sel_fits_tile(bound, 4)) select_kernel<4><<<grid, dim3(kSelThreads), 0, st>>>(DSK_SEL_ARGS);
-  else select_kernel<kSelMaxPerThread><<<grid, dim3(kSelThreads), 0, st>>>(DSK_SEL_ARGS);
+  if (sel_fits_tile(bound, 4, 256)) select_kernel<4, 256><<<grid, dim3(256), 0, st>>>(DSK_SEL_ARGS);
+  else if (sel_fits_tile(bound, 4, 512)) select_kernel<4, 512><<<grid, dim3(512), 0, st>>>(DSK_SEL_ARGS);
+  else if (sel_fits_tile(bound, 4, 1024)) select_kernel<4, 1024><<<grid, dim3(1024), 0, st>>>(DSK_SEL_ARGS);
+  else select_kernel<kSelMaxPerThread, kSelMaxThreads><<<grid, dim3(kSelMaxThreads), 0, st>>>(DSK_SEL_ARGS);
 #undef DSK_SEL_ARGS
   return hipGetLastError();
 }

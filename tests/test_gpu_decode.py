@@ -134,8 +134,8 @@ def test_many_short_sequences_share_score_groups():
 @pytest.mark.parametrize("cfg_id", [2, 3, 5])
 def test_block_count_hint_does_not_change_results(cfg_id):
     """max_blocks_used (a host-side upper bound on the block count; it sizes the score launch and
-    picks the register tile of the selection kernel: 4096 blocks for the first two, 8192 for the
-    third) must leave every output bit-identical, whether exact, loose or absent."""
+    picks the workgroup size and register tile of the selection kernel: 512 x 4, 1024 x 4 and
+    1024 x 8 blocks for these three configurations) must leave every output bit-identical, whether exact, loose or absent."""
     dsk = _dsk()
     case = gpu_case(cfg_id)
     cfg = case.cfg
