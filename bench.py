@@ -79,7 +79,7 @@ def main():
     dev = torch.device("cuda:0")
     cfg = CONFIGS[args.config]
     t0 = time.time()
-    wl = make_workload(args.config)
+    wl = make_workload(args.config, with_kv=True, with_qwin=True)
     gen_s = time.time() - t0
 
     def bf16(bits):
@@ -120,6 +120,19 @@ def main():
         n_c = 10
         compress_ms = event_ms(lambda: [dsk.dsk_compress(cargs, stream) for _ in range(n_c)], stream) / n_c
         compress_bytes = wl.total_tokens * cfg.Hkv * 128 * 2 + nblk * cfg.Hkv * 512 + wl.total_tokens * 4
+
+        # ---- delimiter importance (Alg. 1 on the sampled windows), timed by itself: the weights are
+        #      estimated once per scenario, so it is not part of the per-prefill figure above ---------
+        ikw = dict(ckw)
+        ikw.update(stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_IMPORTANCE, V=None, M=cfg.M, W=cfg.W, R=cfg.R,
+                   alpha_imp=cfg.alpha_imp, qwin=bf16(wl.qwin),
+                   class_weight_q=torch.full((cfg.B, cfg.n_class), 5, dtype=torch.uint8, device=dev))
+        icomp = dsk.compress(**ikw)
+        stream.synchronize()
+        n_samples = int((icomp.samp_pos >= 0).sum().item())
+        icomp.args.stages = dsk.DSK_STAGE_IMPORTANCE
+        dsk.dsk_compress(icomp.args, stream)
+        importance_us = event_ms(lambda: [dsk.dsk_compress(icomp.args, stream) for _ in range(5)], stream) * 1e3 / 5
 
         # ---- decode step: per-query argument structs, buffers shared --------------------------
         nq = len(queries)
@@ -344,7 +357,8 @@ def main():
         "compress": {"us": round(compress_ms * 1e3, 2), "bytes": int(compress_bytes),
                      "GBps": round(compress_bytes / (compress_ms * 1e-3) / 1e9, 1),
                      "frac_of_hbm_peak": round(compress_bytes / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                     "stages": "candidates+segment+summaries(K)"},
+                     "stages": "candidates+segment+summaries(K)",
+                     "importance_us": round(importance_us, 1), "importance_samples": n_samples},
         "roofline": {"bound": "hbm", "kernel": "attn_kernel (K/V gather + online softmax of dsk_sparse_decode_attn)",
                      "achieved": round(attn_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(attn_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
