@@ -334,7 +334,7 @@ def main():
     traffic = MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("attn_kernel")
     step_gbs = step_bytes / (us_per_step * 1e-6) / 1e9
     out = {
-        "metric": "decode attn us/step + achieved HBM GB/s at 128K ctx (Llama-3-8B shape)",
+        "metric": "decode attn \u00b5s/step + achieved HBM GB/s at 128K ctx (Llama-3-8B shape)",
         "value": round(us_per_step, 3),
         "unit": "us/step",
         "n_gpus": 1,
