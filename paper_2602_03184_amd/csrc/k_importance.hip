@@ -10,7 +10,11 @@
 // accumulate per lane with no cross-lane traffic until the very end.  K rows are read straight
 // from HBM into the A-operand layout: the contraction index is permuted so that lane half
 // hf = lane/32 owns channels [64*hf, 64*hf+64) of its key row, i.e. eight contiguous 16-byte
-// loads; Q^T uses the same permutation, so the sum over channels is unchanged.
+// loads; Q^T uses the same permutation, so the sum over channels is unchanged.  Those operand
+// loads (one key row per lane) are what bounds the kernel, so every key tile a wavefront fetches
+// is multiplied with the query windows of 3 sample slots, the next tile is requested before the
+// current one is used, and tiles that lie wholly in a sample's discarded region (nearly all of
+// them) take an unmasked path: one running sum feeds the total and the discarded mass.
 #include "dsk_common.hpp"
 #include "dsk_internal.hpp"
 
@@ -19,8 +23,6 @@ namespace dsk {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
-constexpr int kImpThreads = 512;   // 8 waves share the key tiles of a sample (256 and 1024 threads measured slower)
-constexpr int kImpWaves = kImpThreads / DSK_WAVE;
 constexpr float kImpLog2e = 1.4426950408889634f;
 
 struct RowStat {       // online-softmax statistics of one query row over a subset of keys
@@ -38,121 +40,184 @@ __device__ __forceinline__ void stat_merge(RowStat& a, const RowStat& b) {
   a.m = m;
 }
 
-// grid: (sample slot c*M+m, kv head, sequence)
+// Sample slots sharing the key tiles a wavefront loads (consecutive slots: mostly the same class,
+// neighbouring positions).  2, 3 and 4 were measured: 3 is the most that keeps 2 wavefronts per
+// SIMD (256 VGPRs with the prefetched tile); 4 drops to one and is slower.
+constexpr int kImpSamples = 3;
+
+// grid: (group of kImpSamples sample slots, kv head, sequence)
+template <int kImpThreads>
 __global__ __launch_bounds__(kImpThreads) void importance_kernel(
     const uint16_t* __restrict__ K, int64_t kst, int64_t ksh, const uint16_t* __restrict__ qwin,
     const int32_t* __restrict__ samp_pos, const int32_t* __restrict__ cu_seqlens, int n_samp, int W, int R,
     int Hq, int G, float alpha, float scale_log2, float* __restrict__ imp_part, int Hkv) {
-  __shared__ RowStat sm_stat[kImpWaves][32];
-  __shared__ float sm_val[32];
-  const int j = blockIdx.x;
+  constexpr int kImpWaves = kImpThreads / DSK_WAVE;
+  __shared__ RowStat sm_stat[kImpSamples][kImpWaves][32];
+  __shared__ float sm_val[kImpSamples][32];
   const int hk = blockIdx.y;
   const int s = blockIdx.z;
   const int lane = threadIdx.x & (DSK_WAVE - 1);
   const int wave = threadIdx.x / DSK_WAVE;
   const int col = lane & 31;        // query row of the tile this lane accumulates
   const int hf = lane >> 5;         // channel half / key sub-row selector
-  float* out = imp_part + ((int64_t)s * n_samp + j) * Hkv + hk;
 
   const int seq0 = cu_seqlens[s];
   const int L = cu_seqlens[s + 1] - seq0;
-  const int tg = samp_pos[(int64_t)s * n_samp + j];
-  const int t = tg - seq0;
-  if (tg < 0 || t < 0 || t >= L) {          // no such sample
-    if (threadIdx.x == 0) *out = 0.0f;
-    return;
+  int jn[kImpSamples], t[kImpSamples], o_lo[kImpSamples], d_hi[kImpSamples], last_key[kImpSamples];
+  bool have[kImpSamples];
+  int n_tiles = 0;
+#pragma unroll
+  for (int p = 0; p < kImpSamples; ++p) {
+    jn[p] = blockIdx.x * kImpSamples + p;
+    const int tg = jn[p] < n_samp ? samp_pos[(int64_t)s * n_samp + jn[p]] : -1;
+    t[p] = tg - seq0;
+    have[p] = tg >= 0 && t[p] >= 0 && t[p] < L;
+    if (!have[p]) t[p] = 0;
+    o_lo[p] = t[p] - R + 1 > 0 ? t[p] - R + 1 : 0;          // retained region [o_lo, t]
+    d_hi[p] = t[p] - R > 0 ? t[p] - R : 0;                  // discarded region [0, d_hi]
+    last_key[p] = have[p] ? (t[p] + W < L - 1 ? t[p] + W : L - 1) : -1;
+    const int nt = last_key[p] / 32 + 1;
+    if (have[p] && nt > n_tiles) n_tiles = nt;
+    if (!have[p] && jn[p] < n_samp && threadIdx.x == 0)     // no such sample
+      imp_part[((int64_t)s * n_samp + jn[p]) * Hkv + hk] = 0.0f;
   }
-  const int rows = W * G;                   // query rows of this (sample, kv head)
-  const int o_lo = t - R + 1 > 0 ? t - R + 1 : 0;   // retained region [o_lo, t]
-  const int d_hi = t - R > 0 ? t - R : 0;           // discarded region [0, d_hi]
-  const int last_key = t + W < L - 1 ? t + W : L - 1;
-  const int n_tiles = last_key / 32 + 1;
+  if (n_tiles == 0) return;                                 // uniform over the workgroup
+  const int rows = W * G;                                   // query rows of one (sample, kv head)
   const uint16_t* Kh = K + (int64_t)hk * ksh + (int64_t)seq0 * kst + hf * 64;
-  float total = 0.0f;
+  float total[kImpSamples];
+#pragma unroll
+  for (int p = 0; p < kImpSamples; ++p) total[p] = 0.0f;
 
   for (int row0 = 0; row0 < rows; row0 += 32) {
-    // Q^T operand: lane (col, hf) holds channels [64*hf, 64*hf+64) of query row row0+col
+    // Q^T operands: lane (col, hf) holds channels [64*hf, 64*hf+64) of query row row0+col
     const int row = row0 + col;
     const bool row_ok = row < rows;
     const int w = row_ok ? row / G : 0;
     const int g = row_ok ? row % G : 0;
-    const int qpos = t + 1 + w;             // position of this query; attends keys 0..qpos
-    bf16x8_t qv[8];
-    {
-      const uint16_t* qp = qwin + ((((int64_t)s * n_samp + j) * W + w) * Hq + hk * G + g) * DSK_HEAD_DIM + hf * 64;
+    bf16x8_t qv[kImpSamples][8];
+    int qpos[kImpSamples];
+    RowStat st[kImpSamples];
+#pragma unroll
+    for (int p = 0; p < kImpSamples; ++p) {
+      qpos[p] = t[p] + 1 + w;               // position of this query; attends keys 0..qpos
+      const int jq = have[p] ? jn[p] : 0;   // absent sample: any readable rows, zeroed below
+      const uint16_t* qp = qwin + ((((int64_t)s * n_samp + jq) * W + w) * Hq + hk * G + g) * DSK_HEAD_DIM + hf * 64;
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         uint4 raw = *reinterpret_cast<const uint4*>(qp + u * 8);
-        if (!row_ok) raw = make_uint4(0, 0, 0, 0);
-        qv[u] = *reinterpret_cast<bf16x8_t*>(&raw);
+        if (!row_ok || !have[p]) raw = make_uint4(0, 0, 0, 0);
+        qv[p][u] = *reinterpret_cast<bf16x8_t*>(&raw);
       }
+      st[p].m = -__builtin_inff();
+      st[p].zt = st[p].zo = st[p].zd = 0.0f;
     }
-    RowStat st;
-    st.m = -__builtin_inff();
-    st.zt = st.zo = st.zd = 0.0f;
-    for (int tile = wave; tile < n_tiles; tile += kImpWaves) {
-      const int k0 = tile * 32;
-      int krow = k0 + col;                  // A operand row of this lane
+    // the rows of the wave's next tile are requested before the current tile is multiplied
+    uint4 knext[8];
+    {
+      int krow = wave * 32 + col;           // A operand row of this lane
       krow = krow < L ? krow : L - 1;       // stay inside the sequence; masked below
       const uint16_t* kp = Kh + (int64_t)krow * kst;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) knext[u] = *reinterpret_cast<const uint4*>(kp + u * 8);
+    }
+    for (int tile = wave; tile < n_tiles; tile += kImpWaves) {
+      const int k0 = tile * 32;
       uint4 kraw[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) kraw[u] = *reinterpret_cast<const uint4*>(kp + u * 8);
-      f32x16_t acc;
+      for (int u = 0; u < 8; ++u) kraw[u] = knext[u];
+      {
+        int krow = k0 + kImpWaves * 32 + col;
+        krow = krow < L ? krow : L - 1;     // past the last tile: a harmless re-read inside the sequence
+        const uint16_t* kp = Kh + (int64_t)krow * kst;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8_t*>(&kraw[u]), qv[u], acc, 0, 0, 0);
-      // acc[r] = logit of key k0 + 8*(r/4) + 4*hf + r%4 against query row `col`
-      float z[16];
-      float tmax = -__builtin_inff();
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int kpos = k0 + 8 * (r / 4) + 4 * hf + (r % 4);
-        z[r] = (kpos <= qpos && kpos <= last_key) ? acc[r] * scale_log2 : -__builtin_inff();
-        tmax = fmaxf(tmax, z[r]);
+        for (int u = 0; u < 8; ++u) knext[u] = *reinterpret_cast<const uint4*>(kp + u * 8);
       }
-      if (tmax != -__builtin_inff()) {
-        const float mn = fmaxf(st.m, tmax);
-        const float f = st.m == -__builtin_inff() ? 0.0f : exp2f(st.m - mn);
-        st.zt *= f; st.zo *= f; st.zd *= f;
+#pragma unroll
+      for (int p = 0; p < kImpSamples; ++p) {
+        if (k0 > last_key[p]) continue;     // this sample's keys ended before the tile (uniform)
+        f32x16_t acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8_t*>(&kraw[u]), qv[p][u], acc, 0, 0, 0);
+        // acc[r] = logit of key k0 + 8*(r/4) + 4*hf + r%4 against query row `col`
+        if (k0 + 31 <= d_hi[p]) {
+          // the whole tile lies in the discarded region (hence before every query of the window
+          // and outside the retained region): no masks, one sum feeds both totals
+          float amax = acc[0];
+#pragma unroll
+          for (int r = 1; r < 16; ++r) amax = fmaxf(amax, acc[r]);
+          const float mn = fmaxf(st[p].m, amax * scale_log2);
+          const float f = __builtin_amdgcn_exp2f(st[p].m - mn);   // 0 while st.m is still -inf
+          float esum = 0.0f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) esum += __builtin_amdgcn_exp2f(fmaf(acc[r], scale_log2, -mn));
+          st[p].zt = fmaf(st[p].zt, f, esum);
+          st[p].zd = fmaf(st[p].zd, f, esum);
+          st[p].zo *= f;
+          st[p].m = mn;
+          continue;
+        }
+        float z[16];
+        float tmax = -__builtin_inff();
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int kpos = k0 + 8 * (r / 4) + 4 * hf + (r % 4);
-          const float e = __builtin_amdgcn_exp2f(z[r] - mn);   // z <= mn; 0 for masked keys (-inf)
-          st.zt += e;
-          st.zo += (kpos >= o_lo && kpos <= t) ? e : 0.0f;
-          st.zd += (kpos <= d_hi) ? e : 0.0f;
+          z[r] = (kpos <= qpos[p] && kpos <= last_key[p]) ? acc[r] * scale_log2 : -__builtin_inff();
+          tmax = fmaxf(tmax, z[r]);
         }
-        st.m = mn;
+        if (tmax != -__builtin_inff()) {
+          const float mn = fmaxf(st[p].m, tmax);
+          const float f = st[p].m == -__builtin_inff() ? 0.0f : exp2f(st[p].m - mn);
+          st[p].zt *= f; st[p].zo *= f; st[p].zd *= f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int kpos = k0 + 8 * (r / 4) + 4 * hf + (r % 4);
+            const float e = __builtin_amdgcn_exp2f(z[r] - mn);   // z <= mn; 0 for masked keys (-inf)
+            st[p].zt += e;
+            st[p].zo += (kpos >= o_lo[p] && kpos <= t[p]) ? e : 0.0f;
+            st[p].zd += (kpos <= d_hi[p]) ? e : 0.0f;
+          }
+          st[p].m = mn;
+        }
       }
     }
     // halves of a wave hold disjoint keys of the same row; then waves; fixed order
-    RowStat other;
-    other.m = shfl_xor_f(st.m, 32);
-    other.zt = shfl_xor_f(st.zt, 32);
-    other.zo = shfl_xor_f(st.zo, 32);
-    other.zd = shfl_xor_f(st.zd, 32);
-    if (hf == 0) {
-      stat_merge(st, other);
-      sm_stat[wave][col] = st;
+#pragma unroll
+    for (int p = 0; p < kImpSamples; ++p) {
+      RowStat other;
+      other.m = shfl_xor_f(st[p].m, 32);
+      other.zt = shfl_xor_f(st[p].zt, 32);
+      other.zo = shfl_xor_f(st[p].zo, 32);
+      other.zd = shfl_xor_f(st[p].zd, 32);
+      if (hf == 0) {
+        stat_merge(st[p], other);
+        sm_stat[p][wave][col] = st[p];
+      }
     }
     __syncthreads();
-    if (threadIdx.x < 32) {
-      RowStat a = sm_stat[0][col];
+    if (threadIdx.x < 32 * kImpSamples) {
+      const int p = threadIdx.x >> 5;
+      RowStat a = sm_stat[p][0][col];
 #pragma unroll
-      for (int wv = 1; wv < kImpWaves; ++wv) stat_merge(a, sm_stat[wv][col]);
+      for (int wv = 1; wv < kImpWaves; ++wv) stat_merge(a, sm_stat[p][wv][col]);
       const float v = (row0 + col < rows && a.zt > 0.0f) ? (a.zo - alpha * a.zd) / a.zt : 0.0f;
-      sm_val[col] = v;
+      sm_val[p][col] = v;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-      for (int c2 = 0; c2 < 32; ++c2) total += sm_val[c2];   // fixed order
+#pragma unroll
+      for (int p = 0; p < kImpSamples; ++p)
+        for (int c2 = 0; c2 < 32; ++c2) total[p] += sm_val[p][c2];   // fixed order
     }
     __syncthreads();
   }
-  if (threadIdx.x == 0) *out = total;
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int p = 0; p < kImpSamples; ++p)
+      if (have[p]) imp_part[((int64_t)s * n_samp + jn[p]) * Hkv + hk] = total[p];
+  }
 }
 
 // one workgroup per sequence, one thread per delimiter class
@@ -194,11 +259,19 @@ hipError_t launch_importance(const dsk_compress_args& a, const CompressWs& ws, h
   float* imp_part = reinterpret_cast<float*>(static_cast<unsigned char*>(a.workspace) + ws.imp_part);
   const int n_samp = a.n_class * a.M;
   const float scale = a.imp_scale != 0.0f ? a.imp_scale : 0.08838834764831845f;   // 128^-1/2
-  const dim3 grid((unsigned)n_samp, (unsigned)a.Hkv, (unsigned)a.B);
-  importance_kernel<<<grid, dim3(kImpThreads), 0, st>>>(
-      static_cast<const uint16_t*>(a.K), a.k_stride_tok, a.k_stride_head, static_cast<const uint16_t*>(a.qwin),
-      a.samp_pos, a.cu_seqlens, n_samp, a.W, a.R, a.Hq, a.Hq / a.Hkv, a.alpha_imp, scale * kImpLog2e, imp_part,
-      a.Hkv);
+  const dim3 grid((unsigned)((n_samp + kImpSamples - 1) / kImpSamples), (unsigned)a.Hkv, (unsigned)a.B);
+  // few workgroups (one sequence): 8 wavefronts split the key tiles of the longest samples and
+  // shorten the serial chain; many workgroups: 4 wavefronts keep more of them resident
+  if ((int64_t)grid.x * grid.y * grid.z < 1024)
+    importance_kernel<512><<<grid, dim3(512), 0, st>>>(
+        static_cast<const uint16_t*>(a.K), a.k_stride_tok, a.k_stride_head, static_cast<const uint16_t*>(a.qwin),
+        a.samp_pos, a.cu_seqlens, n_samp, a.W, a.R, a.Hq, a.Hq / a.Hkv, a.alpha_imp, scale * kImpLog2e, imp_part,
+        a.Hkv);
+  else
+    importance_kernel<256><<<grid, dim3(256), 0, st>>>(
+        static_cast<const uint16_t*>(a.K), a.k_stride_tok, a.k_stride_head, static_cast<const uint16_t*>(a.qwin),
+        a.samp_pos, a.cu_seqlens, n_samp, a.W, a.R, a.Hq, a.Hq / a.Hkv, a.alpha_imp, scale * kImpLog2e, imp_part,
+        a.Hkv);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   importance_finalize_kernel<<<dim3((unsigned)a.B), dim3(DSK_MAX_CLASSES), 0, st>>>(
