@@ -9,6 +9,12 @@
  *                           block-to-slot mapped scores (Sec. 4.2; App. B.2 Step 1).
  *   dsk_sparse_decode_attn  per decode step: attention over the K/V of the selected slots
  *                           (App. B.2 Steps 2-3).
+ * and three more sit beside it:
+ *   dsk_append_tokens       incremental update of the block table and summaries while decoding
+ *                           (Sec. 4.1, "Incremental Update during Decoding"), one sequence per call.
+ *   dsk_dense_decode_attn   full attention over the whole cache: the full-KV baseline the method
+ *                           is compared with (Sec. 5, GPU Inference analysis).
+ *   dsk_stream_read_probe   a measurement aid (streaming read of a buffer), no part of the method.
  *
  * Conventions that hold for every call
  *   - Pointers marked [dev] are device (HBM) addresses, [host] are host addresses.
