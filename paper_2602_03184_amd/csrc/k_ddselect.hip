@@ -33,8 +33,13 @@ extern "C" __attribute__((visibility("default"))) void dsk_debug_read2(long long
 #endif
 
 constexpr int kSegThreads = 256;
-constexpr int kSegPerThread = kSegTile / kSegThreads;   // consecutive positions owned by a thread
 constexpr int kSegWaves = kSegThreads / DSK_WAVE;
+constexpr int kTileThreads = 1024;                      // workgroup of the tile kernel: the tiles are few (one per
+                                                        // 2048 positions) and their phases barrier-bound, so
+                                                        // wide workgroups shorten them (256 / 512 / 1024
+                                                        // threads: 95 / 88 / 86.5 us for the pass at 128K)
+constexpr int kSegPerThread = kSegTile / kTileThreads;  // positions owned by a thread of the tile kernel
+constexpr int kTileWaves = kTileThreads / DSK_WAVE;
 constexpr int kChainLdsEntries = 6144;   // uint2 entries staged per chunk in the chain kernel (48 KB)
 
 struct SegParams {
@@ -107,17 +112,17 @@ __global__ __launch_bounds__(256) void seg_scatter_kernel(
 //   ns    u16 [kSegTile]   slots of the chunk starting here
 //   mark  u8  [kSegTile]   (emit mode) reachable from the tile's entry
 //   wq    u8  [64]         class -> weight tenths of this sequence
-//   red   i32 [2*kSegWaves + 2]
+//   red   i32 [2*kTileWaves + 2]
 __host__ __device__ constexpr size_t seg_tile_lds_bytes() {
   return (size_t)kSegTile * 12      // jump arrays (the vote array, 8 bytes per position, overlays them)
          + (size_t)kSegTile * 2     // ns
          + (size_t)kSegTile         // mark
-         + 64 + 64;                 // wq, red
+         + 64 + 192;                // wq, red
 }
-static_assert((2 * kSegWaves + 2) * 4 <= 64, "red fits its slot");
+static_assert((2 * kTileWaves + 2) * 4 <= 192, "red fits its slot");
 
 template <int MODE>
-__global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
+__global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
     SegParams p, const uint8_t* __restrict__ cls_at, uint2* __restrict__ tile_map,
     const int4* __restrict__ tile_info, const int4* __restrict__ seq_info, int32_t* __restrict__ block_start,
     int32_t* __restrict__ slot_base, int32_t* dev_status) {
@@ -160,7 +165,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
     if (w > 10) { set_status(dev_status, DSK_ERR_PARAM); w = 10; }
     wq[tid] = (uint8_t)w;
   }
-  for (int i = tid; i < kSegTile; i += kSegThreads) { best[i] = 0ull; mark[i] = 0; }
+  for (int i = tid; i < kSegTile; i += kTileThreads) { best[i] = 0ull; mark[i] = 0; }
   __syncthreads();
   SEG_TS(1);
 
@@ -172,7 +177,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
   // lane in 30 busy).
   {
     constexpr int kVoteChunk = 2 * kSegTile;                                        // 16 class bytes per thread
-    constexpr int kPerThread = kVoteChunk / kSegThreads;
+    constexpr int kPerThread = kVoteChunk / kTileThreads;
     uint16_t* clist = reinterpret_cast<uint16_t*>(smem + (size_t)kSegTile * 8);     // free until the jump arrays are built
     int* n_list = red;
     const int e_lo = p0 + C - delta > 1 ? p0 + C - delta : 1;
@@ -182,7 +187,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
       uint8_t cb_[kPerThread];
 #pragma unroll
       for (int r = 0; r < kPerThread; ++r) {       // independent byte loads: one round trip
-        int e = e0 + r * kSegThreads + tid;
+        int e = e0 + r * kTileThreads + tid;
         e = e <= e_hi ? e : e_hi;
         cb_[r] = cls_at[seq0 + e - 1];
       }
@@ -190,7 +195,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
       __syncthreads();
 #pragma unroll
       for (int r = 0; r < kPerThread; ++r) {
-        const int eo = r * kSegThreads + tid;        // e - e0 < 4096: 12 bits, weight 0..10: 4 bits
+        const int eo = r * kTileThreads + tid;        // e - e0 < 4096: 12 bits, weight 0..10: 4 bits
         if (e0 + eo <= e_hi && cb_[r] != 255) {
           const int w = cb_[r] < 64 ? wq[cb_[r]] : 0;
           clist[atomicAdd(n_list, 1)] = (uint16_t)((eo << 4) | w);   // at most kVoteChunk entries = 8 KB
@@ -198,7 +203,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
       }
       __syncthreads();
       const int n = *n_list;
-      for (int ci = tid; ci < n; ci += kSegThreads) {
+      for (int ci = tid; ci < n; ci += kTileThreads) {
         const int ent = clist[ci];
         const int e = e0 + (ent >> 4);
         const int w = ent & 15;
@@ -219,11 +224,11 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
   }
   SEG_TS(2);
   // successor table (registers first: `best` is about to be overlaid).  Lane-interleaved
-  // ownership (i = r*256 + tid) keeps these LDS accesses free of bank conflicts.
+  // ownership (i = r*threads + tid) keeps these LDS accesses free of bank conflicts.
   int my_len[kSegPerThread];
 #pragma unroll
   for (int r = 0; r < kSegPerThread; ++r) {
-    const int i = r * kSegThreads + tid;
+    const int i = r * kTileThreads + tid;
     const int q = p0 + i;
     int len = 0;
     if (i < tlen) {
@@ -239,7 +244,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
   __syncthreads();
 #pragma unroll
   for (int r = 0; r < kSegPerThread; ++r) {
-    const int i = r * kSegThreads + tid;
+    const int i = r * kTileThreads + tid;
     const int len = my_len[r];
     const int nslot = (len + p.b - 1) / p.b;
     ns[i] = (uint16_t)nslot;
@@ -253,7 +258,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
   SEG_TS(3);
   // pointer jumping: level r holds 2^r chunks per hop; positions that left the tile are fixed points
   int cur = 0;
-  int* any_active = red + 2 * kSegWaves;   // two flags, used alternately
+  int* any_active = red + 2 * kTileWaves;   // two flags, used alternately
   if (tid == 0) { any_active[0] = 0; any_active[1] = 0; }
   __syncthreads();
   for (int round = 0; round < 16; ++round) {
@@ -262,7 +267,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
     const uint16_t* ss = jcs + cur * kSegTile; uint16_t* sd = jcs + (cur ^ 1) * kSegTile;
 #pragma unroll
     for (int r = 0; r < kSegPerThread; ++r) {
-      const int i = r * kSegThreads + tid;
+      const int i = r * kTileThreads + tid;
       const uint32_t v = ps[i];
       const int t = (int)(v & 0xFFFFu);
       uint32_t nv = v;
@@ -289,7 +294,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
 
   if (MODE == 0) {
     uint2* row = tile_map + (int64_t)tile * p.map_row;
-    for (int ent = tid; ent < p.map_row; ent += kSegThreads) {
+    for (int ent = tid; ent < p.map_row; ent += kTileThreads) {
       uint2 rv = make_uint2(0u, 0u);
       if (ent < tlen) {
         const uint32_t v = fpb[ent];
@@ -301,22 +306,31 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
     return;
   }
 
-  // emit: rank the marked positions of the tile; here a thread owns 8 consecutive positions
-  // (thread order = position order), read as one 8-byte and one 16-byte vector
-  static_assert(kSegPerThread == 8, "vector reads below");
-  const uint2 mk8 = *reinterpret_cast<const uint2*>(mark + tid * 8);
-  const uint4 ns8 = *reinterpret_cast<const uint4*>(ns + tid * 8);
-  int mk[8], nsv[8];
+  // emit: rank the marked positions of the tile; here a thread owns kSegPerThread consecutive
+  // positions (thread order = position order), read as one 4-byte and one 8-byte vector
+  static_assert(kSegPerThread == 4 || kSegPerThread == 2, "vector reads below");
+  int mk[kSegPerThread], nsv[kSegPerThread];
+  if constexpr (kSegPerThread == 4) {
+    const uint32_t mk4 = *reinterpret_cast<const uint32_t*>(mark + tid * 4);
+    const uint2 ns4 = *reinterpret_cast<const uint2*>(ns + tid * 4);
 #pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    const uint32_t mw = r < 4 ? mk8.x : mk8.y;
-    mk[r] = (tid * 8 + r < tlen) ? (int)((mw >> (8 * (r & 3))) & 255u) : 0;
-    const uint32_t nw = r < 2 ? ns8.x : (r < 4 ? ns8.y : (r < 6 ? ns8.z : ns8.w));
-    nsv[r] = (int)((nw >> (16 * (r & 1))) & 0xFFFFu);
+    for (int r = 0; r < kSegPerThread; ++r) {
+      mk[r] = (tid * kSegPerThread + r < tlen) ? (int)((mk4 >> (8 * r)) & 255u) : 0;
+      const uint32_t nw = r < 2 ? ns4.x : ns4.y;
+      nsv[r] = (int)((nw >> (16 * (r & 1))) & 0xFFFFu);
+    }
+  } else {
+    const uint32_t mk2 = *reinterpret_cast<const uint16_t*>(mark + tid * 2);
+    const uint32_t ns2 = *reinterpret_cast<const uint32_t*>(ns + tid * 2);
+#pragma unroll
+    for (int r = 0; r < kSegPerThread; ++r) {
+      mk[r] = (tid * kSegPerThread + r < tlen) ? (int)((mk2 >> (8 * r)) & 255u) : 0;
+      nsv[r] = (int)((ns2 >> (16 * r)) & 0xFFFFu);
+    }
   }
   int nb_local = 0, ns_local = 0;
 #pragma unroll
-  for (int r = 0; r < 8; ++r)
+  for (int r = 0; r < kSegPerThread; ++r)
     if (mk[r]) { ++nb_local; ns_local += nsv[r]; }
   const int lane = tid & (DSK_WAVE - 1), wave = tid / DSK_WAVE;
   const int ib = wave_incl_scan_i(nb_local, lane);
@@ -325,15 +339,15 @@ __global__ __launch_bounds__(kSegThreads) void seg_tile_kernel(
   __syncthreads();
   int ob = 0, os = 0;
 #pragma unroll
-  for (int w = 0; w < kSegWaves; ++w)
+  for (int w = 0; w < kTileWaves; ++w)
     if (w < wave) { ob += red[2 * w]; os += red[2 * w + 1]; }
   int gb = sq.z + info.y + ob + ib - nb_local;
   int gs = sq.w + info.z + os + is - ns_local;
 #pragma unroll
-  for (int r = 0; r < 8; ++r) {
+  for (int r = 0; r < kSegPerThread; ++r) {
     if (mk[r]) {
       if (gb < p.cap) {
-        block_start[gb] = seq0 + p0 + tid * 8 + r;
+        block_start[gb] = seq0 + p0 + tid * kSegPerThread + r;
         slot_base[gb] = gs;
       }
       ++gb;
@@ -455,7 +469,7 @@ hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, bool
   const size_t lds = seg_tile_lds_bytes();
   if (ws.tiles_per_seq > 0) {
     const dim3 grid((unsigned)ws.tiles_per_seq, (unsigned)a.B);
-    seg_tile_kernel<0><<<grid, dim3(kSegThreads), lds, st>>>(p, cls_at, tile_map, tile_info, seq_info,
+    seg_tile_kernel<0><<<grid, dim3(kTileThreads), lds, st>>>(p, cls_at, tile_map, tile_info, seq_info,
                                                              a.block_start, a.slot_base, a.dev_status);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
@@ -469,7 +483,7 @@ hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, bool
   }
   if (ws.tiles_per_seq > 0) {
     const dim3 grid((unsigned)ws.tiles_per_seq, (unsigned)a.B);
-    seg_tile_kernel<1><<<grid, dim3(kSegThreads), lds, st>>>(p, cls_at, tile_map, tile_info, seq_info,
+    seg_tile_kernel<1><<<grid, dim3(kTileThreads), lds, st>>>(p, cls_at, tile_map, tile_info, seq_info,
                                                              a.block_start, a.slot_base, a.dev_status);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
