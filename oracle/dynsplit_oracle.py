@@ -15,8 +15,16 @@ Parity status against the authors' implementation (none is public):
   * block_scores    -- pinned as the exact maximum of q.k over the block's
                        bounding box; whether the authors use this form of the
                        "query-compressed vector product" is unpinned.
-Everything else reduces to a textbook definition and is pinned to it in
-tests/test_oracle_*.py.
+  * dd_select_append -- pinned to dd_select run from scratch on the grown
+                       sequence (every split point of random streams); the
+                       paper only says that the most recent ranges are
+                       recomputed, the finality rule is derived from dd_select.
+  * block_means / block_scores_mean -- the mean and the dot product are
+                       textbook; that the authors score a mean summary with
+                       q.mean is a reading ("parity unpinned").
+Everything else (dense_attention included) reduces to a textbook definition and
+is pinned to it in tests/test_oracle_pins.py; tests/test_oracle_mutations.py
+checks that planted mistakes in any of these functions are rejected by a pin.
 """
 from __future__ import annotations
 
