@@ -220,29 +220,37 @@ __global__ __launch_bounds__(kImpThreads) void importance_kernel(
   }
 }
 
-// one workgroup per sequence, one thread per delimiter class
-__global__ __launch_bounds__(DSK_MAX_CLASSES) void importance_finalize_kernel(
+// one wavefront per (class, sequence), one lane per sample of the class (M <= 64): the lanes sum
+// their KV-head partials side by side (same order per sample as a serial loop), lane 0 then adds
+// the sample scores in sample order
+__global__ __launch_bounds__(DSK_WAVE) void importance_finalize_kernel(
     const float* __restrict__ imp_part, const int32_t* __restrict__ samp_pos, int n_class, int M, int Hkv,
     int Hq, int W, float alpha, uint8_t* __restrict__ class_weight_q, float* __restrict__ class_mean,
     float* __restrict__ samp_score) {
-  const int s = blockIdx.x;
-  const int c = threadIdx.x;
-  if (c >= n_class) return;
+  __shared__ float sm_score[kMaxSamplesPerClass];
+  __shared__ int sm_have[kMaxSamplesPerClass];
+  const int c = blockIdx.x;
+  const int s = blockIdx.y;
+  const int m = threadIdx.x;
   const int n_samp = n_class * M;
-  float sum = 0.0f;
-  int cnt = 0;
-  for (int m = 0; m < M; ++m) {
+  if (m < M) {
     const int64_t js = (int64_t)s * n_samp + c * M + m;
     const bool have = samp_pos[js] >= 0;
     float st = 0.0f;
     if (have) {
       for (int hk = 0; hk < Hkv; ++hk) st += imp_part[js * Hkv + hk];
       st /= (float)(Hq * W);
-      sum += st;
-      ++cnt;
     }
+    sm_score[m] = st;
+    sm_have[m] = have ? 1 : 0;
     if (samp_score) samp_score[js] = have ? st : __builtin_nanf("");
   }
+  __syncthreads();
+  if (m != 0) return;
+  float sum = 0.0f;
+  int cnt = 0;
+  for (int i = 0; i < M; ++i)
+    if (sm_have[i]) { sum += sm_score[i]; ++cnt; }
   const int64_t cs = (int64_t)s * n_class + c;
   if (cnt > 0) {
     const float mean = sum / (float)cnt;
@@ -274,7 +282,7 @@ hipError_t launch_importance(const dsk_compress_args& a, const CompressWs& ws, h
         a.Hkv);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  importance_finalize_kernel<<<dim3((unsigned)a.B), dim3(DSK_MAX_CLASSES), 0, st>>>(
+  importance_finalize_kernel<<<dim3((unsigned)a.n_class, (unsigned)a.B), dim3(DSK_WAVE), 0, st>>>(
       imp_part, a.samp_pos, a.n_class, a.M, a.Hkv, a.Hq, a.W, a.alpha_imp, a.class_weight_q, a.class_mean,
       a.samp_score);
   return hipGetLastError();
