@@ -110,7 +110,9 @@ def main():
         comp = dsk.compress(**ckw)
         stream.synchronize()
         assert int(comp.dev_status.item()) == 0
-        nblk = int(comp.cu_blocks.cpu()[-1])
+        cub = comp.cu_blocks.cpu().numpy()
+        nblk = int(cub[-1])
+        nblk_seq = int((cub[1:] - cub[:-1]).max())     # read back once, like nblk: a launch-sizing hint
         nslots = int(comp.slot_base.cpu()[nblk])
 
         # ---- compression pass, timed by itself (same buffers re-used) -------------------------
@@ -137,9 +139,10 @@ def main():
         # ---- decode step: per-query argument structs, buffers shared --------------------------
         nq = len(queries)
         # the block count was read back once after compression: it sizes the score launch
-        sels = [dsk.make_select_args(comp, queries[0], cfg.T, max_blocks_used=nblk)]
+        sels = [dsk.make_select_args(comp, queries[0], cfg.T, max_blocks_used=nblk, max_blocks_per_seq=nblk_seq)]
         for i in range(1, nq):
-            sels.append(dsk.make_select_args(comp, queries[i], cfg.T, out=sels[0], max_blocks_used=nblk))
+            sels.append(dsk.make_select_args(comp, queries[i], cfg.T, out=sels[0], max_blocks_used=nblk,
+                                             max_blocks_per_seq=nblk_seq))
         atts = [dsk.make_attn_args(queries[0], K, V, sels[0].sel_start, sels[0].sel_len, sels[0].sel_count, cfg.b)]
         for i in range(1, nq):
             atts.append(dsk.make_attn_args(queries[i], K, V, sels[0].sel_start, sels[0].sel_len, sels[0].sel_count,
@@ -248,7 +251,8 @@ def main():
             n_cold = max(nq, n_inst)
             for i in range(n_cold):
                 inst = i % n_inst
-                sa = dsk.make_select_args(comp, queries[i % nq], cfg.T, out=sels[0], max_blocks_used=nblk)
+                sa = dsk.make_select_args(comp, queries[i % nq], cfg.T, out=sels[0], max_blocks_used=nblk,
+                                          max_blocks_per_seq=nblk_seq)
                 sa.args.ksum = ksums[inst].data_ptr()
                 csel.append(sa)
                 catt.append(dsk.make_attn_args(queries[i % nq], Ks[inst], Vs[inst], sels[0].sel_start, sels[0].sel_len,

@@ -187,6 +187,10 @@ typedef struct dsk_select_args {
                                   read back once after dsk_compress; 0 = max_blocks_total.  Only
                                   sizes the launch and bounds speculative reads; the device value
                                   still decides what is scored. */
+  int32_t max_blocks_per_seq;  /* [host] optional upper bound on the blocks of any ONE sequence (0 = the
+                                  bound above).  Picks the workgroup size / register tile of the
+                                  selection kernel; a sequence with more blocks is still selected
+                                  correctly, through the memory-resident path. */
   const int32_t* cu_blocks;    /* [dev] [B+1] */
   const int32_t* block_start;  /* [dev] both tables: 16-byte aligned and readable up to a multiple */
   const int32_t* slot_base;    /* [dev] of 4 entries, i.e. allocate max_blocks_total + 4 ints */

@@ -69,7 +69,7 @@ class dsk_select_args(C.Structure):
     _fields_ = [
         ("struct_size", C.c_uint32),
         ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
-        ("max_blocks_total", C.c_int32), ("max_blocks_used", C.c_int32),
+        ("max_blocks_total", C.c_int32), ("max_blocks_used", C.c_int32), ("max_blocks_per_seq", C.c_int32),
         ("cu_blocks", _p), ("block_start", _p), ("slot_base", _p),
         ("ksum", _p), ("q", _p),
         ("b", C.c_int32), ("budget", C.c_int32),
@@ -413,9 +413,11 @@ class Selection:
 
 
 def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_scores: bool = False,
-                     out: Optional[Selection] = None, max_blocks_used: int = 0) -> Selection:
+                     out: Optional[Selection] = None, max_blocks_used: int = 0,
+                     max_blocks_per_seq: int = 0) -> Selection:
     """Fill dsk_select_args for query q (bf16 [B, Hq, D]); buffers are reused from `out`.
-    `max_blocks_used`: optional host-known bound on the total block count (0 = capacity)."""
+    `max_blocks_used`: optional host-known bound on the total block count (0 = capacity);
+    `max_blocks_per_seq`: optional bound on the blocks of any one sequence."""
     dev = q.device
     B, Hq = comp.B, comp.Hq
     assert q.shape == (B, Hq, DSK_HEAD_DIM) and q.dtype == torch.bfloat16 and q.is_contiguous()
@@ -426,6 +428,7 @@ def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_sco
     a.B, a.Hq, a.Hkv, a.D = B, Hq, comp.Hkv, DSK_HEAD_DIM
     a.max_blocks_total = comp.max_blocks_total
     a.max_blocks_used = max_blocks_used
+    a.max_blocks_per_seq = max_blocks_per_seq
     a.cu_blocks, a.block_start, a.slot_base = _ptr(comp.cu_blocks), _ptr(comp.block_start), _ptr(comp.slot_base)
     a.ksum, a.q = _ptr(comp.ksum), _ptr(q)
     a.b, a.budget = comp.b, budget
@@ -446,8 +449,9 @@ def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_sco
 
 
 def select_topk(comp: Compressed, q: torch.Tensor, budget: int, *, want_scores: bool = False, stream=None,
-                check: bool = True, max_blocks_used: int = 0) -> Selection:
-    sel = make_select_args(comp, q, budget, want_scores=want_scores, max_blocks_used=max_blocks_used)
+                check: bool = True, max_blocks_used: int = 0, max_blocks_per_seq: int = 0) -> Selection:
+    sel = make_select_args(comp, q, budget, want_scores=want_scores, max_blocks_used=max_blocks_used,
+                           max_blocks_per_seq=max_blocks_per_seq)
     dsk_select_topk(sel.args, stream, check=check)
     return sel
 

@@ -106,7 +106,8 @@ static dsk_status validate_select(const dsk_select_args* a) {
   if (a == nullptr) return DSK_ERR_NULL;
   if (a->struct_size != sizeof(dsk_select_args)) return DSK_ERR_VERSION;
   if (!geometry_ok(a->B, a->Hq, a->Hkv, a->D)) return DSK_ERR_SHAPE;
-  if (a->max_blocks_total < 1 || a->max_blocks_used < 0 || a->max_blocks_used > a->max_blocks_total)
+  if (a->max_blocks_total < 1 || a->max_blocks_used < 0 || a->max_blocks_used > a->max_blocks_total ||
+      a->max_blocks_per_seq < 0)
     return DSK_ERR_SHAPE;
   if (a->b < 1 || a->b > 1024 || a->budget < a->b) return DSK_ERR_PARAM;
   if (!a->cu_blocks || !a->block_start || !a->slot_base || !a->ksum || !a->q || !a->sel_slot || !a->sel_start ||

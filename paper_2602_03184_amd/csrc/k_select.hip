@@ -487,7 +487,8 @@ hipError_t launch_select(const dsk_select_args& a, const float* scores, int stri
   const dim3 grid((unsigned)a.Hq, (unsigned)a.B);
   // a sequence has at most `bound` blocks: the smallest register tile that holds them all does
   // the least per-thread work (larger sequences than the tile still work, through select_big)
-  const int bound = a.max_blocks_used > 0 ? a.max_blocks_used : a.max_blocks_total;
+  int bound = a.max_blocks_used > 0 ? a.max_blocks_used : a.max_blocks_total;
+  if (a.max_blocks_per_seq > 0 && a.max_blocks_per_seq < bound) bound = a.max_blocks_per_seq;
 #define DSK_SEL_ARGS                                                                                          \
   scores, stride, a.cu_blocks, a.block_start, a.slot_base, a.max_blocks_total, a.Hq, a.b, k, a.sel_slot, a.sel_start, \
       a.sel_len, a.sel_count

@@ -46,7 +46,7 @@ def test_ctypes_structs_mirror_the_header(dsk, tmp_path):
 int main(void) {
   printf("%zu %zu %zu ", sizeof(dsk_compress_args), sizeof(dsk_select_args), sizeof(dsk_attn_args));
   printf("%zu %zu %zu ", offsetof(dsk_compress_args, qwin), offsetof(dsk_compress_args, C_per_seq), offsetof(dsk_compress_args, workspace_bytes));
-  printf("%zu %zu ", offsetof(dsk_select_args, budget), offsetof(dsk_select_args, workspace_bytes));
+  printf("%zu %zu %zu ", offsetof(dsk_select_args, budget), offsetof(dsk_select_args, workspace_bytes), offsetof(dsk_select_args, max_blocks_per_seq));
   printf("%zu %zu %zu ", offsetof(dsk_attn_args, total_tokens), offsetof(dsk_attn_args, scale), offsetof(dsk_attn_args, workspace_bytes));
   printf("%zu %zu %zu %zu ", sizeof(dsk_dense_attn_args), offsetof(dsk_dense_attn_args, cu_seqlens), offsetof(dsk_dense_attn_args, scale), offsetof(dsk_dense_attn_args, workspace_bytes));
   printf("%zu %zu ", sizeof(dsk_attn_partials), offsetof(dsk_attn_partials, nchunks));
@@ -58,7 +58,7 @@ int main(void) {
     got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
     ca, sa, aa = dsk.dsk_compress_args, dsk.dsk_select_args, dsk.dsk_attn_args
     want = [C.sizeof(ca), C.sizeof(sa), C.sizeof(aa), ca.qwin.offset, ca.C_per_seq.offset, ca.workspace_bytes.offset,
-            sa.budget.offset, sa.workspace_bytes.offset, aa.total_tokens.offset, aa.scale.offset,
+            sa.budget.offset, sa.workspace_bytes.offset, sa.max_blocks_per_seq.offset, aa.total_tokens.offset, aa.scale.offset,
             aa.workspace_bytes.offset]
     da, pa = dsk.dsk_dense_attn_args, dsk.dsk_attn_partials
     want += [C.sizeof(da), da.cu_seqlens.offset, da.scale.offset, da.workspace_bytes.offset, C.sizeof(pa),

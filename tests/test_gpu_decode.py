@@ -150,8 +150,17 @@ def test_block_count_hint_does_not_change_results(cfg_id):
         for name in ("sel_slot", "sel_start", "sel_len", "sel_count"):
             assert torch.equal(getattr(ref, name), getattr(got, name)), (hint, name)
         assert torch.equal(ref.scores[:, :nblk], got.scores[:, :nblk])
+    # the per-sequence bound picks the selection kernel's tile; one that is too small must still
+    # give the same result (such sequences go through the memory-resident path)
+    cub = comp.cu_blocks.cpu().numpy()
+    per_seq = int((cub[1:] - cub[:-1]).max())
+    for hint in (per_seq, 16):
+        got = dsk.select_topk(comp, q, cfg.T, max_blocks_used=nblk, max_blocks_per_seq=hint)
+        torch.cuda.synchronize()
+        for name in ("sel_slot", "sel_start", "sel_len", "sel_count"):
+            assert torch.equal(getattr(ref, name), getattr(got, name)), ("per-sequence hint", hint, name)
     _check_decode(case, 1, [0, cfg.B - 1] if cfg.B > 1 else [0], [0, cfg.Hq - 1],
-                  "cfg%d with block-count hint" % cfg_id, max_blocks_used=nblk)
+                  "cfg%d with block-count hint" % cfg_id, max_blocks_used=nblk, max_blocks_per_seq=per_seq)
 
 
 @pytest.mark.parametrize("cfg_id", [1, 2])
