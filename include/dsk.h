@@ -236,6 +236,7 @@ typedef struct dsk_attn_args {
   float scale;                 /* 0 -> D^-1/2 */
   uint32_t flags;              /* DSK_ATTN_* bits */
   float* out;                  /* [dev] f32 [B, Hq, D] */
+  void* out_bf16;              /* [dev] optional bf16 [B, Hq, D]: `out` rounded to nearest even */
   float* lse;                  /* [dev] f32 [B, Hq], natural log; may be NULL */
   void* workspace;             /* [dev] */
   size_t workspace_bytes;
@@ -264,6 +265,7 @@ typedef struct dsk_dense_attn_args {
   float scale;                 /* 0 -> D^-1/2 */
   uint32_t flags;              /* must be 0 */
   float* out;                  /* [dev] f32 [B, Hq, D] */
+  void* out_bf16;              /* [dev] optional bf16 [B, Hq, D]: `out` rounded to nearest even */
   float* lse;                  /* [dev] f32 [B, Hq], natural log; may be NULL */
   void* workspace;             /* [dev] 256-byte aligned */
   size_t workspace_bytes;

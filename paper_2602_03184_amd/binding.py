@@ -89,7 +89,7 @@ class dsk_attn_args(C.Structure):
         ("total_tokens", C.c_int32), ("k", C.c_int32), ("b", C.c_int32),
         ("sel_start", _p), ("sel_len", _p), ("sel_count", _p),
         ("scale", C.c_float), ("flags", C.c_uint32),
-        ("out", _p), ("lse", _p),
+        ("out", _p), ("out_bf16", _p), ("lse", _p),
         ("workspace", _p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -104,7 +104,7 @@ class dsk_dense_attn_args(C.Structure):
         ("total_tokens", C.c_int32), ("max_seqlen", C.c_int32),
         ("cu_seqlens", _p),
         ("scale", C.c_float), ("flags", C.c_uint32),
-        ("out", _p), ("lse", _p),
+        ("out", _p), ("out_bf16", _p), ("lse", _p),
         ("workspace", _p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -462,11 +462,12 @@ class AttnOut:
     lse: torch.Tensor   # f32 [B, Hq]
     args: dsk_attn_args
     keep: tuple
+    out_bf16: Optional[torch.Tensor] = None   # bf16 [B, Hq, D] when asked for
 
 
 def make_attn_args(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, sel_start: torch.Tensor,
                    sel_len: torch.Tensor, sel_count: torch.Tensor, b: int, *, scale: float = 0.0,
-                   out: Optional[AttnOut] = None, flags: int = 0) -> AttnOut:
+                   out: Optional[AttnOut] = None, flags: int = 0, want_bf16: bool = False) -> AttnOut:
     dev = q.device
     B, Hq, D = q.shape
     assert D == DSK_HEAD_DIM and q.dtype == torch.bfloat16 and q.is_contiguous()
@@ -488,19 +489,24 @@ def make_attn_args(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, sel_start:
     else:
         o, lse, ws = out.out, out.lse, out.keep[-1]
     a.out, a.lse = _ptr(o), _ptr(lse)
+    ob = out.out_bf16 if out is not None else None
+    if want_bf16 and ob is None:
+        ob = torch.empty(B, Hq, D, dtype=torch.bfloat16, device=dev)
+    a.out_bf16 = _ptr(ob)
     a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
-    return AttnOut(out=o, lse=lse, args=a, keep=(q, K, V, sel_start, sel_len, sel_count, ws))
+    return AttnOut(out=o, lse=lse, args=a, keep=(q, K, V, sel_start, sel_len, sel_count, ws), out_bf16=ob)
 
 
 def sparse_decode_attn(q, K, V, sel_start, sel_len, sel_count, b, *, scale: float = 0.0, stream=None,
-                       check: bool = True) -> AttnOut:
-    r = make_attn_args(q, K, V, sel_start, sel_len, sel_count, b, scale=scale)
+                       check: bool = True, want_bf16: bool = False) -> AttnOut:
+    r = make_attn_args(q, K, V, sel_start, sel_len, sel_count, b, scale=scale, want_bf16=want_bf16)
     dsk_sparse_decode_attn(r.args, stream, check=check)
     return r
 
 
 def make_dense_attn_args(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, cu_seqlens: torch.Tensor,
-                         max_seqlen: int, *, scale: float = 0.0, out: Optional[AttnOut] = None) -> AttnOut:
+                         max_seqlen: int, *, scale: float = 0.0, out: Optional[AttnOut] = None,
+                         want_bf16: bool = False) -> AttnOut:
     dev = q.device
     B, Hq, D = q.shape
     assert D == DSK_HEAD_DIM and q.dtype == torch.bfloat16 and q.is_contiguous()
@@ -522,13 +528,17 @@ def make_dense_attn_args(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, cu_s
     else:
         o, lse, ws = out.out, out.lse, out.keep[-1]
     a.out, a.lse = _ptr(o), _ptr(lse)
+    ob = out.out_bf16 if out is not None else None
+    if want_bf16 and ob is None:
+        ob = torch.empty(B, Hq, D, dtype=torch.bfloat16, device=dev)
+    a.out_bf16 = _ptr(ob)
     a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
-    return AttnOut(out=o, lse=lse, args=a, keep=(q, K, V, cu_seqlens, ws))
+    return AttnOut(out=o, lse=lse, args=a, keep=(q, K, V, cu_seqlens, ws), out_bf16=ob)
 
 
 def dense_decode_attn(q, K, V, cu_seqlens, max_seqlen, *, scale: float = 0.0, stream=None,
-                      check: bool = True) -> AttnOut:
-    att = make_dense_attn_args(q, K, V, cu_seqlens, max_seqlen, scale=scale)
+                      check: bool = True, want_bf16: bool = False) -> AttnOut:
+    att = make_dense_attn_args(q, K, V, cu_seqlens, max_seqlen, scale=scale, want_bf16=want_bf16)
     dsk_dense_decode_attn(att.args, stream, check=check)
     return att
 

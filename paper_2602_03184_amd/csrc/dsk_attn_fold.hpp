@@ -39,6 +39,13 @@ __device__ __forceinline__ float dot8_bf16(const QRow& q, const uint4& k) {
 // 0, which is what a softmax weight that small is worth; -inf gives 0.
 __device__ __forceinline__ float exp2_nonpos(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// one channel of a finished attention output: fp32 always, a nearest-even bf16 copy on request
+__device__ __forceinline__ void store_attn_out(float* __restrict__ out, uint16_t* __restrict__ out_bf16, int64_t idx,
+                                               float v) {
+  out[idx] = v;
+  if (out_bf16 != nullptr) out_bf16[idx] = (uint16_t)(__float_as_uint(bf16_round_rne(v)) >> 16);
+}
+
 // Fold 4*NS already-loaded token rows (K rows kv, V rows vv; row 4u+g in kv[u] of lane group g)
 // into the state.  Rows >= nvalid are padding (their loads were redirected to a real row).
 template <int NS>

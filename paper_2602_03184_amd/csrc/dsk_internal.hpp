@@ -60,7 +60,7 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
 // when cu_seqlens is given.
 hipError_t launch_attn_merge(const float2* part_ml, const float* part_acc, const int32_t* counts,
                              const int32_t* cu_seqlens, int B, int Hq, int k, int nchunks, int per_chunk, float* out,
-                             float* lse, hipStream_t st);
+                             uint16_t* out_bf16, float* lse, hipStream_t st);
 
 // ---- dsk_dense_decode_attn workspace ---------------------------------------------------------
 struct DenseWs {

@@ -15,9 +15,7 @@
 
 namespace dsk {
 
-#ifndef DSK_MERGE_BIG
-#define DSK_MERGE_BIG 1024
-#endif
+constexpr int kMergeBigThreads = 1024;
 
 // slots per workgroup for a slot length bound b
 __host__ __device__ constexpr int attn_slots_per_wg(int b) { return b <= 32 ? 16 : 8; }
@@ -70,7 +68,7 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
     const int32_t* __restrict__ sel_start, const int32_t* __restrict__ sel_len,
     const int32_t* __restrict__ sel_count, float scale_log2, int nchunks,
     float2* __restrict__ part_ml, float* __restrict__ part_acc, float* __restrict__ out,
-    float* __restrict__ lse) {
+    uint16_t* __restrict__ out_bf16, float* __restrict__ lse) {
   constexpr int kAttnWaves = WAVES;
   __shared__ float sm_m[kAttnWaves];
   __shared__ float sm_l[kAttnWaves];
@@ -97,7 +95,7 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
   if (count > k) count = k;
   if (count <= 0) {   // nothing selected: chunk 0 writes the defined empty result
     if (chunk == 0 && threadIdx.x < DSK_HEAD_DIM) {
-      out[sh * DSK_HEAD_DIM + threadIdx.x] = 0.0f;
+      store_attn_out(out, out_bf16, sh * DSK_HEAD_DIM + threadIdx.x, 0.0f);
       if (threadIdx.x == 0 && lse) lse[sh] = -__builtin_inff();
     }
     return;
@@ -200,7 +198,7 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
     a = fmaf(sm_acc[w][d], f, a);
   }
   if (used == 1) {   // the only chunk of this head: finish here
-    out[sh * DSK_HEAD_DIM + d] = l > 0.0f ? a / l : 0.0f;
+    store_attn_out(out, out_bf16, sh * DSK_HEAD_DIM + d, l > 0.0f ? a / l : 0.0f);
     if (d == 0 && lse) lse[sh] = l > 0.0f ? (M + log2f(l)) * kLn2 : -__builtin_inff();
     return;
   }
@@ -216,7 +214,7 @@ template <int kMergeThreads>
 __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
     const float2* __restrict__ part_ml, const float* __restrict__ part_acc,
     const int32_t* __restrict__ sel_count, const int32_t* __restrict__ cu_seqlens, int Hq, int k, int nchunks,
-    int slots_per_wg, float* __restrict__ out, float* __restrict__ lse) {
+    int slots_per_wg, float* __restrict__ out, uint16_t* __restrict__ out_bf16, float* __restrict__ lse) {
   constexpr int kMergeGroups = kMergeThreads / 16;
   __shared__ float sm_m[kMergeGroups];
   __shared__ float sm_l[kMergeGroups];
@@ -282,7 +280,7 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
       L = fmaf(sm_l[g2], f, L);
       A = fmaf(sm_acc[g2][d], f, A);
     }
-    out[sh * DSK_HEAD_DIM + d] = L > 0.0f ? A / L : 0.0f;
+    store_attn_out(out, out_bf16, sh * DSK_HEAD_DIM + d, L > 0.0f ? A / L : 0.0f);
     if (d == 0 && lse) lse[sh] = L > 0.0f ? (M + log2f(L)) * kLn2 : -__builtin_inff();
   }
 }
@@ -311,9 +309,7 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
 #define DSK_ATTN_ARGS                                                                                          \
   q, K, V, a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, a.Hq / a.Hkv, a.k, a.b,     \
       a.total_tokens, a.sel_start, a.sel_len, a.sel_count, scale * kLog2e, ws.nchunks, part_ml, part_acc, a.out, \
-      a.lse
-  // Measured on config 3 (b = 32): one slot (16 KB) in flight per wavefront, the next slot issued
-  // after the fold (STAGED), 9.9 us; both slots issued up front 10.9 us; 8 wavefronts x 1 slot 10.3 us.
+      static_cast<uint16_t*>(a.out_bf16), a.lse
   // Slots of at most 32 rows: workgroups of 8 wavefronts, 2 slots each (16 slots per workgroup).
   // Measured against 4 wavefronts x 2 or 4 slots, 8 x 1 or 4, 16 x 1 or 2 on all configurations:
   // the gather takes 7.3 instead of 8.6 us at 128K / b = 32, and 4.6 instead of 5.6 us at
@@ -325,23 +321,23 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || ws.nchunks <= 1 || (a.flags & DSK_ATTN_PARTIALS_ONLY)) return err;
   return launch_attn_merge(part_ml, part_acc, a.sel_count, nullptr, a.B, a.Hq, a.k, ws.nchunks, ws.slots_per_wg, a.out,
-                           a.lse, st);
+                           static_cast<uint16_t*>(a.out_bf16), a.lse, st);
 }
 
 hipError_t launch_attn_merge(const float2* part_ml, const float* part_acc, const int32_t* counts,
                              const int32_t* cu_seqlens, int B, int Hq, int k, int nchunks, int per_chunk, float* out,
-                             float* lse, hipStream_t st) {
+                             uint16_t* out_bf16, float* lse, hipStream_t st) {
   // one lane group of 16 per partial when there are few, several partials per group otherwise
   const dim3 grid((unsigned)(B * Hq));
   if (nchunks <= 8)
     attn_merge_kernel<128><<<grid, dim3(128), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, k, nchunks, per_chunk,
-                                                       out, lse);
+                                                       out, out_bf16, lse);
   else if (nchunks <= 32)
     attn_merge_kernel<256><<<grid, dim3(256), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, k, nchunks, per_chunk,
-                                                       out, lse);
+                                                       out, out_bf16, lse);
   else
-    attn_merge_kernel<DSK_MERGE_BIG><<<grid, dim3(DSK_MERGE_BIG), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, k,
-                                                                           nchunks, per_chunk, out, lse);
+    attn_merge_kernel<kMergeBigThreads><<<grid, dim3(kMergeBigThreads), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, k,
+                                                                           nchunks, per_chunk, out, out_bf16, lse);
   return hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(kDenseThreads) void dense_attn_kernel(
     int64_t kst, int64_t ksh, int64_t vst, int64_t vsh, int Hq, int G, int total_tokens,
     const int32_t* __restrict__ cu_seqlens, int tokens_per_split, int nsplit, float scale_log2,
     float2* __restrict__ part_ml, float* __restrict__ part_acc, float* __restrict__ out,
-    float* __restrict__ lse) {
+    uint16_t* __restrict__ out_bf16, float* __restrict__ lse) {
   __shared__ float sm_m[kDenseWaves];
   __shared__ float sm_l[kDenseWaves];
   __shared__ float sm_acc[kDenseWaves][DSK_HEAD_DIM];
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kDenseThreads) void dense_attn_kernel(
     if (split == 0 && threadIdx.x < DSK_HEAD_DIM) {
       for (int j = 0; j < ng; ++j) {
         const int64_t sh = (int64_t)s * Hq + hk * G + g0 + j;
-        out[sh * DSK_HEAD_DIM + threadIdx.x] = 0.0f;
+        store_attn_out(out, out_bf16, sh * DSK_HEAD_DIM + threadIdx.x, 0.0f);
         if (threadIdx.x == 0 && lse) lse[sh] = -__builtin_inff();
       }
     }
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kDenseThreads) void dense_attn_kernel(
       }
       const int64_t sh = (int64_t)s * Hq + hk * G + g0 + j;
       if (used == 1) {
-        out[sh * DSK_HEAD_DIM + d] = l > 0.0f ? a / l : 0.0f;
+        store_attn_out(out, out_bf16, sh * DSK_HEAD_DIM + d, l > 0.0f ? a / l : 0.0f);
         if (d == 0 && lse) lse[sh] = l > 0.0f ? (M + log2f(l)) * kLn2 : -__builtin_inff();
       } else {
         const int64_t p = sh * nsplit + split;
@@ -165,7 +165,8 @@ hipError_t launch_dense_attn(const dsk_dense_attn_args& a, const DenseWs& ws, hi
   const uint16_t* V = static_cast<const uint16_t*>(a.V);
 #define DSK_DENSE_ARGS                                                                                        \
   q, K, V, a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, G, a.total_tokens,         \
-      a.cu_seqlens, ws.tokens_per_split, ws.nsplit, scale * kLog2e, part_ml, part_acc, a.out, a.lse
+      a.cu_seqlens, ws.tokens_per_split, ws.nsplit, scale * kLog2e, part_ml, part_acc, a.out,         \
+      static_cast<uint16_t*>(a.out_bf16), a.lse
   // 32-row tiles: 16- and 8-row tiles raise occupancy but were measured slower (the per-tile
   // rescale of four heads' states is vector-ALU work the kernel has little room for)
   if (ws.group_tile == 4) dense_attn_kernel<4, 8><<<grid, dim3(kDenseThreads), 0, st>>>(DSK_DENSE_ARGS);
@@ -175,7 +176,7 @@ hipError_t launch_dense_attn(const dsk_dense_attn_args& a, const DenseWs& ws, hi
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || ws.nsplit <= 1) return err;
   return launch_attn_merge(part_ml, part_acc, nullptr, a.cu_seqlens, a.B, a.Hq, 0x7FFFFFFF, ws.nsplit,
-                           ws.tokens_per_split, a.out, a.lse, st);
+                           ws.tokens_per_split, a.out, static_cast<uint16_t*>(a.out_bf16), a.lse, st);
 }
 
 }  // namespace dsk

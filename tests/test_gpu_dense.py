@@ -104,3 +104,29 @@ def test_dense_is_deterministic_and_validates():
     args.max_seqlen = case.max_seqlen
     args.workspace_bytes = 16
     assert dsk.dsk_dense_decode_attn(args, check=False) == dsk.DSK_ERR_WORKSPACE
+
+
+def test_bf16_copies_of_the_outputs_are_the_rounded_fp32_outputs():
+    """out_bf16 (optional, for a consumer that takes bf16 activations) must be `out` rounded to
+    nearest even, on every path that finishes an output: single-chunk heads, the merge kernel,
+    empty selections, and the dense baseline."""
+    dsk = _dsk()
+    for cfg_id in (1, 3):                                  # 1: few slots; 3: 8 chunks per head, merged
+        case = gpu_case(cfg_id)
+        cfg = case.cfg
+        comp = case.compressed()
+        q = dev_bf16(case.wl.q[0])
+        sel = dsk.select_topk(comp, q, cfg.T)
+        att = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b, want_bf16=True)
+        den = dsk.dense_decode_attn(q, case.K, case.V, case.cu_seqlens, case.max_seqlen, want_bf16=True)
+        torch.cuda.synchronize()
+        for r in (att, den):
+            assert torch.equal(r.out_bf16.view(torch.int16), r.out.to(torch.bfloat16).view(torch.int16))
+    # one slot only (a head finished by the gather kernel itself) and an empty selection
+    case = gpu_case(1)
+    q = dev_bf16(case.wl.q[0])
+    starts, lens = dev_i32(np.asarray([[[5, 0]]])), dev_i32(np.asarray([[[7, 0]]]))
+    for count in (1, 0):
+        att = dsk.sparse_decode_attn(q, case.K, case.V, starts, lens, dev_i32([[count]]), 16, want_bf16=True)
+        torch.cuda.synchronize()
+        assert torch.equal(att.out_bf16.view(torch.int16), att.out.to(torch.bfloat16).view(torch.int16))
