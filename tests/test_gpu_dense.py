@@ -130,3 +130,45 @@ def test_bf16_copies_of_the_outputs_are_the_rounded_fp32_outputs():
         att = dsk.sparse_decode_attn(q, case.K, case.V, starts, lens, dev_i32([[count]]), 16, want_bf16=True)
         torch.cuda.synchronize()
         assert torch.equal(att.out_bf16.view(torch.int16), att.out.to(torch.bfloat16).view(torch.int16))
+
+
+def test_token_major_padded_layout_gives_identical_results():
+    """K/V handed over as token-major (NHD) views with a padded token stride: selection, sparse
+    attention, the dense baseline and an incremental update must give bit-identical results to
+    the head-major contiguous layout (same arithmetic, different addresses)."""
+    dsk = _dsk()
+    case = gpu_case(2, seqlens=[5000])
+    cfg, wl = case.cfg, case.wl
+    L = wl.total_tokens
+    buf = torch.zeros(L, cfg.Hkv, 2, 128 + 64, dtype=torch.bfloat16, device="cuda")
+    buf[:, :, 0, :128] = case.K.permute(1, 0, 2)
+    buf[:, :, 1, :128] = case.V.permute(1, 0, 2)
+    Kv = buf[:, :, 0, :128].permute(1, 0, 2)
+    Vv = buf[:, :, 1, :128].permute(1, 0, 2)
+    assert Kv.stride(1) == cfg.Hkv * 2 * 192 and not Kv.is_contiguous()
+    q = dev_bf16(wl.q[0])
+    L0 = 4000
+
+    def run(K, V):
+        kw = case.compress_kwargs(
+            stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_SEGMENT | dsk.DSK_STAGE_SUMMARIES, K=K, V=V,
+            token_ids=case.token_ids, delim_ids=case.delim_ids, cu_seqlens=dev_i32([0, L0]), max_seqlen=L0,
+            total_tokens=L0, Hkv=cfg.Hkv, max_cand_total=L,
+            max_blocks_total=dsk.dsk_block_capacity(L, 1, int((wl.C - wl.delta).min())))
+        comp = dsk.compress(**kw)
+        app = dsk.make_appender(comp, K, V, case.token_ids, case.delim_ids, case.class_weight_q, C_=int(wl.C[0]),
+                                delta=int(wl.delta[0]), alpha_num=cfg.a_num, alpha_den=cfg.a_den, b=cfg.b)
+        app.step(L0, 4700)
+        app.step(4700, L)
+        sel = dsk.select_topk(comp, q, cfg.T)
+        att = dsk.sparse_decode_attn(q, K, V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b)
+        den = dsk.dense_decode_attn(q, K, V, dev_i32([0, L]), L)
+        torch.cuda.synchronize()
+        assert int(comp.dev_status.item()) == 0
+        nblk = int(comp.cu_blocks.cpu()[1])
+        return comp.ksum[:, :nblk].clone(), sel.sel_slot.clone(), att.out.clone(), att.lse.clone(), den.out.clone()
+
+    ref = run(case.K, case.V)
+    got = run(Kv, Vv)
+    for a, b_ in zip(ref, got):
+        assert a.shape == b_.shape and torch.equal(a, b_)
