@@ -136,9 +136,14 @@ DenseWs dense_ws_layout(const dsk_dense_attn_args& a) {
   const int G = a.Hq / a.Hkv;
   ws.group_tile = (G % 4 == 0) ? 4 : (G % 2 == 0 ? 2 : 1);
   const int64_t passes = (int64_t)a.B * a.Hkv * ((G + ws.group_tile - 1) / ws.group_tile);
-  // about 2048 workgroups (8 per CU) when the cache is long enough, 128 tokens at least each
-  int64_t want_split = (2048 + passes - 1) / passes;
+  // about 4096 workgroups (16 per CU) when the cache is long enough, 128 tokens at least each;
+  // at most kDenseMaxSplit ranges per sequence, since the merge runs one workgroup per head and
+  // its time grows with the partials it reads (measured: 32 beats 16, 24, 64, 128 and 256 at
+  // batch 1 with 32K and 128K tokens)
+  constexpr int64_t kDenseMaxSplit = 32;
+  int64_t want_split = (4096 + passes - 1) / passes;
   if (want_split < 1) want_split = 1;
+  if (want_split > kDenseMaxSplit) want_split = kDenseMaxSplit;
   int64_t tps = ((int64_t)a.max_seqlen + want_split - 1) / want_split;
   tps = (tps + kDenseStep - 1) / kDenseStep * kDenseStep;
   if (tps < kDenseStep) tps = kDenseStep;
