@@ -22,6 +22,11 @@ Parity status against the authors' implementation (none is public):
   * block_means / block_scores_mean -- the mean and the dot product are
                        textbook; that the authors score a mean summary with
                        q.mean is a reading ("parity unpinned").
+  * kv_reuse_plan   -- pinned to a set formulation (Python sets, brute force),
+                       to invariants and to hand-worked cases; which reusable
+                       entries the truncation drops, the order of the loads and
+                       "minimum over the heads of one sequence" are readings
+                       ("parity unpinned" vs the authors' choice of those).
 Everything else (dense_attention included) reduces to a textbook definition and
 is pinned to it in tests/test_oracle_pins.py; tests/test_oracle_mutations.py
 checks that planted mistakes in any of these functions are rejected by a pin.
@@ -364,3 +369,67 @@ def block_scores_mean(q: np.ndarray, kmean: np.ndarray) -> np.ndarray:
         for i in range(nblk):
             s[h, i] = float(np.dot(q[h], kmean[h // G, i]))
     return s
+
+
+# ----------------------------------------------------------------------------
+# KV reuse with V2F (App. B.2, "KVCache Reuse with V2F"): a per-head resident
+# buffer of k fixed-size slots is updated from one decode step to the next
+# ----------------------------------------------------------------------------
+def kv_reuse_plan(resident: Sequence[Sequence[int]], sel: Sequence[Sequence[int]],
+                  stale_from: int | None = None) -> Tuple[int, List[List[int]], List[List[Tuple[int, int]]]]:
+    """One sequence.  resident[h][p] is the slot held at position p of head h's buffer (-1 =
+    empty; held slots are distinct), sel[h] the slots selected for this step (ascending, at most
+    k = len(resident[h])).  A held slot whose index is >= stale_from no longer matches the cache
+    (its chunk was re-segmented) and cannot be reused.
+
+    Step 1: head by head, the reusable entries are the held slots that are selected again; all
+            heads are cut to the smallest reusable count r, keeping each head's first r reusable
+            entries in position order.
+    Step 2: what a head must load is every selected slot it does not keep -- the new ones and
+            the reusable ones cut in Step 1 -- so that every head with a full selection loads
+            k - r slots.
+    Step 3: the loads go, in selection order, into the positions that are not kept, in position
+            order; positions left over are empty.
+
+    Returns (r, new resident table, per head the list of (position, slot) loads)."""
+    H = len(resident)
+    k = len(resident[0]) if H else 0
+    reusable: List[List[int]] = []
+    for h in range(H):
+        chosen = set(int(x) for x in sel[h])
+        pos = []
+        for p in range(k):
+            x = int(resident[h][p])
+            if x >= 0 and x in chosen and (stale_from is None or x < stale_from):
+                pos.append(p)
+        reusable.append(pos)
+    r = min((len(pos) for pos in reusable), default=0)
+    new_resident: List[List[int]] = []
+    loads: List[List[Tuple[int, int]]] = []
+    for h in range(H):
+        keep = reusable[h][:r]
+        kept_slots = set(int(resident[h][p]) for p in keep)
+        need = [int(x) for x in sel[h] if int(x) not in kept_slots]
+        free = [p for p in range(k) if p not in set(keep)]
+        row = [-1] * k
+        for p in keep:
+            row[p] = int(resident[h][p])
+        plan = []
+        for i, x in enumerate(need):
+            row[free[i]] = x
+            plan.append((free[i], x))
+        new_resident.append(row)
+        loads.append(plan)
+    return r, new_resident, loads
+
+
+def kv_reuse_apply(buf: np.ndarray, loads: Sequence[Sequence[Tuple[int, int]]], X: np.ndarray,
+                   spans: dict, b: int, G: int) -> None:
+    """Carries out the loads of kv_reuse_plan on head-major resident buffers: buf[h, p*b + j] =
+    X[h // G, start + j] for j < len, zero for len <= j < b, where (start, len) = spans[slot].
+    X is K or V as [Hkv, T, D]; buf is [Hq, k*b, D] and is modified in place."""
+    for h, plan in enumerate(loads):
+        for p, slot in plan:
+            start, ln = spans[slot]
+            buf[h, p * b:(p + 1) * b] = 0
+            buf[h, p * b:p * b + ln] = X[h // G, start:start + ln]

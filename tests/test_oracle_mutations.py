@@ -80,6 +80,16 @@ MUTANTS = [
     ("mean_is_a_sum", "out[h, i] = acc / (e - s)", "out[h, i] = acc"),
     ("mean_skips_first_token", "for t in range(s, e):\n                acc += X[h, t]", "for t in range(s + 1, e):\n                acc += X[h, t]"),
     ("mean_score_gqa_mapping", "s[h, i] = float(np.dot(q[h], kmean[h // G, i]))", "s[h, i] = float(np.dot(q[h], kmean[h % Hkv, i]))"),
+    ("reuse_ignores_selection", "if x >= 0 and x in chosen and", "if x >= 0 and"),
+    ("reuse_stale_edge", "(stale_from is None or x < stale_from)", "(stale_from is None or x <= stale_from)"),
+    ("reuse_max_over_heads", "r = min((len(pos) for pos in reusable), default=0)", "r = max((len(pos) for pos in reusable), default=0)"),
+    ("reuse_keeps_last_r", "keep = reusable[h][:r]", "keep = reusable[h][len(reusable[h]) - r:]"),
+    ("reuse_no_truncation", "keep = reusable[h][:r]", "keep = reusable[h]"),
+    ("reuse_loads_descending_positions", "row[free[i]] = x\n            plan.append((free[i], x))",
+     "row[free[-1 - i]] = x\n            plan.append((free[-1 - i], x))"),
+    ("reuse_reloads_kept_slots", "need = [int(x) for x in sel[h] if int(x) not in kept_slots]", "need = [int(x) for x in sel[h]][: k - r]"),
+    ("reuse_apply_gqa_mapping", "X[h // G, start:start + ln]", "X[h % (X.shape[0]), start:start + ln]"),
+    ("reuse_apply_no_zero_fill", "buf[h, p * b:(p + 1) * b] = 0\n", "pass\n"),
     ("lse_forgets_max", "return o, float(m + math.log(den))", "return o, float(math.log(den))"),
 ]
 

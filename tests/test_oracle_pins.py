@@ -469,6 +469,125 @@ def test_first_open_block_by_hand():
     assert O.first_open_block([0, 9, 17, 26, 31], 31, 8, 2) == 3  # 10, 19, 27 <= 31 final; 26+10 = 36 > 31 open
 
 
+# ---------------------------------------------------------------- KV reuse with V2F (App. B.2)
+def _random_reuse_case(r, H, k, universe):
+    """A resident table (distinct held slots, some empty) and an ascending selection per head."""
+    resident, sel = [], []
+    for _ in range(H):
+        held = r.permutation(universe)[:k].tolist()
+        for p in range(k):
+            if r.random() < 0.15:
+                held[p] = -1
+        resident.append(held)
+        n = int(r.integers(0, k + 1))
+        sel.append(sorted(r.permutation(universe)[:n].tolist()))
+    return resident, sel
+
+
+def test_kv_reuse_handworked_fixture():
+    with open(os.path.join(GOLDEN, "kv_reuse_handworked.json")) as f:
+        cases = json.load(f)["cases"]
+    assert len(cases) >= 5
+    for c in cases:
+        r, new_res, loads = O.kv_reuse_plan(c["resident"], c["sel"], c.get("stale_from"))
+        assert r == c["r"], c["name"]
+        assert new_res == c["new_resident"], c["name"]
+        assert [[list(x) for x in plan] for plan in loads] == c["loads"], c["name"]
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_kv_reuse_plan_set_formulation_and_invariants(seed):
+    r_ = rng(7000 + seed)
+    H, k = int(r_.integers(1, 6)), int(r_.integers(1, 9))
+    universe = int(r_.integers(k, 3 * k + 2))
+    resident, sel = _random_reuse_case(r_, H, k, universe)
+    stale = None if seed % 3 else int(r_.integers(0, universe + 1))
+    r, new_res, loads = O.kv_reuse_plan(resident, sel, stale)
+    # Step 1 through sets: reusable = held AND selected (AND not stale); r = the smallest such set
+    overlap = []
+    for h in range(H):
+        held = {x for x in resident[h] if x >= 0 and (stale is None or x < stale)}
+        overlap.append(held & set(sel[h]))
+    assert r == min(len(o) for o in overlap)
+    for h in range(H):
+        row, plan = new_res[h], loads[h]
+        kept_pos = [p for p in range(k) if p not in {q for q, _ in plan} and row[p] >= 0]
+        # exactly r entries stay where they were, each of them reusable, and they are the first
+        # r reusable ones in position order
+        assert len(kept_pos) == r
+        reusable_pos = [p for p in range(k) if resident[h][p] in overlap[h]]
+        assert kept_pos == reusable_pos[:r]
+        assert all(row[p] == resident[h][p] for p in kept_pos)
+        # the buffer now holds exactly the selection, once each
+        assert sorted(x for x in row if x >= 0) == list(sel[h])
+        # every head loads (selected - r) slots: k - r when its selection is full
+        assert len(plan) == len(sel[h]) - r
+        if len(sel[h]) == k:
+            assert len(plan) == k - r
+        # loads: ascending slots into ascending positions, never onto a kept position
+        assert [x for _, x in plan] == sorted(x for _, x in plan)
+        assert [q for q, _ in plan] == sorted(q for q, _ in plan)
+        free = [p for p in range(k) if p not in kept_pos]
+        assert [q for q, _ in plan] == free[:len(plan)]
+        assert all(row[q] == x for q, x in plan)
+
+
+def test_kv_reuse_special_cases():
+    # the same selection twice: everything is reused, nothing moves, nothing is loaded
+    sel = [[1, 4, 6], [0, 2, 9]]
+    r0, res0, loads0 = O.kv_reuse_plan([[-1] * 3, [-1] * 3], sel)
+    assert r0 == 0 and res0 == sel and [len(p) for p in loads0] == [3, 3]
+    r1, res1, loads1 = O.kv_reuse_plan(res0, sel)
+    assert r1 == 3 and res1 == res0 and loads1 == [[], []]
+    # disjoint selection: nothing reusable, the whole selection is loaded from position 0
+    r2, res2, loads2 = O.kv_reuse_plan(res0, [[2, 3, 5], [1, 4, 7]])
+    assert r2 == 0 and res2 == [[2, 3, 5], [1, 4, 7]]
+    assert loads2 == [[(0, 2), (1, 3), (2, 5)], [(0, 1), (1, 4), (2, 7)]]
+    # a single head is never truncated: r = |held AND selected|
+    r3, res3, loads3 = O.kv_reuse_plan([[8, 3, 5, 1]], [[1, 2, 3, 4]])
+    assert r3 == 2 and res3 == [[2, 3, 4, 1]] and loads3 == [[(0, 2), (2, 4)]]
+    # one head without overlap drags every head to r = 0: all heads reload their selection
+    r4, res4, loads4 = O.kv_reuse_plan([[1, 2], [3, 4]], [[1, 2], [5, 6]])
+    assert r4 == 0 and loads4 == [[(0, 1), (1, 2)], [(0, 5), (1, 6)]]
+    # stale_from = 0 disables reuse altogether; a bound above every slot changes nothing
+    assert O.kv_reuse_plan(res0, sel, stale_from=0)[0] == 0
+    assert O.kv_reuse_plan(res0, sel, stale_from=10) == (r1, res1, loads1)
+
+
+def test_kv_reuse_sequence_of_steps_keeps_buffer_equal_to_selection_and_data_in_place():
+    """Over many steps the buffers built by applying the loads hold, slot by slot, the K rows
+    of the current selection -- so attention over the buffer is attention over the selection."""
+    r_ = rng(7100)
+    Hkv, G, k, b, D, nslots = 2, 2, 6, 4, 8, 20
+    Hq = Hkv * G
+    spans, start = {}, 0
+    for g in range(nslots):
+        ln = int(r_.integers(1, b + 1))
+        spans[g] = (start, ln)
+        start += ln
+    X = r_.standard_normal((Hkv, start, D))
+    buf = np.full((Hq, k * b, D), np.nan)
+    resident = [[-1] * k for _ in range(Hq)]
+    total_loaded = 0
+    for step in range(12):
+        sel = [sorted(r_.permutation(nslots)[:k].tolist()) for _ in range(Hq)]
+        if step % 4 == 3:
+            sel = [list(row) for row in prev_sel]          # a repeated query reuses everything
+        r, resident, loads = O.kv_reuse_plan(resident, sel)
+        O.kv_reuse_apply(buf, loads, X, spans, b, G)
+        total_loaded += sum(len(p) for p in loads)
+        if step % 4 == 3:
+            assert r == k and all(len(p) == 0 for p in loads)
+        for h in range(Hq):
+            assert sorted(resident[h]) == sel[h]
+            for p, slot in enumerate(resident[h]):
+                st, ln = spans[slot]
+                np.testing.assert_array_equal(buf[h, p * b:p * b + ln], X[h // G, st:st + ln])
+                assert not buf[h, p * b + ln:(p + 1) * b].any()
+        prev_sel = sel
+    assert total_loaded < 12 * Hq * k
+
+
 # ---------------------------------------------------------------- attention
 def test_attention_budget_all_equals_dense_sdpa():
     r = rng(12)
