@@ -9,7 +9,9 @@
  *                           block-to-slot mapped scores (Sec. 4.2; App. B.2 Step 1).
  *   dsk_sparse_decode_attn  per decode step: attention over the K/V of the selected slots
  *                           (App. B.2 Steps 2-3).
- * and three more sit beside it:
+ * and four more sit beside it:
+ *   dsk_reuse_update        step-to-step reuse of the gathered K/V in per-head resident buffers of
+ *                           fixed-size slots (App. B.2, "KVCache Reuse with V2F").
  *   dsk_append_tokens       incremental update of the block table and summaries while decoding
  *                           (Sec. 4.1, "Incremental Update during Decoding"), one sequence per call.
  *   dsk_dense_decode_attn   full attention over the whole cache: the full-KV baseline the method
@@ -313,6 +315,67 @@ typedef struct dsk_append_args {
   size_t workspace_bytes;
 } dsk_append_args;
 
+/* ------------------------------------------------------------------------------------------
+ * dsk_reuse_update -- KV reuse with the variable-to-fixed slot map (App. B.2, "KVCache Reuse
+ * with V2F", Steps 1-3), for a cache whose K/V live in a slower tier (e.g. pinned host memory)
+ * while every (sequence, query head) keeps the K/V of its last selection in a resident buffer of
+ * k positions of b rows.  Slots being b rows at most, any selected slot fits any position.
+ *
+ * Per sequence, with the selection of this step (sel_*, as dsk_select_topk writes them):
+ *   Step 1  a held slot is reusable when it is selected again (and its index is below
+ *           stale_from[s], if given: slots from there on were re-segmented and no longer match
+ *           the cache).  r = the smallest reusable count over the heads of the sequence; every
+ *           head keeps its first r reusable entries in position order.
+ *   Step 2  a head loads every selected slot it does not keep: sel_count - r slots, i.e. k - r
+ *           for all heads with a full selection.
+ *   Step 3  the loads go, in ascending slot order, to the positions that are not kept, in
+ *           ascending position order; positions left over become empty.  Unless
+ *           DSK_REUSE_PLAN_ONLY is set the rows are then copied: position p of head h of
+ *           sequence s occupies rows (s*k + p)*b .. +b-1 of head h of Kres / Vres; rows past the
+ *           slot's length are zero-filled.
+ * res_slot must hold -1 (and res_len 0) in every entry before the first call and is carried by
+ * the caller from step to step; held slots are distinct (the call keeps them so).  After the
+ * call res_start / res_len / res_count describe the buffer as a selection, so that
+ * dsk_sparse_decode_attn with K = Kres, V = Vres, Hkv = Hq, k_stride_tok = D, k_stride_head =
+ * B*k*b*D, total_tokens = B*k*b, sel_start = res_start, sel_len = res_len, sel_count = res_count
+ * attends over exactly the tokens of this step's selection.
+ * Three launches; the workspace holds the per-head reusable counts between them.  Spans that leave [0, total_tokens) are
+ * not copied (their rows are zero-filled).
+ * ---------------------------------------------------------------------------------------- */
+#define DSK_REUSE_PLAN_ONLY 1u
+#define DSK_REUSE_MAX_K 2048
+
+typedef struct dsk_reuse_args {
+  uint32_t struct_size;
+  int32_t B, Hq, Hkv, D;
+  int32_t k;                   /* positions per (sequence, head) = slots per head in sel_*; <= DSK_REUSE_MAX_K */
+  int32_t b;                   /* rows per position; upper bound of sel_len entries */
+  uint32_t flags;              /* DSK_REUSE_* bits */
+  const int32_t* sel_slot;     /* [dev] [B, Hq, k] ascending global slot indices */
+  const int32_t* sel_start;    /* [dev] [B, Hq, k] first global token of the slot */
+  const int32_t* sel_len;      /* [dev] [B, Hq, k] tokens in the slot */
+  const int32_t* sel_count;    /* [dev] [B, Hq] */
+  const int32_t* stale_from;   /* [dev] optional [B]; NULL = every held slot may be reused */
+  int32_t* res_slot;           /* [dev] in/out [B, Hq, k] slot held at each position, -1 = empty */
+  int32_t* res_len;            /* [dev] in/out [B, Hq, k] its token count, 0 = empty */
+  int32_t* res_start;          /* [dev] out [B, Hq, k] first row of the position: (s*k + p)*b */
+  int32_t* res_count;          /* [dev] out [B, Hq] 1 + the last position that is not empty */
+  int32_t* load_pos;           /* [dev] out [B, Hq, k] position each load goes to; -1 padding */
+  int32_t* load_slot;          /* [dev] out [B, Hq, k] slot loaded; -1 padding */
+  int32_t* load_start;         /* [dev] out [B, Hq, k] its first global token */
+  int32_t* load_len;           /* [dev] out [B, Hq, k] its token count; 0 padding */
+  int32_t* load_count;         /* [dev] out [B, Hq] */
+  int32_t* reuse_count;        /* [dev] out [B] r of each sequence */
+  const void* K;               /* bf16 source, strides as in dsk_compress_args; any address the device */
+  const void* V;               /*   can read (HBM or pinned host memory).  Unused with PLAN_ONLY. */
+  int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;
+  int32_t total_tokens;        /* [host] tokens per head in K/V */
+  void* Kres;                  /* [dev] bf16 [Hq, B*k*b, D] */
+  void* Vres;                  /* [dev] bf16 [Hq, B*k*b, D] */
+  void* workspace;             /* [dev] 256-byte aligned, dsk_reuse_workspace_bytes() */
+  size_t workspace_bytes;
+} dsk_reuse_args;
+
 /* Library / ABI version (DSK_ABI_VERSION of the build). */
 uint32_t dsk_version(void);
 
@@ -330,6 +393,7 @@ size_t dsk_select_workspace_bytes(const dsk_select_args* args);
 size_t dsk_attn_workspace_bytes(const dsk_attn_args* args);
 size_t dsk_dense_attn_workspace_bytes(const dsk_dense_attn_args* args);
 size_t dsk_append_workspace_bytes(const dsk_append_args* args);
+size_t dsk_reuse_workspace_bytes(const dsk_reuse_args* args);
 
 /* Where dsk_sparse_decode_attn leaves its split-K partials in args->workspace (what a caller
  * that sets DSK_ATTN_PARTIALS_ONLY reads).  Chunk c of (sequence s, head h) covers the selected
@@ -361,6 +425,7 @@ dsk_status dsk_select_topk(const dsk_select_args* args, void* stream);
 dsk_status dsk_sparse_decode_attn(const dsk_attn_args* args, void* stream);
 dsk_status dsk_dense_decode_attn(const dsk_dense_attn_args* args, void* stream);
 dsk_status dsk_append_tokens(const dsk_append_args* args, void* stream);
+dsk_status dsk_reuse_update(const dsk_reuse_args* args, void* stream);
 
 #ifdef __cplusplus
 }

@@ -33,6 +33,8 @@ DSK_STAGE_ALL = 15
 DSK_HEAD_DIM = 128
 DSK_MAX_CLASSES = 64
 DSK_ATTN_PARTIALS_ONLY = 1
+DSK_REUSE_PLAN_ONLY = 1
+DSK_REUSE_MAX_K = 2048
 DSK_SUMMARY_MINMAX, DSK_SUMMARY_MEAN = 0, 1
 
 _p = C.c_void_p
@@ -130,6 +132,25 @@ class dsk_append_args(C.Structure):
     ]
 
 
+class dsk_reuse_args(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+        ("k", C.c_int32), ("b", C.c_int32), ("flags", C.c_uint32),
+        ("sel_slot", _p), ("sel_start", _p), ("sel_len", _p), ("sel_count", _p),
+        ("stale_from", _p),
+        ("res_slot", _p), ("res_len", _p), ("res_start", _p), ("res_count", _p),
+        ("load_pos", _p), ("load_slot", _p), ("load_start", _p), ("load_len", _p), ("load_count", _p),
+        ("reuse_count", _p),
+        ("K", _p), ("V", _p),
+        ("k_stride_tok", C.c_int64), ("k_stride_head", C.c_int64),
+        ("v_stride_tok", C.c_int64), ("v_stride_head", C.c_int64),
+        ("total_tokens", C.c_int32),
+        ("Kres", _p), ("Vres", _p),
+        ("workspace", _p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
 class dsk_attn_partials(C.Structure):
     _fields_ = [
         ("ml_offset", C.c_size_t), ("acc_offset", C.c_size_t),
@@ -144,7 +165,8 @@ _lib.dsk_strerror.argtypes = [C.c_int32]
 _lib.dsk_block_capacity.restype = C.c_int64
 _lib.dsk_block_capacity.argtypes = [C.c_int32, C.c_int32, C.c_int32]
 for _name, _cls in (("compress", dsk_compress_args), ("select", dsk_select_args), ("attn", dsk_attn_args),
-                    ("dense_attn", dsk_dense_attn_args), ("append", dsk_append_args)):
+                    ("dense_attn", dsk_dense_attn_args), ("append", dsk_append_args),
+                    ("reuse", dsk_reuse_args)):
     _f = getattr(_lib, "dsk_%s_workspace_bytes" % _name)
     _f.restype = C.c_size_t
     _f.argtypes = [C.POINTER(_cls)]
@@ -154,6 +176,8 @@ _lib.dsk_dense_decode_attn.restype = C.c_int32
 _lib.dsk_dense_decode_attn.argtypes = [C.POINTER(dsk_dense_attn_args), _p]
 _lib.dsk_append_tokens.restype = C.c_int32
 _lib.dsk_append_tokens.argtypes = [C.POINTER(dsk_append_args), _p]
+_lib.dsk_reuse_update.restype = C.c_int32
+_lib.dsk_reuse_update.argtypes = [C.POINTER(dsk_reuse_args), _p]
 _lib.dsk_stream_read_probe.restype = C.c_int32
 _lib.dsk_stream_read_probe.argtypes = [_p, C.c_size_t, _p, _p]
 _lib.dsk_compress.restype = C.c_int32
@@ -214,6 +238,17 @@ def dsk_append_tokens(args: dsk_append_args, stream=None, check: bool = True) ->
     st = int(_lib.dsk_append_tokens(C.byref(args), _stream_handle(stream)))
     if check and st != DSK_OK:
         raise DskError(st, "dsk_append_tokens")
+    return st
+
+
+def dsk_reuse_workspace_bytes(args: dsk_reuse_args) -> int:
+    return int(_lib.dsk_reuse_workspace_bytes(C.byref(args)))
+
+
+def dsk_reuse_update(args: dsk_reuse_args, stream=None, check: bool = True) -> int:
+    st = int(_lib.dsk_reuse_update(C.byref(args), _stream_handle(stream)))
+    if check and st != DSK_OK:
+        raise DskError(st, "dsk_reuse_update")
     return st
 
 
@@ -584,3 +619,75 @@ def make_appender(comp: Compressed, K: torch.Tensor, V: Optional[torch.Tensor], 
     ws = _ws(dsk_append_workspace_bytes(a), dev)
     a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
     return Appender(args=a, first_recomputed=first, keep=(comp, K, V, token_ids, delim_ids, class_weight_q, ws))
+
+
+@dataclass
+class Reuser:
+    """Resident K/V buffers of one batch and the state dsk_reuse_update carries from step to step."""
+    k: int
+    b: int
+    res_slot: torch.Tensor     # int32 [B, Hq, k], -1 = empty
+    res_len: torch.Tensor
+    res_start: torch.Tensor
+    res_count: torch.Tensor    # int32 [B, Hq]
+    load_pos: torch.Tensor     # int32 [B, Hq, k]
+    load_slot: torch.Tensor
+    load_start: torch.Tensor
+    load_len: torch.Tensor
+    load_count: torch.Tensor   # int32 [B, Hq]
+    reuse_count: torch.Tensor  # int32 [B]
+    Kres: Optional[torch.Tensor]   # bf16 [Hq, B*k*b, D]
+    Vres: Optional[torch.Tensor]
+    args: dsk_reuse_args
+    keep: tuple
+
+    def step(self, stream=None, check: bool = True) -> int:
+        return dsk_reuse_update(self.args, stream, check=check)
+
+    def attn_args(self, q: torch.Tensor, *, scale: float = 0.0, out: Optional[AttnOut] = None) -> AttnOut:
+        """Arguments of dsk_sparse_decode_attn over the resident buffers (every query head its own K/V)."""
+        return make_attn_args(q, self.Kres, self.Vres, self.res_start, self.res_len, self.res_count, self.b,
+                              scale=scale, out=out)
+
+
+def make_reuser(sel: Selection, K: Optional[torch.Tensor], V: Optional[torch.Tensor], Hkv: int, *,
+                stale_from: Optional[torch.Tensor] = None, plan_only: bool = False) -> Reuser:
+    """sel: the Selection whose buffers every step's dsk_select_topk writes.  K / V: bf16
+    [Hkv, tokens, D] views the device can read (HBM, or pinned host memory)."""
+    dev = sel.sel_slot.device
+    B, Hq, k = sel.sel_slot.shape
+    b = sel.b
+    i32 = dict(dtype=torch.int32, device=dev)
+    a = dsk_reuse_args()
+    a.struct_size = C.sizeof(dsk_reuse_args)
+    a.B, a.Hq, a.Hkv, a.D = B, Hq, Hkv, DSK_HEAD_DIM
+    a.k, a.b, a.flags = k, b, DSK_REUSE_PLAN_ONLY if plan_only else 0
+    a.sel_slot, a.sel_start, a.sel_len, a.sel_count = (_ptr(sel.sel_slot), _ptr(sel.sel_start), _ptr(sel.sel_len),
+                                                       _ptr(sel.sel_count))
+    a.stale_from = _ptr(stale_from)
+    res_slot = torch.full((B, Hq, k), -1, **i32)
+    res_len = torch.zeros(B, Hq, k, **i32)
+    res_start = torch.zeros(B, Hq, k, **i32)
+    res_count = torch.zeros(B, Hq, **i32)
+    load_pos, load_slot = torch.empty(B, Hq, k, **i32), torch.empty(B, Hq, k, **i32)
+    load_start, load_len = torch.empty(B, Hq, k, **i32), torch.empty(B, Hq, k, **i32)
+    load_count = torch.zeros(B, Hq, **i32)
+    reuse_count = torch.zeros(B, **i32)
+    a.res_slot, a.res_len, a.res_start, a.res_count = _ptr(res_slot), _ptr(res_len), _ptr(res_start), _ptr(res_count)
+    a.load_pos, a.load_slot, a.load_start, a.load_len = _ptr(load_pos), _ptr(load_slot), _ptr(load_start), _ptr(load_len)
+    a.load_count, a.reuse_count = _ptr(load_count), _ptr(reuse_count)
+    Kres = Vres = None
+    if not plan_only:
+        a.K, a.V = _ptr(K), _ptr(V)
+        a.k_stride_tok, a.k_stride_head = _kv_strides(K)
+        a.v_stride_tok, a.v_stride_head = _kv_strides(V)
+        a.total_tokens = K.shape[1]
+        Kres = torch.zeros(Hq, B * k * b, DSK_HEAD_DIM, dtype=torch.bfloat16, device=dev)
+        Vres = torch.zeros(Hq, B * k * b, DSK_HEAD_DIM, dtype=torch.bfloat16, device=dev)
+        a.Kres, a.Vres = _ptr(Kres), _ptr(Vres)
+    ws = _ws(dsk_reuse_workspace_bytes(a), dev)
+    a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
+    return Reuser(k=k, b=b, res_slot=res_slot, res_len=res_len, res_start=res_start, res_count=res_count,
+                  load_pos=load_pos, load_slot=load_slot, load_start=load_start, load_len=load_len,
+                  load_count=load_count, reuse_count=reuse_count, Kres=Kres, Vres=Vres, args=a,
+                  keep=(sel, K, V, stale_from, ws))

@@ -186,6 +186,31 @@ static dsk_status validate_dense(const dsk_dense_attn_args* a) {
   return DSK_OK;
 }
 
+static dsk_status validate_reuse(const dsk_reuse_args* a) {
+  if (a == nullptr) return DSK_ERR_NULL;
+  if (a->struct_size != sizeof(dsk_reuse_args)) return DSK_ERR_VERSION;
+  if (!geometry_ok(a->B, a->Hq, a->Hkv, a->D)) return DSK_ERR_SHAPE;
+  if (a->k < 1 || a->k > DSK_REUSE_MAX_K || a->b < 1 || a->total_tokens < 0) return DSK_ERR_SHAPE;
+  if ((int64_t)a->B * a->k * a->b > 0x7FFFFFFF) return DSK_ERR_SHAPE;   // rows of a resident head are int32
+  if (a->flags & ~DSK_REUSE_PLAN_ONLY) return DSK_ERR_PARAM;
+  if (!a->sel_slot || !a->sel_start || !a->sel_len || !a->sel_count || !a->res_slot || !a->res_len ||
+      !a->res_start || !a->res_count || !a->load_pos || !a->load_slot || !a->load_start || !a->load_len ||
+      !a->load_count || !a->reuse_count)
+    return DSK_ERR_NULL;
+  if (!(a->flags & DSK_REUSE_PLAN_ONLY)) {
+    if (!a->K || !a->V || !a->Kres || !a->Vres) return DSK_ERR_NULL;
+    if (a->k_stride_tok < DSK_HEAD_DIM || a->v_stride_tok < DSK_HEAD_DIM || a->k_stride_head < 0 ||
+        a->v_stride_head < 0)
+      return DSK_ERR_SHAPE;
+    if (!aligned16(a->K) || !aligned16(a->V) || !aligned16(a->Kres) || !aligned16(a->Vres) || a->k_stride_tok % 8 ||
+        a->k_stride_head % 8 || a->v_stride_tok % 8 || a->v_stride_head % 8)
+      return DSK_ERR_ALIGN;
+  }
+  if (a->workspace == nullptr || a->workspace_bytes < dsk_reuse_workspace_bytes(a)) return DSK_ERR_WORKSPACE;
+  if (!aligned256(a->workspace)) return DSK_ERR_ALIGN;
+  return DSK_OK;
+}
+
 }  // namespace dsk
 
 using namespace dsk;
@@ -256,6 +281,18 @@ dsk_status dsk_append_tokens(const dsk_append_args* a, void* stream) {
   const dsk_status v = validate_append(a);
   if (v != DSK_OK) return v;
   if (launch_append(*a, static_cast<hipStream_t>(stream)) != hipSuccess) return DSK_ERR_LAUNCH;
+  return DSK_OK;
+}
+
+size_t dsk_reuse_workspace_bytes(const dsk_reuse_args* a) {
+  if (a == nullptr || a->struct_size != sizeof(dsk_reuse_args) || a->B < 1 || a->Hq < 1) return 0;
+  return reuse_ws_bytes(*a);
+}
+
+dsk_status dsk_reuse_update(const dsk_reuse_args* a, void* stream) {
+  const dsk_status v = validate_reuse(a);
+  if (v != DSK_OK) return v;
+  if (launch_reuse(*a, static_cast<hipStream_t>(stream)) != hipSuccess) return DSK_ERR_LAUNCH;
   return DSK_OK;
 }
 

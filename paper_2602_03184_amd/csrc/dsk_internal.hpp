@@ -82,6 +82,10 @@ hipError_t launch_summaries_range(const void* X, int64_t stride_tok, int64_t str
 // incremental update: workspace = int32 {first recomputed block, new block count}
 hipError_t launch_append(const dsk_append_args& a, hipStream_t st);
 
+// KV reuse over resident buffers: workspace = int32 [B*Hq] reusable counts
+size_t reuse_ws_bytes(const dsk_reuse_args& a);
+hipError_t launch_reuse(const dsk_reuse_args& a, hipStream_t st);
+
 hipError_t launch_stream_read(const void* buf, size_t bytes, uint32_t* sink, hipStream_t st);
 
 }  // namespace dsk

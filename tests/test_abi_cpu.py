@@ -68,6 +68,60 @@ int main(void) {
     assert got == want
 
 
+def test_reuse_struct_mirrors_the_header_field_by_field(dsk, tmp_path):
+    ra = dsk.dsk_reuse_args
+    fields = [f[0] for f in ra._fields_]
+    prog = tmp_path / "reuse.c"
+    prog.write_text("#include <stdio.h>\n#include <stddef.h>\n#include \"dsk.h\"\nint main(void) {\n"
+                    "  printf(\"%zu \", sizeof(dsk_reuse_args));\n"
+                    + "".join('  printf("%%zu ", offsetof(dsk_reuse_args, %s));\n' % f for f in fields)
+                    + "  printf(\"%d %d\\n\", (int)DSK_REUSE_PLAN_ONLY, (int)DSK_REUSE_MAX_K);\n  return 0;\n}\n")
+    exe = tmp_path / "reuse"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(prog), "-o", str(exe)])
+    got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    want = [C.sizeof(ra)] + [getattr(ra, f).offset for f in fields] + [dsk.DSK_REUSE_PLAN_ONLY, dsk.DSK_REUSE_MAX_K]
+    assert got == want
+
+
+def test_reuse_validation(dsk):
+    fake = 0x10000
+
+    def args():
+        a = dsk.dsk_reuse_args()
+        a.struct_size = C.sizeof(a)
+        a.B, a.Hq, a.Hkv, a.D = 2, 4, 2, 128
+        a.k, a.b = 8, 16
+        for f in ("sel_slot", "sel_start", "sel_len", "sel_count", "res_slot", "res_len", "res_start", "res_count",
+                  "load_pos", "load_slot", "load_start", "load_len", "load_count", "reuse_count", "K", "V", "Kres",
+                  "Vres"):
+            setattr(a, f, fake)
+        a.k_stride_tok = a.v_stride_tok = 128
+        a.k_stride_head = a.v_stride_head = 128000
+        a.total_tokens = 1000
+        return a
+    assert dsk.dsk_reuse_update(args(), 0, check=False) == dsk.DSK_ERR_WORKSPACE
+    assert dsk.dsk_reuse_workspace_bytes(args()) >= 2 * 4 * 4
+    for field, value, want in (("struct_size", 4, dsk.DSK_ERR_VERSION), ("Hkv", 3, dsk.DSK_ERR_SHAPE),
+                               ("k", 0, dsk.DSK_ERR_SHAPE), ("k", dsk.DSK_REUSE_MAX_K + 1, dsk.DSK_ERR_SHAPE),
+                               ("b", 0, dsk.DSK_ERR_SHAPE), ("flags", 2, dsk.DSK_ERR_PARAM),
+                               ("sel_slot", None, dsk.DSK_ERR_NULL), ("res_slot", None, dsk.DSK_ERR_NULL),
+                               ("load_len", None, dsk.DSK_ERR_NULL), ("reuse_count", None, dsk.DSK_ERR_NULL),
+                               ("K", None, dsk.DSK_ERR_NULL), ("Vres", None, dsk.DSK_ERR_NULL),
+                               ("K", fake + 2, dsk.DSK_ERR_ALIGN), ("k_stride_tok", 64, dsk.DSK_ERR_SHAPE),
+                               ("v_stride_head", 4, dsk.DSK_ERR_ALIGN)):
+        a = args()
+        setattr(a, field, value)
+        assert dsk.dsk_reuse_update(a, 0, check=False) == want, field
+    # the plan alone needs neither the source nor the buffers
+    a = args()
+    a.flags = dsk.DSK_REUSE_PLAN_ONLY
+    a.K = a.V = a.Kres = a.Vres = None
+    assert dsk.dsk_reuse_update(a, 0, check=False) == dsk.DSK_ERR_WORKSPACE
+    a = args()
+    a.B, a.k, a.b = 65535, 2048, 1024       # more rows per resident head than int32 holds
+    assert dsk.dsk_reuse_update(a, 0, check=False) == dsk.DSK_ERR_SHAPE
+
+
 def _valid_compress(dsk):
     a = dsk.dsk_compress_args()
     a.struct_size = C.sizeof(a)

@@ -14,5 +14,6 @@ from .synth import (  # noqa: F401
     make_tokens,
     make_kv,
     make_queries,
+    make_drifting_queries,
     make_qwin,
 )

@@ -9,6 +9,7 @@ the method: it only draws inputs and converts fp32 draws to bf16 bit patterns.
 from __future__ import annotations
 
 import dataclasses
+import math
 from dataclasses import dataclass, field
 from typing import List, Optional, Sequence
 
@@ -156,6 +157,19 @@ def make_kv(rng: np.random.Generator, Hkv: int, L: int, D: int, outliers: np.nda
 
 def make_queries(rng: np.random.Generator, n: int, B: int, Hq: int, D: int) -> np.ndarray:
     return f32_to_bf16_bits(rng.standard_normal((n, B, Hq, D), dtype=np.float32))
+
+
+def make_drifting_queries(rng: np.random.Generator, n: int, B: int, Hq: int, D: int, rho: float) -> np.ndarray:
+    """bf16 bits [n, B, Hq, D] of a decode-like query stream: a first-order autoregressive walk
+    q[t+1] = rho*q[t] + sqrt(1 - rho^2)*noise, every q[t] ~ N(0,1) per channel, so that
+    consecutive steps resemble each other (rho = 0 gives independent queries)."""
+    out = np.empty((n, B, Hq, D), dtype=np.float32)
+    cur = rng.standard_normal((B, Hq, D), dtype=np.float32)
+    mix = np.float32(math.sqrt(max(0.0, 1.0 - rho * rho)))
+    for t in range(n):
+        out[t] = cur
+        cur = np.float32(rho) * cur + mix * rng.standard_normal((B, Hq, D), dtype=np.float32)
+    return f32_to_bf16_bits(out)
 
 
 def make_qwin(rng: np.random.Generator, B: int, n_samp: int, W: int, Hq: int, D: int) -> np.ndarray:
