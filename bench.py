@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # counter reads for the plain 256 MiB device copy of --calib-copy-mib (FETCH_SIZE reads half the
 # copied bytes on this part -> x2; WRITE_SIZE reads them exactly -> x1).  Keyed by workload.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg3_llama3_8b_128k": {"attn_kernel": int(18914.2 * 1024 * 2.000 + 136.0 * 1024 * 1.000)},
+    "cfg3_llama3_8b_128k": {"attn_kernel": int(18923.2 * 1024 * 2.000 + 136.0 * 1024 * 1.000)},
 }
 
 
@@ -42,6 +42,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--append-steps", type=int, default=256,
                     help="steps of the decode loop that appends one token per step before selecting; 0 = skip")
+    ap.add_argument("--reuse-steps", type=int, default=48,
+                    help="decode steps of the KV-reuse leg (K/V in pinned host memory); 0 disables it")
+    ap.add_argument("--reuse-rho", type=float, default=0.98,
+                    help="step-to-step correlation of the drifting query stream of the KV-reuse leg")
     ap.add_argument("--cold-instances", type=int, default=16,
                     help="copies of the cache (K, V, summaries) the cold-cache measurement rotates over; 0 = skip")
     ap.add_argument("--stream-read-mib", type=int, default=2048,
@@ -332,6 +336,95 @@ def main():
             loop = {"steps": n_app, "us_per_step": round(loop_us, 3),
                     "append_us": round(loop_us - us_per_step, 3),
                     "grown_table_equals_full_compress": bool(ok)}
+
+        # ---- KV reuse with the slot map (App. B.2): K/V live in pinned host memory, every (sequence,
+        #      head) keeps its last selection in a resident buffer, and a step loads only the slots
+        #      it does not hold.  Queries drift (AR(1)), so consecutive selections overlap. -------------
+        reuse = None
+        kv_bytes = 2 * K.numel() * 2
+        if args.reuse_steps > 0 and kv_bytes <= (8 << 30):
+            from workloads import make_drifting_queries
+            n_r = args.reuse_steps
+            dq = make_drifting_queries(np.random.default_rng(20260203), n_r + 1, cfg.B, cfg.Hq, cfg.D, args.reuse_rho)
+            dqs = [bf16(dq[i]) for i in range(n_r + 1)]
+            Kh = torch.empty(K.shape, dtype=torch.bfloat16, pin_memory=True)
+            Vh = torch.empty(V.shape, dtype=torch.bfloat16, pin_memory=True)
+            Kh.copy_(K)
+            Vh.copy_(V)
+            torch.cuda.synchronize()
+            rsel = [dsk.make_select_args(comp, dqs[0], cfg.T, max_blocks_used=nblk, max_blocks_per_seq=nblk_seq)]
+            for i in range(1, n_r + 1):
+                rsel.append(dsk.make_select_args(comp, dqs[i], cfg.T, out=rsel[0], max_blocks_used=nblk,
+                                                 max_blocks_per_seq=nblk_seq))
+            r_per_step = torch.zeros(n_r + 1, cfg.B, dtype=torch.int32, device=dev)
+            loads_per_step = torch.zeros(n_r + 1, cfg.B, cfg.Hq, dtype=torch.int32, device=dev)
+
+            def reuse_variant(Ksrc, Vsrc):
+                ru = dsk.make_reuser(rsel[0], Ksrc, Vsrc, cfg.Hkv)
+                rargs = []
+                for i in range(n_r + 1):
+                    a = type(ru.args).from_buffer_copy(ru.args)
+                    a.reuse_count = r_per_step[i].data_ptr()
+                    a.load_count = loads_per_step[i].data_ptr()
+                    rargs.append(a)
+                ratt = [ru.attn_args(dqs[0])]
+                for i in range(1, n_r + 1):
+                    ratt.append(ru.attn_args(dqs[i], out=ratt[0]))
+
+                def rstep(i):
+                    dsk.dsk_select_topk(rsel[i].args, stream)
+                    dsk.dsk_reuse_update(rargs[i], stream)
+                    dsk.dsk_sparse_decode_attn(ratt[i].args, stream)
+
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    for i in range(1, n_r + 1):
+                        rstep(i)
+                us = []
+                for _ in range(2):                       # same work both times: the buffer restarts empty
+                    ru.res_slot.fill_(-1)
+                    ru.res_len.zero_()
+                    stream.wait_stream(torch.cuda.current_stream())
+                    rstep(0)                             # untimed: fills the empty buffer
+                    us.append(event_ms(g.replay, stream) * 1e3 / n_r)
+                stream.synchronize()
+                return us[-1], (ru, rargs, ratt, g)
+
+            host_us, keep_h = reuse_variant(Kh, Vh)
+            mean_r = float(r_per_step[1:].float().mean().item())
+            mean_loads = float(loads_per_step[1:].float().sum(dim=(1, 2)).mean().item())
+            hbm_us, keep_d = reuse_variant(K, V)
+            # without reuse: the attention gathers every selected slot from host memory, every step
+            natt = [dsk.make_attn_args(dqs[i], Kh, Vh, rsel[0].sel_start, rsel[0].sel_len, rsel[0].sel_count, cfg.b,
+                                       out=atts[0]) for i in range(n_r + 1)]
+            g_nr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_nr, stream=stream):
+                for i in range(1, n_r + 1):
+                    dsk.dsk_select_topk(rsel[i].args, stream)
+                    dsk.dsk_sparse_decode_attn(natt[i].args, stream)
+            g_nr.replay()
+            stream.synchronize()
+            noreuse_us = event_ms(g_nr.replay, stream) * 1e3 / n_r
+            # full attention with K/V in host memory: every byte of the cache crosses the link
+            hd = dsk.make_dense_attn_args(dqs[0], Kh, Vh, cu, int(wl.seqlens.max()))
+            dsk.dsk_dense_decode_attn(hd.args, stream)
+            dense_host_us = event_ms(lambda: [dsk.dsk_dense_decode_attn(hd.args, stream) for _ in range(2)], stream) * 1e3 / 2
+            tok_per_slot = mean_sel_tokens / max(1, cfg.B * cfg.Hq * cfg.k)
+            load_bytes = mean_loads * tok_per_slot * 512
+            reuse = {"steps": n_r, "rho": args.reuse_rho, "k": cfg.k,
+                     "mean_reused_slots_per_head": round(mean_r, 1),
+                     "slots_loaded_per_step": round(mean_loads, 1),
+                     "link_bytes_per_step": int(load_bytes),
+                     "host_kv_with_reuse_us": round(host_us, 2),
+                     "host_kv_with_reuse_link_GBps": round(load_bytes / (host_us * 1e-6) / 1e9, 1),
+                     "host_kv_without_reuse_us": round(noreuse_us, 2),
+                     "host_kv_full_attention_us": round(dense_host_us, 1),
+                     "hbm_kv_with_reuse_us": round(hbm_us, 2),
+                     "speedup_reuse_vs_no_reuse": round(noreuse_us / host_us, 2),
+                     "speedup_reuse_vs_full_attention_host": round(dense_host_us / host_us, 1),
+                     "what": "select + dsk_reuse_update + attention over the resident buffers; K/V source in "
+                             "pinned host memory read in place by the kernels"}
+            del keep_h, keep_d, g_nr, natt, hd, Kh, Vh
     torch.cuda.synchronize()
 
     attn_gbs = bytes_attn / (gather_us * 1e-6) / 1e9
@@ -386,6 +479,8 @@ def main():
         out["cold"] = cold
     if loop is not None:
         out["decode_loop_with_append"] = loop
+    if reuse is not None:
+        out["kv_reuse"] = reuse
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, comp, nblk)
     print(json.dumps(out))
