@@ -310,6 +310,8 @@ typedef struct dsk_append_args {
   void* vsum;                  /* [dev] in/out or NULL */
   int32_t summary_mode;        /* as in dsk_compress_args */
   int32_t* first_recomputed;   /* [dev] optional out: index of the first rewritten chunk */
+  int32_t* first_stale_slot;   /* [dev] optional out: slot_base of that chunk -- slots from there on were
+                                  re-mapped (what dsk_reuse_update takes as stale_from) */
   int32_t* dev_status;         /* [dev] optional */
   void* workspace;             /* [dev] 256-byte aligned, dsk_append_workspace_bytes() */
   size_t workspace_bytes;

@@ -127,7 +127,7 @@ class dsk_append_args(C.Structure):
         ("block_start", _p), ("cu_blocks", _p), ("slot_base", _p),
         ("ksum", _p), ("vsum", _p),
         ("summary_mode", C.c_int32),
-        ("first_recomputed", _p), ("dev_status", _p),
+        ("first_recomputed", _p), ("first_stale_slot", _p), ("dev_status", _p),
         ("workspace", _p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -584,6 +584,7 @@ class Appender:
     Compressed; set len_old / len_new and call step()."""
     args: dsk_append_args
     first_recomputed: torch.Tensor
+    first_stale_slot: torch.Tensor      # int32 [1]: usable as stale_from of dsk_reuse_update
     keep: tuple
 
     def step(self, len_old: int, len_new: int, stream=None, check: bool = True) -> int:
@@ -615,10 +616,12 @@ def make_appender(comp: Compressed, K: torch.Tensor, V: Optional[torch.Tensor], 
     a.summary_mode = comp.args.summary_mode
     first = torch.zeros(1, dtype=torch.int32, device=dev)
     a.first_recomputed = _ptr(first)
+    stale = torch.zeros(1, dtype=torch.int32, device=dev)
+    a.first_stale_slot = _ptr(stale)
     a.dev_status = _ptr(comp.dev_status)
     ws = _ws(dsk_append_workspace_bytes(a), dev)
     a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
-    return Appender(args=a, first_recomputed=first, keep=(comp, K, V, token_ids, delim_ids, class_weight_q, ws))
+    return Appender(args=a, first_recomputed=first, first_stale_slot=stale, keep=(comp, K, V, token_ids, delim_ids, class_weight_q, ws))
 
 
 @dataclass

@@ -23,7 +23,7 @@ __global__ __launch_bounds__(DSK_WAVE) void append_segment_kernel(
     const uint8_t* __restrict__ class_weight_q, int len_old, int len_new, int C, int delta, int a_num,
     int a_den, int b, int cap, int32_t* __restrict__ block_start, int32_t* __restrict__ cu_blocks,
     int32_t* __restrict__ slot_base, int32_t* __restrict__ range, int32_t* __restrict__ first_recomputed,
-    int32_t* dev_status) {
+    int32_t* __restrict__ first_stale_slot, int32_t* dev_status) {
   __shared__ int32_t ids[DSK_MAX_CLASSES];
   __shared__ int32_t wqs[DSK_MAX_CLASSES];
   const int lane = threadIdx.x;
@@ -39,6 +39,7 @@ __global__ __launch_bounds__(DSK_WAVE) void append_segment_kernel(
       set_status(dev_status, DSK_ERR_SHAPE);
       range[0] = 0; range[1] = 0;
       if (first_recomputed) *first_recomputed = nblk;
+      if (first_stale_slot) *first_stale_slot = 0;         // the table is not trusted: nothing is reusable
     }
     return;
   }
@@ -54,6 +55,7 @@ __global__ __launch_bounds__(DSK_WAVE) void append_segment_kernel(
   const int i0 = nblk - n_open;
   int s_c = i0 < nblk ? block_start[i0] : len_old;
   int slot = slot_base[i0];                                // slot_base[nblk] is the slot total when i0 == nblk
+  const int stale_slot = slot;
   int i = i0;
   bool overflow = false;
   const int dd = delta > 1 ? delta : 1;
@@ -92,6 +94,7 @@ __global__ __launch_bounds__(DSK_WAVE) void append_segment_kernel(
     range[0] = i0;
     range[1] = i;
     if (first_recomputed) *first_recomputed = i0;
+    if (first_stale_slot) *first_stale_slot = stale_slot;
     if (overflow) set_status(dev_status, DSK_ERR_CAPACITY);
   }
 }
@@ -101,7 +104,7 @@ hipError_t launch_append(const dsk_append_args& a, hipStream_t st) {
   append_segment_kernel<<<dim3(1), dim3(DSK_WAVE), 0, st>>>(
       a.token_ids, a.delim_ids, a.n_class, a.class_weight_q, a.len_old, a.len_new, a.C, a.delta, a.alpha_num,
       a.alpha_den, a.b, a.max_blocks_total, a.block_start, a.cu_blocks, a.slot_base, range, a.first_recomputed,
-      a.dev_status);
+      a.first_stale_slot, a.dev_status);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   // chunks that can be rewritten: the open ones start after len_old - C - delta, and every chunk

@@ -74,6 +74,8 @@ class _Seq:
         np.testing.assert_array_equal(self.comp.block_start.cpu().numpy()[: nblk + 1], want)
         np.testing.assert_array_equal(self.comp.slot_base.cpu().numpy()[: nblk + 1], O.slot_map(want, self.b))
         assert int(self.app.first_recomputed.item()) == i0
+        # chunks before i0 are untouched, so slot_base[i0] is the same in the old and the new table
+        assert int(self.app.first_stale_slot.item()) == int(O.slot_map(want, self.b)[i0])
 
     def check_summaries(self, want, vsum=False):
         nblk = len(want) - 1

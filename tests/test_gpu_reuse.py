@@ -239,3 +239,41 @@ def test_reuse_parity_full_size(cfg_id):
     hist, k = _run(case, 3, 0.98, heads, repeat_at=(2,))
     assert k == cfg.k
     print("config %d reuse counts:" % cfg_id, hist, "of k =", k)
+
+
+def test_reuse_in_a_decode_loop_with_appends():
+    """The cache grows while decoding: dsk_append_tokens re-maps the slots of the open chunks and
+    hands the first re-mapped slot to dsk_reuse_update as stale_from (device to device, nothing is
+    read back).  Every step: plan and buffers against the oracle run with the oracle's own stale
+    bound, attention over the buffers against the oracle on the current cache."""
+    from test_gpu_append import _Seq
+    dsk = _dsk()
+    case = gpu_case(2, seqlens=[6000], T=512, n_queries=1)
+    wl, cfg = case.wl, case.cfg
+    seq = _Seq(wl.K, wl.V, wl.token_ids, wl.delim_ids, wl.class_weight_q[0], 4000, int(wl.C[0]), int(wl.delta[0]),
+               cfg.a_num, cfg.a_den, cfg.b, Hq=cfg.Hq)
+    n_steps = 10
+    qs = make_drifting_queries(np.random.default_rng(3), n_steps, 1, cfg.Hq, cfg.D, 0.98)
+    q = dev_bf16(qs[0])
+    sel = dsk.make_select_args(seq.comp, q, 512)
+    reuser = dsk.make_reuser(sel, seq.K, seq.V, cfg.Hkv, stale_from=seq.app.first_stale_slot)
+    mir = _Mirror(1, cfg.Hq, sel.k, cfg.b, cfg.D)
+    att_res = att_dir = None
+    r_seen = []
+    grow = [1, 1, 3, 1, 40, 1, 1, 200, 1, 1]
+    for t in range(n_steps):
+        q.copy_(dev_bf16(qs[t]))
+        want, i0 = seq.append(grow[t])
+        seq.check_tables(want, i0)
+        stale = [int(O.slot_map(want, cfg.b)[i0])]
+        dsk.dsk_select_topk(sel.args)
+        reuser.step()
+        att_res = reuser.attn_args(q, out=att_res)
+        dsk.dsk_sparse_decode_attn(att_res.args)
+        att_dir = dsk.make_attn_args(q, seq.K, seq.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b, out=att_dir)
+        dsk.dsk_sparse_decode_attn(att_dir.args)
+        torch.cuda.synchronize()
+        rs = _check_step(dsk, case, mir, sel, reuser, qs[t], att_res, att_dir, [0, 9, 31], stale)
+        r_seen.append(rs[0])
+    assert r_seen[0] == 0 and max(r_seen[1:]) > 0
+    print("reuse counts while the cache grows:", r_seen, "of k =", sel.k)
