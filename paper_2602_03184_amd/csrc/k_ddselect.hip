@@ -33,7 +33,6 @@ extern "C" __attribute__((visibility("default"))) void dsk_debug_read2(long long
 #endif
 
 constexpr int kSegThreads = 256;
-constexpr int kSegWaves = kSegThreads / DSK_WAVE;
 constexpr int kTileThreads = 1024;                      // workgroup of the tile kernel: the tiles are few (one per
                                                         // 2048 positions) and their phases barrier-bound, so
                                                         // wide workgroups shorten them (256 / 512 / 1024

@@ -277,3 +277,13 @@ def test_reuse_in_a_decode_loop_with_appends():
         r_seen.append(rs[0])
     assert r_seen[0] == 0 and max(r_seen[1:]) > 0
     print("reuse counts while the cache grows:", r_seen, "of k =", sel.k)
+
+
+def test_reuse_at_the_position_limit():
+    """k = DSK_REUSE_MAX_K = 2048 positions per head (the most the per-wavefront LDS rows hold), on the
+    32K-token cache of configuration 2, where that budget takes nearly every slot."""
+    dsk = _dsk()
+    case = gpu_case(2)
+    hist, k = _run(case, 3, 0.9, [0, 31], T=dsk.DSK_REUSE_MAX_K * case.cfg.b, repeat_at=(2,))
+    assert k == dsk.DSK_REUSE_MAX_K
+    print("k = 2048 reuse counts:", hist)
