@@ -22,6 +22,9 @@ Parity status against the authors' implementation (none is public):
   * block_means / block_scores_mean -- the mean and the dot product are
                        textbook; that the authors score a mean summary with
                        q.mean is a reading ("parity unpinned").
+  * group_block_scores -- the extension "one selection per KV group" (maximum over the
+                       group's query heads) is NOT in the paper; pinned to its
+                       defining properties only ("parity unpinned").
   * kv_reuse_plan   -- pinned to a set formulation (Python sets, brute force),
                        to invariants and to hand-worked cases; which reusable
                        entries the truncation drops, the order of the loads and
@@ -254,6 +257,23 @@ def select_slots(score: np.ndarray, slot_base: np.ndarray, k: int) -> Tuple[np.n
     take = order[: min(k, n_slots)]
     tau = float(slot_score[take[-1]]) if take else float("nan")
     return np.asarray(sorted(take), dtype=np.int64), tau
+
+
+def group_block_scores(score: np.ndarray, G: int) -> np.ndarray:
+    """Selection shared by the query heads of a KV group -- an extension, NOT in the paper (which
+    selects per head and is silent on grouped-query models): the group's score of a block is the
+    largest score any of its G query heads gives it, so a block that matters to one head of the
+    group is kept for all of them and the group gathers one slot set.  score[hq, i] -> [Hq//G, i]."""
+    Hq, nblk = score.shape
+    out = np.empty((Hq // G, nblk), dtype=np.float64)
+    for hk in range(Hq // G):
+        for i in range(nblk):
+            best = score[hk * G, i]
+            for g in range(1, G):
+                if score[hk * G + g, i] > best:
+                    best = score[hk * G + g, i]
+            out[hk, i] = best
+    return out
 
 
 def selected_tokens(sel_slots: Sequence[int], block_start: np.ndarray, slot_base: np.ndarray,

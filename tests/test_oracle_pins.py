@@ -390,6 +390,50 @@ def test_select_slots_general_b_and_budget_all():
     assert list(toks) == [0, 1, 2, 3, 4, 16, 17, 18, 19]
 
 
+# ---------------------------------------------------------------- selection shared by a KV group (extension)
+def test_group_scores_defining_properties():
+    r = rng(8100)
+    Hkv, G, nblk = 3, 4, 37
+    s = r.standard_normal((Hkv * G, nblk))
+    g = O.group_block_scores(s, G)
+    assert g.shape == (Hkv, nblk)
+    for hk in range(Hkv):
+        rows = s[hk * G:(hk + 1) * G]
+        # an upper bound of every head of the group, attained by one of them, and by no head outside it
+        assert (g[hk][None, :] >= rows).all()
+        assert ((g[hk][None, :] == rows).sum(axis=0) >= 1).all()
+        np.testing.assert_array_equal(g[hk], np.sort(rows, axis=0)[-1])
+    # G = 1 changes nothing; identical heads in a group give that head's scores
+    np.testing.assert_array_equal(O.group_block_scores(s, 1), s)
+    same = np.repeat(r.standard_normal((Hkv, nblk)), G, axis=0)
+    np.testing.assert_array_equal(O.group_block_scores(same, G), same[::G])
+
+
+def test_group_selection_keeps_every_heads_favourite_and_reduces_to_per_head():
+    r = rng(8101)
+    G, nblk, b = 4, 50, 4
+    bs = np.concatenate([[0], np.cumsum(r.integers(1, 10, size=nblk))])
+    sb = O.slot_map(bs, b)
+    s = r.standard_normal((G, nblk))
+    g = O.group_block_scores(s, G)[0]
+    for k in (1, 3, 17, int(sb[-1])):
+        sel, tau = O.select_slots(g, sb, k)
+        # a slot is taken iff fewer than k slots rank before it by (largest head score, slot index)
+        slot_blk = np.searchsorted(sb, np.arange(sb[-1]), side="right") - 1
+        best = s.max(axis=0)[slot_blk]
+        for slot in range(int(sb[-1])):
+            before = int(((best > best[slot]) | ((best == best[slot]) & (np.arange(sb[-1]) < slot))).sum())
+            assert (slot in set(sel.tolist())) == (before < k)
+    # the block any head likes best is selected as soon as k covers its slots and those of the better-liked ones
+    top_blocks = {int(np.argmax(s[h])) for h in range(G)}
+    sel, _ = O.select_slots(g, sb, int(sb[-1]) // 2)
+    picked_blocks = set((np.searchsorted(sb, sel, side="right") - 1).tolist())
+    assert top_blocks <= picked_blocks
+    # one query head per group: the shared selection is the per-head selection
+    np.testing.assert_array_equal(O.select_slots(O.group_block_scores(s[:1], 1)[0], sb, 9)[0],
+                                  O.select_slots(s[0], sb, 9)[0])
+
+
 # ---------------------------------------------------------------- mean pooling (App. A.2)
 def test_block_means_and_their_scores():
     r = rng(40)
