@@ -181,6 +181,12 @@ typedef struct dsk_compress_args {
  *   min(k, slots of the sequence) best slots are selected, k = budget / b, ranked by
  *   (score descending, slot index ascending), and returned in ascending slot order.
  * ---------------------------------------------------------------------------------------- */
+/* dsk_select_args.flags.  DSK_SELECT_SHARED_BY_KV_GROUP is an extension that is NOT in the paper
+ * (which selects per head, App. B.2 Step 1, and does not say how grouped-query models are
+ * handled): the Hq/Hkv query heads of a KV head share one selection, made on the largest score
+ * any of them gives a block, so that the group gathers one set of K/V rows per step. */
+#define DSK_SELECT_SHARED_BY_KV_GROUP 1u
+
 typedef struct dsk_select_args {
   uint32_t struct_size;
   int32_t B, Hq, Hkv, D;
@@ -200,6 +206,8 @@ typedef struct dsk_select_args {
   const void* q;               /* [dev] bf16 [B, Hq, D] */
   int32_t b;                   /* slot length used by dsk_compress */
   int32_t budget;              /* token budget per sequence; k = budget / b >= 1 */
+  uint32_t flags;              /* DSK_SELECT_* bits; with DSK_SELECT_SHARED_BY_KV_GROUP read Hkv for Hq in
+                                  the shapes of the five outputs below */
   int32_t* sel_slot;           /* [dev] [B, Hq, k] global slot index, ascending; -1 padding */
   int32_t* sel_start;          /* [dev] [B, Hq, k] first global token of the slot */
   int32_t* sel_len;            /* [dev] [B, Hq, k] tokens in the slot (1..b); 0 padding */
@@ -221,6 +229,10 @@ typedef struct dsk_select_args {
  * itself, e.g. across devices that each hold part of a sequence.  out / lse are then final only
  * for heads whose selection fits one chunk. */
 #define DSK_ATTN_PARTIALS_ONLY 1u
+/* the sel_* arrays hold one selection per (sequence, KV head) -- [B, Hkv, k] and [B, Hkv], as
+ * dsk_select_topk writes them with DSK_SELECT_SHARED_BY_KV_GROUP -- used by all Hq/Hkv query heads
+ * of that KV head */
+#define DSK_ATTN_SHARED_SELECTION 2u
 
 typedef struct dsk_attn_args {
   uint32_t struct_size;

@@ -33,6 +33,8 @@ DSK_STAGE_ALL = 15
 DSK_HEAD_DIM = 128
 DSK_MAX_CLASSES = 64
 DSK_ATTN_PARTIALS_ONLY = 1
+DSK_ATTN_SHARED_SELECTION = 2
+DSK_SELECT_SHARED_BY_KV_GROUP = 1
 DSK_REUSE_PLAN_ONLY = 1
 DSK_REUSE_MAX_K = 2048
 DSK_SUMMARY_MINMAX, DSK_SUMMARY_MEAN = 0, 1
@@ -74,7 +76,7 @@ class dsk_select_args(C.Structure):
         ("max_blocks_total", C.c_int32), ("max_blocks_used", C.c_int32), ("max_blocks_per_seq", C.c_int32),
         ("cu_blocks", _p), ("block_start", _p), ("slot_base", _p),
         ("ksum", _p), ("q", _p),
-        ("b", C.c_int32), ("budget", C.c_int32),
+        ("b", C.c_int32), ("budget", C.c_int32), ("flags", C.c_uint32),
         ("sel_slot", _p), ("sel_start", _p), ("sel_len", _p), ("sel_count", _p),
         ("scores", _p),
         ("workspace", _p), ("workspace_bytes", C.c_size_t),
@@ -445,14 +447,16 @@ class Selection:
     scores: Optional[torch.Tensor]
     args: dsk_select_args
     keep: tuple
+    shared: bool = False       # one selection per KV head (the arrays are [B, Hkv, ...])
 
 
 def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_scores: bool = False,
                      out: Optional[Selection] = None, max_blocks_used: int = 0,
-                     max_blocks_per_seq: int = 0) -> Selection:
+                     max_blocks_per_seq: int = 0, shared: bool = False) -> Selection:
     """Fill dsk_select_args for query q (bf16 [B, Hq, D]); buffers are reused from `out`.
     `max_blocks_used`: optional host-known bound on the total block count (0 = capacity);
-    `max_blocks_per_seq`: optional bound on the blocks of any one sequence."""
+    `max_blocks_per_seq`: optional bound on the blocks of any one sequence;
+    `shared`: one selection per KV head instead of per query head (DSK_SELECT_SHARED_BY_KV_GROUP)."""
     dev = q.device
     B, Hq = comp.B, comp.Hq
     assert q.shape == (B, Hq, DSK_HEAD_DIM) and q.dtype == torch.bfloat16 and q.is_contiguous()
@@ -467,26 +471,30 @@ def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_sco
     a.cu_blocks, a.block_start, a.slot_base = _ptr(comp.cu_blocks), _ptr(comp.block_start), _ptr(comp.slot_base)
     a.ksum, a.q = _ptr(comp.ksum), _ptr(q)
     a.b, a.budget = comp.b, budget
+    a.flags = DSK_SELECT_SHARED_BY_KV_GROUP if shared else 0
+    Hsel = comp.Hkv if shared else Hq
     if out is None:
-        sel_slot = torch.empty(B, Hq, max(k, 1), **i32)
-        sel_start = torch.empty(B, Hq, max(k, 1), **i32)
-        sel_len = torch.empty(B, Hq, max(k, 1), **i32)
-        sel_count = torch.empty(B, Hq, **i32)
-        scores = torch.empty(Hq, comp.max_blocks_total, dtype=torch.float32, device=dev) if want_scores else None
+        sel_slot = torch.empty(B, Hsel, max(k, 1), **i32)
+        sel_start = torch.empty(B, Hsel, max(k, 1), **i32)
+        sel_len = torch.empty(B, Hsel, max(k, 1), **i32)
+        sel_count = torch.empty(B, Hsel, **i32)
+        scores = torch.empty(Hsel, comp.max_blocks_total, dtype=torch.float32, device=dev) if want_scores else None
     else:
+        assert out.shared == shared
         sel_slot, sel_start, sel_len, sel_count, scores = out.sel_slot, out.sel_start, out.sel_len, out.sel_count, out.scores
     a.sel_slot, a.sel_start, a.sel_len, a.sel_count = _ptr(sel_slot), _ptr(sel_start), _ptr(sel_len), _ptr(sel_count)
     a.scores = _ptr(scores)
     ws = _ws(dsk_select_workspace_bytes(a), dev) if out is None else out.keep[-1]
     a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
     return Selection(k=k, b=comp.b, sel_slot=sel_slot, sel_start=sel_start, sel_len=sel_len, sel_count=sel_count,
-                     scores=scores, args=a, keep=(comp, q, ws))
+                     scores=scores, args=a, keep=(comp, q, ws), shared=shared)
 
 
 def select_topk(comp: Compressed, q: torch.Tensor, budget: int, *, want_scores: bool = False, stream=None,
-                check: bool = True, max_blocks_used: int = 0, max_blocks_per_seq: int = 0) -> Selection:
+                check: bool = True, max_blocks_used: int = 0, max_blocks_per_seq: int = 0,
+                shared: bool = False) -> Selection:
     sel = make_select_args(comp, q, budget, want_scores=want_scores, max_blocks_used=max_blocks_used,
-                           max_blocks_per_seq=max_blocks_per_seq)
+                           max_blocks_per_seq=max_blocks_per_seq, shared=shared)
     dsk_select_topk(sel.args, stream, check=check)
     return sel
 
@@ -533,8 +541,8 @@ def make_attn_args(q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, sel_start:
 
 
 def sparse_decode_attn(q, K, V, sel_start, sel_len, sel_count, b, *, scale: float = 0.0, stream=None,
-                       check: bool = True, want_bf16: bool = False) -> AttnOut:
-    r = make_attn_args(q, K, V, sel_start, sel_len, sel_count, b, scale=scale, want_bf16=want_bf16)
+                       check: bool = True, want_bf16: bool = False, flags: int = 0) -> AttnOut:
+    r = make_attn_args(q, K, V, sel_start, sel_len, sel_count, b, scale=scale, want_bf16=want_bf16, flags=flags)
     dsk_sparse_decode_attn(r.args, stream, check=check)
     return r
 

@@ -110,6 +110,7 @@ static dsk_status validate_select(const dsk_select_args* a) {
       a->max_blocks_per_seq < 0)
     return DSK_ERR_SHAPE;
   if (a->b < 1 || a->b > 1024 || a->budget < a->b) return DSK_ERR_PARAM;
+  if (a->flags & ~(uint32_t)DSK_SELECT_SHARED_BY_KV_GROUP) return DSK_ERR_PARAM;
   if (!a->cu_blocks || !a->block_start || !a->slot_base || !a->ksum || !a->q || !a->sel_slot || !a->sel_start ||
       !a->sel_len || !a->sel_count)
     return DSK_ERR_NULL;
@@ -126,7 +127,8 @@ static dsk_status validate_attn(const dsk_attn_args* a) {
   if (!geometry_ok(a->B, a->Hq, a->Hkv, a->D)) return DSK_ERR_SHAPE;
   if (a->total_tokens < 0) return DSK_ERR_SHAPE;
   if (a->k < 1 || a->b < 1 || a->b > 1024) return DSK_ERR_PARAM;
-  if (!(a->scale >= 0.0f) || (a->flags & ~(uint32_t)DSK_ATTN_PARTIALS_ONLY)) return DSK_ERR_PARAM;
+  if (!(a->scale >= 0.0f) || (a->flags & ~(uint32_t)(DSK_ATTN_PARTIALS_ONLY | DSK_ATTN_SHARED_SELECTION)))
+    return DSK_ERR_PARAM;
   if (!a->q || !a->K || !a->V || !a->sel_start || !a->sel_len || !a->sel_count || !a->out) return DSK_ERR_NULL;
   if (a->k_stride_tok < DSK_HEAD_DIM || a->v_stride_tok < DSK_HEAD_DIM || a->k_stride_head < 0 ||
       a->v_stride_head < 0)

@@ -57,10 +57,10 @@ AttnWs attn_ws_layout(const dsk_attn_args& a);
 hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st);
 // Fixed-order merge of nchunks partials per (sequence, head); chunk c is valid for
 // c < ceil(min(count, k) / per_chunk) where count = counts[s*Hq+h], or the length of sequence s
-// when cu_seqlens is given.
+// when cu_seqlens is given.  sel_div consecutive heads read one entry of counts ([B, Hq/sel_div]).
 hipError_t launch_attn_merge(const float2* part_ml, const float* part_acc, const int32_t* counts,
-                             const int32_t* cu_seqlens, int B, int Hq, int k, int nchunks, int per_chunk, float* out,
-                             uint16_t* out_bf16, float* lse, hipStream_t st);
+                             const int32_t* cu_seqlens, int B, int Hq, int sel_div, int k, int nchunks, int per_chunk,
+                             float* out, uint16_t* out_bf16, float* lse, hipStream_t st);
 
 // ---- dsk_dense_decode_attn workspace ---------------------------------------------------------
 struct DenseWs {

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     int64_t kst, int64_t ksh, int64_t vst, int64_t vsh, int Hq, int G, int k, int b, int total_tokens,
     const int32_t* __restrict__ sel_start, const int32_t* __restrict__ sel_len,
-    const int32_t* __restrict__ sel_count, float scale_log2, int nchunks,
+    const int32_t* __restrict__ sel_count, int sel_div, float scale_log2, int nchunks,
     float2* __restrict__ part_ml, float* __restrict__ part_acc, float* __restrict__ out,
     uint16_t* __restrict__ out_bf16, float* __restrict__ lse) {
   constexpr int kAttnWaves = WAVES;
@@ -79,18 +79,20 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
   const int h = blockIdx.y;
   const int s = blockIdx.z;
   const int64_t sh = (int64_t)s * Hq + h;
+  // row of the selection arrays: the head's own, or its KV head's when sel_div = Hq/Hkv heads share one
+  const int64_t sr = (int64_t)s * (Hq / sel_div) + h / sel_div;
   const int lane = threadIdx.x & (DSK_WAVE - 1);
   const int wave = threadIdx.x / DSK_WAVE;
   const int slot0 = chunk * kSlotsPerWg;
 
   // the wave's slots: slot0 + wave + kAttnWaves * r; their spans are fetched together with the count
-  int count = sel_count[sh];
+  int count = sel_count[sr];
   int st_[SPW], ln_[SPW];
 #pragma unroll
   for (int r = 0; r < SPW; ++r) {
     const int j = slot0 + wave + kAttnWaves * r;
-    st_[r] = j < k ? sel_start[sh * k + j] : 0;
-    ln_[r] = j < k ? sel_len[sh * k + j] : 0;
+    st_[r] = j < k ? sel_start[sr * k + j] : 0;
+    ln_[r] = j < k ? sel_len[sr * k + j] : 0;
   }
   if (count > k) count = k;
   if (count <= 0) {   // nothing selected: chunk 0 writes the defined empty result
@@ -213,8 +215,9 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
 template <int kMergeThreads>
 __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
     const float2* __restrict__ part_ml, const float* __restrict__ part_acc,
-    const int32_t* __restrict__ sel_count, const int32_t* __restrict__ cu_seqlens, int Hq, int k, int nchunks,
-    int slots_per_wg, float* __restrict__ out, uint16_t* __restrict__ out_bf16, float* __restrict__ lse) {
+    const int32_t* __restrict__ sel_count, const int32_t* __restrict__ cu_seqlens, int Hq, int sel_div, int k,
+    int nchunks, int slots_per_wg, float* __restrict__ out, uint16_t* __restrict__ out_bf16,
+    float* __restrict__ lse) {
   constexpr int kMergeGroups = kMergeThreads / 16;
   __shared__ float sm_m[kMergeGroups];
   __shared__ float sm_l[kMergeGroups];
@@ -239,7 +242,8 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
     const int s = (int)(sh / Hq);
     count = cu_seqlens[s + 1] - cu_seqlens[s];
   } else {
-    count = sel_count[sh];
+    const int s = (int)(sh / Hq), h = (int)(sh % Hq);
+    count = sel_count[(int64_t)s * (Hq / sel_div) + h / sel_div];
   }
   if (count > k) count = k;
   const int used = (count + slots_per_wg - 1) / slots_per_wg;
@@ -306,9 +310,12 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   const uint16_t* q = static_cast<const uint16_t*>(a.q);
   const uint16_t* K = static_cast<const uint16_t*>(a.K);
   const uint16_t* V = static_cast<const uint16_t*>(a.V);
+  // heads that read one row of the selection arrays; the workgroups of a group's heads gather the
+  // same rows (chunk c of every head runs on XCD c mod 8), so only one of them misses in L2
+  const int sel_div = (a.flags & DSK_ATTN_SHARED_SELECTION) ? a.Hq / a.Hkv : 1;
 #define DSK_ATTN_ARGS                                                                                          \
   q, K, V, a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, a.Hq / a.Hkv, a.k, a.b,     \
-      a.total_tokens, a.sel_start, a.sel_len, a.sel_count, scale * kLog2e, ws.nchunks, part_ml, part_acc, a.out, \
+      a.total_tokens, a.sel_start, a.sel_len, a.sel_count, sel_div, scale * kLog2e, ws.nchunks, part_ml, part_acc, a.out, \
       static_cast<uint16_t*>(a.out_bf16), a.lse
   // Slots of at most 32 rows: workgroups of 8 wavefronts, 2 slots each (16 slots per workgroup).
   // Measured against 4 wavefronts x 2 or 4 slots, 8 x 1 or 4, 16 x 1 or 2 on all configurations:
@@ -320,24 +327,24 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
 #undef DSK_ATTN_ARGS
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || ws.nchunks <= 1 || (a.flags & DSK_ATTN_PARTIALS_ONLY)) return err;
-  return launch_attn_merge(part_ml, part_acc, a.sel_count, nullptr, a.B, a.Hq, a.k, ws.nchunks, ws.slots_per_wg, a.out,
-                           static_cast<uint16_t*>(a.out_bf16), a.lse, st);
+  return launch_attn_merge(part_ml, part_acc, a.sel_count, nullptr, a.B, a.Hq, sel_div, a.k, ws.nchunks,
+                           ws.slots_per_wg, a.out, static_cast<uint16_t*>(a.out_bf16), a.lse, st);
 }
 
 hipError_t launch_attn_merge(const float2* part_ml, const float* part_acc, const int32_t* counts,
-                             const int32_t* cu_seqlens, int B, int Hq, int k, int nchunks, int per_chunk, float* out,
-                             uint16_t* out_bf16, float* lse, hipStream_t st) {
+                             const int32_t* cu_seqlens, int B, int Hq, int sel_div, int k, int nchunks, int per_chunk,
+                             float* out, uint16_t* out_bf16, float* lse, hipStream_t st) {
   // one lane group of 16 per partial when there are few, several partials per group otherwise
   const dim3 grid((unsigned)(B * Hq));
   if (nchunks <= 8)
-    attn_merge_kernel<128><<<grid, dim3(128), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, k, nchunks, per_chunk,
-                                                       out, out_bf16, lse);
+    attn_merge_kernel<128><<<grid, dim3(128), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, sel_div, k, nchunks,
+                                                       per_chunk, out, out_bf16, lse);
   else if (nchunks <= 32)
-    attn_merge_kernel<256><<<grid, dim3(256), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, k, nchunks, per_chunk,
-                                                       out, out_bf16, lse);
+    attn_merge_kernel<256><<<grid, dim3(256), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, sel_div, k, nchunks,
+                                                       per_chunk, out, out_bf16, lse);
   else
-    attn_merge_kernel<kMergeBigThreads><<<grid, dim3(kMergeBigThreads), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, k,
-                                                                           nchunks, per_chunk, out, out_bf16, lse);
+    attn_merge_kernel<kMergeBigThreads><<<grid, dim3(kMergeBigThreads), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, sel_div,
+                                                                           k, nchunks, per_chunk, out, out_bf16, lse);
   return hipGetLastError();
 }
 

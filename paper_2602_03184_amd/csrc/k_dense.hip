@@ -180,7 +180,7 @@ hipError_t launch_dense_attn(const dsk_dense_attn_args& a, const DenseWs& ws, hi
 #undef DSK_DENSE_ARGS
   hipError_t err = hipGetLastError();
   if (err != hipSuccess || ws.nsplit <= 1) return err;
-  return launch_attn_merge(part_ml, part_acc, nullptr, a.cu_seqlens, a.B, a.Hq, 0x7FFFFFFF, ws.nsplit,
+  return launch_attn_merge(part_ml, part_acc, nullptr, a.cu_seqlens, a.B, a.Hq, 1, 0x7FFFFFFF, ws.nsplit,
                            ws.tokens_per_split, a.out, static_cast<uint16_t*>(a.out_bf16), a.lse, st);
 }
 

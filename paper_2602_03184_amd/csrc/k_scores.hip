@@ -45,8 +45,10 @@ __device__ __forceinline__ void half_wave_reduce(float (&v)[N], int lane, int& i
   }
 }
 
-// value index = block_in_group * G + g
-template <int G>
+// value index = block_in_group * G + g.  GROUPMAX: one row per KV head, the largest of the G
+// heads' scores (selection shared by the group); the G values of a block sit in lanes that
+// differ only in log2(G) consecutive lane bits, so the maximum is a few exchanges.
+template <int G, bool GROUPMAX = false>
 __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
     const uint16_t* __restrict__ ksum, const uint16_t* __restrict__ q, const int32_t* __restrict__ cu_blocks,
     int B, int Hq, int cap, int bound, int stride, float* __restrict__ scores, float* __restrict__ user) {
@@ -149,7 +151,15 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
       half_wave_reduce<V, V, 16>(v, c, idx);
       const bool writer = (c & (32 / V - 1)) == 0;   // lanes differing only in non-halving bits hold copies
       const int u = idx / G, g = idx % G;
-      if (writer && i0 + u >= cur && i0 + u < seg_end) {
+      if constexpr (GROUPMAX) {
+        float best = v[0];
+#pragma unroll
+        for (int m = 32 / V; m < (32 / V) * G; m <<= 1) best = fmaxf(best, shfl_xor_f(best, m));
+        if (writer && g == 0 && i0 + u >= cur && i0 + u < seg_end) {
+          scores[(int64_t)hk * stride + i0 + u] = best;
+          if (user) user[(int64_t)hk * cap + i0 + u] = best;
+        }
+      } else if (writer && i0 + u >= cur && i0 + u < seg_end) {
         scores[(int64_t)(hk * G + g) * stride + i0 + u] = v[0];
         if (user) user[(int64_t)(hk * G + g) * cap + i0 + u] = v[0];
       }
@@ -166,7 +176,8 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
 // any group width: one block per half-wave step, q re-read per block (it stays in the vector cache)
 __global__ __launch_bounds__(kScoreThreads) void scores_kernel_anyg(
     const uint16_t* __restrict__ ksum, const uint16_t* __restrict__ q, const int32_t* __restrict__ cu_blocks,
-    int B, int Hq, int G, int cap, int stride, float* __restrict__ scores, float* __restrict__ user) {
+    int B, int Hq, int G, int cap, int stride, bool group_max, float* __restrict__ scores,
+    float* __restrict__ user) {
   const int hk = blockIdx.y;
   int nblk = cu_blocks[B];
   if (nblk > cap) nblk = cap;
@@ -184,6 +195,7 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel_anyg(
     const uint4 kv = *reinterpret_cast<const uint4*>(kh + (int64_t)i * (2 * DSK_HEAD_DIM) + c * 8);
     float f[8];
     unpack8(kv, f);
+    float best = -__builtin_inff();
     for (int g = 0; g < G; ++g) {
       const uint4 qv = *reinterpret_cast<const uint4*>(q + ((int64_t)s * Hq + hk * G + g) * DSK_HEAD_DIM + d0);
       float qf[8];
@@ -193,7 +205,15 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel_anyg(
       for (int k = 0; k < 8; ++k) acc = fmaf(is_max ? fmaxf(qf[k], 0.0f) : fminf(qf[k], 0.0f), f[k], acc);
       acc = group16_sum(acc);
       acc += shfl_xor_f(acc, 16);
-      if (c == 0) scores[(int64_t)(hk * G + g) * cap + i] = acc;
+      best = fmaxf(best, acc);
+      if (c == 0 && !group_max) {
+        scores[(int64_t)(hk * G + g) * stride + i] = acc;
+        if (user) user[(int64_t)(hk * G + g) * cap + i] = acc;
+      }
+    }
+    if (c == 0 && group_max) {
+      scores[(int64_t)hk * stride + i] = best;
+      if (user) user[(int64_t)hk * cap + i] = best;
     }
   }
 }
@@ -207,14 +227,21 @@ hipError_t launch_scores(const dsk_select_args& a, float* scores, int stride, hi
   const dim3 block(kScoreThreads);
   const uint16_t* ksum = static_cast<const uint16_t*>(a.ksum);
   const uint16_t* q = static_cast<const uint16_t*>(a.q);
-  switch (G) {
-    case 1: scores_kernel<1><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, bound, stride, scores, a.scores); break;
-    case 2: scores_kernel<2><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, bound, stride, scores, a.scores); break;
-    case 4: scores_kernel<4><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, bound, stride, scores, a.scores); break;
-    case 8: scores_kernel<8><<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, bound, stride, scores, a.scores); break;
+  const bool shared = (a.flags & DSK_SELECT_SHARED_BY_KV_GROUP) != 0 && G > 1;
+#define DSK_SCORE_ARGS ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, bound, stride, scores, a.scores
+  switch (shared ? -G : G) {
+    case 1: scores_kernel<1><<<grid, block, 0, st>>>(DSK_SCORE_ARGS); break;
+    case 2: scores_kernel<2><<<grid, block, 0, st>>>(DSK_SCORE_ARGS); break;
+    case 4: scores_kernel<4><<<grid, block, 0, st>>>(DSK_SCORE_ARGS); break;
+    case 8: scores_kernel<8><<<grid, block, 0, st>>>(DSK_SCORE_ARGS); break;
+    case -2: scores_kernel<2, true><<<grid, block, 0, st>>>(DSK_SCORE_ARGS); break;
+    case -4: scores_kernel<4, true><<<grid, block, 0, st>>>(DSK_SCORE_ARGS); break;
+    case -8: scores_kernel<8, true><<<grid, block, 0, st>>>(DSK_SCORE_ARGS); break;
     default:
-      scores_kernel_anyg<<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, G, a.max_blocks_total, stride, scores, a.scores);
+      scores_kernel_anyg<<<grid, block, 0, st>>>(ksum, q, a.cu_blocks, a.B, a.Hq, G, a.max_blocks_total, stride, shared,
+                                                 scores, a.scores);
   }
+#undef DSK_SCORE_ARGS
   return hipGetLastError();
 }
 

@@ -484,13 +484,15 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
 
 hipError_t launch_select(const dsk_select_args& a, const float* scores, int stride, hipStream_t st) {
   const int k = a.budget / a.b;
-  const dim3 grid((unsigned)a.Hq, (unsigned)a.B);
+  // selecting heads: the query heads, or the KV heads when a group shares its selection
+  const int Hsel = (a.flags & DSK_SELECT_SHARED_BY_KV_GROUP) ? a.Hkv : a.Hq;
+  const dim3 grid((unsigned)Hsel, (unsigned)a.B);
   // a sequence has at most `bound` blocks: the smallest register tile that holds them all does
   // the least per-thread work (larger sequences than the tile still work, through select_big)
   int bound = a.max_blocks_used > 0 ? a.max_blocks_used : a.max_blocks_total;
   if (a.max_blocks_per_seq > 0 && a.max_blocks_per_seq < bound) bound = a.max_blocks_per_seq;
 #define DSK_SEL_ARGS                                                                                          \
-  scores, stride, a.cu_blocks, a.block_start, a.slot_base, a.max_blocks_total, a.Hq, a.b, k, a.sel_slot, a.sel_start, \
+  scores, stride, a.cu_blocks, a.block_start, a.slot_base, a.max_blocks_total, Hsel, a.b, k, a.sel_slot, a.sel_start, \
       a.sel_len, a.sel_count
   if (sel_fits_tile(bound, 4, 256)) select_kernel<4, 256><<<grid, dim3(256), 0, st>>>(DSK_SEL_ARGS);
   else if (sel_fits_tile(bound, 4, 512)) select_kernel<4, 512><<<grid, dim3(512), 0, st>>>(DSK_SEL_ARGS);

@@ -47,6 +47,7 @@ int main(void) {
   printf("%zu %zu %zu ", sizeof(dsk_compress_args), sizeof(dsk_select_args), sizeof(dsk_attn_args));
   printf("%zu %zu %zu ", offsetof(dsk_compress_args, qwin), offsetof(dsk_compress_args, C_per_seq), offsetof(dsk_compress_args, workspace_bytes));
   printf("%zu %zu %zu ", offsetof(dsk_select_args, budget), offsetof(dsk_select_args, workspace_bytes), offsetof(dsk_select_args, max_blocks_per_seq));
+  printf("%zu %zu ", offsetof(dsk_select_args, flags), offsetof(dsk_select_args, sel_slot));
   printf("%zu %zu %zu ", offsetof(dsk_attn_args, total_tokens), offsetof(dsk_attn_args, scale), offsetof(dsk_attn_args, workspace_bytes));
   printf("%zu %zu %zu %zu ", sizeof(dsk_dense_attn_args), offsetof(dsk_dense_attn_args, cu_seqlens), offsetof(dsk_dense_attn_args, scale), offsetof(dsk_dense_attn_args, workspace_bytes));
   printf("%zu %zu ", sizeof(dsk_attn_partials), offsetof(dsk_attn_partials, nchunks));
@@ -58,7 +59,8 @@ int main(void) {
     got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
     ca, sa, aa = dsk.dsk_compress_args, dsk.dsk_select_args, dsk.dsk_attn_args
     want = [C.sizeof(ca), C.sizeof(sa), C.sizeof(aa), ca.qwin.offset, ca.C_per_seq.offset, ca.workspace_bytes.offset,
-            sa.budget.offset, sa.workspace_bytes.offset, sa.max_blocks_per_seq.offset, aa.total_tokens.offset, aa.scale.offset,
+            sa.budget.offset, sa.workspace_bytes.offset, sa.max_blocks_per_seq.offset, sa.flags.offset, sa.sel_slot.offset,
+            aa.total_tokens.offset, aa.scale.offset,
             aa.workspace_bytes.offset]
     da, pa = dsk.dsk_dense_attn_args, dsk.dsk_attn_partials
     want += [C.sizeof(da), da.cu_seqlens.offset, da.scale.offset, da.workspace_bytes.offset, C.sizeof(pa),
@@ -193,7 +195,8 @@ def test_select_and_attn_validation(dsk):
     for field, value, want in (("struct_size", 1, dsk.DSK_ERR_VERSION), ("Hq", 5, dsk.DSK_ERR_SHAPE),
                                ("budget", 15, dsk.DSK_ERR_PARAM), ("b", 0, dsk.DSK_ERR_PARAM),
                                ("q", None, dsk.DSK_ERR_NULL), ("q", fake + 4, dsk.DSK_ERR_ALIGN),
-                               ("max_blocks_total", 0, dsk.DSK_ERR_SHAPE), ("sel_count", None, dsk.DSK_ERR_NULL)):
+                               ("max_blocks_total", 0, dsk.DSK_ERR_SHAPE), ("sel_count", None, dsk.DSK_ERR_NULL),
+                               ("flags", 2, dsk.DSK_ERR_PARAM)):
         a = sel()
         setattr(a, field, value)
         assert dsk.dsk_select_topk(a, 0, check=False) == want, field
@@ -211,7 +214,7 @@ def test_select_and_attn_validation(dsk):
     assert dsk.dsk_sparse_decode_attn(att(), 0, check=False) == dsk.DSK_ERR_WORKSPACE
     assert dsk.dsk_attn_workspace_bytes(att()) > 0
     for field, value, want in (("k", 0, dsk.DSK_ERR_PARAM), ("scale", -1.0, dsk.DSK_ERR_PARAM),
-                               ("scale", float("nan"), dsk.DSK_ERR_PARAM), ("flags", 2, dsk.DSK_ERR_PARAM),
+                               ("scale", float("nan"), dsk.DSK_ERR_PARAM), ("flags", 4, dsk.DSK_ERR_PARAM),
                                ("V", None, dsk.DSK_ERR_NULL),
                                ("v_stride_tok", 100, dsk.DSK_ERR_SHAPE), ("k_stride_tok", 129, dsk.DSK_ERR_ALIGN),
                                ("out", None, dsk.DSK_ERR_NULL), ("D", 256, dsk.DSK_ERR_SHAPE)):
