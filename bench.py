@@ -214,6 +214,51 @@ def main():
         stream.synchronize()
         select_us = event_ms(g_sel.replay, stream) * 1e3 / args.steps
 
+        # ---- extension (not in the paper): one selection per KV head, shared by its query heads ----
+        shared = None
+        if cfg.G > 1:
+            ssel = [dsk.make_select_args(comp, queries[0], cfg.T, max_blocks_used=nblk, max_blocks_per_seq=nblk_seq,
+                                         shared=True)]
+            for i in range(1, nq):
+                ssel.append(dsk.make_select_args(comp, queries[i], cfg.T, out=ssel[0], max_blocks_used=nblk,
+                                                 max_blocks_per_seq=nblk_seq, shared=True))
+            sflag = dsk.DSK_ATTN_SHARED_SELECTION
+            satt = [dsk.make_attn_args(queries[0], K, V, ssel[0].sel_start, ssel[0].sel_len, ssel[0].sel_count, cfg.b,
+                                       flags=sflag)]
+            for i in range(1, nq):
+                satt.append(dsk.make_attn_args(queries[i], K, V, ssel[0].sel_start, ssel[0].sel_len, ssel[0].sel_count,
+                                               cfg.b, out=satt[0], flags=sflag))
+            sgat = [dsk.make_attn_args(queries[i], K, V, ssel[0].sel_start, ssel[0].sel_len, ssel[0].sel_count, cfg.b,
+                                       out=satt[0], flags=sflag | dsk.DSK_ATTN_PARTIALS_ONLY) for i in range(nq)]
+            stok = []
+            for i in range(nq):
+                dsk.dsk_select_topk(ssel[i].args, stream)
+                stream.synchronize()
+                stok.append(int(ssel[0].sel_len.sum().item()))
+            g_sh = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_sh, stream=stream):
+                for i in range(args.steps):
+                    dsk.dsk_select_topk(ssel[i % nq].args, stream)
+                    dsk.dsk_sparse_decode_attn(satt[i % nq].args, stream)
+            g_sh.replay()
+            stream.synchronize()
+            shared_us = event_ms(g_sh.replay, stream) * 1e3 / args.steps
+            g_sg = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_sg, stream=stream):
+                for i in range(args.steps):
+                    dsk.dsk_sparse_decode_attn(sgat[i % nq].args, stream)
+            g_sg.replay()
+            stream.synchronize()
+            shared_gather_us = event_ms(g_sg.replay, stream) * 1e3 / args.steps
+            sbytes = float(np.mean(stok)) * 512           # K/V rows the group gathers once
+            shared = {"us_per_step": round(shared_us, 3), "gather_us": round(shared_gather_us, 3),
+                      "gather_bytes_per_kv_head_model": int(sbytes),
+                      "gather_GBps": round(sbytes / (shared_gather_us * 1e-6) / 1e9, 1),
+                      "gather_frac": round(sbytes / (shared_gather_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                      "what": "DSK_SELECT_SHARED_BY_KV_GROUP + DSK_ATTN_SHARED_SELECTION: group score = max over "
+                              "the group's query heads; not the paper's per-head selection"}
+            del g_sh, g_sg
+
         # ---- full attention over the whole cache on the same device (the full-KV baseline) --------
         dense = dsk.make_dense_attn_args(queries[0], K, V, cu, int(wl.seqlens.max()))
         dense_args = [dense] + [dsk.make_dense_attn_args(queries[i], K, V, cu, int(wl.seqlens.max()), out=dense)
@@ -481,6 +526,8 @@ def main():
         out["decode_loop_with_append"] = loop
     if reuse is not None:
         out["kv_reuse"] = reuse
+    if shared is not None:
+        out["shared_selection_extension"] = shared
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, comp, nblk)
     print(json.dumps(out))

@@ -20,6 +20,22 @@ constexpr int kMergeBigThreads = 1024;
 // slots per workgroup for a slot length bound b
 __host__ __device__ constexpr int attn_slots_per_wg(int b) { return b <= 32 ? 16 : 8; }
 
+// Shared selection: the tiled kernel (attn_shared_kernel, WAVES x SPW slots per workgroup) takes
+// group widths 2, 4, 8 and slots of at most 32 rows.  It reads every selected row once, where
+// attn_kernel run per query head reads it once per head with all but the first read served by
+// L2; that is as fast while the launch is small (config 3, 1024 selected slots per step:
+// 5.9 us either way, and 8 instead of 16 partials to merge), and slower from a few thousand
+// slots on (8 sequences of config 5, 8192 slots: 15.3 against 18.6 us), so the tiled kernel is
+// used from 4096 slots per step.  Measured against 4 x 1, 8 x 1 and 8 x 2.
+constexpr int kSharedWaves = 4;
+constexpr int kSharedSpw = 2;
+constexpr int64_t kSharedTiledMinSlots = 4096;
+static bool attn_shared_tiled(const dsk_attn_args& a) {
+  const int G = a.Hq / a.Hkv;
+  return (a.flags & DSK_ATTN_SHARED_SELECTION) && (G == 2 || G == 4 || G == 8) && a.b <= 32 &&
+         (int64_t)a.B * a.Hkv * a.k >= kSharedTiledMinSlots;
+}
+
 // ordinary (compiler-scheduled) loads; used for slots longer than 32 rows
 template <int NS>
 __device__ __forceinline__ void fold_rows(WaveState& st, const QRow& qf, const uint16_t* __restrict__ kbase,
@@ -209,6 +225,154 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
   if (d == 0) part_ml[pbase + chunk] = make_float2(M, l);
 }
 
+// Shared selection (one slot list per KV head, used by all its query heads): a workgroup per
+// (chunk of WAVES*SPW slots, KV head x tile of GT query heads, sequence).  Every K/V row a
+// wavefront loads is folded into the GT heads' states, so the group's rows are read once instead
+// of once per query head.  Same partial layout as attn_kernel (one partial per query head and
+// chunk), merged by attn_merge_kernel.
+template <int NS, int SPW, int WAVES, int GT>
+__global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_shared_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+    int64_t kst, int64_t ksh, int64_t vst, int64_t vsh, int Hq, int G, int k, int b, int total_tokens,
+    const int32_t* __restrict__ sel_start, const int32_t* __restrict__ sel_len,
+    const int32_t* __restrict__ sel_count, float scale_log2, int nchunks,
+    float2* __restrict__ part_ml, float* __restrict__ part_acc, float* __restrict__ out,
+    uint16_t* __restrict__ out_bf16, float* __restrict__ lse) {
+  static_assert(NS > 0, "slots of at most 4*NS rows");
+  __shared__ float sm_m[WAVES][GT];
+  __shared__ float sm_l[WAVES][GT];
+  __shared__ float sm_acc[WAVES][GT][DSK_HEAD_DIM];
+  constexpr int kSlotsPerWg = WAVES * SPW;
+
+  const int chunk = blockIdx.x;
+  const int tiles_g = G / GT;
+  const int hk = blockIdx.y / tiles_g;
+  const int h0 = hk * G + (blockIdx.y % tiles_g) * GT;     // first query head of this tile
+  const int s = blockIdx.z;
+  const int64_t sr = (int64_t)s * (Hq / G) + hk;            // row of the selection arrays
+  const int64_t sh0 = (int64_t)s * Hq + h0;
+  const int lane = threadIdx.x & (DSK_WAVE - 1);
+  const int wave = threadIdx.x / DSK_WAVE;
+  const int slot0 = chunk * kSlotsPerWg;
+
+  int count = sel_count[sr];
+  int st_[SPW], ln_[SPW];
+#pragma unroll
+  for (int r = 0; r < SPW; ++r) {
+    const int j = slot0 + wave + WAVES * r;
+    st_[r] = j < k ? sel_start[sr * k + j] : 0;
+    ln_[r] = j < k ? sel_len[sr * k + j] : 0;
+  }
+  if (count > k) count = k;
+  if (count <= 0) {   // nothing selected: chunk 0 writes the defined empty result of the tile's heads
+    if (chunk == 0 && threadIdx.x < DSK_HEAD_DIM) {
+#pragma unroll
+      for (int j = 0; j < GT; ++j) {
+        store_attn_out(out, out_bf16, (sh0 + j) * DSK_HEAD_DIM + threadIdx.x, 0.0f);
+        if (threadIdx.x == 0 && lse) lse[sh0 + j] = -__builtin_inff();
+      }
+    }
+    return;
+  }
+  if (slot0 >= count) return;
+  const int used = (count + kSlotsPerWg - 1) / kSlotsPerWg;
+
+  const int g = lane >> 4;
+  const int c = lane & 15;
+  QRow qf[GT];
+#pragma unroll
+  for (int j = 0; j < GT; ++j) qf[j] = make_qrow(*reinterpret_cast<const uint4*>(q + (sh0 + j) * DSK_HEAD_DIM + c * 8));
+  const uint16_t* Kh = K + (int64_t)hk * ksh + c * 8;
+  const uint16_t* Vh = V + (int64_t)hk * vsh + c * 8;
+
+  WaveState st[GT];
+#pragma unroll
+  for (int j = 0; j < GT; ++j) {
+    st[j].m = -__builtin_inff();
+    st[j].l = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) st[j].acc[i] = 0.0f;
+  }
+
+  uint4 kd[SPW][NS], vd[SPW][NS];
+  int nv[SPW];
+#pragma unroll
+  for (int r = 0; r < SPW; ++r) {
+    const int j = slot0 + wave + WAVES * r;
+    int start = st_[r];
+    int len = ln_[r] < b ? ln_[r] : b;
+    len = len < 4 * NS ? len : 4 * NS;
+    const bool ok = j < count && start >= 0 && len > 0 && start <= total_tokens - len;   // never read outside K/V
+    nv[r] = ok ? len : 0;
+    start = ok ? start : 0;
+    len = ok ? len : 1;
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+      int row = 4 * u + g;
+      row = row < len ? row : len - 1;
+      kd[r][u] = *reinterpret_cast<const uint4*>(Kh + (int64_t)(start + row) * kst);
+    }
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+      int row = 4 * u + g;
+      row = row < len ? row : len - 1;
+      vd[r][u] = *reinterpret_cast<const uint4*>(Vh + (int64_t)(start + row) * vst);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < SPW; ++r) {
+#pragma unroll
+    for (int u = 0; u < NS; ++u) pin_loaded(kd[r][u]);
+#pragma unroll
+    for (int u = 0; u < NS; ++u) pin_loaded(vd[r][u]);
+    if (nv[r] > 0) {
+#pragma unroll
+      for (int j = 0; j < GT; ++j) fold_loaded<NS>(st[j], qf[j], kd[r], vd[r], nv[r], g, scale_log2);
+    }
+  }
+
+#pragma unroll
+  for (int j = 0; j < GT; ++j) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      st[j].acc[i] += shfl_xor_f(st[j].acc[i], 16);
+      st[j].acc[i] += shfl_xor_f(st[j].acc[i], 32);
+    }
+    st[j].l += shfl_xor_f(st[j].l, 16);
+    st[j].l += shfl_xor_f(st[j].l, 32);
+    if (lane == 0) { sm_m[wave][j] = st[j].m; sm_l[wave][j] = st[j].l; }
+    if (g == 0) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sm_acc[wave][j][c * 8 + i] = st[j].acc[i];
+    }
+  }
+  __syncthreads();
+
+  // waves -> one partial per head of the tile, fixed order
+  for (int idx = threadIdx.x; idx < GT * DSK_HEAD_DIM; idx += WAVES * DSK_WAVE) {
+    const int j = idx / DSK_HEAD_DIM;
+    const int d = idx % DSK_HEAD_DIM;
+    float M = sm_m[0][j];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) M = fmaxf(M, sm_m[w][j]);
+    float l = 0.0f, a = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+      const float f = sm_m[w][j] == -__builtin_inff() ? 0.0f : exp2f(sm_m[w][j] - M);   // idle wave
+      l = fmaf(sm_l[w][j], f, l);
+      a = fmaf(sm_acc[w][j][d], f, a);
+    }
+    const int64_t sh = sh0 + j;
+    if (used == 1) {
+      store_attn_out(out, out_bf16, sh * DSK_HEAD_DIM + d, l > 0.0f ? a / l : 0.0f);
+      if (d == 0 && lse) lse[sh] = l > 0.0f ? (M + log2f(l)) * kLn2 : -__builtin_inff();
+    } else {
+      part_acc[(sh * nchunks + chunk) * DSK_HEAD_DIM + d] = a;
+      if (d == 0) part_ml[sh * nchunks + chunk] = make_float2(M, l);
+    }
+  }
+}
+
 // Merge of the partials of one (sequence, head) in a fixed order: 16 lane groups each fold the
 // chunks ch = group, group+16, ... (all loads of a round are independent), then one pass over
 // the 16 group states in LDS.  Heads with a single chunk were finished by attn_kernel.
@@ -291,7 +455,7 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
 
 AttnWs attn_ws_layout(const dsk_attn_args& a) {
   AttnWs ws;
-  ws.slots_per_wg = attn_slots_per_wg(a.b);
+  ws.slots_per_wg = attn_shared_tiled(a) ? kSharedWaves * kSharedSpw : attn_slots_per_wg(a.b);
   ws.nchunks = (a.k + ws.slots_per_wg - 1) / ws.slots_per_wg;
   const size_t n = (size_t)a.B * a.Hq * ws.nchunks;
   ws.part_ml = 0;
@@ -313,6 +477,28 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   // heads that read one row of the selection arrays; the workgroups of a group's heads gather the
   // same rows (chunk c of every head runs on XCD c mod 8), so only one of them misses in L2
   const int sel_div = (a.flags & DSK_ATTN_SHARED_SELECTION) ? a.Hq / a.Hkv : 1;
+  if (attn_shared_tiled(a)) {
+    const int G = a.Hq / a.Hkv;
+    const int GT = G == 2 ? 2 : 4;
+    const dim3 sgrid((unsigned)ws.nchunks, (unsigned)(a.Hkv * (G / GT)), (unsigned)a.B);
+    const dim3 sblock(kSharedWaves * DSK_WAVE);
+#define DSK_SHARED_ARGS                                                                                        \
+  q, K, V, a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, G, a.k, a.b, a.total_tokens, \
+      a.sel_start, a.sel_len, a.sel_count, scale * kLog2e, ws.nchunks, part_ml, part_acc, a.out,                \
+      static_cast<uint16_t*>(a.out_bf16), a.lse
+    if (GT == 2) {
+      if (a.b <= 16) attn_shared_kernel<4, kSharedSpw, kSharedWaves, 2><<<sgrid, sblock, 0, st>>>(DSK_SHARED_ARGS);
+      else attn_shared_kernel<8, kSharedSpw, kSharedWaves, 2><<<sgrid, sblock, 0, st>>>(DSK_SHARED_ARGS);
+    } else {
+      if (a.b <= 16) attn_shared_kernel<4, kSharedSpw, kSharedWaves, 4><<<sgrid, sblock, 0, st>>>(DSK_SHARED_ARGS);
+      else attn_shared_kernel<8, kSharedSpw, kSharedWaves, 4><<<sgrid, sblock, 0, st>>>(DSK_SHARED_ARGS);
+    }
+#undef DSK_SHARED_ARGS
+    hipError_t serr = hipGetLastError();
+    if (serr != hipSuccess || ws.nchunks <= 1 || (a.flags & DSK_ATTN_PARTIALS_ONLY)) return serr;
+    return launch_attn_merge(part_ml, part_acc, a.sel_count, nullptr, a.B, a.Hq, sel_div, a.k, ws.nchunks,
+                             ws.slots_per_wg, a.out, static_cast<uint16_t*>(a.out_bf16), a.lse, st);
+  }
 #define DSK_ATTN_ARGS                                                                                          \
   q, K, V, a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, a.Hq / a.Hkv, a.k, a.b,     \
       a.total_tokens, a.sel_start, a.sel_len, a.sel_count, sel_div, scale * kLog2e, ws.nchunks, part_ml, part_acc, a.out, \

@@ -120,3 +120,18 @@ def test_shared_selection_with_one_head_per_group_is_the_per_head_selection():
 def test_shared_selection_ragged_batch_with_empty_and_short_sequences():
     case = gpu_case(5, B=5, seqlens=[2500, 0, 40, 7000, 1], T=256, n_queries=2)
     _check_shared(case, 2, list(range(5)), [0, 3, 7], "ragged shared")
+
+
+@pytest.mark.parametrize("cfg_id,Hq,Hkv,B", [(5, 4, 2, 16), (5, 16, 2, 16), (3, 32, 8, 4)])
+def test_shared_selection_tiled_gather(cfg_id, Hq, Hkv, B):
+    """Launches of 4096 slots and more go through the kernel that folds every loaded K/V row
+    into all query heads of the group: group widths 2, 8 (16 sequences, b = 16) and 4 (b = 32),
+    ragged lengths with one empty sequence."""
+    rng = np.random.default_rng(100 + Hq)
+    seqlens = [int(x) for x in rng.integers(4200, 6000, size=B)]
+    seqlens[1] = 0
+    seqlens[2] = 5 * 128 * (32 if cfg_id == 3 else 16) // 8      # fewer slots than k: short selection
+    case = gpu_case(cfg_id, B=B, Hq=Hq, Hkv=Hkv, seqlens=seqlens, n_queries=1,
+                    T=128 * (32 if cfg_id == 3 else 16))
+    assert case.cfg.B * case.cfg.Hkv * case.cfg.k >= 4096
+    _check_shared(case, 1, [0, 1, 2, B - 1], sorted({0, Hkv - 1}), "tiled G=%d" % (Hq // Hkv))
