@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--append-steps", type=int, default=256,
                     help="steps of the decode loop that appends one token per step before selecting; 0 = skip")
+    ap.add_argument("--no-shared-selection", action="store_true",
+                    help="skip the leg that measures the shared-selection extension")
     ap.add_argument("--reuse-steps", type=int, default=48,
                     help="decode steps of the KV-reuse leg (K/V in pinned host memory); 0 disables it")
     ap.add_argument("--reuse-rho", type=float, default=0.98,
@@ -216,7 +218,7 @@ def main():
 
         # ---- extension (not in the paper): one selection per KV head, shared by its query heads ----
         shared = None
-        if cfg.G > 1:
+        if cfg.G > 1 and not args.no_shared_selection:
             ssel = [dsk.make_select_args(comp, queries[0], cfg.T, max_blocks_used=nblk, max_blocks_per_seq=nblk_seq,
                                          shared=True)]
             for i in range(1, nq):
