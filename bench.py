@@ -406,13 +406,14 @@ def main():
             r_per_step = torch.zeros(n_r + 1, cfg.B, dtype=torch.int32, device=dev)
             loads_per_step = torch.zeros(n_r + 1, cfg.B, cfg.Hq, dtype=torch.int32, device=dev)
 
-            def reuse_variant(Ksrc, Vsrc):
+            def reuse_variant(Ksrc, Vsrc, rsel=rsel):
                 ru = dsk.make_reuser(rsel[0], Ksrc, Vsrc, cfg.Hkv)
                 rargs = []
+                loads_per_step.zero_()
                 for i in range(n_r + 1):
                     a = type(ru.args).from_buffer_copy(ru.args)
                     a.reuse_count = r_per_step[i].data_ptr()
-                    a.load_count = loads_per_step[i].data_ptr()
+                    a.load_count = loads_per_step[i].data_ptr()      # [B, heads of the selection] of a [B, Hq] row
                     rargs.append(a)
                 ratt = [ru.attn_args(dqs[0])]
                 for i in range(1, n_r + 1):
@@ -441,6 +442,18 @@ def main():
             mean_r = float(r_per_step[1:].float().mean().item())
             mean_loads = float(loads_per_step[1:].float().sum(dim=(1, 2)).mean().item())
             hbm_us, keep_d = reuse_variant(K, V)
+            shared_host = None
+            if cfg.G > 1 and not args.no_shared_selection:
+                rsel_sh = [dsk.make_select_args(comp, dqs[0], cfg.T, max_blocks_used=nblk, max_blocks_per_seq=nblk_seq,
+                                                shared=True)]
+                for i in range(1, n_r + 1):
+                    rsel_sh.append(dsk.make_select_args(comp, dqs[i], cfg.T, out=rsel_sh[0], max_blocks_used=nblk,
+                                                        max_blocks_per_seq=nblk_seq, shared=True))
+                sh_us, keep_s = reuse_variant(Kh, Vh, rsel_sh)
+                shared_host = {"us": round(sh_us, 2),
+                               "mean_reused_slots_per_head": round(float(r_per_step[1:].float().mean().item()), 1),
+                               "slots_loaded_per_step": round(float(loads_per_step[1:].float().sum(dim=(1, 2)).mean().item()), 1)}
+                del keep_s
             # without reuse: the attention gathers every selected slot from host memory, every step
             natt = [dsk.make_attn_args(dqs[i], Kh, Vh, rsel[0].sel_start, rsel[0].sel_len, rsel[0].sel_count, cfg.b,
                                        out=atts[0]) for i in range(n_r + 1)]
@@ -467,6 +480,7 @@ def main():
                      "host_kv_without_reuse_us": round(noreuse_us, 2),
                      "host_kv_full_attention_us": round(dense_host_us, 1),
                      "hbm_kv_with_reuse_us": round(hbm_us, 2),
+                     "host_kv_with_reuse_shared_selection_extension": shared_host,
                      "speedup_reuse_vs_no_reuse": round(noreuse_us / host_us, 2),
                      "speedup_reuse_vs_full_attention_host": round(dense_host_us / host_us, 1),
                      "what": "select + dsk_reuse_update + attention over the resident buffers; K/V source in "

@@ -656,9 +656,12 @@ class Reuser:
         return dsk_reuse_update(self.args, stream, check=check)
 
     def attn_args(self, q: torch.Tensor, *, scale: float = 0.0, out: Optional[AttnOut] = None) -> AttnOut:
-        """Arguments of dsk_sparse_decode_attn over the resident buffers (every query head its own K/V)."""
+        """Arguments of dsk_sparse_decode_attn over the resident buffers: every query head its own
+        K/V, or -- when the reuser was built on a selection shared per KV head -- one buffer per KV
+        head read by all its query heads."""
+        shared = self.res_start.shape[1] != q.shape[1]
         return make_attn_args(q, self.Kres, self.Vres, self.res_start, self.res_len, self.res_count, self.b,
-                              scale=scale, out=out)
+                              scale=scale, out=out, flags=DSK_ATTN_SHARED_SELECTION if shared else 0)
 
 
 def make_reuser(sel: Selection, K: Optional[torch.Tensor], V: Optional[torch.Tensor], Hkv: int, *,

@@ -287,3 +287,43 @@ def test_reuse_at_the_position_limit():
     hist, k = _run(case, 3, 0.9, [0, 31], T=dsk.DSK_REUSE_MAX_K * case.cfg.b, repeat_at=(2,))
     assert k == dsk.DSK_REUSE_MAX_K
     print("k = 2048 reuse counts:", hist)
+
+
+def test_reuse_on_a_selection_shared_per_kv_head():
+    """The two additions compose: with one selection per KV head the resident buffers are per KV
+    head too (a quarter of the rows to hold and to load at G = 4), and all query heads of the group
+    attend over their KV head's buffer."""
+    dsk = _dsk()
+    case = gpu_case(2, seqlens=[6000], T=512, n_queries=1)
+    cfg, wl = case.cfg, case.wl
+    comp = case.compressed()
+    n_steps = 4
+    qs = make_drifting_queries(np.random.default_rng(21), n_steps, 1, cfg.Hq, cfg.D, 0.97)
+    q = dev_bf16(qs[0])
+    sel = dsk.make_select_args(comp, q, 512, shared=True)
+    reuser = dsk.make_reuser(sel, case.K, case.V, cfg.Hkv)
+    assert reuser.Kres.shape[0] == cfg.Hkv
+    resident = [[-1] * sel.k for _ in range(cfg.Hkv)]
+    att = None
+    seen = []
+    for t in range(n_steps):
+        q.copy_(dev_bf16(qs[t]))
+        dsk.dsk_select_topk(sel.args)
+        reuser.step()
+        att = reuser.attn_args(q, out=att)
+        dsk.dsk_sparse_decode_attn(att.args)
+        torch.cuda.synchronize()
+        g_slot, g_cnt = sel.sel_slot.cpu().numpy()[0], sel.sel_count.cpu().numpy()[0]
+        g_start, g_len = sel.sel_start.cpu().numpy()[0], sel.sel_len.cpu().numpy()[0]
+        r, resident, loads = O.kv_reuse_plan(resident, [g_slot[h, :g_cnt[h]].tolist() for h in range(cfg.Hkv)])
+        seen.append(r)
+        assert int(reuser.reuse_count[0]) == r
+        assert reuser.res_slot.cpu().numpy()[0].tolist() == resident
+        out, lse = att.out.cpu().numpy()[0], att.lse.cpu().numpy()[0]
+        for hk in (0, cfg.Hkv - 1):
+            toks = np.concatenate([np.arange(g_start[hk, j], g_start[hk, j] + g_len[hk, j]) for j in range(g_cnt[hk])])
+            Kh, Vh = O.widen_bf16(wl.K[hk][toks]), O.widen_bf16(wl.V[hk][toks])
+            for h in range(hk * cfg.G, (hk + 1) * cfg.G):
+                o, l = O.sparse_attention(O.widen_bf16(qs[t][0, h]), Kh, Vh, np.arange(len(toks)), DEFAULT_SCALE)
+                assert rel_err(out[h], o) <= ATTN_TOL and abs(float(lse[h]) - l) <= LSE_TOL
+    assert seen[0] == 0 and max(seen[1:]) > 0
