@@ -327,3 +327,53 @@ def test_reuse_on_a_selection_shared_per_kv_head():
                 o, l = O.sparse_attention(O.widen_bf16(qs[t][0, h]), Kh, Vh, np.arange(len(toks)), DEFAULT_SCALE)
                 assert rel_err(out[h], o) <= ATTN_TOL and abs(float(lse[h]) - l) <= LSE_TOL
     assert seen[0] == 0 and max(seen[1:]) > 0
+
+
+def test_reuse_step_replays_correctly_from_a_hip_graph():
+    """select + reuse update + attention over the buffers captured once; each replay continues from
+    the resident state the previous one left (with eager work and synchronisations in between) and
+    must equal, bit for bit, an eager twin fed the same queries."""
+    dsk = _dsk()
+    case = gpu_case(2, seqlens=[6000], T=512, n_queries=1)
+    cfg = case.cfg
+    comp = case.compressed()
+    stream = torch.cuda.Stream()
+    qs = make_drifting_queries(np.random.default_rng(33), 6, 1, cfg.Hq, cfg.D, 0.97)
+    qbuf, qref = dev_bf16(qs[0]).clone(), dev_bf16(qs[0]).clone()
+    with torch.cuda.stream(stream):
+        twins = []
+        for qq in (qbuf, qref):
+            sel = dsk.make_select_args(comp, qq, 512)
+            ru = dsk.make_reuser(sel, case.K, case.V, cfg.Hkv)
+            att = ru.attn_args(qq)
+            twins.append((sel, ru, att))
+        (gsel, gru, gatt), (esel, eru, eatt) = twins
+
+        def step(sel, ru, att):
+            dsk.dsk_select_topk(sel.args, stream)
+            dsk.dsk_reuse_update(ru.args, stream)
+            dsk.dsk_sparse_decode_attn(att.args, stream)
+
+        step(gsel, gru, gatt)                                # warm-up outside the capture, then back to empty
+        stream.synchronize()
+        gru.res_slot.fill_(-1)
+        gru.res_len.zero_()
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            step(gsel, gru, gatt)
+        for t in range(6):
+            qref.copy_(dev_bf16(qs[t]))
+            stream.synchronize()
+            step(esel, eru, eatt)                            # the program's own eager work between replays
+            stream.synchronize()
+            qbuf.copy_(dev_bf16(qs[t]))
+            gatt.out.fill_(-1.0)
+            stream.synchronize()
+            graph.replay()
+            stream.synchronize()
+            for name in ("res_slot", "res_len", "res_count", "load_pos", "load_slot", "load_count", "reuse_count",
+                         "Kres", "Vres"):
+                assert torch.equal(getattr(gru, name), getattr(eru, name)), (t, name)
+            assert torch.equal(gatt.out, eatt.out) and torch.equal(gatt.lse, eatt.lse), t
+        assert int(gru.reuse_count[0]) > 0
