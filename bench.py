@@ -128,6 +128,14 @@ def main():
         n_c = 10
         compress_ms = event_ms(lambda: [dsk.dsk_compress(cargs, stream) for _ in range(n_c)], stream) / n_c
         compress_bytes = wl.total_tokens * cfg.Hkv * 128 * 2 + nblk * cfg.Hkv * 512 + wl.total_tokens * 4
+        # the same pass without the candidate lists (weights from a table need none: the classes go
+        # straight to the segmentation), reported beside the full figure
+        lean = dsk.compress(**dict(ckw, want_candidates=False))
+        for _ in range(3):
+            dsk.dsk_compress(lean.args, stream)
+        compress_lean_ms = event_ms(lambda: [dsk.dsk_compress(lean.args, stream) for _ in range(n_c)], stream) / n_c
+        stream.synchronize()
+        assert torch.equal(lean.block_start[: nblk + 1], comp.block_start[: nblk + 1])
 
         # ---- delimiter importance (Alg. 1 on the sampled windows), timed by itself: the weights are
         #      estimated once per scenario, so it is not part of the per-prefill figure above ---------
@@ -516,6 +524,7 @@ def main():
                      "GBps": round(compress_bytes / (compress_ms * 1e-3) / 1e9, 1),
                      "frac_of_hbm_peak": round(compress_bytes / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                      "stages": "candidates+segment+summaries(K)",
+                     "us_without_candidate_lists": round(compress_lean_ms * 1e3, 2),
                      "importance_us": round(importance_us, 1), "importance_samples": n_samples},
         "roofline": {"bound": "hbm", "kernel": "attn_kernel (K/V gather + online softmax of dsk_sparse_decode_attn)",
                      "achieved": round(attn_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -84,6 +84,10 @@ enum {
  *   in delim_ids.  Output lists are ascending in global position.  Also chooses the
  *   sampled candidates for Alg. 1: per sequence and class the first M occurrences whose
  *   sequence-local position t satisfies R <= t <= L-1-W.
+ *   When only the segmentation of the same call needs the candidates (weights from a table:
+ *   no sampling), the lists may be left out: cand_pos == cand_class == NULL with
+ *   max_cand_total == 0 keeps the per-token classes in the workspace for stage SEGMENT and
+ *   writes neither the lists nor cand_cu (which may then be NULL too).
  * Stage IMPORTANCE (Alg. 1 and the equation of Sec. 3, on the one layer given):
  *   for each sampled candidate t, each query head and each of the W queries following t,
  *   the causal softmax row over keys 0..q is split into the retained region
@@ -129,7 +133,7 @@ typedef struct dsk_compress_args {
   int32_t n_class;             /* 1..DSK_MAX_CLASSES */
   int32_t max_cand_total;      /* capacity of cand_pos / cand_class */
   int32_t* cand_pos;           /* [dev] [max_cand_total] global positions, ascending (out of
-                                  CANDIDATES, in of SEGMENT) */
+                                  CANDIDATES, in of SEGMENT); NULL: see stage CANDIDATES */
   uint8_t* cand_class;         /* [dev] [max_cand_total] */
   int32_t* cand_cu;            /* [dev] [B+1] candidate range of each sequence */
 

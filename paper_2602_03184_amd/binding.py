@@ -357,8 +357,12 @@ def compress(*, cu_seqlens: torch.Tensor, max_seqlen: int, Hq: int, K: Optional[
              max_blocks_total: Optional[int] = None, block_start: Optional[torch.Tensor] = None,
              cu_blocks: Optional[torch.Tensor] = None, slot_base: Optional[torch.Tensor] = None,
              want_vsum: bool = False, Hkv: Optional[int] = None, total_tokens: Optional[int] = None,
-             summary_mode: int = DSK_SUMMARY_MINMAX, stream=None, check: bool = True) -> Compressed:
+             summary_mode: int = DSK_SUMMARY_MINMAX, want_candidates: bool = True, stream=None,
+             check: bool = True) -> Compressed:
     """Allocate outputs / workspace with torch, fill dsk_compress_args and call dsk_compress.
+
+    `want_candidates=False` (stages CANDIDATES + SEGMENT, no sampling): the candidate lists are
+    not produced; the per-token classes go straight to the segmentation.
 
     `total_tokens` defaults to the token extent of K (or of token_ids).  Buffers a skipped
     stage would have produced must be passed in."""
@@ -385,7 +389,11 @@ def compress(*, cu_seqlens: torch.Tensor, max_seqlen: int, Hq: int, K: Optional[
     i32 = dict(dtype=torch.int32, device=dev)
     if max_cand_total is None:
         max_cand_total = cand_pos.numel() if cand_pos is not None else total_tokens
-    if stages & DSK_STAGE_CANDIDATES:
+    if stages & DSK_STAGE_CANDIDATES and not want_candidates:
+        assert stages & DSK_STAGE_SEGMENT and M == 0
+        cand_pos = cand_class = cand_cu = None
+        max_cand_total = 0
+    elif stages & DSK_STAGE_CANDIDATES:
         cand_pos = torch.empty(max(max_cand_total, 1), **i32)
         cand_class = torch.empty(max(max_cand_total, 1), dtype=torch.uint8, device=dev)
         cand_cu = torch.empty(B + 1, **i32)

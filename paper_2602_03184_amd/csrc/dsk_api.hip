@@ -46,11 +46,15 @@ static dsk_status validate_compress(const dsk_compress_args* a) {
   if (st_cand || st_imp || st_seg) {
     if (a->n_class < 1 || a->n_class > DSK_MAX_CLASSES) return DSK_ERR_PARAM;
   }
+  // candidates for the segmentation of this call only: no lists, the class map stays in the workspace
+  const bool no_lists = st_cand && st_seg && a->cand_pos == nullptr && a->cand_class == nullptr &&
+                        a->max_cand_total == 0;
   if (st_cand || st_seg) {
     if (a->max_cand_total < 0) return DSK_ERR_PARAM;
-    if (a->cand_cu == nullptr) return DSK_ERR_NULL;
+    if (a->cand_cu == nullptr && !no_lists) return DSK_ERR_NULL;
     if (a->max_cand_total > 0 && (a->cand_pos == nullptr || a->cand_class == nullptr)) return DSK_ERR_NULL;
   }
+  if (no_lists && (st_imp || (a->samp_pos != nullptr && a->M > 0))) return DSK_ERR_NULL;   // sampling reads the lists
   if (st_cand) {
     if (a->token_ids == nullptr || a->delim_ids == nullptr) return DSK_ERR_NULL;
     if (a->samp_pos != nullptr && a->M > 0) {

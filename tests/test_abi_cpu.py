@@ -163,6 +163,18 @@ def test_compress_validation_rejects_before_launch(dsk):
         assert dsk.dsk_compress(a, 0, check=False) == want, field
     with pytest.raises(dsk.DskError):
         dsk.dsk_compress(_valid_compress(dsk), 0)
+    # candidate lists left out: only together with the segmentation, without sampling
+    a = _valid_compress(dsk)
+    a.stages = dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_SEGMENT
+    a.token_ids = a.delim_ids = 0x10000
+    a.cand_pos = a.cand_class = a.cand_cu = None
+    a.max_cand_total = 0
+    assert dsk.dsk_compress(a, 0, check=False) == dsk.DSK_ERR_WORKSPACE      # accepted up to the workspace
+    a.samp_pos, a.M = 0x10000, 4
+    assert dsk.dsk_compress(a, 0, check=False) == dsk.DSK_ERR_NULL          # sampling reads the lists
+    a.samp_pos, a.M = None, 0
+    a.stages = dsk.DSK_STAGE_CANDIDATES
+    assert dsk.dsk_compress(a, 0, check=False) == dsk.DSK_ERR_NULL          # nothing would be produced
     # summaries stage: alignment and stride rules
     for field, value, want in (("K", 0x10002, dsk.DSK_ERR_ALIGN), ("k_stride_tok", 132, dsk.DSK_ERR_ALIGN),
                                ("k_stride_tok", 64, dsk.DSK_ERR_SHAPE), ("ksum", None, dsk.DSK_ERR_NULL),

@@ -67,6 +67,24 @@ def test_segmentation_with_paper_window_14(cfg_id):
     _check_tables(comp, seg)
 
 
+@pytest.mark.parametrize("cfg_id", [1, 3, 5])
+def test_compression_without_candidate_lists(cfg_id):
+    """Table-mode weights need no candidate list: with the lists left out the class map goes
+    straight to the segmentation, and the tables and summaries are those of the full call."""
+    dsk = _dsk()
+    case = gpu_case(cfg_id)
+    full = case.compressed()
+    lean = dsk.compress(**case.compress_kwargs(
+        stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_SEGMENT | dsk.DSK_STAGE_SUMMARIES,
+        token_ids=case.token_ids, delim_ids=case.delim_ids, want_candidates=False))
+    torch.cuda.synchronize()
+    assert lean.cand_pos is None and lean.args.max_cand_total == 0
+    assert int(lean.dev_status.item()) == 0
+    _check_tables(lean, case.seg)
+    nb = int(case.seg.cu_blocks[-1])
+    assert torch.equal(lean.ksum[:, :nb], full.ksum[:, :nb])
+
+
 @pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5])
 def test_summaries_bit_exact(cfg_id):
     case = gpu_case(cfg_id)
