@@ -37,6 +37,9 @@
  *   - K, V, q and summaries are bf16 (raw 16-bit patterns), head_dim D must be 128.
  *   - Same inputs give bit-identical outputs (fixed reduction orders, no float atomics).
  *   - Non-finite K/V/q values give unspecified results but never hang.
+ *   - A batch without any token (total_tokens == 0) is valid everywhere: tables come out empty,
+ *     nothing is selected, attention returns out = 0 and lse = -inf; K, V and token_ids are not
+ *     read and may be NULL in that case only.
  */
 #ifndef DSK_H_
 #define DSK_H_

@@ -311,7 +311,10 @@ def _ws(nbytes: int, device) -> torch.Tensor:
 
 def _kv_strides(X: torch.Tensor):
     """X: bf16 [Hkv, tokens, D] view (any head/token strides, unit channel stride)."""
-    assert X.dim() == 3 and X.stride(2) == 1 and X.dtype == torch.bfloat16
+    assert X.dim() == 3 and X.dtype == torch.bfloat16
+    if X.numel() == 0:                       # no token: nothing is read, any valid strides do
+        return DSK_HEAD_DIM, DSK_HEAD_DIM
+    assert X.stride(2) == 1
     return X.stride(1), X.stride(0)
 
 

@@ -56,7 +56,7 @@ static dsk_status validate_compress(const dsk_compress_args* a) {
   }
   if (no_lists && (st_imp || (a->samp_pos != nullptr && a->M > 0))) return DSK_ERR_NULL;   // sampling reads the lists
   if (st_cand) {
-    if (a->token_ids == nullptr || a->delim_ids == nullptr) return DSK_ERR_NULL;
+    if ((a->token_ids == nullptr && a->total_tokens > 0) || a->delim_ids == nullptr) return DSK_ERR_NULL;
     if (a->samp_pos != nullptr && a->M > 0) {
       if (a->M > kMaxSamplesPerClass || a->W < 1 || a->R < 1) return DSK_ERR_PARAM;
     }
@@ -82,8 +82,9 @@ static dsk_status validate_compress(const dsk_compress_args* a) {
   if (st_seg && a->slot_base == nullptr) return DSK_ERR_NULL;
   if (st_sum) {
     if (a->summary_mode != DSK_SUMMARY_MINMAX && a->summary_mode != DSK_SUMMARY_MEAN) return DSK_ERR_PARAM;
-    if (a->K == nullptr || a->ksum == nullptr) return DSK_ERR_NULL;
-    if (a->vsum != nullptr && a->V == nullptr) return DSK_ERR_NULL;
+    // an empty batch (no token at all) has no K/V row to read: the pointers may then be NULL
+    if ((a->K == nullptr && a->total_tokens > 0) || a->ksum == nullptr) return DSK_ERR_NULL;
+    if (a->vsum != nullptr && a->V == nullptr && a->total_tokens > 0) return DSK_ERR_NULL;
     if (!aligned16(a->ksum) || (a->vsum && !aligned16(a->vsum))) return DSK_ERR_ALIGN;
   }
   if (st_sum || st_imp) {
@@ -133,7 +134,8 @@ static dsk_status validate_attn(const dsk_attn_args* a) {
   if (a->k < 1 || a->b < 1 || a->b > 1024) return DSK_ERR_PARAM;
   if (!(a->scale >= 0.0f) || (a->flags & ~(uint32_t)(DSK_ATTN_PARTIALS_ONLY | DSK_ATTN_SHARED_SELECTION)))
     return DSK_ERR_PARAM;
-  if (!a->q || !a->K || !a->V || !a->sel_start || !a->sel_len || !a->sel_count || !a->out) return DSK_ERR_NULL;
+  if (!a->q || !a->sel_start || !a->sel_len || !a->sel_count || !a->out) return DSK_ERR_NULL;
+  if ((!a->K || !a->V) && a->total_tokens > 0) return DSK_ERR_NULL;   // no token, no row to read
   if (a->k_stride_tok < DSK_HEAD_DIM || a->v_stride_tok < DSK_HEAD_DIM || a->k_stride_head < 0 ||
       a->v_stride_head < 0)
     return DSK_ERR_SHAPE;
@@ -180,7 +182,8 @@ static dsk_status validate_dense(const dsk_dense_attn_args* a) {
   if (!geometry_ok(a->B, a->Hq, a->Hkv, a->D)) return DSK_ERR_SHAPE;
   if (a->total_tokens < 0 || a->max_seqlen < 1) return DSK_ERR_SHAPE;
   if (!(a->scale >= 0.0f) || a->flags != 0) return DSK_ERR_PARAM;
-  if (!a->q || !a->K || !a->V || !a->cu_seqlens || !a->out) return DSK_ERR_NULL;
+  if (!a->q || !a->cu_seqlens || !a->out) return DSK_ERR_NULL;
+  if ((!a->K || !a->V) && a->total_tokens > 0) return DSK_ERR_NULL;   // no token, no row to read
   if (a->k_stride_tok < DSK_HEAD_DIM || a->v_stride_tok < DSK_HEAD_DIM || a->k_stride_head < 0 ||
       a->v_stride_head < 0)
     return DSK_ERR_SHAPE;

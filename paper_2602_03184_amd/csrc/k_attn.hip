@@ -111,6 +111,7 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
     ln_[r] = j < k ? sel_len[sr * k + j] : 0;
   }
   if (count > k) count = k;
+  if (total_tokens <= 0) count = 0;   // no K/V row exists: not even the redirected loads of skipped slots may run
   if (count <= 0) {   // nothing selected: chunk 0 writes the defined empty result
     if (chunk == 0 && threadIdx.x < DSK_HEAD_DIM) {
       store_attn_out(out, out_bf16, sh * DSK_HEAD_DIM + threadIdx.x, 0.0f);
@@ -264,6 +265,7 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_shared_kernel(
     ln_[r] = j < k ? sel_len[sr * k + j] : 0;
   }
   if (count > k) count = k;
+  if (total_tokens <= 0) count = 0;   // no K/V row exists: not even the redirected loads of skipped slots may run
   if (count <= 0) {   // nothing selected: chunk 0 writes the defined empty result of the tile's heads
     if (chunk == 0 && threadIdx.x < DSK_HEAD_DIM) {
 #pragma unroll
@@ -495,7 +497,7 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
     }
 #undef DSK_SHARED_ARGS
     hipError_t serr = hipGetLastError();
-    if (serr != hipSuccess || ws.nchunks <= 1 || (a.flags & DSK_ATTN_PARTIALS_ONLY)) return serr;
+    if (serr != hipSuccess || ws.nchunks <= 1 || (a.flags & DSK_ATTN_PARTIALS_ONLY) || a.total_tokens <= 0) return serr;
     return launch_attn_merge(part_ml, part_acc, a.sel_count, nullptr, a.B, a.Hq, sel_div, a.k, ws.nchunks,
                              ws.slots_per_wg, a.out, static_cast<uint16_t*>(a.out_bf16), a.lse, st);
   }
@@ -512,7 +514,8 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   else attn_kernel<0, 2, 4><<<grid, dim3(256), 0, st>>>(DSK_ATTN_ARGS);
 #undef DSK_ATTN_ARGS
   hipError_t err = hipGetLastError();
-  if (err != hipSuccess || ws.nchunks <= 1 || (a.flags & DSK_ATTN_PARTIALS_ONLY)) return err;
+  // a cache without tokens: every head already holds the defined empty result, no partial exists
+  if (err != hipSuccess || ws.nchunks <= 1 || (a.flags & DSK_ATTN_PARTIALS_ONLY) || a.total_tokens <= 0) return err;
   return launch_attn_merge(part_ml, part_acc, a.sel_count, nullptr, a.B, a.Hq, sel_div, a.k, ws.nchunks,
                            ws.slots_per_wg, a.out, static_cast<uint16_t*>(a.out_bf16), a.lse, st);
 }

@@ -233,6 +233,12 @@ def test_select_and_attn_validation(dsk):
         a = att()
         setattr(a, field, value)
         assert dsk.dsk_sparse_decode_attn(a, 0, check=False) == want, field
+    # a cache without any token has no K/V row: the pointers may be NULL then, and only then
+    a = att()
+    a.K = a.V = None
+    assert dsk.dsk_sparse_decode_attn(a, 0, check=False) == dsk.DSK_ERR_NULL
+    a.total_tokens = 0
+    assert dsk.dsk_sparse_decode_attn(a, 0, check=False) == dsk.DSK_ERR_WORKSPACE
 
 
 def test_binding_never_imports_the_oracle(dsk):

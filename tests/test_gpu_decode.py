@@ -429,3 +429,25 @@ def test_decode_step_replays_correctly_from_a_hip_graph():
             stream.synchronize()
             assert torch.equal(sel.sel_slot, ref_sel.sel_slot) and torch.equal(sel.sel_count, ref_sel.sel_count)
             assert torch.equal(att.out, ref_att.out) and torch.equal(att.lse, ref_att.lse)
+
+
+def test_batch_without_any_token():
+    """Every sequence of the batch is empty: the tables are empty, nothing is selected, attention
+    (sparse and full) returns the defined empty result; K and V have no row and are never read."""
+    dsk = _dsk()
+    case = gpu_case(5, B=3, seqlens=[0, 0, 0], T=256, n_queries=1)
+    cfg = case.cfg
+    assert case.K.numel() == 0
+    comp = case.compressed()
+    assert int(comp.dev_status.item()) == 0 and (comp.cu_blocks.cpu().numpy() == 0).all()
+    q = dev_bf16(case.wl.q[0])
+    sel = dsk.select_topk(comp, q, cfg.T)
+    att = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b)
+    # selection arrays that claim slots although no token exists must not make the kernels read
+    bogus = sel.sel_count.clone().fill_(cfg.k)
+    att2 = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, bogus, cfg.b)
+    dense = dsk.dense_decode_attn(q, case.K, case.V, case.cu_seqlens, 1)
+    torch.cuda.synchronize()
+    assert (sel.sel_count == 0).all() and (sel.sel_slot == -1).all()
+    for r in (att, att2, dense):
+        assert (r.out == 0).all() and torch.isneginf(r.lse).all()
