@@ -281,7 +281,8 @@ typedef struct dsk_dense_attn_args {
   const void* V;               /* [dev] */
   int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;
   int32_t total_tokens;        /* [host] tokens per head in K/V; cu_seqlens[B] must not exceed it */
-  int32_t max_seqlen;          /* [host] upper bound of the sequence lengths (sizes the split) */
+  int32_t max_seqlen;          /* [host] upper bound of the sequence lengths (sizes the split); >= 1
+                                  unless total_tokens == 0 */
   const int32_t* cu_seqlens;   /* [dev] [B+1] */
   float scale;                 /* 0 -> D^-1/2 */
   uint32_t flags;              /* must be 0 */

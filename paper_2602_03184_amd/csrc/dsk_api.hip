@@ -180,7 +180,7 @@ static dsk_status validate_dense(const dsk_dense_attn_args* a) {
   if (a == nullptr) return DSK_ERR_NULL;
   if (a->struct_size != sizeof(dsk_dense_attn_args)) return DSK_ERR_VERSION;
   if (!geometry_ok(a->B, a->Hq, a->Hkv, a->D)) return DSK_ERR_SHAPE;
-  if (a->total_tokens < 0 || a->max_seqlen < 1) return DSK_ERR_SHAPE;
+  if (a->total_tokens < 0 || a->max_seqlen < 0 || (a->max_seqlen == 0 && a->total_tokens > 0)) return DSK_ERR_SHAPE;
   if (!(a->scale >= 0.0f) || a->flags != 0) return DSK_ERR_PARAM;
   if (!a->q || !a->cu_seqlens || !a->out) return DSK_ERR_NULL;
   if ((!a->K || !a->V) && a->total_tokens > 0) return DSK_ERR_NULL;   // no token, no row to read

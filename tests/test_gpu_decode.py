@@ -446,7 +446,7 @@ def test_batch_without_any_token():
     # selection arrays that claim slots although no token exists must not make the kernels read
     bogus = sel.sel_count.clone().fill_(cfg.k)
     att2 = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, bogus, cfg.b)
-    dense = dsk.dense_decode_attn(q, case.K, case.V, case.cu_seqlens, 1)
+    dense = dsk.dense_decode_attn(q, case.K, case.V, case.cu_seqlens, 0)
     torch.cuda.synchronize()
     assert (sel.sel_count == 0).all() and (sel.sel_slot == -1).all()
     for r in (att, att2, dense):
