@@ -16,6 +16,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libdsk.so")
+EXAMPLE_SRC = os.path.join(PKG_DIR, "examples", "dsk_example.cpp")
+EXAMPLE_PATH = os.path.join(PKG_DIR, "dsk_example")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",
@@ -61,7 +63,18 @@ def build_library(jobs: int = 8) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
+    build_example()
     return LIB_PATH
+
+
+def build_example() -> str:
+    """The host-only example on the C ABI (no Python, no torch), linked against the library beside it."""
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-I", os.path.join(os.path.dirname(PKG_DIR), "include"),
+           EXAMPLE_SRC, "-L", PKG_DIR, "-ldsk", "-Wl,-rpath,$ORIGIN", "-o", EXAMPLE_PATH]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("building the example failed:\n%s\n%s" % (r.stdout, r.stderr))
+    return EXAMPLE_PATH
 
 
 if __name__ == "__main__":
