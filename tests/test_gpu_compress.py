@@ -244,3 +244,41 @@ def test_compress_is_deterministic():
         outs.append((comp.block_start.cpu().numpy()[: nb + 1].copy(), bf16_bits_of(comp.ksum)[:, :nb].copy()))
     np.testing.assert_array_equal(outs[0][0], outs[1][0])
     np.testing.assert_array_equal(outs[0][1], outs[1][1])
+
+
+def test_compression_pass_replays_correctly_from_a_hip_graph():
+    """The pass enqueues kernels only (no allocation, no memset, no synchronisation), so it can be
+    captured once and replayed on new token ids and K written into the same buffers: every replay,
+    with eager work and synchronisations in between, must reproduce the eager result bit for bit."""
+    dsk = _dsk()
+    case = gpu_case(2, seqlens=[9000])
+    wl = case.wl
+    stream = torch.cuda.Stream()
+    tok = case.token_ids.clone()
+    K = case.K.clone()
+    kw = case.compress_kwargs(stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_SEGMENT | dsk.DSK_STAGE_SUMMARIES,
+                              delim_ids=case.delim_ids)
+    with torch.cuda.stream(stream):
+        captured = dsk.compress(**dict(kw, token_ids=tok, K=K, stream=stream))       # also the warm-up
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            dsk.dsk_compress(captured.args, stream)
+        for shift in (0, 1, 17, 300):
+            tok.copy_(torch.roll(case.token_ids, shift))
+            K.copy_(torch.roll(case.K, shift, dims=1))
+            stream.synchronize()
+            eager = dsk.compress(**dict(kw, token_ids=tok, K=K, stream=stream))       # the program's own eager work
+            stream.synchronize()
+            captured.ksum.fill_(0)
+            captured.block_start.fill_(-7)
+            stream.synchronize()
+            graph.replay()
+            stream.synchronize()
+            nb = int(eager.cu_blocks.cpu()[1])
+            assert int(captured.dev_status.item()) == 0 and int(captured.cu_blocks.cpu()[1]) == nb
+            assert torch.equal(captured.block_start[: nb + 1], eager.block_start[: nb + 1])
+            assert torch.equal(captured.slot_base[: nb + 1], eager.slot_base[: nb + 1])
+            assert torch.equal(captured.ksum[:, :nb], eager.ksum[:, :nb])
+            n = int(eager.cand_cu.cpu()[1])
+            assert torch.equal(captured.cand_pos[:n], eager.cand_pos[:n])
