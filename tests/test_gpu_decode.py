@@ -451,3 +451,33 @@ def test_batch_without_any_token():
     assert (sel.sel_count == 0).all() and (sel.sel_slot == -1).all()
     for r in (att, att2, dense):
         assert (r.out == 0).all() and torch.isneginf(r.lse).all()
+
+
+def test_two_streams_with_their_own_workspaces_do_not_interfere():
+    """The library keeps no state of its own: decode steps enqueued on two streams at once, each
+    with its own outputs and workspace, give exactly what each gives alone."""
+    dsk = _dsk()
+    case = gpu_case(2)
+    cfg, wl = case.cfg, case.wl
+    comp = case.compressed()
+    gen = torch.Generator(device="cpu").manual_seed(3)
+    qs = [torch.randn(cfg.B, cfg.Hq, 128, generator=gen).to(torch.bfloat16).cuda() for _ in range(2)]
+    alone = []
+    for q in qs:
+        sel = dsk.select_topk(comp, q, cfg.T)
+        att = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b)
+        torch.cuda.synchronize()
+        alone.append((sel.sel_slot.clone(), att.out.clone(), att.lse.clone()))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]          # default priority both
+    sels = [dsk.make_select_args(comp, q, cfg.T) for q in qs]
+    atts = [dsk.make_attn_args(q, case.K, case.V, s.sel_start, s.sel_len, s.sel_count, cfg.b) for q, s in zip(qs, sels)]
+    torch.cuda.synchronize()
+    for _ in range(50):
+        for i in (0, 1):
+            dsk.dsk_select_topk(sels[i].args, streams[i])
+            dsk.dsk_sparse_decode_attn(atts[i].args, streams[i])
+    for st in streams:
+        st.synchronize()
+    for i in (0, 1):
+        assert torch.equal(sels[i].sel_slot, alone[i][0])
+        assert torch.equal(atts[i].out, alone[i][1]) and torch.equal(atts[i].lse, alone[i][2])
