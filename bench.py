@@ -223,6 +223,17 @@ def main():
         g_sel.replay()
         stream.synchronize()
         select_us = event_ms(g_sel.replay, stream) * 1e3 / args.steps
+        # the gather's share of a step (the kernel right behind the selection whose lists it reads,
+        # and the dependency gap in front of it): (selection + gather) - (selection), both as graphs
+        # of the same length
+        g_sgat = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_sgat, stream=stream):
+            for i in range(args.steps):
+                dsk.dsk_select_topk(sels[i % nq].args, stream)
+                dsk.dsk_sparse_decode_attn(gathers[i % nq].args, stream)
+        g_sgat.replay()
+        stream.synchronize()
+        gather_in_step_us = event_ms(g_sgat.replay, stream) * 1e3 / args.steps - select_us
 
         # ---- extension (not in the paper): one selection per KV head, shared by its query heads ----
         shared = None
@@ -530,6 +541,8 @@ def main():
                      "achieved": round(attn_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(attn_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "bytes_per_launch": int(bytes_attn), "us_per_launch": round(gather_us, 3),
+                     "in_step_share_us": round(gather_in_step_us, 3),
+                     "in_step_share_frac": round(bytes_attn / (gather_in_step_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                      "attn_call_us": round(attn_us, 3),
                      "attn_call_frac": round(bytes_attn / (attn_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                      "step_frac": round(step_gbs / HBM_PEAK_GBS, 4)},
