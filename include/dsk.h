@@ -97,7 +97,8 @@ enum {
  *   {max(0,t-R+1)..t} and the discarded region {0..max(0,t-R)};
  *   s_t = mean(retained mass - alpha_imp * discarded mass).  Class means are mapped to
  *   [0,1] by (mean + alpha_imp) / (1 + alpha_imp), clamped, and rounded half-up to tenths.
- *   Classes without a sample keep the value already in class_weight_q.
+ *   Classes without a sample keep the value already in class_weight_q.  One call covers one
+ *   layer; samp_score_sum carries the mean over several layers from call to call.
  * Stage SEGMENT (Sec. 4.1, Dynamic Segmentation Procedure; Sec. 4.2 variable-to-fixed map):
  *   a candidate at position t offers the boundary e = t+1.  From s_c (0 at first):
  *   s_e = s_c + C; if s_e >= L the last chunk ends at L; else the offered boundary in
@@ -151,7 +152,13 @@ typedef struct dsk_compress_args {
   uint8_t* class_weight_q;     /* [dev] [B, n_class] weights in tenths, 0..10 (in/out) */
   float* class_mean;           /* [dev] [B, n_class] optional out: class mean score, NaN if
                                   the class had no sample */
-  float* samp_score;           /* [dev] [B, n_class, M] optional out: s_t per sample */
+  float* samp_score;           /* [dev] [B, n_class, M] optional out: s_t per sample (this layer) */
+  float* samp_score_sum;       /* [dev] [B, n_class, M] optional in/out.  The expectation of Alg. 1 also runs
+                                  over layers: call stage IMPORTANCE once per layer (its K and qwin) with this
+                                  array -- zeroed before the first layer -- and imp_layers = 1, 2, ...; each
+                                  call adds its s_t, and class_mean / class_weight_q are then taken from
+                                  sum / imp_layers, i.e. after the last layer from the mean over all layers. */
+  int32_t imp_layers;          /* layers in samp_score_sum including this call; read only with samp_score_sum */
 
   /* segmentation */
   int32_t C, delta;            /* base chunk size, max deviation: C >= 1, 0 <= delta < C,

@@ -118,6 +118,20 @@ def delimiter_importance(qwin: np.ndarray, K: np.ndarray, t: int, R: int, alpha_
     return acc / (Hq * W)
 
 
+def delimiter_importance_layers(qwins: Sequence[np.ndarray], Ks: Sequence[np.ndarray], t: int, R: int,
+                                alpha_imp: float, scale: float) -> float:
+    """Importance s_t with the expectation of Alg. 1 taken over several layers as well: layer l
+    has its own queries qwins[l] and keys Ks[l]; every (layer, head, window query) row weighs the
+    same, so with equally many heads per layer the result is the mean of the layers' values."""
+    n_rows = 0
+    acc = 0.0
+    for qwin, K in zip(qwins, Ks):
+        W, Hq, _ = qwin.shape
+        acc += delimiter_importance(qwin, K, t, R, alpha_imp, scale) * (Hq * W)
+        n_rows += Hq * W
+    return acc / n_rows
+
+
 def class_weights(s: np.ndarray, samp_pos: np.ndarray, alpha_imp: float,
                   prior_wq: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """Per-class weight in tenths from the sampled importance scores (Sec. 4.1:

@@ -57,6 +57,7 @@ class dsk_compress_args(C.Structure):
         ("M", C.c_int32), ("W", C.c_int32), ("R", C.c_int32),
         ("alpha_imp", C.c_float), ("imp_scale", C.c_float),
         ("samp_pos", _p), ("qwin", _p), ("class_weight_q", _p), ("class_mean", _p), ("samp_score", _p),
+        ("samp_score_sum", _p), ("imp_layers", C.c_int32),
         ("C", C.c_int32), ("delta", C.c_int32),
         ("C_per_seq", _p), ("delta_per_seq", _p),
         ("alpha_num", C.c_int32), ("alpha_den", C.c_int32),
@@ -360,7 +361,8 @@ def compress(*, cu_seqlens: torch.Tensor, max_seqlen: int, Hq: int, K: Optional[
              max_blocks_total: Optional[int] = None, block_start: Optional[torch.Tensor] = None,
              cu_blocks: Optional[torch.Tensor] = None, slot_base: Optional[torch.Tensor] = None,
              want_vsum: bool = False, Hkv: Optional[int] = None, total_tokens: Optional[int] = None,
-             summary_mode: int = DSK_SUMMARY_MINMAX, want_candidates: bool = True, stream=None,
+             summary_mode: int = DSK_SUMMARY_MINMAX, want_candidates: bool = True,
+             samp_score_sum: Optional[torch.Tensor] = None, imp_layers: int = 0, stream=None,
              check: bool = True) -> Compressed:
     """Allocate outputs / workspace with torch, fill dsk_compress_args and call dsk_compress.
 
@@ -412,6 +414,7 @@ def compress(*, cu_seqlens: torch.Tensor, max_seqlen: int, Hq: int, K: Optional[
     a.samp_pos, a.qwin = _ptr(samp_pos), _ptr(qwin)
     a.class_weight_q = _ptr(class_weight_q)
     a.class_mean, a.samp_score = _ptr(class_mean), _ptr(samp_score)
+    a.samp_score_sum, a.imp_layers = _ptr(samp_score_sum), imp_layers
     a.C, a.delta = C_, delta
     a.C_per_seq, a.delta_per_seq = _ptr(C_per_seq), _ptr(delta_per_seq)
     a.alpha_num, a.alpha_den, a.b = alpha_num, alpha_den, b

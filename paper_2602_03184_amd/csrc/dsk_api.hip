@@ -67,6 +67,7 @@ static dsk_status validate_compress(const dsk_compress_args* a) {
     if (a->M < 1 || a->M > kMaxSamplesPerClass || a->W < 1 || a->W > 64 || a->R < 1) return DSK_ERR_PARAM;
     if (!(a->alpha_imp >= 0.0f) || !(a->alpha_imp <= 1.0e6f) || !(a->imp_scale >= 0.0f)) return DSK_ERR_PARAM;
     if (!aligned16(a->qwin)) return DSK_ERR_ALIGN;
+    if (a->samp_score_sum != nullptr && a->imp_layers < 1) return DSK_ERR_PARAM;
   }
   if (st_seg) {
     if (a->class_weight_q == nullptr) return DSK_ERR_NULL;

@@ -226,7 +226,7 @@ __global__ __launch_bounds__(kImpThreads) void importance_kernel(
 __global__ __launch_bounds__(DSK_WAVE) void importance_finalize_kernel(
     const float* __restrict__ imp_part, const int32_t* __restrict__ samp_pos, int n_class, int M, int Hkv,
     int Hq, int W, float alpha, uint8_t* __restrict__ class_weight_q, float* __restrict__ class_mean,
-    float* __restrict__ samp_score) {
+    float* __restrict__ samp_score, float* __restrict__ samp_score_sum, int layers) {
   __shared__ float sm_score[kMaxSamplesPerClass];
   __shared__ int sm_have[kMaxSamplesPerClass];
   const int c = blockIdx.x;
@@ -241,9 +241,14 @@ __global__ __launch_bounds__(DSK_WAVE) void importance_finalize_kernel(
       for (int hk = 0; hk < Hkv; ++hk) st += imp_part[js * Hkv + hk];
       st /= (float)(Hq * W);
     }
+    if (samp_score) samp_score[js] = have ? st : __builtin_nanf("");
+    if (samp_score_sum != nullptr && have) {      // expectation over layers: this layer joins the running sum
+      const float tot = samp_score_sum[js] + st;
+      samp_score_sum[js] = tot;
+      st = tot / (float)layers;
+    }
     sm_score[m] = st;
     sm_have[m] = have ? 1 : 0;
-    if (samp_score) samp_score[js] = have ? st : __builtin_nanf("");
   }
   __syncthreads();
   if (m != 0) return;
@@ -284,7 +289,7 @@ hipError_t launch_importance(const dsk_compress_args& a, const CompressWs& ws, h
   if (err != hipSuccess) return err;
   importance_finalize_kernel<<<dim3((unsigned)a.n_class, (unsigned)a.B), dim3(DSK_WAVE), 0, st>>>(
       imp_part, a.samp_pos, a.n_class, a.M, a.Hkv, a.Hq, a.W, a.alpha_imp, a.class_weight_q, a.class_mean,
-      a.samp_score);
+      a.samp_score, a.samp_score_sum, a.imp_layers > 0 ? a.imp_layers : 1);
   return hipGetLastError();
 }
 

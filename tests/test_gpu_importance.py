@@ -110,3 +110,60 @@ def test_importance_feeds_segmentation_in_one_call():
     nb = len(bs) - 1
     assert int(comp.cu_blocks.cpu()[1]) == nb
     np.testing.assert_array_equal(comp.block_start.cpu().numpy()[: nb + 1], bs)
+
+
+def test_importance_mean_over_layers():
+    """Three layers (their own keys and window queries) through stage IMPORTANCE with the running
+    sum: after the last call the class means and weights are those of the oracle's expectation
+    over (layer, head, query); the per-layer scores of each call are still reported."""
+    import paper_2602_03184_amd as dsk
+    layers = [make_workload(2, with_kv=True, with_qwin=True, seqlens=[7000], M=4) for _ in range(1)]
+    wl = layers[0]
+    cfg = wl.cfg
+    # further layers: same tokens (the positions are a property of the text), other keys and queries
+    r = np.random.default_rng(77)
+    from workloads import f32_to_bf16_bits
+    Ks = [wl.K, wl.V, f32_to_bf16_bits(r.standard_normal(wl.K.shape, dtype=np.float32))]
+    qwins = [wl.qwin, f32_to_bf16_bits(r.standard_normal(wl.qwin.shape, dtype=np.float32)),
+             f32_to_bf16_bits(r.standard_normal(wl.qwin.shape, dtype=np.float32))]
+    prior = np.full((1, cfg.n_class), 3, np.uint8)
+    wq_dev = dev_u8(prior)
+    acc = torch.zeros(1, cfg.n_class, cfg.M, dtype=torch.float32, device="cuda")
+    comp = None
+    per_layer = []
+    for l in range(3):
+        comp = dsk.compress(
+            cu_seqlens=dev_i32(wl.cu_seqlens), max_seqlen=7000, Hq=cfg.Hq, K=dev_bf16(Ks[l]), V=None,
+            stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_IMPORTANCE,
+            token_ids=dev_i32(wl.token_ids), delim_ids=dev_i32(wl.delim_ids), n_class=cfg.n_class,
+            M=cfg.M, W=cfg.W, R=cfg.R, alpha_imp=cfg.alpha_imp, qwin=dev_bf16(qwins[l]), class_weight_q=wq_dev,
+            samp_score_sum=acc, imp_layers=l + 1)
+        torch.cuda.synchronize()
+        per_layer.append(comp.samp_score.cpu().numpy()[0].copy())
+    samp = comp.samp_pos.cpu().numpy()[0]
+    scale = 1.0 / math.sqrt(128.0)
+    Kf = [O.widen_bf16(k) for k in Ks]
+    s_or = np.zeros((cfg.n_class, cfg.M))
+    for c in range(cfg.n_class):
+        for m in range(cfg.M):
+            t = int(samp[c, m])
+            if t < 0:
+                continue
+            qs = [O.widen_bf16(qw[0, c * cfg.M + m]) for qw in qwins]
+            s_or[c, m] = O.delimiter_importance_layers(qs, Kf, t, cfg.R, cfg.alpha_imp, scale)
+            for l in range(3):           # each call still reports its own layer
+                one = O.delimiter_importance(qs[l], Kf[l], t, cfg.R, cfg.alpha_imp, scale)
+                assert abs(float(per_layer[l][c, m]) - one) <= SCORE_TOL
+            assert abs(float(acc[0, c, m]) / 3.0 - s_or[c, m]) <= SCORE_TOL
+    wq_or, mean_or, edge = O.class_weights(s_or, samp, cfg.alpha_imp, prior[0])
+    mean = comp.class_mean.cpu().numpy()[0]
+    wq = wq_dev.cpu().numpy()[0]
+    for c in range(cfg.n_class):
+        if math.isnan(mean_or[c]):
+            assert math.isnan(mean[c]) and wq[c] == prior[0, c]
+            continue
+        assert abs(float(mean[c]) - mean_or[c]) <= SCORE_TOL
+        if edge[c] > EDGE_TOL:
+            assert int(wq[c]) == int(wq_or[c])
+        else:
+            assert abs(int(wq[c]) - int(wq_or[c])) <= 1

@@ -80,6 +80,8 @@ MUTANTS = [
     ("mean_is_a_sum", "out[h, i] = acc / (e - s)", "out[h, i] = acc"),
     ("mean_skips_first_token", "for t in range(s, e):\n                acc += X[h, t]", "for t in range(s + 1, e):\n                acc += X[h, t]"),
     ("mean_score_gqa_mapping", "s[h, i] = float(np.dot(q[h], kmean[h // G, i]))", "s[h, i] = float(np.dot(q[h], kmean[h % Hkv, i]))"),
+    ("layers_unweighted_by_rows", "acc += delimiter_importance(qwin, K, t, R, alpha_imp, scale) * (Hq * W)", "acc += delimiter_importance(qwin, K, t, R, alpha_imp, scale) * W"),
+    ("layers_sum_not_mean", "    return acc / n_rows\n", "    return acc\n"),
     ("group_score_takes_min", "if score[hk * G + g, i] > best:", "if score[hk * G + g, i] < best:"),
     ("group_score_skips_last_head", "for g in range(1, G):\n                if score[hk * G + g, i]", "for g in range(1, G - 1):\n                if score[hk * G + g, i]"),
     ("group_score_interleaved_heads", "best = score[hk * G, i]\n            for g in range(1, G):\n                if score[hk * G + g, i] > best:\n                    best = score[hk * G + g, i]",

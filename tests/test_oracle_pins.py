@@ -133,6 +133,24 @@ def test_importance_concentrated_attention_hits_the_right_region():
         assert s == pytest.approx(want, abs=1e-9), (hot, s)
 
 
+def test_importance_over_layers_is_the_pooled_expectation():
+    """Two layers through the layer-wise function = one call on a model whose heads are the two
+    layers' heads side by side (every (layer, head, query) row weighs the same)."""
+    r = rng(5200)
+    W, Hq, Hkv, D, L, t, R = 3, 4, 2, 8, 40, 20, 6
+    q1, q2 = r.standard_normal((W, Hq, D)), r.standard_normal((W, Hq, D))
+    K1, K2 = r.standard_normal((Hkv, L, D)), r.standard_normal((Hkv, L, D))
+    got = O.delimiter_importance_layers([q1, q2], [K1, K2], t, R, 1.0, 0.3)
+    pooled = O.delimiter_importance(np.concatenate([q1, q2], axis=1), np.concatenate([K1, K2], axis=0), t, R, 1.0, 0.3)
+    assert abs(got - pooled) < 1e-14
+    one = O.delimiter_importance_layers([q1], [K1], t, R, 1.0, 0.3)
+    assert one == O.delimiter_importance(q1, K1, t, R, 1.0, 0.3)
+    # layers with different head counts are weighted by their rows
+    q3, K3 = r.standard_normal((W, 2, D)), r.standard_normal((1, L, D))
+    a, b = O.delimiter_importance(q1, K1, t, R, 1.0, 0.3), O.delimiter_importance(q3, K3, t, R, 1.0, 0.3)
+    assert abs(O.delimiter_importance_layers([q1, q3], [K1, K3], t, R, 1.0, 0.3) - (4 * a + 2 * b) / 6) < 1e-14
+
+
 def test_class_weights_table():
     samp = np.asarray([[5, 9], [7, -1], [-1, -1], [3, 4], [8, 9], [1, 2]])
     s = np.asarray([[1.0, 1.0], [0.12, 99.0], [0.0, 0.0], [-1.0, -1.0], [0.08, 0.08], [-0.3, 0.5]])
