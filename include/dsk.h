@@ -220,6 +220,9 @@ typedef struct dsk_select_args {
   const void* q;               /* [dev] bf16 [B, Hq, D] */
   int32_t b;                   /* slot length used by dsk_compress */
   int32_t budget;              /* token budget per sequence; k = budget / b >= 1 */
+  const int32_t* budget_per_seq; /* [dev] optional [B]: each sequence's own token budget (a budget that
+                                  follows the sequence length, say); sequence s takes
+                                  min(k, max(1, budget_per_seq[s] / b)) slots, the arrays keep k entries */
   uint32_t flags;              /* DSK_SELECT_* bits; with DSK_SELECT_SHARED_BY_KV_GROUP read Hkv for Hq in
                                   the shapes of the five outputs below */
   int32_t* sel_slot;           /* [dev] [B, Hq, k] global slot index, ascending; -1 padding */

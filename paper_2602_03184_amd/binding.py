@@ -77,7 +77,7 @@ class dsk_select_args(C.Structure):
         ("max_blocks_total", C.c_int32), ("max_blocks_used", C.c_int32), ("max_blocks_per_seq", C.c_int32),
         ("cu_blocks", _p), ("block_start", _p), ("slot_base", _p),
         ("ksum", _p), ("q", _p),
-        ("b", C.c_int32), ("budget", C.c_int32), ("flags", C.c_uint32),
+        ("b", C.c_int32), ("budget", C.c_int32), ("budget_per_seq", _p), ("flags", C.c_uint32),
         ("sel_slot", _p), ("sel_start", _p), ("sel_len", _p), ("sel_count", _p),
         ("scores", _p),
         ("workspace", _p), ("workspace_bytes", C.c_size_t),
@@ -466,7 +466,8 @@ class Selection:
 
 def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_scores: bool = False,
                      out: Optional[Selection] = None, max_blocks_used: int = 0,
-                     max_blocks_per_seq: int = 0, shared: bool = False) -> Selection:
+                     max_blocks_per_seq: int = 0, shared: bool = False,
+                     budget_per_seq: Optional[torch.Tensor] = None) -> Selection:
     """Fill dsk_select_args for query q (bf16 [B, Hq, D]); buffers are reused from `out`.
     `max_blocks_used`: optional host-known bound on the total block count (0 = capacity);
     `max_blocks_per_seq`: optional bound on the blocks of any one sequence;
@@ -486,6 +487,7 @@ def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_sco
     a.ksum, a.q = _ptr(comp.ksum), _ptr(q)
     a.b, a.budget = comp.b, budget
     a.flags = DSK_SELECT_SHARED_BY_KV_GROUP if shared else 0
+    a.budget_per_seq = _ptr(budget_per_seq)
     Hsel = comp.Hkv if shared else Hq
     if out is None:
         sel_slot = torch.empty(B, Hsel, max(k, 1), **i32)
@@ -501,14 +503,14 @@ def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_sco
     ws = _ws(dsk_select_workspace_bytes(a), dev) if out is None else out.keep[-1]
     a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
     return Selection(k=k, b=comp.b, sel_slot=sel_slot, sel_start=sel_start, sel_len=sel_len, sel_count=sel_count,
-                     scores=scores, args=a, keep=(comp, q, ws), shared=shared)
+                     scores=scores, args=a, keep=(comp, q, budget_per_seq, ws), shared=shared)
 
 
 def select_topk(comp: Compressed, q: torch.Tensor, budget: int, *, want_scores: bool = False, stream=None,
                 check: bool = True, max_blocks_used: int = 0, max_blocks_per_seq: int = 0,
-                shared: bool = False) -> Selection:
+                shared: bool = False, budget_per_seq: Optional[torch.Tensor] = None) -> Selection:
     sel = make_select_args(comp, q, budget, want_scores=want_scores, max_blocks_used=max_blocks_used,
-                           max_blocks_per_seq=max_blocks_per_seq, shared=shared)
+                           max_blocks_per_seq=max_blocks_per_seq, shared=shared, budget_per_seq=budget_per_seq)
     dsk_select_topk(sel.args, stream, check=check)
     return sel
 

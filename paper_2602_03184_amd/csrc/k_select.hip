@@ -134,7 +134,7 @@ template <int THREADS>
 __device__ __noinline__ void select_big(
     SelShared& sh, const float* __restrict__ scores, int stride, const int32_t* __restrict__ cu_blocks,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ slot_base, int cap, int Hq,
-    int b, int k, int per_thread, int32_t* __restrict__ sel_slot, int32_t* __restrict__ sel_start,
+    int b, int k, int kcap, int per_thread, int32_t* __restrict__ sel_slot, int32_t* __restrict__ sel_start,
     int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
   const int h = blockIdx.x;
   const int s = blockIdx.y;
@@ -142,7 +142,7 @@ __device__ __noinline__ void select_big(
   const int lane = tid & (DSK_WAVE - 1);
   const int wave = tid / DSK_WAVE;
   const int64_t sh_idx = (int64_t)s * Hq + h;
-  const int64_t obase = sh_idx * k;
+  const int64_t obase = sh_idx * kcap;   // k slots are taken, the arrays have kcap entries per head
   int blk0 = s == 0 ? 0 : cu_blocks[s];
   blk0 = blk0 < cap ? (blk0 > 0 ? blk0 : 0) : cap;       // same clamping as select_kernel
   int blk1 = cu_blocks[s + 1];
@@ -180,7 +180,7 @@ __device__ __noinline__ void select_big(
     nslots += sh.red_sum[wv];
   }
   const int count = nslots < k ? nslots : k;
-  write_padding(count, k, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
+  write_padding(count, kcap, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
   if (count <= 0) return;
 
   const bool take_all = nslots <= k;
@@ -271,8 +271,8 @@ template <int PT, int THREADS>
 __global__ __launch_bounds__(THREADS) void select_kernel(
     const float* __restrict__ scores, int stride, const int32_t* __restrict__ cu_blocks,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ slot_base, int cap, int Hq,
-    int b, int k, int32_t* __restrict__ sel_slot, int32_t* __restrict__ sel_start,
-    int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
+    int b, int kcap, const int32_t* __restrict__ budget_per_seq, int32_t* __restrict__ sel_slot,
+    int32_t* __restrict__ sel_start, int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
   static_assert(PT == 4 || PT == 8, "register tile");
   constexpr int NW = THREADS / DSK_WAVE;
   constexpr int kSelPerThread = PT;
@@ -284,7 +284,14 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
   const int lane = tid & (DSK_WAVE - 1);
   const int wave = tid / DSK_WAVE;
   const int64_t sh_idx = (int64_t)s * Hq + h;
-  const int64_t obase = sh_idx * k;
+  const int64_t obase = sh_idx * kcap;
+  // slots to take: kcap, or this sequence's own budget (clamped to 1..kcap slots)
+  int k = kcap;
+  if (budget_per_seq != nullptr) {
+    int ks = budget_per_seq[s] / b;
+    ks = ks < 1 ? 1 : ks;
+    k = ks < kcap ? ks : kcap;
+  }
   DSK_TS(0);
 
   // cu_blocks[0] is 0 by definition: sequence 0 can address its loads before anything arrives
@@ -324,11 +331,11 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
   if (blk1 > cap) blk1 = cap;
   const int n = blk1 - blk0;
   if (n <= 0) {
-    write_padding(0, k, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
+    write_padding(0, kcap, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
     return;
   }
   if (!sel_fits_tile(n, PT, THREADS)) {                            // too many blocks for the register tile
-    select_big<THREADS>(sh, scores, stride, cu_blocks, block_start, slot_base, cap, Hq, b, k, PT, sel_slot, sel_start,
+    select_big<THREADS>(sh, scores, stride, cu_blocks, block_start, slot_base, cap, Hq, b, k, kcap, PT, sel_slot, sel_start,
                sel_len, sel_count);
     return;
   }
@@ -371,7 +378,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
     nslots += sh.red_sum[wv];
   }
   const int count = nslots < k ? nslots : k;
-  write_padding(count, k, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
+  write_padding(count, kcap, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
   if (count <= 0) return;
   DSK_TS(2);
 
@@ -492,7 +499,7 @@ hipError_t launch_select(const dsk_select_args& a, const float* scores, int stri
   int bound = a.max_blocks_used > 0 ? a.max_blocks_used : a.max_blocks_total;
   if (a.max_blocks_per_seq > 0 && a.max_blocks_per_seq < bound) bound = a.max_blocks_per_seq;
 #define DSK_SEL_ARGS                                                                                          \
-  scores, stride, a.cu_blocks, a.block_start, a.slot_base, a.max_blocks_total, Hsel, a.b, k, a.sel_slot, a.sel_start, \
+  scores, stride, a.cu_blocks, a.block_start, a.slot_base, a.max_blocks_total, Hsel, a.b, k, a.budget_per_seq, a.sel_slot, a.sel_start, \
       a.sel_len, a.sel_count
   if (sel_fits_tile(bound, 4, 256)) select_kernel<4, 256><<<grid, dim3(256), 0, st>>>(DSK_SEL_ARGS);
   else if (sel_fits_tile(bound, 4, 512)) select_kernel<4, 512><<<grid, dim3(512), 0, st>>>(DSK_SEL_ARGS);

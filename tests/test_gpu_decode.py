@@ -481,3 +481,71 @@ def test_two_streams_with_their_own_workspaces_do_not_interfere():
     for i in (0, 1):
         assert torch.equal(sels[i].sel_slot, alone[i][0])
         assert torch.equal(atts[i].out, alone[i][1]) and torch.equal(atts[i].lse, alone[i][2])
+
+
+@pytest.mark.parametrize("shared", [False, True])
+def test_per_sequence_budgets(shared):
+    """budget_per_seq: every sequence takes its own number of slots (a budget that follows the
+    sequence length), clamped to 1..k; the arrays keep k entries per head."""
+    dsk = _dsk()
+    case = gpu_case(5, B=5, seqlens=[6000, 900, 0, 3000, 40], T=512, n_queries=1)
+    cfg, seg, wl = case.cfg, case.seg, case.wl
+    comp = case.compressed()
+    budgets = np.asarray([512, 100, 64, 7, 100000], dtype=np.int32)      # 7 < b -> one slot; 100000 -> k
+    want_k = [min(cfg.k, max(1, int(x) // cfg.b)) for x in budgets]
+    q_bits = wl.q[0]
+    q = dev_bf16(q_bits)
+    sel = dsk.select_topk(comp, q, cfg.T, want_scores=True, shared=shared, budget_per_seq=dev_i32(budgets))
+    att = dsk.sparse_decode_attn(q, case.K, case.V, sel.sel_start, sel.sel_len, sel.sel_count, cfg.b,
+                                 flags=dsk.DSK_ATTN_SHARED_SELECTION if shared else 0)
+    torch.cuda.synchronize()
+    sums = bf16_bits_of(comp.ksum)
+    g_slot, g_cnt, g_len = sel.sel_slot.cpu().numpy(), sel.sel_count.cpu().numpy(), sel.sel_len.cpu().numpy()
+    g_start = sel.sel_start.cpu().numpy()
+    out = att.out.cpu().numpy()
+    G = cfg.G
+    rows = [0, cfg.Hkv - 1] if shared else [0, 5, cfg.Hq - 1]
+    for s in range(cfg.B):
+        b0, b1 = int(seg.cu_blocks[s]), int(seg.cu_blocks[s + 1])
+        if b1 == b0:
+            assert (g_cnt[s] == 0).all()
+            continue
+        sb = seg.slot_base[b0: b1 + 1]
+        for row in rows:
+            heads = list(range(row * G, (row + 1) * G)) if shared else [row]
+            osc = _oracle_scores(case, sums[:, :, 0], sums[:, :, 1], q_bits, s, heads)
+            sc = O.group_block_scores(np.stack([osc[h] for h in heads]), G)[0] if shared else osc[row]
+            o_sel, tau = O.select_slots(sc, sb - sb[0], want_k[s])
+            cnt = int(g_cnt[s, row])
+            assert cnt == len(o_sel) == min(want_k[s], int(sb[-1] - sb[0]))
+            selection_check(g_slot[s, row, :cnt], o_sel + int(sb[0]), tau, sc, sb)
+            assert (g_slot[s, row, cnt:] == -1).all() and (g_len[s, row, cnt:] == 0).all()
+            toks = np.concatenate([np.arange(g_start[s, row, j], g_start[s, row, j] + g_len[s, row, j]) for j in range(cnt)])
+            for h in heads:
+                hk = h // G
+                o, _ = O.sparse_attention(O.widen_bf16(q_bits[s, h]), O.widen_bf16(wl.K[hk][toks]),
+                                          O.widen_bf16(wl.V[hk][toks]), np.arange(len(toks)), DEFAULT_SCALE)
+                assert rel_err(out[s, h], o) <= ATTN_TOL
+    # the same budget for every sequence through the array = the scalar budget
+    same = dsk.select_topk(comp, q, cfg.T, shared=shared, budget_per_seq=dev_i32(np.full(cfg.B, cfg.T)))
+    plain = dsk.select_topk(comp, q, cfg.T, shared=shared)
+    torch.cuda.synchronize()
+    assert torch.equal(same.sel_slot, plain.sel_slot) and torch.equal(same.sel_count, plain.sel_count)
+
+
+def test_per_sequence_budget_on_the_memory_resident_selection_path():
+    """A block-count hint that is too small sends a long sequence through the selection variant
+    that keeps its keys in memory; the per-sequence budget must act there as well."""
+    dsk = _dsk()
+    case = gpu_case(5, B=2, seqlens=[80000, 900], T=1024, n_queries=1)
+    cfg, seg = case.cfg, case.seg
+    assert int(seg.cu_blocks[1]) > 1024                         # more blocks than the smallest register tile
+    comp = case.compressed()
+    q = dev_bf16(case.wl.q[0])
+    budgets = dev_i32([160, 48])
+    small_tile = dsk.select_topk(comp, q, cfg.T, budget_per_seq=budgets, max_blocks_per_seq=32)
+    fitting = dsk.select_topk(comp, q, cfg.T, budget_per_seq=budgets)
+    torch.cuda.synchronize()
+    for name in ("sel_slot", "sel_start", "sel_len", "sel_count"):
+        assert torch.equal(getattr(small_tile, name), getattr(fitting, name)), name
+    assert (fitting.sel_count.cpu().numpy() == np.asarray([[160 // cfg.b] * cfg.Hq, [48 // cfg.b] * cfg.Hq])).all()
