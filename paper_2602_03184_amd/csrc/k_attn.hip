@@ -96,7 +96,7 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
   const int s = blockIdx.z;
   const int64_t sh = (int64_t)s * Hq + h;
   // row of the selection arrays: the head's own, or its KV head's when sel_div = Hq/Hkv heads share one
-  const int64_t sr = (int64_t)s * (Hq / sel_div) + h / sel_div;
+  const int64_t sr = sel_div == 1 ? sh : (int64_t)s * (Hq / sel_div) + h / sel_div;   // no division on the per-head path
   const int lane = threadIdx.x & (DSK_WAVE - 1);
   const int wave = threadIdx.x / DSK_WAVE;
   const int slot0 = chunk * kSlotsPerWg;
@@ -408,8 +408,12 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
     const int s = (int)(sh / Hq);
     count = cu_seqlens[s + 1] - cu_seqlens[s];
   } else {
-    const int s = (int)(sh / Hq), h = (int)(sh % Hq);
-    count = sel_count[(int64_t)s * (Hq / sel_div) + h / sel_div];
+    if (sel_div == 1) {
+      count = sel_count[sh];
+    } else {
+      const int s = (int)(sh / Hq), h = (int)(sh % Hq);
+      count = sel_count[(int64_t)s * (Hq / sel_div) + h / sel_div];
+    }
   }
   if (count > k) count = k;
   const int used = (count + slots_per_wg - 1) / slots_per_wg;
