@@ -80,7 +80,7 @@ struct FoldSlots {
 template <int NS, int SPW, int WAVES, bool STAGED = false>
 __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    int64_t kst, int64_t ksh, int64_t vst, int64_t vsh, int Hq, int G, int k, int b, int total_tokens,
+    int64_t kst, int64_t ksh, int64_t vst, int64_t vsh, int Hq, int G, uint32_t g_inv, int k, int b, int total_tokens,
     const int32_t* __restrict__ sel_start, const int32_t* __restrict__ sel_len,
     const int32_t* __restrict__ sel_count, int sel_div, float scale_log2, int nchunks,
     float2* __restrict__ part_ml, float* __restrict__ part_acc, float* __restrict__ out,
@@ -124,7 +124,8 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
 
   const int g = lane >> 4;
   const int c = lane & 15;
-  const int hk = h / G;
+  // h / G without a division: g_inv = ceil(2^32 / G) is exact for h < 2^16 (G = 1 has no 32-bit inverse)
+  const int hk = G == 1 ? h : (int)__umulhi((uint32_t)h, g_inv);
   const QRow qf = make_qrow(*reinterpret_cast<const uint4*>(q + sh * DSK_HEAD_DIM + c * 8));
   const uint16_t* Kh = K + (int64_t)hk * ksh + c * 8;
   const uint16_t* Vh = V + (int64_t)hk * vsh + c * 8;
@@ -483,6 +484,7 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   // heads that read one row of the selection arrays; the workgroups of a group's heads gather the
   // same rows (chunk c of every head runs on XCD c mod 8), so only one of them misses in L2
   const int sel_div = (a.flags & DSK_ATTN_SHARED_SELECTION) ? a.Hq / a.Hkv : 1;
+  const uint32_t g_inv = (uint32_t)((0x100000000ull + (uint64_t)(a.Hq / a.Hkv) - 1) / (uint64_t)(a.Hq / a.Hkv));   // unused for G = 1
   if (attn_shared_tiled(a)) {
     const int G = a.Hq / a.Hkv;
     const int GT = G == 2 ? 2 : 4;
@@ -506,7 +508,7 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
                              ws.slots_per_wg, a.out, static_cast<uint16_t*>(a.out_bf16), a.lse, st);
   }
 #define DSK_ATTN_ARGS                                                                                          \
-  q, K, V, a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, a.Hq / a.Hkv, a.k, a.b,     \
+  q, K, V, a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, a.Hq / a.Hkv, g_inv, a.k, a.b, \
       a.total_tokens, a.sel_start, a.sel_len, a.sel_count, sel_div, scale * kLog2e, ws.nchunks, part_ml, part_acc, a.out, \
       static_cast<uint16_t*>(a.out_bf16), a.lse
   // Slots of at most 32 rows: workgroups of 8 wavefronts, 2 slots each (16 slots per workgroup).
