@@ -10,11 +10,12 @@
 // accumulate per lane with no cross-lane traffic until the very end.  K rows are read straight
 // from HBM into the A-operand layout: the contraction index is permuted so that lane half
 // hf = lane/32 owns channels [64*hf, 64*hf+64) of its key row, i.e. eight contiguous 16-byte
-// loads; Q^T uses the same permutation, so the sum over channels is unchanged.  Those operand
-// loads (one key row per lane) are what bounds the kernel, so every key tile a wavefront fetches
-// is multiplied with the query windows of 3 sample slots, the next tile is requested before the
-// current one is used, and tiles that lie wholly in a sample's discarded region (nearly all of
-// them) take an unmasked path: one running sum feeds the total and the discarded mass.
+// loads; Q^T (staged in LDS once per workgroup) is read with the same permutation, so the sum
+// over channels is unchanged.  Those operand loads (one key row per lane) are what bounds the
+// kernel, so every key tile a wavefront fetches is multiplied with the query windows of 3 or 4
+// sample slots, the next tile is requested before the current one is used, and tiles that lie
+// wholly in a sample's discarded region (nearly all of them) take an unmasked path: one running
+// sum feeds the total and the discarded mass.
 #include "dsk_common.hpp"
 #include "dsk_internal.hpp"
 
@@ -41,12 +42,16 @@ __device__ __forceinline__ void stat_merge(RowStat& a, const RowStat& b) {
 }
 
 // Sample slots sharing the key tiles a wavefront loads (consecutive slots: mostly the same class,
-// neighbouring positions).  2, 3 and 4 were measured: 3 is the most that keeps 2 wavefronts per
-// SIMD (256 VGPRs with the prefetched tile); 4 drops to one and is slower.
-constexpr int kImpSamples = 3;
+// neighbouring positions).  Their Q^T operands live in LDS (rows of 128 channels padded to 136 so
+// that the 16-byte reads of 16 consecutive query rows cover all banks), which leaves the registers
+// to the key tiles and the statistics.
+// 4 slots per group with 8 wavefronts when the launch is small (one sequence: 32 groups x 8 KV heads
+// fill the 256 CUs in one round, 90 instead of 118 us at 128 windows), 3 with 4 wavefronts when
+// there are many workgroups anyway (4 and 6 were measured there: 617 and 551 against 554 us).
+constexpr int kImpQRow = DSK_HEAD_DIM + 8;   // bf16 elements per query row in LDS
 
 // grid: (group of kImpSamples sample slots, kv head, sequence)
-template <int kImpThreads>
+template <int kImpThreads, int kImpSamples>
 __global__ __launch_bounds__(kImpThreads) void importance_kernel(
     const uint16_t* __restrict__ K, int64_t kst, int64_t ksh, const uint16_t* __restrict__ qwin,
     const int32_t* __restrict__ samp_pos, const int32_t* __restrict__ cu_seqlens, int n_samp, int W, int R,
@@ -54,6 +59,7 @@ __global__ __launch_bounds__(kImpThreads) void importance_kernel(
   constexpr int kImpWaves = kImpThreads / DSK_WAVE;
   __shared__ RowStat sm_stat[kImpSamples][kImpWaves][32];
   __shared__ float sm_val[kImpSamples][32];
+  __shared__ __attribute__((aligned(16))) uint16_t sm_q[kImpSamples][32][kImpQRow];
   const int hk = blockIdx.y;
   const int s = blockIdx.z;
   const int lane = threadIdx.x & (DSK_WAVE - 1);
@@ -89,28 +95,33 @@ __global__ __launch_bounds__(kImpThreads) void importance_kernel(
   for (int p = 0; p < kImpSamples; ++p) total[p] = 0.0f;
 
   for (int row0 = 0; row0 < rows; row0 += 32) {
-    // Q^T operands: lane (col, hf) holds channels [64*hf, 64*hf+64) of query row row0+col
+    // Q^T operands of the group's samples -> LDS: row r of sample p is query row row0 + r (window
+    // position w = row / G, head g = row % G), zero for rows or samples that do not exist
+    for (int idx = threadIdx.x; idx < kImpSamples * 32 * 16; idx += kImpThreads) {
+      const int p = idx / (32 * 16);
+      const int r = (idx / 16) & 31;
+      const int c16 = idx & 15;
+      const int rowq = row0 + r;
+      uint4 raw = make_uint4(0, 0, 0, 0);
+      if (rowq < rows && have[p]) {
+        const int wq_ = rowq / G, gq_ = rowq % G;
+        raw = *reinterpret_cast<const uint4*>(
+            qwin + ((((int64_t)s * n_samp + jn[p]) * W + wq_) * Hq + hk * G + gq_) * DSK_HEAD_DIM + c16 * 8);
+      }
+      *reinterpret_cast<uint4*>(&sm_q[p][r][c16 * 8]) = raw;
+    }
     const int row = row0 + col;
     const bool row_ok = row < rows;
     const int w = row_ok ? row / G : 0;
-    const int g = row_ok ? row % G : 0;
-    bf16x8_t qv[kImpSamples][8];
     int qpos[kImpSamples];
     RowStat st[kImpSamples];
 #pragma unroll
     for (int p = 0; p < kImpSamples; ++p) {
       qpos[p] = t[p] + 1 + w;               // position of this query; attends keys 0..qpos
-      const int jq = have[p] ? jn[p] : 0;   // absent sample: any readable rows, zeroed below
-      const uint16_t* qp = qwin + ((((int64_t)s * n_samp + jq) * W + w) * Hq + hk * G + g) * DSK_HEAD_DIM + hf * 64;
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        uint4 raw = *reinterpret_cast<const uint4*>(qp + u * 8);
-        if (!row_ok || !have[p]) raw = make_uint4(0, 0, 0, 0);
-        qv[p][u] = *reinterpret_cast<bf16x8_t*>(&raw);
-      }
       st[p].m = -__builtin_inff();
       st[p].zt = st[p].zo = st[p].zd = 0.0f;
     }
+    __syncthreads();
     // the rows of the wave's next tile are requested before the current tile is multiplied
     uint4 knext[8];
     {
@@ -139,8 +150,11 @@ __global__ __launch_bounds__(kImpThreads) void importance_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8_t*>(&kraw[u]), qv[p][u], acc, 0, 0, 0);
+        for (int u = 0; u < 8; ++u) {
+          // lane (col, hf) supplies channels [64*hf + 8u, +8) of query row col
+          const bf16x8_t qb = *reinterpret_cast<const bf16x8_t*>(&sm_q[p][col][hf * 64 + u * 8]);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8_t*>(&kraw[u]), qb, acc, 0, 0, 0);
+        }
         // acc[r] = logit of key k0 + 8*(r/4) + 4*hf + r%4 against query row `col`
         if (k0 + 31 <= d_hi[p]) {
           // the whole tile lies in the discarded region (hence before every query of the window
@@ -272,19 +286,19 @@ hipError_t launch_importance(const dsk_compress_args& a, const CompressWs& ws, h
   float* imp_part = reinterpret_cast<float*>(static_cast<unsigned char*>(a.workspace) + ws.imp_part);
   const int n_samp = a.n_class * a.M;
   const float scale = a.imp_scale != 0.0f ? a.imp_scale : 0.08838834764831845f;   // 128^-1/2
-  const dim3 grid((unsigned)((n_samp + kImpSamples - 1) / kImpSamples), (unsigned)a.Hkv, (unsigned)a.B);
-  // few workgroups (one sequence): 8 wavefronts split the key tiles of the longest samples and
-  // shorten the serial chain; many workgroups: 4 wavefronts keep more of them resident
-  if ((int64_t)grid.x * grid.y * grid.z < 1024)
-    importance_kernel<512><<<grid, dim3(512), 0, st>>>(
-        static_cast<const uint16_t*>(a.K), a.k_stride_tok, a.k_stride_head, static_cast<const uint16_t*>(a.qwin),
-        a.samp_pos, a.cu_seqlens, n_samp, a.W, a.R, a.Hq, a.Hq / a.Hkv, a.alpha_imp, scale * kImpLog2e, imp_part,
-        a.Hkv);
-  else
-    importance_kernel<256><<<grid, dim3(256), 0, st>>>(
-        static_cast<const uint16_t*>(a.K), a.k_stride_tok, a.k_stride_head, static_cast<const uint16_t*>(a.qwin),
-        a.samp_pos, a.cu_seqlens, n_samp, a.W, a.R, a.Hq, a.Hq / a.Hkv, a.alpha_imp, scale * kImpLog2e, imp_part,
-        a.Hkv);
+  const int64_t heads_seqs = (int64_t)a.Hkv * a.B;
+#define DSK_IMP_ARGS                                                                                          \
+  static_cast<const uint16_t*>(a.K), a.k_stride_tok, a.k_stride_head, static_cast<const uint16_t*>(a.qwin),    \
+      a.samp_pos, a.cu_seqlens, n_samp, a.W, a.R, a.Hq, a.Hq / a.Hkv, a.alpha_imp, scale * kImpLog2e, imp_part, \
+      a.Hkv
+  if ((int64_t)((n_samp + 3) / 4) * heads_seqs < 1024) {
+    const dim3 grid((unsigned)((n_samp + 3) / 4), (unsigned)a.Hkv, (unsigned)a.B);
+    importance_kernel<512, 4><<<grid, dim3(512), 0, st>>>(DSK_IMP_ARGS);
+  } else {
+    const dim3 grid((unsigned)((n_samp + 2) / 3), (unsigned)a.Hkv, (unsigned)a.B);
+    importance_kernel<256, 3><<<grid, dim3(256), 0, st>>>(DSK_IMP_ARGS);
+  }
+#undef DSK_IMP_ARGS
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   importance_finalize_kernel<<<dim3((unsigned)a.n_class, (unsigned)a.B), dim3(DSK_WAVE), 0, st>>>(
