@@ -36,7 +36,7 @@ __global__ __launch_bounds__(kCandThreads) void cand_classify_kernel(
     int n_class, uint8_t* __restrict__ cls_at, int32_t* __restrict__ tile_count) {
   __shared__ int32_t ids[DSK_MAX_CLASSES];
   __shared__ int wave_tot[kCandWaves];
-  if (threadIdx.x < n_class) ids[threadIdx.x] = delim_ids[threadIdx.x];
+  if ((int)threadIdx.x < n_class) ids[threadIdx.x] = delim_ids[threadIdx.x];
   __syncthreads();
   const int t0 = blockIdx.x * kCandTile + threadIdx.x * 4;
   int cnt = 0;
