@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # counter reads for the plain 256 MiB device copy of --calib-copy-mib (FETCH_SIZE reads half the
 # copied bytes on this part -> x2; WRITE_SIZE reads them exactly -> x1).  Keyed by workload.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg3_llama3_8b_128k": {"attn_kernel": int(18888.2 * 1024 * 2.000 + 136.0 * 1024 * 1.000)},
+    "cfg3_llama3_8b_128k": {"attn_kernel": int(18783.3 * 1024 * 2.000 + 136.0 * 1024 * 1.000)},
 }
 
 
@@ -198,8 +198,17 @@ def main():
         eager_ms = event_ms(lambda: [step(i) for i in range(args.steps)], stream)
         eager_us = eager_ms * 1e3 / args.steps
 
-        # ---- dominant kernel: the attention gather (attn_kernel) alone, HIP events on its stream ---
-        gathers = [dsk.make_attn_args(queries[i], K, V, sels[0].sel_start, sels[0].sel_len, sels[0].sel_count,
+        # ---- dominant kernel: the attention gather (attn_kernel) alone, HIP events on its stream.
+        #      Every query keeps the selection made for it (its own span lists), so that consecutive
+        #      launches gather different rows, as consecutive steps do. -----------------------------
+        own = [dsk.make_select_args(comp, queries[i], cfg.T, max_blocks_used=nblk, max_blocks_per_seq=nblk_seq)
+               for i in range(nq)]
+        for i in range(nq):
+            dsk.dsk_select_topk(own[i].args, stream)
+        stream.synchronize()
+        own_tokens = float(np.mean([int(o.sel_len.sum().item()) for o in own]))
+        assert own_tokens == mean_sel_tokens
+        gathers = [dsk.make_attn_args(queries[i], K, V, own[i].sel_start, own[i].sel_len, own[i].sel_count,
                                       cfg.b, out=atts[0], flags=dsk.DSK_ATTN_PARTIALS_ONLY) for i in range(nq)]
         g_gather = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g_gather, stream=stream):
@@ -208,11 +217,24 @@ def main():
         g_gather.replay()
         stream.synchronize()
         gather_us = event_ms(g_gather.replay, stream) * 1e3 / args.steps
+        # the same launches on ONE selection (the rows of every launch then sit in the memory-side
+        # cache): what the kernel does when HBM is out of the way
+        same = [dsk.make_attn_args(queries[i], K, V, own[0].sel_start, own[0].sel_len, own[0].sel_count,
+                                   cfg.b, out=atts[0], flags=dsk.DSK_ATTN_PARTIALS_ONLY) for i in range(nq)]
+        g_same = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g_same, stream=stream):
+            for i in range(args.steps):
+                dsk.dsk_sparse_decode_attn(same[i % nq].args, stream)
+        g_same.replay()
+        stream.synchronize()
+        gather_same_rows_us = event_ms(g_same.replay, stream) * 1e3 / args.steps
         # the whole attention call (gather + merge of the partials) and the whole selection call
+        own_att = [dsk.make_attn_args(queries[i], K, V, own[i].sel_start, own[i].sel_len, own[i].sel_count, cfg.b,
+                                      out=atts[0]) for i in range(nq)]
         g_attn = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g_attn, stream=stream):
             for i in range(args.steps):
-                dsk.dsk_sparse_decode_attn(atts[i % nq].args, stream)
+                dsk.dsk_sparse_decode_attn(own_att[i % nq].args, stream)
         g_attn.replay()
         stream.synchronize()
         attn_us = event_ms(g_attn.replay, stream) * 1e3 / args.steps
@@ -541,6 +563,8 @@ def main():
                      "achieved": round(attn_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(attn_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "bytes_per_launch": int(bytes_attn), "us_per_launch": round(gather_us, 3),
+                     "same_rows_us_per_launch": round(gather_same_rows_us, 3),
+                     "same_rows_frac": round(bytes_attn / (gather_same_rows_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                      "in_step_share_us": round(gather_in_step_us, 3),
                      "in_step_share_frac": round(bytes_attn / (gather_in_step_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                      "attn_call_us": round(attn_us, 3),
