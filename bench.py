@@ -271,13 +271,16 @@ def main():
             for i in range(1, nq):
                 satt.append(dsk.make_attn_args(queries[i], K, V, ssel[0].sel_start, ssel[0].sel_len, ssel[0].sel_count,
                                                cfg.b, out=satt[0], flags=sflag))
-            sgat = [dsk.make_attn_args(queries[i], K, V, ssel[0].sel_start, ssel[0].sel_len, ssel[0].sel_count, cfg.b,
-                                       out=satt[0], flags=sflag | dsk.DSK_ATTN_PARTIALS_ONLY) for i in range(nq)]
+            # gather alone: every query on its own shared selection (different rows per launch)
+            sown = [dsk.make_select_args(comp, queries[i], cfg.T, max_blocks_used=nblk, max_blocks_per_seq=nblk_seq,
+                                         shared=True) for i in range(nq)]
             stok = []
             for i in range(nq):
-                dsk.dsk_select_topk(ssel[i].args, stream)
+                dsk.dsk_select_topk(sown[i].args, stream)
                 stream.synchronize()
-                stok.append(int(ssel[0].sel_len.sum().item()))
+                stok.append(int(sown[i].sel_len.sum().item()))
+            sgat = [dsk.make_attn_args(queries[i], K, V, sown[i].sel_start, sown[i].sel_len, sown[i].sel_count, cfg.b,
+                                       out=satt[0], flags=sflag | dsk.DSK_ATTN_PARTIALS_ONLY) for i in range(nq)]
             g_sh = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g_sh, stream=stream):
                 for i in range(args.steps):
