@@ -58,6 +58,24 @@ def parse():
     return ap.parse_args()
 
 
+def stream_read_probe():
+    """The streaming-read yardstick of the bench (its own shared object, not part of libdsk)."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2602_03184_amd", "libdsk_benchaid.so")
+    if not os.path.exists(path):
+        raise RuntimeError("libdsk_benchaid.so is not built: run `python paper_2602_03184_amd/build.py`")
+    lib = ctypes.CDLL(path)
+    lib.dsk_benchaid_stream_read.restype = ctypes.c_int
+    lib.dsk_benchaid_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+
+    def read_once(buf, stream, sink):
+        rc = lib.dsk_benchaid_stream_read(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(),
+                                          stream.cuda_stream or None)
+        if rc != 0:
+            raise RuntimeError("dsk_benchaid_stream_read failed (%d)" % rc)
+    return read_once
+
+
 def event_ms(fn, stream):
     import torch
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -325,10 +343,11 @@ def main():
             big = torch.empty(args.stream_read_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
             sink = torch.zeros(1, dtype=torch.int32, device=dev)
             stream.wait_stream(torch.cuda.current_stream())
+            read_once = stream_read_probe()
             for _ in range(2):
-                dsk.dsk_stream_read_probe(big, stream, sink)
+                read_once(big, stream, sink)
             reps = 10
-            ms = event_ms(lambda: [dsk.dsk_stream_read_probe(big, stream, sink) for _ in range(reps)], stream) / reps
+            ms = event_ms(lambda: [read_once(big, stream, sink) for _ in range(reps)], stream) / reps
             stream_read_gbs = big.numel() / (ms * 1e-3) / 1e9
             del big
             torch.cuda.empty_cache()

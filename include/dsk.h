@@ -9,14 +9,13 @@
  *                           block-to-slot mapped scores (Sec. 4.2; App. B.2 Step 1).
  *   dsk_sparse_decode_attn  per decode step: attention over the K/V of the selected slots
  *                           (App. B.2 Steps 2-3).
- * and four more sit beside it:
+ * and three more sit beside it:
  *   dsk_reuse_update        step-to-step reuse of the gathered K/V in per-head resident buffers of
  *                           fixed-size slots (App. B.2, "KVCache Reuse with V2F").
  *   dsk_append_tokens       incremental update of the block table and summaries while decoding
  *                           (Sec. 4.1, "Incremental Update during Decoding"), one sequence per call.
  *   dsk_dense_decode_attn   full attention over the whole cache: the full-KV baseline the method
  *                           is compared with (Sec. 5, GPU Inference analysis).
- *   dsk_stream_read_probe   a measurement aid (streaming read of a buffer), no part of the method.
  *
  * Conventions that hold for every call
  *   - Pointers marked [dev] are device (HBM) addresses, [host] are host addresses.
@@ -51,7 +50,7 @@
 extern "C" {
 #endif
 
-#define DSK_ABI_VERSION 1u
+#define DSK_ABI_VERSION 2u
 #define DSK_HEAD_DIM 128
 #define DSK_MAX_CLASSES 64
 
@@ -63,8 +62,10 @@ typedef enum dsk_status {
   DSK_ERR_ALIGN = -4,     /* K/V/q/summary/workspace pointer or stride not 16-byte aligned */
   DSK_ERR_WORKSPACE = -5, /* workspace missing or smaller than *_workspace_bytes() */
   DSK_ERR_CAPACITY = -6,  /* more blocks/candidates produced than the outputs can hold */
-  DSK_ERR_LAUNCH = -7,    /* the HIP runtime refused a launch */
-  DSK_ERR_VERSION = -8    /* struct_size does not match this library */
+  DSK_ERR_ORDER = -7,     /* caller-provided candidate positions of a sequence are not strictly ascending
+                             (found on the device, reported through dev_status) */
+  DSK_ERR_LAUNCH = -8,    /* the HIP runtime refused a launch */
+  DSK_ERR_VERSION = -9    /* struct_size does not match this library */
 } dsk_status;
 
 /* Stages of dsk_compress (bit mask).  A stage that is not run takes its inputs from the
@@ -173,6 +174,8 @@ typedef struct dsk_compress_args {
   int32_t* cu_blocks;          /* [dev] [B+1] block range of each sequence */
   int32_t* slot_base;          /* [dev] [max_blocks_total+4] (entries 0..max_blocks_total used;
                                   dsk_select_topk reads it in 16-byte vectors) */
+  int32_t* cu_slots;           /* [dev] optional out of SEGMENT, [B+1]: slot range of each sequence,
+                                  cu_slots[s] = slot_base[cu_blocks[s]], cu_slots[B] = all slots */
 
   /* summaries: [Hkv, max_blocks_total, 2, D] bf16; [.., 0, :] = min, [.., 1, :] = max
      (DSK_SUMMARY_MEAN: both rows hold the mean) */
@@ -412,7 +415,7 @@ typedef struct dsk_reuse_args {
 uint32_t dsk_version(void);
 
 /* Static, human-readable text for a status code. */
-const char* dsk_strerror(int32_t status);
+const char* dsk_strerror(dsk_status status);
 
 /* Upper bound on the number of blocks DD-Select can emit for a batch of B sequences with
  * total_tokens tokens when every non-final chunk has at least min_chunk = C - delta tokens
@@ -444,18 +447,11 @@ typedef struct dsk_attn_partials {
 } dsk_attn_partials;
 dsk_status dsk_attn_partials_layout(const dsk_attn_args* args, dsk_attn_partials* layout);
 
-/* Measurement aid, no part of the method: reads the `bytes` (rounded down to a multiple of 16)
- * at device pointer `buf` (16-byte aligned) exactly once with coalesced 16-byte loads on
- * `stream`.  Timed by the caller, it gives the streaming-read rate of the device, the practical
- * ceiling next to which the HBM-bound kernels here are reported.  `sink` is a device word (or
- * NULL) that the kernel may write; nothing else is modified.  Errors: DSK_ERR_NULL (buf),
- * DSK_ERR_ALIGN, DSK_ERR_LAUNCH. */
-dsk_status dsk_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
-
 dsk_status dsk_compress(const dsk_compress_args* args, void* stream);
 dsk_status dsk_select_topk(const dsk_select_args* args, void* stream);
 dsk_status dsk_sparse_decode_attn(const dsk_attn_args* args, void* stream);
 dsk_status dsk_dense_decode_attn(const dsk_dense_attn_args* args, void* stream);
+
 dsk_status dsk_append_tokens(const dsk_append_args* args, void* stream);
 dsk_status dsk_reuse_update(const dsk_reuse_args* args, void* stream);
 

@@ -27,7 +27,7 @@ _lib = C.CDLL(LIB_PATH)
 # ---- status codes / stages (mirror include/dsk.h) ------------------------------------------
 DSK_OK = 0
 DSK_ERR_NULL, DSK_ERR_SHAPE, DSK_ERR_PARAM, DSK_ERR_ALIGN = -1, -2, -3, -4
-DSK_ERR_WORKSPACE, DSK_ERR_CAPACITY, DSK_ERR_LAUNCH, DSK_ERR_VERSION = -5, -6, -7, -8
+DSK_ERR_WORKSPACE, DSK_ERR_CAPACITY, DSK_ERR_ORDER, DSK_ERR_LAUNCH, DSK_ERR_VERSION = -5, -6, -7, -8, -9
 DSK_STAGE_CANDIDATES, DSK_STAGE_IMPORTANCE, DSK_STAGE_SEGMENT, DSK_STAGE_SUMMARIES = 1, 2, 4, 8
 DSK_STAGE_ALL = 15
 DSK_HEAD_DIM = 128
@@ -62,7 +62,7 @@ class dsk_compress_args(C.Structure):
         ("C_per_seq", _p), ("delta_per_seq", _p),
         ("alpha_num", C.c_int32), ("alpha_den", C.c_int32),
         ("b", C.c_int32), ("max_blocks_total", C.c_int32),
-        ("block_start", _p), ("cu_blocks", _p), ("slot_base", _p),
+        ("block_start", _p), ("cu_blocks", _p), ("slot_base", _p), ("cu_slots", _p),
         ("ksum", _p), ("vsum", _p),
         ("summary_mode", C.c_int32),
         ("dev_status", _p),
@@ -181,8 +181,6 @@ _lib.dsk_append_tokens.restype = C.c_int32
 _lib.dsk_append_tokens.argtypes = [C.POINTER(dsk_append_args), _p]
 _lib.dsk_reuse_update.restype = C.c_int32
 _lib.dsk_reuse_update.argtypes = [C.POINTER(dsk_reuse_args), _p]
-_lib.dsk_stream_read_probe.restype = C.c_int32
-_lib.dsk_stream_read_probe.argtypes = [_p, C.c_size_t, _p, _p]
 _lib.dsk_compress.restype = C.c_int32
 _lib.dsk_compress.argtypes = [C.POINTER(dsk_compress_args), _p]
 _lib.dsk_select_topk.restype = C.c_int32
@@ -255,14 +253,6 @@ def dsk_reuse_update(args: dsk_reuse_args, stream=None, check: bool = True) -> i
     return st
 
 
-def dsk_stream_read_probe(buf: torch.Tensor, stream=None, sink: Optional[torch.Tensor] = None) -> None:
-    """Enqueue one streaming read of the whole tensor (a measurement aid; see include/dsk.h)."""
-    status = int(_lib.dsk_stream_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink),
-                                            _stream_handle(stream)))
-    if status != DSK_OK:
-        raise DskError(status, "dsk_stream_read_probe")
-
-
 def dsk_attn_partials_layout(args: dsk_attn_args) -> dsk_attn_partials:
     lay = dsk_attn_partials()
     status = int(_lib.dsk_attn_partials_layout(C.byref(args), C.byref(lay)))
@@ -332,6 +322,7 @@ class Compressed:
     block_start: torch.Tensor
     cu_blocks: torch.Tensor
     slot_base: torch.Tensor
+    cu_slots: Optional[torch.Tensor]
     ksum: Optional[torch.Tensor]
     vsum: Optional[torch.Tensor]
     cand_pos: Optional[torch.Tensor]
@@ -360,7 +351,7 @@ def compress(*, cu_seqlens: torch.Tensor, max_seqlen: int, Hq: int, K: Optional[
              alpha_num: int = 5, alpha_den: int = 10, b: int = 16,
              max_blocks_total: Optional[int] = None, block_start: Optional[torch.Tensor] = None,
              cu_blocks: Optional[torch.Tensor] = None, slot_base: Optional[torch.Tensor] = None,
-             want_vsum: bool = False, Hkv: Optional[int] = None, total_tokens: Optional[int] = None,
+             cu_slots: Optional[torch.Tensor] = None, want_vsum: bool = False, Hkv: Optional[int] = None, total_tokens: Optional[int] = None,
              summary_mode: int = DSK_SUMMARY_MINMAX, want_candidates: bool = True,
              samp_score_sum: Optional[torch.Tensor] = None, imp_layers: int = 0, stream=None,
              check: bool = True) -> Compressed:
@@ -428,8 +419,10 @@ def compress(*, cu_seqlens: torch.Tensor, max_seqlen: int, Hq: int, K: Optional[
         block_start = torch.zeros(max_blocks_total + 4, **i32)  # both tables are read in 16-byte vectors
         slot_base = torch.zeros(max_blocks_total + 4, **i32)   # read in 16-byte vectors by dsk_select_topk
         cu_blocks = torch.empty(B + 1, **i32)
+        cu_slots = torch.empty(B + 1, **i32)
     a.max_blocks_total = max_blocks_total
     a.block_start, a.cu_blocks, a.slot_base = _ptr(block_start), _ptr(cu_blocks), _ptr(slot_base)
+    a.cu_slots = _ptr(cu_slots)
     ksum = vsum = None
     if stages & DSK_STAGE_SUMMARIES:
         ksum = torch.empty(Hkv, max_blocks_total, 2, DSK_HEAD_DIM, dtype=torch.bfloat16, device=dev)
@@ -445,7 +438,7 @@ def compress(*, cu_seqlens: torch.Tensor, max_seqlen: int, Hq: int, K: Optional[
     dsk_compress(a, stream, check=check)
     return Compressed(B=B, Hq=Hq, Hkv=Hkv, b=b, total_tokens=total_tokens, max_blocks_total=max_blocks_total,
                       cu_seqlens=cu_seqlens, block_start=block_start, cu_blocks=cu_blocks, slot_base=slot_base,
-                      ksum=ksum, vsum=vsum, cand_pos=cand_pos, cand_class=cand_class, cand_cu=cand_cu,
+                      cu_slots=cu_slots, ksum=ksum, vsum=vsum, cand_pos=cand_pos, cand_class=cand_class, cand_cu=cand_cu,
                       samp_pos=samp_pos, class_weight_q=class_weight_q, class_mean=class_mean,
                       samp_score=samp_score, dev_status=dev_status, args=a, keep=keep)
 

@@ -3,6 +3,8 @@
     python paper_2602_03184_amd/build.py
 
 Objects go to paper_2602_03184_amd/_build/, the library to paper_2602_03184_amd/libdsk.so.
+Beside it: the host-only C example (dsk_example) and libdsk_benchaid.so, a streaming-read
+yardstick that only bench.py loads (it is not part of the library).
 """
 from __future__ import annotations
 
@@ -18,6 +20,8 @@ BUILD_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libdsk.so")
 EXAMPLE_SRC = os.path.join(PKG_DIR, "examples", "dsk_example.cpp")
 EXAMPLE_PATH = os.path.join(PKG_DIR, "dsk_example")
+BENCHAID_SRC = os.path.join(PKG_DIR, "benchaid", "stream_read_probe.hip")
+BENCHAID_PATH = os.path.join(PKG_DIR, "libdsk_benchaid.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",
@@ -45,7 +49,7 @@ def sources():
 
 def _compile(src: str) -> str:
     obj = os.path.join(BUILD_DIR, os.path.basename(src)[:-4] + ".o")
-    cmd = [_hipcc(), *HIPCC_FLAGS, *os.environ.get("DSK_EXTRA_HIPCC_FLAGS", "").split(), "-c", src, "-o", obj]
+    cmd = [_hipcc(), *HIPCC_FLAGS, "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed on %s:\n%s\n%s" % (src, r.stdout, r.stderr))
@@ -64,7 +68,17 @@ def build_library(jobs: int = 8) -> str:
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
     build_example()
+    build_benchaid()
     return LIB_PATH
+
+
+def build_benchaid() -> str:
+    """The benchmark's streaming-read yardstick: one source file, its own shared object."""
+    cmd = [_hipcc(), *HIPCC_FLAGS, "-shared", BENCHAID_SRC, "-o", BENCHAID_PATH]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("building the bench aid failed:\n%s\n%s" % (r.stdout, r.stderr))
+    return BENCHAID_PATH
 
 
 def build_example() -> str:

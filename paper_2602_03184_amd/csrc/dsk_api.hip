@@ -127,7 +127,8 @@ static dsk_status validate_select(const dsk_select_args* a) {
   return DSK_OK;
 }
 
-static dsk_status validate_attn(const dsk_attn_args* a) {
+// own_workspace: the partials go to the library's static scratch array, args->workspace is not used
+static dsk_status validate_attn(const dsk_attn_args* a, bool own_workspace = false) {
   if (a == nullptr) return DSK_ERR_NULL;
   if (a->struct_size != sizeof(dsk_attn_args)) return DSK_ERR_VERSION;
   if (!geometry_ok(a->B, a->Hq, a->Hkv, a->D)) return DSK_ERR_SHAPE;
@@ -143,6 +144,7 @@ static dsk_status validate_attn(const dsk_attn_args* a) {
   if (!aligned16(a->q) || !aligned16(a->K) || !aligned16(a->V) || a->k_stride_tok % 8 || a->k_stride_head % 8 ||
       a->v_stride_tok % 8 || a->v_stride_head % 8)
     return DSK_ERR_ALIGN;
+  if (own_workspace) return DSK_OK;
   if (a->workspace == nullptr || a->workspace_bytes < dsk_attn_workspace_bytes(a)) return DSK_ERR_WORKSPACE;
   if (!aligned256(a->workspace)) return DSK_ERR_ALIGN;
   return DSK_OK;
@@ -230,7 +232,7 @@ extern "C" {
 
 uint32_t dsk_version(void) { return DSK_ABI_VERSION; }
 
-const char* dsk_strerror(int32_t status) {
+const char* dsk_strerror(dsk_status status) {
   switch (status) {
     case DSK_OK: return "ok";
     case DSK_ERR_NULL: return "a required pointer is NULL";
@@ -239,6 +241,7 @@ const char* dsk_strerror(int32_t status) {
     case DSK_ERR_ALIGN: return "pointer or stride not sufficiently aligned";
     case DSK_ERR_WORKSPACE: return "workspace missing or too small";
     case DSK_ERR_CAPACITY: return "output capacity exceeded";
+    case DSK_ERR_ORDER: return "candidate positions of a sequence are not strictly ascending";
     case DSK_ERR_LAUNCH: return "HIP launch failed";
     case DSK_ERR_VERSION: return "argument struct size does not match this library";
     default: return "unknown status";
@@ -303,14 +306,6 @@ dsk_status dsk_reuse_update(const dsk_reuse_args* a, void* stream) {
   const dsk_status v = validate_reuse(a);
   if (v != DSK_OK) return v;
   if (launch_reuse(*a, static_cast<hipStream_t>(stream)) != hipSuccess) return DSK_ERR_LAUNCH;
-  return DSK_OK;
-}
-
-dsk_status dsk_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
-  if (buf == nullptr) return DSK_ERR_NULL;
-  if (!aligned16(buf) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return DSK_ERR_ALIGN;
-  if (launch_stream_read(buf, bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream)) != hipSuccess)
-    return DSK_ERR_LAUNCH;
   return DSK_OK;
 }
 

@@ -86,6 +86,4 @@ hipError_t launch_append(const dsk_append_args& a, hipStream_t st);
 size_t reuse_ws_bytes(const dsk_reuse_args& a);
 hipError_t launch_reuse(const dsk_reuse_args& a, hipStream_t st);
 
-hipError_t launch_stream_read(const void* buf, size_t bytes, uint32_t* sink, hipStream_t st);
-
 }  // namespace dsk

@@ -417,7 +417,8 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
     }
   }
   if (count > k) count = k;
-  const int used = (count + slots_per_wg - 1) / slots_per_wg;
+  int used = (int)(((int64_t)count + slots_per_wg - 1) / slots_per_wg);
+  if (used > nchunks) used = nchunks;   // never past the partials this head owns
   if (used <= 1) return;   // empty or single-chunk heads are complete already
   float m = -__builtin_inff(), l = 0.0f, a[8];
 #pragma unroll

@@ -22,16 +22,6 @@
 
 namespace dsk {
 
-#ifdef DSK_SEG_TIMING
-__device__ long long dsk_dbg2[64 * 16];
-#define SEG_TS(slot) do { if (MODE == 0 && threadIdx.x == 0) dsk_dbg2[(blockIdx.x % 64) * 16 + (slot)] = wall_clock64(); } while (0)
-extern "C" __attribute__((visibility("default"))) void dsk_debug_read2(long long* host) {
-  (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(dsk_dbg2), sizeof(long long) * 64 * 16);
-}
-#else
-#define SEG_TS(slot) do {} while (0)
-#endif
-
 constexpr int kSegThreads = 256;
 constexpr int kTileThreads = 1024;                      // workgroup of the tile kernel: the tiles are few (one per
                                                         // 2048 positions) and their phases barrier-bound, so
@@ -100,6 +90,9 @@ __global__ __launch_bounds__(256) void seg_scatter_kernel(
       set_status(dev_status, DSK_ERR_SHAPE);
       continue;
     }
+    // the lists are ascending within a sequence by contract; the dense class bytes do not depend
+    // on the order, so the segmentation still runs, but the caller is told
+    if (j > cand_cu[s] && cand_pos[j - 1] >= t) set_status(dev_status, DSK_ERR_ORDER);
     cls_at[t] = (uint8_t)cls;
   }
 }
@@ -111,14 +104,14 @@ __global__ __launch_bounds__(256) void seg_scatter_kernel(
 //   ns    u16 [kSegTile]   slots of the chunk starting here
 //   mark  u8  [kSegTile]   (emit mode) reachable from the tile's entry
 //   wq    u8  [64]         class -> weight tenths of this sequence
-//   red   i32 [2*kTileWaves + 2]
+//   red   i32 [2*kTileWaves + 3]
 __host__ __device__ constexpr size_t seg_tile_lds_bytes() {
   return (size_t)kSegTile * 12      // jump arrays (the vote array, 8 bytes per position, overlays them)
          + (size_t)kSegTile * 2     // ns
          + (size_t)kSegTile         // mark
          + 64 + 192;                // wq, red
 }
-static_assert((2 * kTileWaves + 2) * 4 <= 192, "red fits its slot");
+static_assert((2 * kTileWaves + 3) * 4 <= 192, "red fits its slot");
 
 template <int MODE>
 __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
@@ -138,7 +131,6 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
   const int s = blockIdx.y;
   const int j = blockIdx.x;
   const int tid = threadIdx.x;
-  SEG_TS(0);
   const int seq0 = p.cu_seqlens[s];
   const int L = p.cu_seqlens[s + 1] - seq0;
   if (!seq_ok(p, seq0, L)) {
@@ -166,7 +158,6 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
   }
   for (int i = tid; i < kSegTile; i += kTileThreads) { best[i] = 0ull; mark[i] = 0; }
   __syncthreads();
-  SEG_TS(1);
 
   // votes: boundary e (offered by a delimiter at e-1) can end a chunk that starts at q with
   // s_e = q + C in [e - delta, e + delta] and s_e < L.  key = score << 16 | (0xFFFF - (e - q)):
@@ -221,7 +212,6 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
       __syncthreads();
     }
   }
-  SEG_TS(2);
   // successor table (registers first: `best` is about to be overlaid).  Lane-interleaved
   // ownership (i = r*threads + tid) keeps these LDS accesses free of bank conflicts.
   int my_len[kSegPerThread];
@@ -254,11 +244,14 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
   if (MODE == 1 && tid == 0 && info.x >= p0 && info.x < p1) mark[info.x - p0] = 1;
   __syncthreads();
 
-  SEG_TS(3);
   // pointer jumping: level r holds 2^r chunks per hop; positions that left the tile are fixed points
   int cur = 0;
-  int* any_active = red + 2 * kTileWaves;   // two flags, used alternately
-  if (tid == 0) { any_active[0] = 0; any_active[1] = 0; }
+  // Three flags in rotation: round r raises flag r % 3 and reads it after the round's barrier,
+  // while thread 0 clears flag (r + 1) % 3 for the next round.  The flag a wavefront may still be
+  // reading after barrier r is therefore not cleared before round r + 2, i.e. after barrier r + 1,
+  // which that wavefront has passed by then.
+  int* any_active = red + 2 * kTileWaves;
+  if (tid == 0) { any_active[0] = 0; any_active[1] = 0; any_active[2] = 0; }
   __syncthreads();
   for (int round = 0; round < 16; ++round) {
     int active = 0;
@@ -282,12 +275,12 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
       sd[i] = (uint16_t)nsl;
     }
     cur ^= 1;
-    if (active) any_active[round & 1] = 1;          // benign race: everyone writes the same value
-    if (tid == 0) any_active[(round + 1) & 1] = 0;  // not read again before the next barrier
+    const int flag = round % 3;
+    if (active) any_active[flag] = 1;                       // everyone writes the same value
+    if (tid == 0) any_active[flag == 2 ? 0 : flag + 1] = 0; // last read before the previous barrier
     __syncthreads();
-    if (!any_active[round & 1]) break;
+    if (!any_active[flag]) break;
   }
-  SEG_TS(4);
   const uint32_t* fpb = jpb + cur * kSegTile;
   const uint16_t* fcs = jcs + cur * kSegTile;
 
@@ -301,7 +294,6 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
       }
       row[ent] = rv;
     }
-    SEG_TS(5);
     return;
   }
 
@@ -358,8 +350,8 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
 // ---- chain ----------------------------------------------------------------------------------
 __global__ __launch_bounds__(kSegThreads) void seg_chain_kernel(
     SegParams p, const uint2* __restrict__ tile_map, int4* __restrict__ tile_info,
-    int4* __restrict__ seq_info, int32_t* __restrict__ cu_blocks, int32_t* __restrict__ block_start,
-    int32_t* __restrict__ slot_base, int32_t* dev_status) {
+    int4* __restrict__ seq_info, int32_t* __restrict__ cu_blocks, int32_t* __restrict__ cu_slots,
+    int32_t* __restrict__ block_start, int32_t* __restrict__ slot_base, int32_t* dev_status) {
   __shared__ uint2 rows[kChainLdsEntries];
   __shared__ int carry[3];
   const int s = blockIdx.x;
@@ -398,6 +390,7 @@ __global__ __launch_bounds__(kSegThreads) void seg_chain_kernel(
     if (p.B == 1) {   // single sequence: the batch scan is trivial, finish here
       cu_blocks[0] = 0;
       cu_blocks[1] = carry[1];
+      if (cu_slots) { cu_slots[0] = 0; cu_slots[1] = carry[2]; }
       if (carry[1] > p.cap) set_status(dev_status, DSK_ERR_CAPACITY);
       else { block_start[carry[1]] = p.total_tokens; slot_base[carry[1]] = carry[2]; }
     }
@@ -407,12 +400,14 @@ __global__ __launch_bounds__(kSegThreads) void seg_chain_kernel(
 // ---- scan over the sequences of the batch (B > 1) ----------------------------------------------
 __global__ __launch_bounds__(64) void seg_seqscan_kernel(
     int4* __restrict__ seq_info, int B, int cap, int total_tokens, int32_t* __restrict__ cu_blocks,
-    int32_t* __restrict__ block_start, int32_t* __restrict__ slot_base, int32_t* dev_status) {
+    int32_t* __restrict__ cu_slots, int32_t* __restrict__ block_start, int32_t* __restrict__ slot_base,
+    int32_t* dev_status) {
   if (threadIdx.x != 0) return;
   int blk = 0, slots = 0;
   for (int s = 0; s < B; ++s) {
     int4 v = seq_info[s];
     cu_blocks[s] = blk;
+    if (cu_slots) cu_slots[s] = slots;
     v.z = blk;
     v.w = slots;
     seq_info[s] = v;
@@ -420,6 +415,7 @@ __global__ __launch_bounds__(64) void seg_seqscan_kernel(
     slots += v.y;
   }
   cu_blocks[B] = blk;
+  if (cu_slots) cu_slots[B] = slots;
   if (blk > cap) {
     set_status(dev_status, DSK_ERR_CAPACITY);
     return;   // the tables stay self-consistent for the truncated prefix
@@ -473,11 +469,13 @@ hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, bool
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
   seg_chain_kernel<<<dim3((unsigned)a.B), dim3(kSegThreads), 0, st>>>(p, tile_map, tile_info, seq_info, a.cu_blocks,
-                                                                      a.block_start, a.slot_base, a.dev_status);
+                                                                      a.cu_slots, a.block_start, a.slot_base,
+                                                                      a.dev_status);
   if ((err = hipGetLastError()) != hipSuccess) return err;
   if (a.B > 1) {
     seg_seqscan_kernel<<<dim3(1), dim3(64), 0, st>>>(seq_info, a.B, a.max_blocks_total, a.total_tokens,
-                                                     a.cu_blocks, a.block_start, a.slot_base, a.dev_status);
+                                                     a.cu_blocks, a.cu_slots, a.block_start, a.slot_base,
+                                                     a.dev_status);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
   if (ws.tiles_per_seq > 0) {

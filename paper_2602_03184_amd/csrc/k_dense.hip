@@ -38,6 +38,9 @@ __global__ __launch_bounds__(kDenseThreads) void dense_attn_kernel(
   const int seq0 = cu_seqlens[s];
   int L = cu_seqlens[s + 1] - seq0;
   if (seq0 < 0 || L < 0 || seq0 > total_tokens - L) L = 0;     // malformed table: treated as empty
+  // the host's max_seqlen sized the split: a longer sequence on the device is cut to the tokens the
+  // nsplit ranges cover, so that the merge finds exactly the partials that were written
+  if (L > nsplit * (int64_t)tokens_per_split) L = nsplit * tokens_per_split;
   const int ng = (G - g0 < GT) ? G - g0 : GT;                  // heads of this pass that exist
   if (L <= 0) {
     if (split == 0 && threadIdx.x < DSK_HEAD_DIM) {

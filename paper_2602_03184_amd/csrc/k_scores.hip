@@ -12,10 +12,7 @@
 
 namespace dsk {
 
-#ifndef DSK_SCORE_THREADS
-#define DSK_SCORE_THREADS 256
-#endif
-constexpr int kScoreThreads = DSK_SCORE_THREADS;
+constexpr int kScoreThreads = 256;
 constexpr int kHalvesPerWg = kScoreThreads / 32;
 __host__ __device__ constexpr int score_blocks_per_half(int G) { return G >= 8 ? 4 : 8; }
 

@@ -44,16 +44,6 @@ struct SelShared {
   int work_take[kSelWork];
 };
 
-#ifdef DSK_SELECT_TIMING
-__device__ long long dsk_dbg[64 * 16];
-#define DSK_TS(slot) do { if (threadIdx.x == 0) dsk_dbg[(blockIdx.y * gridDim.x + blockIdx.x) % 64 * 16 + (slot)] = wall_clock64(); } while (0)
-extern "C" __attribute__((visibility("default"))) void dsk_debug_read(long long* host) {
-  (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(dsk_dbg), sizeof(long long) * 64 * 16);
-}
-#else
-#define DSK_TS(slot) do {} while (0)
-#endif
-
 // exclusive prefix sum of one int per thread over the workgroup, in thread order
 template <int NW>
 __device__ __forceinline__ int wg_excl_scan(int v, int* wave_tot, int& total) {
@@ -292,7 +282,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
     ks = ks < 1 ? 1 : ks;
     k = ks < kcap ? ks : kcap;
   }
-  DSK_TS(0);
 
   // cu_blocks[0] is 0 by definition: sequence 0 can address its loads before anything arrives
   const int blk0_raw = s == 0 ? 0 : cu_blocks[s];
@@ -361,7 +350,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
       nslots += wr;
     }
   }
-  DSK_TS(1);
   // 1. workgroup reductions
   kmin = wave_min_u(kmin);
   kmax = wave_max_u(kmax);
@@ -380,7 +368,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
   const int count = nslots < k ? nslots : k;
   write_padding(count, kcap, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
   if (count <= 0) return;
-  DSK_TS(2);
 
   // 2. threshold
   const bool take_all = nslots <= k;
@@ -416,7 +403,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
       tau = prefix;
     }
   }
-  DSK_TS(3);
 
   // 3. ties by lowest index, output positions (thread order = block order).  One scan of the
   //    pair (slots of tau-scored blocks, slots of better blocks) per thread is enough: the slots
@@ -431,7 +417,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
   int tie_before, gt_before;
   wg_excl_scan2<NW>(tie_local, gt_local, sh.wave_tot2, tie_before, gt_before);
   int off = gt_before + (tie_before < krem ? tie_before : krem);
-  DSK_TS(4);
   // Chosen blocks go through an LDS work list (any order: every entry carries its output
   // offset) so that their slots are written by all threads in parallel; block_start is already
   // in registers.  Entries outside the current round's window are skipped.
@@ -486,7 +471,6 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
     }
     __syncthreads();
   }
-  DSK_TS(5);
 }
 
 hipError_t launch_select(const dsk_select_args& a, const float* scores, int stride, hipStream_t st) {

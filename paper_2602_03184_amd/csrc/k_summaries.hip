@@ -9,19 +9,11 @@ namespace dsk {
 
 constexpr int kSumThreads = 256;
 constexpr int kSumWaves = kSumThreads / DSK_WAVE;
-#ifndef DSK_SUM_UNROLL
-#define DSK_SUM_UNROLL 8
-#endif
-constexpr int kSumUnroll = DSK_SUM_UNROLL;  // row-groups of 4 rows in flight per wave
-#ifdef DSK_SUM_WPE
-#define DSK_SUM_OCC __attribute__((amdgpu_waves_per_eu(DSK_SUM_WPE, DSK_SUM_WPE)))
-#else
-#define DSK_SUM_OCC
-#endif
+constexpr int kSumUnroll = 8;  // row-groups of 4 rows in flight per wave
 
 // 8 waves per SIMD (32 per CU) so that one launch keeps every wave of the grid resident
 template <bool MEAN>
-__global__ __launch_bounds__(kSumThreads) DSK_SUM_OCC void summaries_kernel(
+__global__ __launch_bounds__(kSumThreads) void summaries_kernel(
     const uint16_t* __restrict__ X, int64_t stride_tok, int64_t stride_head, int Hkv,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ cu_blocks, int B,
     const int32_t* __restrict__ blk_range, int cap, int total_tokens, uint16_t* __restrict__ out,

@@ -155,7 +155,7 @@ int main() {
   HIP_OK(hipMemcpy(cnt.data(), d_cnt, cnt.size() * 4, hipMemcpyDeviceToHost));
   HIP_OK(hipMemcpy(out.data(), d_out, out.size() * 4, hipMemcpyDeviceToHost));
   HIP_OK(hipMemcpy(lse.data(), d_lse, lse.size() * 4, hipMemcpyDeviceToHost));
-  if (status != 0) { std::fprintf(stderr, "device status %d: %s\n", status, dsk_strerror(status)); return 4; }
+  if (status != 0) { std::fprintf(stderr, "device status %d: %s\n", status, dsk_strerror((dsk_status)status)); return 4; }
 
   const double scale = 1.0 / std::sqrt((double)D);
   double worst = 0.0;

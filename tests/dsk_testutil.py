@@ -133,6 +133,20 @@ def rel_err(got: np.ndarray, want: np.ndarray) -> float:
 DEFAULT_SCALE = 1.0 / math.sqrt(128.0)
 
 
+def heads_to_check(cfg) -> List[int]:
+    """Query heads the full-size decode parity samples (all of them up to 8 heads)."""
+    return list(range(cfg.Hq)) if cfg.Hq <= 8 else sorted({0, 1, cfg.G, cfg.Hq // 2 + 1, cfg.Hq - 1})
+
+
+def kv_heads_to_check(cfg) -> List[int]:
+    """KV heads whose summaries are compared with the oracle: all of them up to 8, else exactly
+    the KV heads behind heads_to_check(), so that every summary the decode parity reads from the
+    GPU has itself been checked bit for bit."""
+    if cfg.Hkv <= 8:
+        return list(range(cfg.Hkv))
+    return sorted({h // cfg.G for h in heads_to_check(cfg)})
+
+
 # ---------------------------------------------------------------------------------------------
 # cached workloads on host and device
 # ---------------------------------------------------------------------------------------------

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol(dsk):
     lib = C.CDLL(dsk.binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
-    assert dsk.dsk_version() == 1
+    assert dsk.dsk_version() == 2
     assert dsk.dsk_strerror(0) == "ok" and "capacity" in dsk.dsk_strerror(dsk.DSK_ERR_CAPACITY)
     assert dsk.dsk_block_capacity(131072, 1, 16) == 8193
     assert dsk.dsk_block_capacity(10, 0, 16) == -1

@@ -7,7 +7,7 @@ import torch
 from oracle import dynsplit_oracle as O
 from workloads import CONFIGS, f32_to_bf16_bits
 from dsk_testutil import (GpuCase, bf16_bits_of, canon_zero, dev_bf16, dev_i32, dev_u8, gpu_case,
-                          oracle_segment, oracle_summaries)
+                          kv_heads_to_check, oracle_segment, oracle_summaries)
 
 pytestmark = pytest.mark.gpu
 
@@ -23,6 +23,8 @@ def _check_tables(comp, seg):
     np.testing.assert_array_equal(comp.cu_blocks.cpu().numpy(), seg.cu_blocks)
     np.testing.assert_array_equal(comp.block_start.cpu().numpy()[: nb + 1], seg.block_start)
     np.testing.assert_array_equal(comp.slot_base.cpu().numpy()[: nb + 1], seg.slot_base)
+    if comp.cu_slots is not None:      # slot range of every sequence = slot_base at its first block
+        np.testing.assert_array_equal(comp.cu_slots.cpu().numpy(), seg.slot_base[seg.cu_blocks])
 
 
 # --------------------------------------------------------------------------- full configs
@@ -92,7 +94,7 @@ def test_summaries_bit_exact(cfg_id):
     comp = case.compressed()
     _check_tables(comp, seg)
     nb = int(seg.cu_blocks[-1])
-    heads = list(range(cfg.Hkv)) if cfg.Hkv <= 8 else [0, cfg.Hkv // 2 + 1, cfg.Hkv - 1]
+    heads = kv_heads_to_check(cfg)           # covers every KV head the decode parity reads summaries of
     got = bf16_bits_of(comp.ksum)            # [Hkv, cap, 2, D]
     kmin, kmax = oracle_summaries(wl.K, seg.block_start, heads)
     for j, h in enumerate(heads):
@@ -171,6 +173,7 @@ def _assert_seg(comp, bs, cub, sb):
     np.testing.assert_array_equal(comp.cu_blocks.cpu().numpy(), cub)
     np.testing.assert_array_equal(comp.block_start.cpu().numpy()[: nb + 1], bs)
     np.testing.assert_array_equal(comp.slot_base.cpu().numpy()[: nb + 1], sb)
+    np.testing.assert_array_equal(comp.cu_slots.cpu().numpy(), sb[cub])
 
 
 @pytest.mark.parametrize("L", [1, 2, 23, 24, 25, 36, 37, 1023, 1024, 1025, 2048 + 17])
@@ -282,3 +285,29 @@ def test_compression_pass_replays_correctly_from_a_hip_graph():
             assert torch.equal(captured.ksum[:, :nb], eager.ksum[:, :nb])
             n = int(eager.cand_cu.cpu()[1])
             assert torch.equal(captured.cand_pos[:n], eager.cand_pos[:n])
+
+
+def test_unordered_candidate_list_is_reported():
+    """Caller-provided candidate positions must ascend within a sequence: a swapped pair is
+    reported through dev_status (DSK_ERR_ORDER) while the tables, which depend only on which
+    positions are delimiters, still come out as for the sorted list."""
+    dsk = _dsk()
+    L, C, delta, b = 3000, 24, 12, 16
+    rng = np.random.default_rng(5)
+    pos = np.sort(rng.choice(L, size=120, replace=False))
+    cls = rng.integers(0, 4, size=120)
+    wq = [np.asarray([10, 5, 8, 6], np.uint8)]
+    good, bs, cub, sb = _segment_from_lists([L], [(pos, cls)], wq, C, delta, 5, 10, b)
+    _assert_seg(good, bs, cub, sb)
+    bad_pos, bad_cls = pos.copy(), cls.copy()
+    bad_pos[[40, 41]] = bad_pos[[41, 40]]
+    bad_cls[[40, 41]] = bad_cls[[41, 40]]
+    bad, _, _, _ = _segment_from_lists([L], [(bad_pos, bad_cls)], wq, C, delta, 5, 10, b)
+    assert int(bad.dev_status.item()) == dsk.DSK_ERR_ORDER
+    nb = int(cub[-1])
+    np.testing.assert_array_equal(bad.block_start.cpu().numpy()[: nb + 1], bs)
+    # a repeated position is not ascending either
+    dup_pos = pos.copy()
+    dup_pos[7] = dup_pos[6]
+    dup, _, _, _ = _segment_from_lists([L], [(dup_pos, cls)], wq, C, delta, 5, 10, b)
+    assert int(dup.dev_status.item()) == dsk.DSK_ERR_ORDER

@@ -10,7 +10,8 @@ import pytest
 import torch
 
 from oracle import dynsplit_oracle as O
-from dsk_testutil import (DEFAULT_SCALE, bf16_bits_of, dev_bf16, dev_i32, gpu_case, rel_err, selection_check)
+from dsk_testutil import (DEFAULT_SCALE, bf16_bits_of, dev_bf16, dev_i32, gpu_case, heads_to_check, rel_err,
+                          selection_check)
 
 pytestmark = pytest.mark.gpu
 
@@ -40,7 +41,7 @@ def _oracle_scores(case, comp_bits_min, comp_bits_max, q_bits, s, heads):
 
 
 def _heads_to_check(cfg):
-    return list(range(cfg.Hq)) if cfg.Hq <= 8 else sorted({0, 1, cfg.G, cfg.Hq // 2 + 1, cfg.Hq - 1})
+    return heads_to_check(cfg)
 
 
 def _seqs_to_check(cfg):

@@ -167,3 +167,77 @@ def test_importance_mean_over_layers():
             assert int(wq[c]) == int(wq_or[c])
         else:
             assert abs(int(wq[c]) - int(wq_or[c])) <= 1
+
+
+# ---------------------------------------------------------------------------------------------
+# the many-workgroup launch shape (3 sample slots x 4 wavefronts), taken when
+# ceil(n_samp / 4) * Hkv * B >= 1024, and Alg. 1 at the full 128K context
+# ---------------------------------------------------------------------------------------------
+def test_importance_many_workgroups_gqa_batch():
+    """Llama-3-8B head shape, 4 sequences, 16 classes x 8 samples: 32 * 8 * 4 = 1024 sample groups."""
+    wl, comp, prior = _run(5, B=4, seqlens=[3300, 2100, 4000, 2600])
+    cfg = wl.cfg
+    assert (cfg.n_class * cfg.M + 3) // 4 * cfg.Hkv * cfg.B >= 1024
+    print("many-workgroup GQA batch worst = %.2e" % _check(wl, comp, prior))
+
+
+def test_importance_many_workgroups_mha():
+    """Llama2-13B head shape (40 KV heads, no grouping), one sequence: 32 * 40 = 1280 sample groups."""
+    wl, comp, prior = _run(4, seqlens=[6000])
+    cfg = wl.cfg
+    assert (cfg.n_class * cfg.M + 3) // 4 * cfg.Hkv * cfg.B >= 1024
+    print("many-workgroup MHA worst = %.2e" % _check(wl, comp, prior))
+
+
+def test_importance_at_full_128k_context_both_launch_shapes():
+    """Stage IMPORTANCE alone at 131072 tokens with sample positions given by the caller, spread
+    over the whole context (the first and the last admissible position, the middle, tile edges),
+    so that the key loop runs thousands of tiles and nearly all of them lie in the discarded
+    region.  512 samples take the many-workgroup launch, a 6-sample call the other one; a
+    handful of samples (all 32 heads, every window query) is compared with the oracle."""
+    import paper_2602_03184_amd as dsk
+    from workloads import f32_to_bf16_bits
+    wl = make_workload(3, with_kv=True, with_qwin=False)
+    cfg = wl.cfg
+    L = wl.total_tokens
+    assert L == 131072
+    n_class, M = 16, 32
+    n_samp = n_class * M
+    assert (n_samp + 3) // 4 * cfg.Hkv >= 1024
+    r = np.random.default_rng(2024)
+    t_all = r.integers(cfg.R, L - cfg.W, size=n_samp).astype(np.int64)
+    t_all[0] = cfg.R                      # first admissible position
+    t_all[1] = L - 1 - cfg.W              # last admissible position: the window ends at the last token
+    t_all[2] = L // 2                     # middle
+    t_all[3] = 32 * 1000 - 1              # last key of a 32-key tile
+    t_all[4] = 4096 + cfg.R               # retained region starts on a tile edge
+    t_all[n_samp - 1] = 97 * 1024 + 13
+    checked = [0, 1, 2, 3, 4, n_samp - 1]
+    qwin_bits = f32_to_bf16_bits(r.standard_normal((1, n_samp, cfg.W, cfg.Hq, 128), dtype=np.float32))
+    K = dev_bf16(wl.K)
+    scale = 1.0 / math.sqrt(128.0)
+    Kf = O.widen_bf16(wl.K)
+    want = {j: O.delimiter_importance(O.widen_bf16(qwin_bits[0, j]), Kf, int(t_all[j]), cfg.R, cfg.alpha_imp, scale)
+            for j in checked}
+    del Kf
+
+    def run(samp_idx, n_class_, M_):
+        samp = torch.from_numpy(t_all[samp_idx].astype(np.int32).reshape(1, n_class_, M_)).cuda()
+        qw = dev_bf16(np.ascontiguousarray(qwin_bits[:, samp_idx]))
+        comp = dsk.compress(
+            cu_seqlens=dev_i32(wl.cu_seqlens), max_seqlen=L, Hq=cfg.Hq, K=K, V=None,
+            stages=dsk.DSK_STAGE_IMPORTANCE, n_class=n_class_, M=M_, W=cfg.W, R=cfg.R, alpha_imp=cfg.alpha_imp,
+            samp_pos=samp, qwin=qw, class_weight_q=dev_u8(np.full((1, n_class_), 3, np.uint8)))
+        torch.cuda.synchronize()
+        assert int(comp.dev_status.item()) == 0
+        return comp.samp_score.cpu().numpy().reshape(-1)
+
+    big = run(np.arange(n_samp), n_class, M)              # many-workgroup launch
+    assert np.isfinite(big).all() and (big >= -cfg.alpha_imp - 1e-5).all() and (big <= 1.0 + 1e-5).all()
+    small = run(np.asarray(checked), 2, 3)                # few-workgroup launch on the checked samples
+    worst = 0.0
+    for i, j in enumerate(checked):
+        for got in (float(big[j]), float(small[i])):
+            worst = max(worst, abs(got - want[j]))
+            assert abs(got - want[j]) <= SCORE_TOL, (j, int(t_all[j]), got, want[j])
+    print("128K importance worst |s_gpu - s_oracle| = %.2e over %d samples" % (worst, len(checked)))
