@@ -452,6 +452,28 @@ dsk_status dsk_select_topk(const dsk_select_args* args, void* stream);
 dsk_status dsk_sparse_decode_attn(const dsk_attn_args* args, void* stream);
 dsk_status dsk_dense_decode_attn(const dsk_dense_attn_args* args, void* stream);
 
+/* dsk_sparse_decode_attn for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as dsk_sparse_decode_attn, except that args->workspace and
+ * args->workspace_bytes are ignored: the split-K partials go to a static device array of
+ * DSK_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the process ends).
+ * The call allocates and frees nothing.
+ *   - Size limit: dsk_attn_workspace_bytes(args) must not exceed DSK_STATIC_SCRATCH_BYTES, i.e.
+ *     about B * Hq * ceil(k / slots_per_chunk) <= 4000 partials of 520 bytes (configuration 5 of the
+ *     benchmark, 8 sequences x 32 heads x 8 chunks, needs 2048); beyond it the call returns
+ *     DSK_ERR_WORKSPACE and enqueues nothing.
+ *   - Every call on a GPU uses that GPU's one array, and the array keeps the last call's contents.
+ *     Nothing in it has to start at zero (a partial is always written before it is read within a
+ *     call), so no clearing is enqueued.  Two calls that overlap on one GPU (different streams, or
+ *     graphs replayed concurrently) race on the array: serialise them, or use dsk_sparse_decode_attn
+ *     with a workspace per stream.
+ *   - With DSK_ATTN_PARTIALS_ONLY the partials stay in the library's array, which the caller cannot
+ *     address: the flag is accepted but only useful with the workspace variant.
+ *   - The array's device address is looked up on the first call on each device (a host-side symbol
+ *     query, no allocation); make that first call outside stream capture.  DSK_ERR_LAUNCH if the
+ *     lookup or a launch fails. */
+#define DSK_STATIC_SCRATCH_BYTES (2112 * 1024)
+dsk_status dsk_sparse_decode_attn_static(const dsk_attn_args* args, void* stream);
 dsk_status dsk_append_tokens(const dsk_append_args* args, void* stream);
 dsk_status dsk_reuse_update(const dsk_reuse_args* args, void* stream);
 

@@ -187,6 +187,9 @@ _lib.dsk_select_topk.restype = C.c_int32
 _lib.dsk_select_topk.argtypes = [C.POINTER(dsk_select_args), _p]
 _lib.dsk_sparse_decode_attn.restype = C.c_int32
 _lib.dsk_sparse_decode_attn.argtypes = [C.POINTER(dsk_attn_args), _p]
+_lib.dsk_sparse_decode_attn_static.restype = C.c_int32
+_lib.dsk_sparse_decode_attn_static.argtypes = [C.POINTER(dsk_attn_args), _p]
+DSK_STATIC_SCRATCH_BYTES = 2112 * 1024
 
 
 class DskError(RuntimeError):
@@ -287,6 +290,14 @@ def dsk_sparse_decode_attn(args: dsk_attn_args, stream=None, check: bool = True)
     st = int(_lib.dsk_sparse_decode_attn(C.byref(args), _stream_handle(stream)))
     if check and st != DSK_OK:
         raise DskError(st, "dsk_sparse_decode_attn")
+    return st
+
+
+def dsk_sparse_decode_attn_static(args: dsk_attn_args, stream=None, check: bool = True) -> int:
+    """dsk_sparse_decode_attn with the partials in the library's static scratch array (no workspace)."""
+    st = int(_lib.dsk_sparse_decode_attn_static(C.byref(args), _stream_handle(stream)))
+    if check and st != DSK_OK:
+        raise DskError(st, "dsk_sparse_decode_attn_static")
     return st
 
 

@@ -2,6 +2,8 @@
 // launch sequence of each call.  No allocation, no synchronisation, no retained pointers.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "dsk_internal.hpp"
 
 namespace dsk {
@@ -223,6 +225,29 @@ static dsk_status validate_reuse(const dsk_reuse_args* a) {
   return DSK_OK;
 }
 
+// ---- scratch of dsk_sparse_decode_attn_static ------------------------------------------------
+// One array per GPU the library runs on, held until the process ends.  Host code never uses the
+// array's name as an address: the device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[DSK_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device, or nullptr (device index out of range or
+// the symbol lookup failed)
+static void* static_scratch_ptr() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
 }  // namespace dsk
 
 using namespace dsk;
@@ -354,6 +379,20 @@ dsk_status dsk_sparse_decode_attn(const dsk_attn_args* a, void* stream) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   const AttnWs ws = attn_ws_layout(*a);
   if (launch_attn(*a, ws, st) != hipSuccess) return DSK_ERR_LAUNCH;
+  return DSK_OK;
+}
+
+dsk_status dsk_sparse_decode_attn_static(const dsk_attn_args* a, void* stream) {
+  const dsk_status v = validate_attn(a, /*own_workspace=*/true);
+  if (v != DSK_OK) return v;
+  const AttnWs ws = attn_ws_layout(*a);
+  if (ws.total > (size_t)DSK_STATIC_SCRATCH_BYTES) return DSK_ERR_WORKSPACE;   // more partials than the array holds
+  void* ptr = static_scratch_ptr();
+  if (ptr == nullptr) return DSK_ERR_LAUNCH;
+  dsk_attn_args own = *a;
+  own.workspace = ptr;
+  own.workspace_bytes = DSK_STATIC_SCRATCH_BYTES;
+  if (launch_attn(own, ws, static_cast<hipStream_t>(stream)) != hipSuccess) return DSK_ERR_LAUNCH;
   return DSK_OK;
 }
 
