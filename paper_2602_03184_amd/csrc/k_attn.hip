@@ -6,9 +6,17 @@
 // before it touches the data, then folds the slot into an online-softmax state (m, l, acc).
 // The wavefronts of a workgroup (8 for slots of up to 32 rows, 2 slots each) merge through LDS
 // into one partial per (sequence, head, chunk of 16 slots); a second small kernel merges the
-// partials in a fixed order
-// (a single-kernel merge was measured slower: both a device-wide fence per workgroup and
-// write-through partials with an arrival counter cost more than the extra launch).
+// partials of a head in a fixed order.  (Merging inside this kernel -- the workgroup of a head that
+// finishes last, found with an arrival counter, folds the head's partials -- was built three ways:
+// write-through partials with a device-scope counter, ordinary stores with a device-scope counter,
+// ordinary stores with a counter that stays in the XCD's L2.  At 128K / 32 heads the attention call
+// took 9.8 / 9.6 / 9.3 us against 9.3 us with the merge launch, whose cost in a graph is that of an
+// empty kernel, about 1.5 us: the store-acknowledge, counter and reload round trips of the last
+// workgroup cost as much.  Not kept.)
+// The launch is a 1-D grid in which workgroup id = 8 * j + x runs on XCD x: all chunks of all
+// query heads of a (sequence, KV head) group are given the same x, so that rows selected by
+// several heads of the group are fetched into one L2 once (9.3 instead of 10.5 us for the call at
+// 128K / 32 heads against a grid that spread a head's chunks over the XCDs).
 #include "dsk_attn_fold.hpp"
 #include "dsk_common.hpp"
 #include "dsk_internal.hpp"
@@ -80,7 +88,7 @@ struct FoldSlots {
 template <int NS, int SPW, int WAVES, bool STAGED = false>
 __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    int64_t kst, int64_t ksh, int64_t vst, int64_t vsh, int Hq, int G, uint32_t g_inv, int k, int b, int total_tokens,
+    int64_t kst, int64_t ksh, int64_t vst, int64_t vsh, int Hq, int G, int n_groups, int k, int b, int total_tokens,
     const int32_t* __restrict__ sel_start, const int32_t* __restrict__ sel_len,
     const int32_t* __restrict__ sel_count, int sel_div, float scale_log2, int nchunks,
     float2* __restrict__ part_ml, float* __restrict__ part_acc, float* __restrict__ out,
@@ -91,9 +99,21 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
   __shared__ float sm_acc[kAttnWaves][DSK_HEAD_DIM];
   constexpr int kSlotsPerWg = kAttnWaves * SPW;
 
-  const int chunk = blockIdx.x;
-  const int h = blockIdx.y;
-  const int s = blockIdx.z;
+  // workgroup id = 8 * j + x lands on XCD x.  Group gi = s * Hkv + hk takes x = gi % 8; its
+  // G * nchunks workgroups are consecutive in j.
+  const int Hkv = Hq / G;
+  const int per_group = G * nchunks;
+  const int xcd = blockIdx.x & 7;
+  const int j = blockIdx.x >> 3;
+  const int gl = j / per_group;
+  const int r = j - gl * per_group;
+  const int gi = gl * 8 + xcd;
+  if (gi >= n_groups) return;                    // padding of the last round of groups
+  const int s = gi / Hkv;
+  const int hk = gi - s * Hkv;
+  const int gq = r / nchunks;
+  const int chunk = r - gq * nchunks;
+  const int h = hk * G + gq;
   const int64_t sh = (int64_t)s * Hq + h;
   // row of the selection arrays: the head's own, or its KV head's when sel_div = Hq/Hkv heads share one
   const int64_t sr = sel_div == 1 ? sh : (int64_t)s * (Hq / sel_div) + h / sel_div;   // no division on the per-head path
@@ -124,8 +144,6 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
 
   const int g = lane >> 4;
   const int c = lane & 15;
-  // h / G without a division: g_inv = ceil(2^32 / G) is exact for h < 2^16 (G = 1 has no 32-bit inverse)
-  const int hk = G == 1 ? h : (int)__umulhi((uint32_t)h, g_inv);
   const QRow qf = make_qrow(*reinterpret_cast<const uint4*>(q + sh * DSK_HEAD_DIM + c * 8));
   const uint16_t* Kh = K + (int64_t)hk * ksh + c * 8;
   const uint16_t* Vh = V + (int64_t)hk * vsh + c * 8;
@@ -477,15 +495,15 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   float2* part_ml = reinterpret_cast<float2*>(w + ws.part_ml);
   float* part_acc = reinterpret_cast<float*>(w + ws.part_acc);
   const float scale = a.scale != 0.0f ? a.scale : 0.08838834764831845f;   // 128^-1/2
-  const dim3 grid((unsigned)ws.nchunks, (unsigned)a.Hq, (unsigned)a.B);
+  const int n_groups = a.B * a.Hkv;
+  const dim3 grid((unsigned)(8 * ((n_groups + 7) / 8) * (a.Hq / a.Hkv) * ws.nchunks));
 
   const uint16_t* q = static_cast<const uint16_t*>(a.q);
   const uint16_t* K = static_cast<const uint16_t*>(a.K);
   const uint16_t* V = static_cast<const uint16_t*>(a.V);
   // heads that read one row of the selection arrays; the workgroups of a group's heads gather the
-  // same rows (chunk c of every head runs on XCD c mod 8), so only one of them misses in L2
+  // same rows on one XCD, so only one of them misses in L2
   const int sel_div = (a.flags & DSK_ATTN_SHARED_SELECTION) ? a.Hq / a.Hkv : 1;
-  const uint32_t g_inv = (uint32_t)((0x100000000ull + (uint64_t)(a.Hq / a.Hkv) - 1) / (uint64_t)(a.Hq / a.Hkv));   // unused for G = 1
   if (attn_shared_tiled(a)) {
     const int G = a.Hq / a.Hkv;
     const int GT = G == 2 ? 2 : 4;
@@ -509,7 +527,7 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
                              ws.slots_per_wg, a.out, static_cast<uint16_t*>(a.out_bf16), a.lse, st);
   }
 #define DSK_ATTN_ARGS                                                                                          \
-  q, K, V, a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, a.Hq / a.Hkv, g_inv, a.k, a.b, \
+  q, K, V, a.k_stride_tok, a.k_stride_head, a.v_stride_tok, a.v_stride_head, a.Hq, a.Hq / a.Hkv, n_groups, a.k, a.b, \
       a.total_tokens, a.sel_start, a.sel_len, a.sel_count, sel_div, scale * kLog2e, ws.nchunks, part_ml, part_acc, a.out, \
       static_cast<uint16_t*>(a.out_bf16), a.lse
   // Slots of at most 32 rows: workgroups of 8 wavefronts, 2 slots each (16 slots per workgroup).
@@ -539,8 +557,8 @@ hipError_t launch_attn_merge(const float2* part_ml, const float* part_acc, const
     attn_merge_kernel<256><<<grid, dim3(256), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, sel_div, k, nchunks,
                                                        per_chunk, out, out_bf16, lse);
   else
-    attn_merge_kernel<kMergeBigThreads><<<grid, dim3(kMergeBigThreads), 0, st>>>(part_ml, part_acc, counts, cu_seqlens, Hq, sel_div,
-                                                                           k, nchunks, per_chunk, out, out_bf16, lse);
+    attn_merge_kernel<kMergeBigThreads><<<grid, dim3(kMergeBigThreads), 0, st>>>(
+        part_ml, part_acc, counts, cu_seqlens, Hq, sel_div, k, nchunks, per_chunk, out, out_bf16, lse);
   return hipGetLastError();
 }
 
