@@ -7,6 +7,7 @@
 // reduces the blocks x heads partial sums over its 32 lanes with a transposing butterfly
 // (each exchange halves the values a lane still carries), so a lane ends up owning the
 // finished score of one (block, head) pair.
+#include "dsk_attn_fold.hpp"
 #include "dsk_common.hpp"
 #include "dsk_internal.hpp"
 
@@ -16,28 +17,42 @@ constexpr int kScoreThreads = 256;
 constexpr int kHalvesPerWg = kScoreThreads / 32;
 __host__ __device__ constexpr int score_blocks_per_half(int G) { return G >= 8 ? 4 : 8; }
 
+// value of lane (lane ^ M) of the same half-wave: on the vector ALU's data-parallel path for
+// M < 16 (quad permutes and row mirrors; a mirror of 8 followed by a reversal inside quads flips
+// lane bit 2, a mirror of 16 followed by a mirror of 8 flips bit 3), through the LDS crossbar for 16
+constexpr int kDppQuadReverse = 0x1B;  // quad_perm [3,2,1,0]
+template <int M>
+__device__ __forceinline__ float xchg_half_wave(float v) {
+  if constexpr (M == 1) return dpp_f<kDppSwap1>(v);
+  else if constexpr (M == 2) return dpp_f<kDppSwap2>(v);
+  else if constexpr (M == 4) return dpp_f<kDppQuadReverse>(dpp_f<kDppHalfMirror>(v));
+  else if constexpr (M == 8) return dpp_f<kDppHalfMirror>(dpp_f<kDppMirror>(v));
+  else return shfl_xor_f(v, M);
+}
+
 // Sum V (a power of two, <= 32) per-lane values over the 32 lanes of a half-wave.  While more
 // than one value is left, a step over lane bit M halves them: the lane keeps the upper half of
 // the value indices if its bit M is set (the lower half otherwise) and adds what its partner
-// (lane ^ M) carried for that half; afterwards plain exchanges finish the sum.  On return
-// v[0] is the finished sum of original value index `idx` (built MSB-first from the lane bits
-// of the halving steps).
+// (lane ^ M) carried for that half; afterwards plain exchanges finish the sum.  Steps run from
+// lane bit 0 upwards, so that the steps with many values to exchange are the cheap ones.  On
+// return v[0] is the finished sum of original value index `idx` (built MSB-first from the lane
+// bits of the halving steps, i.e. from the low log2(V) lane bits, bit 0 first).
 template <int N, int V, int M>
 __device__ __forceinline__ void half_wave_reduce(float (&v)[N], int lane, int& idx) {
-  if constexpr (M >= 1) {
+  if constexpr (M <= 16) {
     if constexpr (V >= 2) {
       const bool up = (lane & M) != 0;
 #pragma unroll
       for (int x = 0; x < V / 2; ++x) {
         const float send = up ? v[x] : v[x + V / 2];
         const float keep = up ? v[x + V / 2] : v[x];
-        v[x] = keep + shfl_xor_f(send, M);
+        v[x] = keep + xchg_half_wave<M>(send);
       }
       idx = idx * 2 + (up ? 1 : 0);
-      half_wave_reduce<N, V / 2, M / 2>(v, lane, idx);
+      half_wave_reduce<N, V / 2, M * 2>(v, lane, idx);
     } else {
-      v[0] += shfl_xor_f(v[0], M);
-      half_wave_reduce<N, 1, M / 2>(v, lane, idx);
+      v[0] += xchg_half_wave<M>(v[0]);
+      half_wave_reduce<N, 1, M * 2>(v, lane, idx);
     }
   }
 }
@@ -123,35 +138,41 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
       seg_end = seg_end < ilast + 1 ? seg_end : ilast + 1;
     }
     if (seg_end > cur) {
-      float qs[G][8];
+      // q+ (lanes holding kmax) or q- (lanes holding kmin) as packed bf16 pairs: the halves whose
+      // sign does not fit are zeroed, both are exact in bf16; the products then run on the packed
+      // bf16 dot instruction with neither operand widened
+      uint32_t qp[G][4];
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float f[8];
-        unpack8(qv[g], f);
+        const uint32_t wds[4] = {qv[g].x, qv[g].y, qv[g].z, qv[g].w};
 #pragma unroll
-        for (int k = 0; k < 8; ++k) qs[g][k] = is_max ? fmaxf(f[k], 0.0f) : fminf(f[k], 0.0f);
+        for (int k = 0; k < 4; ++k) {
+          const uint32_t neg = ((uint32_t)((int32_t)(wds[k] << 16) >> 31) & 0xFFFFu) |
+                               ((uint32_t)((int32_t)wds[k] >> 31) & 0xFFFF0000u);   // ones over negative halves
+          qp[g][k] = wds[k] & (is_max ? ~neg : neg);
+        }
       }
       float v[V];
 #pragma unroll
       for (int u = 0; u < NB; ++u) {
-        float f[8];
-        unpack8(kv[u], f);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-          float acc = 0.0f;
-#pragma unroll
-          for (int k = 0; k < 8; ++k) acc = fmaf(qs[g][k], f[k], acc);
-          v[u * G + g] = acc;
+          float acc = dot2_bf16(qp[g][0], kv[u].x, 0.0f);
+          acc = dot2_bf16(qp[g][1], kv[u].y, acc);
+          acc = dot2_bf16(qp[g][2], kv[u].z, acc);
+          v[u * G + g] = dot2_bf16(qp[g][3], kv[u].w, acc);
         }
       }
       int idx = 0;
-      half_wave_reduce<V, V, 16>(v, c, idx);
-      const bool writer = (c & (32 / V - 1)) == 0;   // lanes differing only in non-halving bits hold copies
+      half_wave_reduce<V, V, 1>(v, c, idx);
+      const bool writer = c < V;                     // lanes differing only in non-halving (high) bits hold copies
       const int u = idx / G, g = idx % G;
       if constexpr (GROUPMAX) {
+        // the G heads of a block: value indices that differ in their low log2(G) bits, i.e. lanes
+        // that differ in lane bits log2(V / G) .. log2(V) - 1
         float best = v[0];
 #pragma unroll
-        for (int m = 32 / V; m < (32 / V) * G; m <<= 1) best = fmaxf(best, shfl_xor_f(best, m));
+        for (int m = V / G; m < V; m <<= 1) best = fmaxf(best, shfl_xor_f(best, m));
         if (writer && g == 0 && i0 + u >= cur && i0 + u < seg_end) {
           scores[(int64_t)hk * stride + i0 + u] = best;
           if (user) user[(int64_t)hk * cap + i0 + u] = best;

@@ -32,17 +32,50 @@ __host__ __device__ constexpr bool sel_fits_tile(int n, int per_thread, int thre
   return n + 3 <= threads * per_thread;
 }
 
+constexpr int kSelBinBits = 10;                         // the histogram pass: 1024 bins over the key range
+constexpr int kSelBins = 1 << kSelBinBits;
+constexpr int kSelCand = 64;                            // blocks of the threshold bin resolved by one wavefront
+static_assert(kSelMaxWaves <= 16, "per-wave values are combined inside one row of 16 lanes");
+
 struct SelShared {
-  uint32_t hist[256];
-  int wave_tot[kSelMaxWaves];
-  uint32_t red_min[kSelMaxWaves], red_max[kSelMaxWaves];
-  int red_sum[kSelMaxWaves];
-  int wave_tot2[2 * kSelMaxWaves];
+  uint32_t hist[kSelBins];
+  int wave_tot[16];                    // per-wave values; entries past the last wave hold the identity
+  uint32_t red_min[16], red_max[16];
+  int red_sum[16];
+  int wave_tot3[3][16];
+  uint32_t cand_key[kSelCand];
+  int cand_w[kSelCand];
+  int n_cand;
+  uint32_t tau;
   int digit, krem;
-  int n_work;
   int4 work[kSelWork];                 // (first token, end token, first slot, output offset)
   int work_take[kSelWork];
 };
+
+// ---- combining one value per wavefront over the workgroup (at most 16 wavefronts) ----------------
+// Every wavefront stores its value at arr[wave]; after a barrier each lane reads arr[lane & 15]
+// and a reduction (or scan) inside its row of 16 lanes, on the vector ALU's data-parallel path,
+// gives it the workgroup's result: one LDS read and four lane steps instead of a loop over the waves.
+__device__ __forceinline__ uint32_t group16_min_u(uint32_t v) {
+  uint32_t o;
+  o = (uint32_t)dpp_i<kDppSwap1>((int)v); v = o < v ? o : v;
+  o = (uint32_t)dpp_i<kDppSwap2>((int)v); v = o < v ? o : v;
+  o = (uint32_t)dpp_i<kDppHalfMirror>((int)v); v = o < v ? o : v;
+  o = (uint32_t)dpp_i<kDppMirror>((int)v); v = o < v ? o : v;
+  return v;
+}
+// inclusive prefix sum inside each row of 16 lanes
+__device__ __forceinline__ int row16_incl_scan_i(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, kDppRowShr + 1, 0xF, 0xF, false);
+  v += __builtin_amdgcn_update_dpp(0, v, kDppRowShr + 2, 0xF, 0xF, false);
+  v += __builtin_amdgcn_update_dpp(0, v, kDppRowShr + 4, 0xF, 0xF, false);
+  v += __builtin_amdgcn_update_dpp(0, v, kDppRowShr + 8, 0xF, 0xF, false);
+  return v;
+}
+// sum of the entries of the waves before `wave` (wave-uniform), given the row scan of the per-wave totals
+__device__ __forceinline__ int waves_before(int row_scan, int wave) {
+  return wave == 0 ? 0 : __builtin_amdgcn_readlane(row_scan, wave - 1);
+}
 
 // exclusive prefix sum of one int per thread over the workgroup, in thread order
 template <int NW>
@@ -64,23 +97,25 @@ __device__ __forceinline__ int wg_excl_scan(int v, int* wave_tot, int& total) {
   return off + incl - v;
 }
 
-// the same for two ints per thread at once
+// Exclusive prefix sums of three ints per thread over the workgroup, in thread order, and the
+// workgroup total of the third.  wave_tot3 entries past the last wave must hold 0.
 template <int NW>
-__device__ __forceinline__ void wg_excl_scan2(int a, int b, int* wave_tot2, int& a_excl, int& b_excl) {
+__device__ __forceinline__ void wg_excl_scan3(int a, int b, int c, int (*wave_tot3)[16], int& a_excl, int& b_excl,
+                                              int& c_excl, int& c_total) {
   const int lane = threadIdx.x & (DSK_WAVE - 1);
-  const int wave = threadIdx.x / DSK_WAVE;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DSK_WAVE);
   const int ia = wave_incl_scan_i(a, lane);
   const int ib = wave_incl_scan_i(b, lane);
+  const int ic = wave_incl_scan_i(c, lane);
+  if (lane == DSK_WAVE - 1) { wave_tot3[0][wave] = ia; wave_tot3[1][wave] = ib; wave_tot3[2][wave] = ic; }
   __syncthreads();
-  if (lane == DSK_WAVE - 1) { wave_tot2[2 * wave] = ia; wave_tot2[2 * wave + 1] = ib; }
-  __syncthreads();
-  int oa = 0, ob = 0;
-#pragma unroll
-  for (int w = 0; w < NW; ++w) {
-    if (w < wave) { oa += wave_tot2[2 * w]; ob += wave_tot2[2 * w + 1]; }
-  }
-  a_excl = oa + ia - a;
-  b_excl = ob + ib - b;
+  const int sa = row16_incl_scan_i(wave_tot3[0][lane & 15]);
+  const int sb = row16_incl_scan_i(wave_tot3[1][lane & 15]);
+  const int sc = row16_incl_scan_i(wave_tot3[2][lane & 15]);
+  a_excl = waves_before(sa, wave) + ia - a;
+  b_excl = waves_before(sb, wave) + ib - b;
+  c_excl = waves_before(sc, wave) + ic - c;
+  c_total = __builtin_amdgcn_readlane(sc, NW - 1);
 }
 
 // After the histogram of one pass is complete: wave 0 finds the digit holding the krem-th slot
@@ -104,6 +139,37 @@ __device__ __forceinline__ void pick_digit(SelShared& sh, int krem, int& digit_o
   }
   __syncthreads();
   digit_out = sh.digit;
+  krem_out = sh.krem;
+}
+
+// The bin of the kSelBins-bin histogram that holds the k-th slot counted from the top bin down,
+// found by the whole workgroup: thread t owns the BPT bins below kSelBins - t * BPT, a wavefront
+// scan and the row scan of the per-wave totals give the slots in higher bins.  wave_tot entries
+// past the last wave must hold 0.  Two barriers.
+template <int THREADS>
+__device__ __forceinline__ void pick_bin(SelShared& sh, int k, int& bin_out, int& krem_out) {
+  constexpr int BPT = kSelBins / THREADS;
+  constexpr int kTop = kSelBins - 1;
+  const int lane = threadIdx.x & (DSK_WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / DSK_WAVE);
+  int hv[BPT];
+  int mine = 0;
+#pragma unroll
+  for (int u = 0; u < BPT; ++u) { hv[u] = (int)sh.hist[kTop - (threadIdx.x * BPT + u)]; mine += hv[u]; }
+  const int incl = wave_incl_scan_i(mine, lane);
+  if (lane == DSK_WAVE - 1) sh.wave_tot[wave] = incl;
+  __syncthreads();
+  int excl = waves_before(row16_incl_scan_i(sh.wave_tot[lane & 15]), wave) + incl - mine;
+#pragma unroll
+  for (int u = 0; u < BPT; ++u) {
+    if (excl < k && k <= excl + hv[u]) {   // true for exactly one (thread, u)
+      sh.digit = kTop - (threadIdx.x * BPT + u);
+      sh.krem = k - excl;
+    }
+    excl += hv[u];
+  }
+  __syncthreads();
+  bin_out = sh.digit;
   krem_out = sh.krem;
 }
 
@@ -350,77 +416,131 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
       nslots += wr;
     }
   }
-  // 1. workgroup reductions
+  // 1. workgroup reductions: smallest and largest key, slot total
   kmin = wave_min_u(kmin);
   kmax = wave_max_u(kmax);
   nslots = wave_sum_i(nslots);
   if (lane == 0) { sh.red_min[wave] = kmin; sh.red_max[wave] = kmax; sh.red_sum[wave] = nslots; }
-  if (tid < 256) sh.hist[tid] = 0;
-  if (tid == 0) sh.n_work = 0;
-  __syncthreads();
-  nslots = 0;
-#pragma unroll
-  for (int wv = 0; wv < NW; ++wv) {
-    kmin = sh.red_min[wv] < kmin ? sh.red_min[wv] : kmin;
-    kmax = sh.red_max[wv] > kmax ? sh.red_max[wv] : kmax;
-    nslots += sh.red_sum[wv];
+  if (tid >= NW && tid < 16) {                           // identities of the waves that do not exist
+    sh.red_min[tid] = 0xFFFFFFFFu; sh.red_max[tid] = 0u; sh.red_sum[tid] = 0;
+    sh.wave_tot[tid] = 0; sh.wave_tot3[0][tid] = 0; sh.wave_tot3[1][tid] = 0; sh.wave_tot3[2][tid] = 0;
   }
+  for (int i = tid; i < kSelBins; i += THREADS) sh.hist[i] = 0;
+  if (tid == 0) sh.n_cand = 0;
+  __syncthreads();
+  kmin = group16_min_u(sh.red_min[lane & 15]);
+  kmax = ~group16_min_u(~sh.red_max[lane & 15]);
+  nslots = group16_sum_i(sh.red_sum[lane & 15]);
   const int count = nslots < k ? nslots : k;
   write_padding(count, kcap, obase, sh_idx, sel_slot, sel_start, sel_len, sel_count);
   if (count <= 0) return;
 
-  // 2. threshold
+  // 2. threshold key tau and krem = slots still needed from the blocks whose key == tau.
+  //    One slot-weighted histogram pass over the top kSelBinBits bits of (key - smallest key) finds
+  //    the bin that holds the k-th best slot; the bin's few blocks go to an LDS list and one
+  //    wavefront ranks them against each other (for every listed key: slots of listed keys above
+  //    it, slots of listed keys equal to it), which gives tau and krem exactly.  Only when more
+  //    than kSelCand blocks share the bin (clustered or tied scores) do 8-bit radix passes over
+  //    the remaining low bits decide.
   const bool take_all = nslots <= k;
   uint32_t tau = 0u;       // take_all: every block qualifies
-  int krem = 0;            // slots still needed from blocks whose key == tau
+  int krem = 0;
   if (!take_all) {
-    const uint32_t diff = kmin ^ kmax;
-    if (diff == 0) {       // all scores equal: pure index-order tie
+    const uint32_t range = kmax - kmin;
+    if (range == 0) {      // all scores equal: pure index-order tie
       tau = kmax;
       krem = k;
     } else {
-      int rbits = 32 - __clz((int)diff);                 // low bits in which keys can differ
-      uint32_t prefix = rbits >= 32 ? 0u : (kmax >> rbits) << rbits;
-      uint32_t mask = rbits >= 32 ? 0u : ~((1u << rbits) - 1u);
-      krem = k;
-      while (rbits > 0) {                                // hist is zero on entry
-        const int dbits = rbits < 8 ? rbits : 8;
-        const int shift_d = rbits - dbits;
-        const uint32_t dmask = (1u << dbits) - 1u;
+      const int rb = 32 - __clz((int)range);               // bits of key - kmin that can be set
+      const int sh_b = rb > kSelBinBits ? rb - kSelBinBits : 0;
 #pragma unroll
-        for (int r = 0; r < kSelPerThread; ++r)
-          if (w[r] != 0 && (key[r] & mask) == prefix) atomicAdd(&sh.hist[(key[r] >> shift_d) & dmask], (uint32_t)w[r]);
-        __syncthreads();
-        int digit, knew;
-        pick_digit(sh, krem, digit, knew);
-        krem = knew;
-        prefix |= (uint32_t)digit << shift_d;
-        mask |= dmask << shift_d;
-        rbits = shift_d;
-        if (tid < 256) sh.hist[tid] = 0;                 // everyone has read digit / krem
-        __syncthreads();
+      for (int r = 0; r < kSelPerThread; ++r)
+        if (w[r] != 0) atomicAdd(&sh.hist[(key[r] - kmin) >> sh_b], (uint32_t)w[r]);
+      __syncthreads();
+      int bin, kbin;
+      pick_bin<THREADS>(sh, k, bin, kbin);
+#pragma unroll
+      for (int r = 0; r < kSelPerThread; ++r) {
+        if (w[r] != 0 && (int)((key[r] - kmin) >> sh_b) == bin) {
+          const int e = atomicAdd(&sh.n_cand, 1);
+          if (e < kSelCand) { sh.cand_key[e] = key[r]; sh.cand_w[e] = w[r]; }
+        }
       }
-      tau = prefix;
+      __syncthreads();
+      const int n_cand = sh.n_cand;
+      if (n_cand <= kSelCand) {
+        if (tid < DSK_WAVE) {
+          const bool have = tid < n_cand;
+          const uint32_t mykey = have ? sh.cand_key[tid] : 0u;
+          int above = 0, equal = 0;
+          for (int jj = 0; jj < n_cand; ++jj) {            // LDS broadcast reads
+            const uint32_t kj = sh.cand_key[jj];
+            const int wj = sh.cand_w[jj];
+            above += kj > mykey ? wj : 0;
+            equal += kj == mykey ? wj : 0;
+          }
+          if (have && above < kbin && kbin <= above + equal) {   // lanes holding the same key agree
+            sh.tau = mykey;
+            sh.krem = kbin - above;
+          }
+        }
+        __syncthreads();
+        tau = sh.tau;
+        krem = sh.krem;
+      } else {
+        uint32_t prefix = (uint32_t)bin << sh_b;           // of key - kmin
+        uint32_t mask = ~((1u << sh_b) - 1u);              // sh_b >= 1: a bin of one key value has one candidate key
+        int rbits = sh_b;
+        krem = kbin;
+        for (int i = tid; i < 256; i += THREADS) sh.hist[i] = 0;
+        __syncthreads();
+        while (rbits > 0) {
+          const int dbits = rbits < 8 ? rbits : 8;
+          const int shift_d = rbits - dbits;
+          const uint32_t dmask = (1u << dbits) - 1u;
+#pragma unroll
+          for (int r = 0; r < kSelPerThread; ++r) {
+            const uint32_t nk = key[r] - kmin;
+            if (w[r] != 0 && (nk & mask) == prefix) atomicAdd(&sh.hist[(nk >> shift_d) & dmask], (uint32_t)w[r]);
+          }
+          __syncthreads();
+          int digit, knew;
+          pick_digit(sh, krem, digit, knew);
+          krem = knew;
+          prefix |= (uint32_t)digit << shift_d;
+          mask |= dmask << shift_d;
+          rbits = shift_d;
+          if (tid < 256) sh.hist[tid] = 0;                 // everyone has read digit / krem
+          __syncthreads();
+        }
+        tau = kmin + prefix;
+      }
     }
   }
 
   // 3. ties by lowest index, output positions (thread order = block order).  One scan of the
-  //    pair (slots of tau-scored blocks, slots of better blocks) per thread is enough: the slots
-  //    emitted before a thread are  better_before + min(tie_before, krem).
-  int tie_local = 0, gt_local = 0;
+  //    triple (slots of tau-scored blocks, slots of better blocks, blocks of either kind) per
+  //    thread: the slots emitted before a thread are  better_before + min(tie_before, krem), and
+  //    the block count numbers the entries of the work list below.
+  int tie_local = 0, gt_local = 0, cnt_local = 0;
+  uint32_t on_mask = 0;                                  // blocks r of this thread that get an entry
 #pragma unroll
   for (int r = 0; r < kSelPerThread; ++r) {
     const bool gt = take_all || key[r] > tau;
+    const bool tie = !gt && key[r] == tau;
     gt_local += gt ? w[r] : 0;
-    tie_local += (!gt && key[r] == tau) ? w[r] : 0;
+    tie_local += tie ? w[r] : 0;
+    const bool on = (gt || tie) && w[r] != 0;
+    cnt_local += on ? 1 : 0;
+    on_mask |= on ? (1u << r) : 0u;
   }
-  int tie_before, gt_before;
-  wg_excl_scan2<NW>(tie_local, gt_local, sh.wave_tot2, tie_before, gt_before);
+  int tie_before, gt_before, e0, n_work;
+  wg_excl_scan3<NW>(tie_local, gt_local, cnt_local, sh.wave_tot3, tie_before, gt_before, e0, n_work);
   int off = gt_before + (tie_before < krem ? tie_before : krem);
-  // Chosen blocks go through an LDS work list (any order: every entry carries its output
-  // offset) so that their slots are written by all threads in parallel; block_start is already
-  // in registers.  Entries outside the current round's window are skipped.
-  int n_mine = 0;
+  // Blocks at or above the threshold go through an LDS work list (every entry carries its output
+  // offset and the slots taken from it, 0 for tau-scored blocks past the last needed slot) so that
+  // their slots are written by all threads in parallel; block_start is already in registers.
+  // Entries outside the current round's window are skipped.
   {
     int tb = tie_before;
 #pragma unroll
@@ -433,19 +553,15 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
         tb += w[r];
       }
       w[r] = take;                                       // from here on: slots taken from block r
-      n_mine += take > 0 ? 1 : 0;
     }
   }
   const int* xs = reinterpret_cast<const int*>(iv);
   const int* xb = reinterpret_cast<const int*>(bv);
-  const int e0 = n_mine > 0 ? atomicAdd(&sh.n_work, n_mine) : 0;   // one reservation per thread
-  __syncthreads();
-  const int n_work = sh.n_work;
   for (int base = 0; base < n_work; base += kSelWork) {
     int e = e0 - base, o = off;
 #pragma unroll
     for (int r = 0; r < kSelPerThread; ++r) {
-      const bool on = w[r] > 0;
+      const bool on = (on_mask >> r) & 1u;
       if (on && e >= 0 && e < kSelWork) {                  // few lanes per step: masked LDS writes
         sh.work[e] = make_int4(xb[r], xb[r + 1], xs[r], o);
         sh.work_take[e] = w[r];
