@@ -16,4 +16,5 @@ from .synth import (  # noqa: F401
     make_queries,
     make_drifting_queries,
     make_qwin,
+    extra_queries,
 )

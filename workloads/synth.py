@@ -226,3 +226,11 @@ def make_workload(cfg, *, with_kv: bool = True, with_qwin: bool = False, **overr
     return Workload(cfg=cfg, seqlens=seqlens, cu_seqlens=cu, C=C, delta=delta, gap_mean=gap_mean,
                     delim_ids=delim_ids, token_ids=token_ids, class_weight_q=class_weight_q,
                     K=K, V=V, q=q, qwin=qwin, outlier_k=outlier_k, outlier_v=outlier_v)
+
+
+def extra_queries(cfg: WorkloadConfig, n: int) -> np.ndarray:
+    """n further seeded decode queries [n, B, Hq, D] (bf16 bits) for a configuration whose own
+    query list is shorter than a measurement needs; a stream of its own, so the configuration's
+    queries are unchanged."""
+    return make_queries(_rng(cfg.cfg_id, 0, 6), n, cfg.B, cfg.Hq, cfg.D)
+
