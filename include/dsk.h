@@ -90,8 +90,8 @@ enum {
  *   sequence-local position t satisfies R <= t <= L-1-W.
  *   When only the segmentation of the same call needs the candidates (weights from a table:
  *   no sampling), the lists may be left out: cand_pos == cand_class == NULL with
- *   max_cand_total == 0 keeps the per-token classes in the workspace for stage SEGMENT and
- *   writes neither the lists nor cand_cu (which may then be NULL too).
+ *   max_cand_total == 0 writes neither the lists nor cand_cu (which may then be NULL too); stage
+ *   SEGMENT then classifies the tokens it needs itself.
  * Stage IMPORTANCE (Alg. 1 and the equation of Sec. 3, on the one layer given):
  *   for each sampled candidate t, each query head and each of the W queries following t,
  *   the causal softmax row over keys 0..q is split into the retained region

@@ -28,6 +28,7 @@ CompressWs compress_ws_layout(const dsk_compress_args& a) {
   ws.tile_info = off;  off += align_up(n_tiles * sizeof(int4));
   ws.seq_info = off;   off += align_up((size_t)a.B * sizeof(int4));
   ws.cls_at = off;     off += align_up((size_t)a.total_tokens + 16);
+  ws.seg_len = off;    off += align_up(((size_t)a.total_tokens + 16) * sizeof(uint16_t));
   ws.tile_count = off; off += align_up(((size_t)ws.n_cand_tiles + 1) * sizeof(int32_t));
   const size_t n_samp = (size_t)a.B * (a.n_class > 0 ? a.n_class : 0) * (a.M > 0 ? a.M : 0);
   ws.imp_part = off;   off += align_up(n_samp * (size_t)a.Hkv * 2 * sizeof(float));
@@ -351,12 +352,20 @@ dsk_status dsk_compress(const dsk_compress_args* a, void* stream) {
   if (v != DSK_OK) return v;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const CompressWs ws = compress_ws_layout(*a);
-  if (a->stages & DSK_STAGE_CANDIDATES)
+  // candidates wanted only by the segmentation of this call (no lists): nothing to launch for them,
+  // the tile kernel classifies the tokens it needs
+  const bool st_cand = (a->stages & DSK_STAGE_CANDIDATES) != 0;
+  const bool no_lists = st_cand && (a->stages & DSK_STAGE_SEGMENT) && a->cand_pos == nullptr &&
+                        a->cand_class == nullptr && a->max_cand_total == 0;
+  if (st_cand && !no_lists)
     if (launch_candidates(*a, ws, st) != hipSuccess) return DSK_ERR_LAUNCH;
   if (a->stages & DSK_STAGE_IMPORTANCE)
     if (launch_importance(*a, ws, st) != hipSuccess) return DSK_ERR_LAUNCH;
-  if (a->stages & DSK_STAGE_SEGMENT)
-    if (launch_segment(*a, ws, (a->stages & DSK_STAGE_CANDIDATES) != 0, st) != hipSuccess) return DSK_ERR_LAUNCH;
+  if (a->stages & DSK_STAGE_SEGMENT) {
+    const SegClassSource src = no_lists ? SegClassSource::kTokenIds
+                               : (st_cand ? SegClassSource::kClassBytes : SegClassSource::kCallerLists);
+    if (launch_segment(*a, ws, src, st) != hipSuccess) return DSK_ERR_LAUNCH;
+  }
   if (a->stages & DSK_STAGE_SUMMARIES)
     if (launch_summaries(*a, st) != hipSuccess) return DSK_ERR_LAUNCH;
   return DSK_OK;

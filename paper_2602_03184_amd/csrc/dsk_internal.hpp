@@ -24,6 +24,7 @@ struct CompressWs {
   size_t tile_info;   // int4 [n_tiles]              entry position, block offset, slot offset
   size_t seq_info;    // int4 [B]                    blocks, slots, block base, slot base
   size_t cls_at;      // u8  [total_tokens]          dense class of each token, 255 = none
+  size_t seg_len;     // u16 [total_tokens]          length of the chunk that would start at each position
   size_t tile_count;  // i32 [n_cand_tiles + 1]      candidates per tile, then exclusive scan
   size_t imp_part;    // f32 [B * n_class * M * Hkv] per-(sample, kv head) partial sums
   size_t total;
@@ -35,8 +36,13 @@ CompressWs compress_ws_layout(const dsk_compress_args& a);
 
 hipError_t launch_candidates(const dsk_compress_args& a, const CompressWs& ws, hipStream_t st);
 hipError_t launch_importance(const dsk_compress_args& a, const CompressWs& ws, hipStream_t st);
-// have_cls_at: the dense class bytes in the workspace were just written by launch_candidates
-hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, bool have_cls_at, hipStream_t st);
+// where stage SEGMENT finds the delimiter class of a token
+enum class SegClassSource {
+  kClassBytes,    // dense class bytes in the workspace, just written by launch_candidates
+  kCallerLists,   // the caller's candidate lists (scattered into the class bytes first)
+  kTokenIds       // token_ids / delim_ids, classified inside the tile kernel (no lists were asked for)
+};
+hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, SegClassSource src, hipStream_t st);
 hipError_t launch_summaries(const dsk_compress_args& a, hipStream_t st);
 
 // ---- dsk_select_topk ----------------------------------------------------------------------

@@ -172,9 +172,6 @@ hipError_t launch_candidates(const dsk_compress_args& a, const CompressWs& ws, h
         a.token_ids, a.total_tokens, a.delim_ids, a.n_class, cls_at, tile_count);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
-  // no lists asked for: the class map just written is all the segmentation of this call reads
-  if (a.cand_pos == nullptr && a.cand_class == nullptr && a.max_cand_total == 0 && (a.stages & DSK_STAGE_SEGMENT))
-    return hipSuccess;
   cand_scan_kernel<<<dim3(1), dim3(kCandThreads), 0, st>>>(tile_count, ws.n_cand_tiles, cls_at, a.cu_seqlens, a.B,
                                                            a.total_tokens, a.max_cand_total, a.cand_cu,
                                                            a.dev_status);

@@ -22,7 +22,6 @@
 
 namespace dsk {
 
-constexpr int kSegThreads = 256;
 constexpr int kTileThreads = 1024;                      // workgroup of the tile kernel: the tiles are few (one per
                                                         // 2048 positions) and their phases barrier-bound, so
                                                         // wide workgroups shorten them (256 / 512 / 1024
@@ -42,6 +41,14 @@ struct SegParams {
   int max_seqlen, total_tokens;
   int B, cap;
 };
+
+// first token and length of sequence s.  A batch of one sequence is [0, total_tokens) by the
+// host's copy of cu_seqlens, which saves every kernel of the chain a dependent memory round trip.
+__device__ __forceinline__ void seq_range(const SegParams& p, int s, int& seq0, int& L) {
+  if (p.B == 1) { seq0 = 0; L = p.total_tokens; return; }
+  seq0 = p.cu_seqlens[s];
+  L = p.cu_seqlens[s + 1] - seq0;
+}
 
 // cu_seqlens must agree with the host copies the launch geometry and buffers were sized on
 __device__ __forceinline__ bool seq_ok(const SegParams& p, int seq0, int L) {
@@ -104,18 +111,23 @@ __global__ __launch_bounds__(256) void seg_scatter_kernel(
 //   ns    u16 [kSegTile]   slots of the chunk starting here
 //   mark  u8  [kSegTile]   (emit mode) reachable from the tile's entry
 //   wq    u8  [64]         class -> weight tenths of this sequence
-//   red   i32 [2*kTileWaves + 3]
+//   red   i32 [2*kTileWaves + 3], then at red + 40 the delimiter ids i32 [64]
 __host__ __device__ constexpr size_t seg_tile_lds_bytes() {
   return (size_t)kSegTile * 12      // jump arrays (the vote array, 8 bytes per position, overlays them)
          + (size_t)kSegTile * 2     // ns
          + (size_t)kSegTile         // mark
-         + 64 + 192;                // wq, red
+         + 64 + 448;                // wq, red (reduction words, then 64 delimiter ids)
 }
-static_assert((2 * kTileWaves + 3) * 4 <= 192, "red fits its slot");
+static_assert(2 * kTileWaves + 3 <= 40 && (40 + 64) * 4 <= 448, "red fits its slot");
 
+// MODE 0 (entry maps): the successor of every position comes from the votes of the delimiters in
+// reach -- read as class bytes (cls_at), or, when cls_at is NULL, classified here from token_ids /
+// delim_ids -- and the chunk lengths found are kept in seg_len for MODE 1 (emit), which starts from
+// them and casts no vote.
 template <int MODE>
 __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
-    SegParams p, const uint8_t* __restrict__ cls_at, uint2* __restrict__ tile_map,
+    SegParams p, const uint8_t* __restrict__ cls_at, const int32_t* __restrict__ token_ids,
+    const int32_t* __restrict__ delim_ids, uint16_t* __restrict__ seg_len, uint2* __restrict__ tile_map,
     const int4* __restrict__ tile_info, const int4* __restrict__ seq_info, int32_t* __restrict__ block_start,
     int32_t* __restrict__ slot_base, int32_t* dev_status) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -131,8 +143,8 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
   const int s = blockIdx.y;
   const int j = blockIdx.x;
   const int tid = threadIdx.x;
-  const int seq0 = p.cu_seqlens[s];
-  const int L = p.cu_seqlens[s + 1] - seq0;
+  int seq0, L;
+  seq_range(p, s, seq0, L);
   if (!seq_ok(p, seq0, L)) {
     if (tid == 0) set_status(dev_status, DSK_ERR_SHAPE);
     return;
@@ -151,84 +163,140 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
   seq_params(p, s, C, delta, dev_status);
   const int dd = delta > 1 ? delta : 1;
 
-  if (tid < 64) {
-    int w = tid < p.n_class ? p.class_weight_q[s * p.n_class + tid] : 0;
-    if (w > 10) { set_status(dev_status, DSK_ERR_PARAM); w = 10; }
-    wq[tid] = (uint8_t)w;
-  }
-  for (int i = tid; i < kSegTile; i += kTileThreads) { best[i] = 0ull; mark[i] = 0; }
-  __syncthreads();
-
-  // votes: boundary e (offered by a delimiter at e-1) can end a chunk that starts at q with
-  // s_e = q + C in [e - delta, e + delta] and s_e < L.  key = score << 16 | (0xFFFF - (e - q)):
-  // highest score wins, then the smallest e; 0 = no vote.  The boundaries in reach are scanned
-  // kVoteChunk at a time (normally once); the delimiters found are first compacted into an LDS
-  // list so that the vote loops run on threads that all have one (a dense scan would leave 1
-  // lane in 30 busy).
-  {
-    constexpr int kVoteChunk = 2 * kSegTile;                                        // 16 class bytes per thread
-    constexpr int kPerThread = kVoteChunk / kTileThreads;
-    uint16_t* clist = reinterpret_cast<uint16_t*>(smem + (size_t)kSegTile * 8);     // free until the jump arrays are built
-    int* n_list = red;
-    const int e_lo = p0 + C - delta > 1 ? p0 + C - delta : 1;
-    int e_hi = p1 - 1 + C + delta;
-    if (e_hi > L) e_hi = L;
-    for (int e0 = e_lo; e0 <= e_hi; e0 += kVoteChunk) {
-      uint8_t cb_[kPerThread];
-#pragma unroll
-      for (int r = 0; r < kPerThread; ++r) {       // independent byte loads: one round trip
-        int e = e0 + r * kTileThreads + tid;
-        e = e <= e_hi ? e : e_hi;
-        cb_[r] = cls_at[seq0 + e - 1];
-      }
-      if (tid == 0) *n_list = 0;
-      __syncthreads();
-#pragma unroll
-      for (int r = 0; r < kPerThread; ++r) {
-        const int eo = r * kTileThreads + tid;        // e - e0 < 4096: 12 bits, weight 0..10: 4 bits
-        if (e0 + eo <= e_hi && cb_[r] != 255) {
-          const int w = cb_[r] < 64 ? wq[cb_[r]] : 0;
-          clist[atomicAdd(n_list, 1)] = (uint16_t)((eo << 4) | w);   // at most kVoteChunk entries = 8 KB
-        }
-      }
-      __syncthreads();
-      const int n = *n_list;
-      for (int ci = tid; ci < n; ci += kTileThreads) {
-        const int ent = clist[ci];
-        const int e = e0 + (ent >> 4);
-        const int w = ent & 15;
-        int q_lo = e - C - delta, q_hi = e - C + delta;
-        if (q_lo < p0) q_lo = p0;
-        if (q_hi > p1 - 1) q_hi = p1 - 1;
-        if (q_hi > L - C - 1) q_hi = L - C - 1;      // s_e = q + C must stay below L
-        for (int q = q_lo; q <= q_hi; ++q) {
-          const int s_e = q + C;
-          const int dist = e > s_e ? e - s_e : s_e - e;
-          const unsigned long long sc = (unsigned long long)(p.a_num * w * dd + (p.a_den - p.a_num) * 10 * (dd - dist));
-          const unsigned long long key = ((sc + 1ull) << 16) | (unsigned long long)(0xFFFF - (e - q));
-          atomicMax(&best[q - p0], key);
-        }
-      }
-      __syncthreads();
-    }
-  }
-  // successor table (registers first: `best` is about to be overlaid).  Lane-interleaved
-  // ownership (i = r*threads + tid) keeps these LDS accesses free of bank conflicts.
   int my_len[kSegPerThread];
+  if (MODE == 0) {
+    if (tid < 64) {
+      int w = tid < p.n_class ? p.class_weight_q[s * p.n_class + tid] : 0;
+      if (w > 10) { set_status(dev_status, DSK_ERR_PARAM); w = 10; }
+      wq[tid] = (uint8_t)w;
+    }
+    for (int i = tid; i < kSegTile; i += kTileThreads) best[i] = 0ull;
+    int* n_list = red;
+    if (tid == 0) *n_list = 0;
+    // delimiter ids for the in-kernel classification; the entries past n_class repeat id 0 and are
+    // never compared
+    int32_t* ids = red + 40;                                          // 64 ints behind the reduction words
+    if (cls_at == nullptr && tid < 64) ids[tid] = delim_ids[tid < p.n_class ? tid : 0];
+    __syncthreads();
+
+    // votes: boundary e (offered by a delimiter at e-1) can end a chunk that starts at q with
+    // s_e = q + C in [e - delta, e + delta] and s_e < L.  key = score << 16 | (0xFFFF - (e - q)):
+    // highest score wins, then the smallest e; 0 = no vote.  The boundaries in reach are scanned
+    // kVoteChunk at a time (normally once); the delimiters found are first compacted into an LDS
+    // list (one reservation per wavefront, ballots inside it) so that the vote loops run on threads
+    // that all have one (a dense scan would leave 1 lane in 30 busy).
+    {
+      constexpr int kVoteChunk = 2 * kSegTile;                                        // 4 positions per thread
+      constexpr int kPerThread = kVoteChunk / kTileThreads;
+      uint16_t* clist = reinterpret_cast<uint16_t*>(smem + (size_t)kSegTile * 8);     // free until the jump arrays are built
+      const int lane = tid & (DSK_WAVE - 1);
+      const int e_lo = p0 + C - delta > 1 ? p0 + C - delta : 1;
+      int e_hi = p1 - 1 + C + delta;
+      if (e_hi > L) e_hi = L;
+      for (int e0 = e_lo; e0 <= e_hi; e0 += kVoteChunk) {
+        int cb_[kPerThread];
+        if (cls_at != nullptr) {
 #pragma unroll
-  for (int r = 0; r < kSegPerThread; ++r) {
-    const int i = r * kTileThreads + tid;
-    const int q = p0 + i;
-    int len = 0;
-    if (i < tlen) {
-      const int s_e = q + C;
-      if (s_e >= L) len = L - q;
-      else {
-        const unsigned long long key = best[i];
-        len = key ? 0xFFFF - (int)(key & 0xFFFFull) : C;
+          for (int r = 0; r < kPerThread; ++r) {       // independent byte loads: one round trip
+            int e = e0 + r * kTileThreads + tid;
+            e = e <= e_hi ? e : e_hi;
+            cb_[r] = cls_at[seq0 + e - 1];
+          }
+        } else {
+          int tok[kPerThread];
+#pragma unroll
+          for (int r = 0; r < kPerThread; ++r) {
+            int e = e0 + r * kTileThreads + tid;
+            e = e <= e_hi ? e : e_hi;
+            tok[r] = token_ids[seq0 + e - 1];
+          }
+#pragma unroll
+          for (int r = 0; r < kPerThread; ++r) cb_[r] = 255;
+          for (int c4 = (p.n_class - 1) / 4 * 4; c4 >= 0; c4 -= 4) {   // lowest class index wins, as in the candidate stage
+            const int4 id4 = *reinterpret_cast<const int4*>(ids + c4);      // LDS broadcast read
+            const int idv[4] = {id4.x, id4.y, id4.z, id4.w};
+#pragma unroll
+            for (int cc = 3; cc >= 0; --cc) {
+              const int c = c4 + cc;
+              if (c < p.n_class) {
+#pragma unroll
+                for (int r = 0; r < kPerThread; ++r) cb_[r] = tok[r] == idv[cc] ? c : cb_[r];
+              }
+            }
+          }
+        }
+        // compaction: position of each delimiter inside its wavefront from ballots, one LDS
+        // reservation per wavefront
+        unsigned long long bal[kPerThread];
+        int n_wave = 0;
+#pragma unroll
+        for (int r = 0; r < kPerThread; ++r) {
+          const int eo = r * kTileThreads + tid;
+          bal[r] = __ballot(e0 + eo <= e_hi && cb_[r] != 255);
+          n_wave += __popcll(bal[r]);
+        }
+        int base = 0;
+        if (lane == 0 && n_wave > 0) base = atomicAdd(n_list, n_wave);
+        base = __builtin_amdgcn_readfirstlane(base);
+#pragma unroll
+        for (int r = 0; r < kPerThread; ++r) {
+          const int eo = r * kTileThreads + tid;        // e - e0 < 4096: 12 bits, weight 0..10: 4 bits
+          if ((bal[r] >> lane) & 1ull) {
+            const int w = cb_[r] < 64 ? wq[cb_[r]] : 0;
+            clist[base + __popcll(bal[r] & ((1ull << lane) - 1ull))] = (uint16_t)((eo << 4) | w);   // at most kVoteChunk entries = 8 KB
+          }
+          base += __popcll(bal[r]);
+        }
+        __syncthreads();
+        const int n = *n_list;
+        for (int ci = tid; ci < n; ci += kTileThreads) {
+          const int ent = clist[ci];
+          const int e = e0 + (ent >> 4);
+          const int w = ent & 15;
+          int q_lo = e - C - delta, q_hi = e - C + delta;
+          if (q_lo < p0) q_lo = p0;
+          if (q_hi > p1 - 1) q_hi = p1 - 1;
+          if (q_hi > L - C - 1) q_hi = L - C - 1;      // s_e = q + C must stay below L
+          for (int q = q_lo; q <= q_hi; ++q) {
+            const int s_e = q + C;
+            const int dist = e > s_e ? e - s_e : s_e - e;
+            const unsigned long long sc = (unsigned long long)(p.a_num * w * dd + (p.a_den - p.a_num) * 10 * (dd - dist));
+            const unsigned long long key = ((sc + 1ull) << 16) | (unsigned long long)(0xFFFF - (e - q));
+            atomicMax(&best[q - p0], key);
+          }
+        }
+        __syncthreads();
+        if (e0 + kVoteChunk <= e_hi) {                 // another chunk of boundaries follows (rare)
+          if (tid == 0) *n_list = 0;
+          __syncthreads();
+        }
       }
     }
-    my_len[r] = len;
+    // successor table (registers first: `best` is about to be overlaid).  Lane-interleaved
+    // ownership (i = r*threads + tid) keeps these LDS accesses free of bank conflicts.
+#pragma unroll
+    for (int r = 0; r < kSegPerThread; ++r) {
+      const int i = r * kTileThreads + tid;
+      const int q = p0 + i;
+      int len = 0;
+      if (i < tlen) {
+        const int s_e = q + C;
+        if (s_e >= L) len = L - q;
+        else {
+          const unsigned long long key = best[i];
+          len = key ? 0xFFFF - (int)(key & 0xFFFFull) : C;
+        }
+        seg_len[seq0 + q] = (uint16_t)len;             // chunk lengths stay below 2^16 (C + delta <= 8192)
+      }
+      my_len[r] = len;
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < kSegPerThread; ++r) {
+      const int i = r * kTileThreads + tid;
+      my_len[r] = i < tlen ? (int)seg_len[seq0 + p0 + i] : 0;
+    }
+    for (int i = tid; i < kSegTile; i += kTileThreads) mark[i] = 0;
   }
   __syncthreads();
 #pragma unroll
@@ -348,40 +416,127 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
 }
 
 // ---- chain ----------------------------------------------------------------------------------
-__global__ __launch_bounds__(kSegThreads) void seg_chain_kernel(
+// Entry maps are functions (entry offset into a tile) -> (entry offset into the next tile, chunks
+// and slots laid down on the way), so the walk from tile to tile is a prefix "sum" under function
+// composition and runs as a doubling scan: after round r, row j holds the composite of tiles
+// j - 2^r + 1 .. j.  Rows are staged in LDS, kChainLdsEntries / 2 entries per buffer; longer
+// sequences are cut into runs of tiles that pass a carry.  An LDS entry packs (offset: 16 bits,
+// chunks: 24 bits, slots: 24 bits): a run is at most kChainLdsEntries / 2 tiles, each with at most
+// 2048 chunks or slots.  Search ranges wider than kChainFastSpan take the plain walk, one lookup
+// per tile.
+constexpr int kChainThreads = 512;
+constexpr int kChainFastSpan = 512;                      // C + delta up to here: >= 6 tiles per run
+static_assert((kChainLdsEntries / 2) * kSegTile < (1 << 24), "packed counts of a run");
+
+__device__ __forceinline__ int chain_off(uint2 v) { return (int)(v.x & 0xFFFFu); }
+__device__ __forceinline__ int chain_blocks(uint2 v) { return (int)((v.x >> 16) | ((v.y >> 24) << 16)); }
+__device__ __forceinline__ int chain_slots(uint2 v) { return (int)(v.y & 0xFFFFFFu); }
+__device__ __forceinline__ uint2 chain_pack(int off, int blocks, int slots) {
+  return make_uint2((uint32_t)off | ((uint32_t)(blocks & 0xFFFF) << 16),
+                    (uint32_t)slots | ((uint32_t)(blocks >> 16) << 24));
+}
+
+__global__ __launch_bounds__(kChainThreads) void seg_chain_kernel(
     SegParams p, const uint2* __restrict__ tile_map, int4* __restrict__ tile_info,
     int4* __restrict__ seq_info, int32_t* __restrict__ cu_blocks, int32_t* __restrict__ cu_slots,
     int32_t* __restrict__ block_start, int32_t* __restrict__ slot_base, int32_t* dev_status) {
   __shared__ uint2 rows[kChainLdsEntries];
   __shared__ int carry[3];
   const int s = blockIdx.x;
-  int L = p.cu_seqlens[s + 1] - p.cu_seqlens[s];
-  if (!seq_ok(p, p.cu_seqlens[s], L)) L = 0;   // flagged by the tile kernel; emit nothing
+  int seq0, L;
+  seq_range(p, s, seq0, L);
+  if (!seq_ok(p, seq0, L)) L = 0;   // flagged by the tile kernel; emit nothing
   int n_tiles = (L + kSegTile - 1) / kSegTile;
   if (n_tiles > p.tiles_per_seq) n_tiles = p.tiles_per_seq;
-  const int tiles_per_chunk = kChainLdsEntries / p.map_row;   // map_row <= kSegTile <= entries
   if (threadIdx.x == 0) { carry[0] = 0; carry[1] = 0; carry[2] = 0; }
-  for (int j0 = 0; j0 < n_tiles; j0 += tiles_per_chunk) {
-    const int jn = (n_tiles - j0 < tiles_per_chunk) ? n_tiles - j0 : tiles_per_chunk;
-    const uint2* src = tile_map + ((int64_t)s * p.tiles_per_seq + j0) * p.map_row;
-    __syncthreads();
-    for (int i = threadIdx.x; i < jn * p.map_row; i += kSegThreads) rows[i] = src[i];
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int entry = carry[0], blk = carry[1], slots = carry[2];
-      for (int jj = 0; jj < jn; ++jj) {
-        const int j = j0 + jj;
-        const int t0 = j * kSegTile;
-        const int t1 = (t0 + kSegTile < L) ? t0 + kSegTile : L;
-        tile_info[s * p.tiles_per_seq + j] = make_int4(entry, blk, slots, 0);
-        if (entry < t1) {   // entry >= t1: a chunk longer than a tile jumps over it
-          const uint2 r = rows[jj * p.map_row + (entry - t0)];
-          blk += (int)(r.x >> 16);
-          slots += (int)r.y;
-          entry = t1 + (int)(r.x & 0xFFFFu);
+  if (p.map_row <= kChainFastSpan) {
+    // carry[0] is the entry offset into the first tile of the run.  i / map_row without a division:
+    // inv = floor(2^32 / map_row) + 1 is exact for i * map_row < 2^32.
+    const uint32_t inv = 0xFFFFFFFFu / (uint32_t)p.map_row + 1u;
+    const int run = (kChainLdsEntries / 2) / p.map_row;
+    for (int j0 = 0; j0 < n_tiles; j0 += run) {
+      const int T = (n_tiles - j0 < run) ? n_tiles - j0 : run;
+      const int n_ent = T * p.map_row;
+      const uint2* src = tile_map + ((int64_t)s * p.tiles_per_seq + j0) * p.map_row;
+      uint2* cur = rows;
+      uint2* nxt = rows + kChainLdsEntries / 2;
+      __syncthreads();
+      constexpr int kPer = (kChainLdsEntries / 2 + kChainThreads - 1) / kChainThreads;
+      uint2 ld[kPer];
+#pragma unroll
+      for (int u = 0; u < kPer; ++u) {                    // the run's rows: one round trip, not kPer
+        const int i = threadIdx.x + u * kChainThreads;
+        ld[u] = src[i < n_ent ? i : 0];
+      }
+#pragma unroll
+      for (int u = 0; u < kPer; ++u) {
+        const int i = threadIdx.x + u * kChainThreads;
+        if (i < n_ent) {
+          const int j = (int)__umulhi((uint32_t)i, inv), e = i - j * p.map_row;
+          const int t0 = (j0 + j) * kSegTile;
+          const int tl = (t0 + kSegTile < L) ? kSegTile : L - t0;
+          cur[i] = e >= tl ? chain_pack(e - tl, 0, 0) : ld[u];   // beyond a short last tile: passes through
         }
       }
-      carry[0] = entry; carry[1] = blk; carry[2] = slots;
+      __syncthreads();
+      for (int d = 1; d < T; d <<= 1) {
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+          const int i = threadIdx.x + u * kChainThreads;
+          if (i < n_ent) {
+            const int j = (int)__umulhi((uint32_t)i, inv), e = i - j * p.map_row;
+            uint2 v = cur[i];
+            if (j >= d) {                                 // tiles j-2d+1 .. j-d first, then j-d+1 .. j
+              const uint2 a = cur[(j - d) * p.map_row + e];
+              const uint2 c = cur[j * p.map_row + chain_off(a)];
+              v = chain_pack(chain_off(c), chain_blocks(a) + chain_blocks(c), chain_slots(a) + chain_slots(c));
+            }
+            nxt[i] = v;
+          }
+        }
+        __syncthreads();
+        uint2* t = cur; cur = nxt; nxt = t;
+      }
+      // row j now maps an entry of the run's first tile to the state behind tile j0 + j
+      const int e0 = carry[0], blk0 = carry[1], slots0 = carry[2];
+      for (int j = threadIdx.x; j < T; j += kChainThreads) {
+        int e = e0, blk = blk0, sl = slots0;
+        if (j > 0) {
+          const uint2 c = cur[(j - 1) * p.map_row + e0];
+          e = chain_off(c); blk += chain_blocks(c); sl += chain_slots(c);
+        }
+        tile_info[s * p.tiles_per_seq + j0 + j] = make_int4((j0 + j) * kSegTile + e, blk, sl, 0);
+      }
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        const uint2 c = cur[(T - 1) * p.map_row + e0];
+        carry[0] = chain_off(c); carry[1] = blk0 + chain_blocks(c); carry[2] = slots0 + chain_slots(c);
+      }
+    }
+  } else {
+    const int tiles_per_chunk = kChainLdsEntries / p.map_row;   // map_row <= kSegTile <= entries
+    for (int j0 = 0; j0 < n_tiles; j0 += tiles_per_chunk) {
+      const int jn = (n_tiles - j0 < tiles_per_chunk) ? n_tiles - j0 : tiles_per_chunk;
+      const uint2* src = tile_map + ((int64_t)s * p.tiles_per_seq + j0) * p.map_row;
+      __syncthreads();
+      for (int i = threadIdx.x; i < jn * p.map_row; i += kChainThreads) rows[i] = src[i];
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        int entry = carry[0], blk = carry[1], slots = carry[2];   // here carry[0] is an absolute position
+        for (int jj = 0; jj < jn; ++jj) {
+          const int j = j0 + jj;
+          const int t0 = j * kSegTile;
+          const int t1 = (t0 + kSegTile < L) ? t0 + kSegTile : L;
+          tile_info[s * p.tiles_per_seq + j] = make_int4(entry, blk, slots, 0);
+          if (entry < t1) {   // entry >= t1: a chunk longer than a tile jumps over it
+            const uint2 r = rows[jj * p.map_row + (entry - t0)];
+            blk += (int)(r.x >> 16);
+            slots += (int)r.y;
+            entry = t1 + (int)(r.x & 0xFFFFu);
+          }
+        }
+        carry[0] = entry; carry[1] = blk; carry[2] = slots;
+      }
     }
   }
   __syncthreads();
@@ -425,9 +580,10 @@ __global__ __launch_bounds__(64) void seg_seqscan_kernel(
 }
 
 // ---- host -----------------------------------------------------------------------------------
-hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, bool have_cls_at, hipStream_t st) {
+hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, SegClassSource src, hipStream_t st) {
   unsigned char* w = static_cast<unsigned char*>(a.workspace);
   uint8_t* cls_at = w + ws.cls_at;
+  uint16_t* seg_len = reinterpret_cast<uint16_t*>(w + ws.seg_len);
   uint2* tile_map = reinterpret_cast<uint2*>(w + ws.tile_map);
   int4* tile_info = reinterpret_cast<int4*>(w + ws.tile_info);
   int4* seq_info = reinterpret_cast<int4*>(w + ws.seq_info);
@@ -444,7 +600,7 @@ hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, bool
   p.B = a.B; p.cap = a.max_blocks_total;
 
   hipError_t err;
-  if (!have_cls_at) {   // candidates came from the caller: scatter them into the dense class array
+  if (src == SegClassSource::kCallerLists) {   // scatter the caller's candidates into the dense class array
     const int n = a.total_tokens;
     int n16 = (n + 15) / 16;
     int wgs = (n16 + 255) / 256;
@@ -464,11 +620,13 @@ hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, bool
   const size_t lds = seg_tile_lds_bytes();
   if (ws.tiles_per_seq > 0) {
     const dim3 grid((unsigned)ws.tiles_per_seq, (unsigned)a.B);
-    seg_tile_kernel<0><<<grid, dim3(kTileThreads), lds, st>>>(p, cls_at, tile_map, tile_info, seq_info,
-                                                             a.block_start, a.slot_base, a.dev_status);
+    // kTokenIds: no class bytes exist; the tile kernel classifies the tokens of its reach itself
+    seg_tile_kernel<0><<<grid, dim3(kTileThreads), lds, st>>>(
+        p, src == SegClassSource::kTokenIds ? nullptr : cls_at, a.token_ids, a.delim_ids, seg_len, tile_map,
+        tile_info, seq_info, a.block_start, a.slot_base, a.dev_status);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
-  seg_chain_kernel<<<dim3((unsigned)a.B), dim3(kSegThreads), 0, st>>>(p, tile_map, tile_info, seq_info, a.cu_blocks,
+  seg_chain_kernel<<<dim3((unsigned)a.B), dim3(kChainThreads), 0, st>>>(p, tile_map, tile_info, seq_info, a.cu_blocks,
                                                                       a.cu_slots, a.block_start, a.slot_base,
                                                                       a.dev_status);
   if ((err = hipGetLastError()) != hipSuccess) return err;
@@ -480,8 +638,9 @@ hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, bool
   }
   if (ws.tiles_per_seq > 0) {
     const dim3 grid((unsigned)ws.tiles_per_seq, (unsigned)a.B);
-    seg_tile_kernel<1><<<grid, dim3(kTileThreads), lds, st>>>(p, cls_at, tile_map, tile_info, seq_info,
-                                                             a.block_start, a.slot_base, a.dev_status);
+    seg_tile_kernel<1><<<grid, dim3(kTileThreads), lds, st>>>(p, nullptr, nullptr, nullptr, seg_len, tile_map,
+                                                             tile_info, seq_info, a.block_start, a.slot_base,
+                                                             a.dev_status);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
   return hipSuccess;
