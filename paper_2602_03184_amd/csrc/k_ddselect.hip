@@ -106,14 +106,16 @@ __global__ __launch_bounds__(256) void seg_scatter_kernel(
 
 // ---- tile kernel -----------------------------------------------------------------------------
 // dynamic LDS layout (bytes):
-//   best  u64 [kSegTile]                      votes; dead after the successor table is built,
-//   jpb u32 [2][kSegTile], jcs u16 [2][kSegTile]   ... so the pointer-jumping arrays overlay it
-//   ns    u16 [kSegTile]   slots of the chunk starting here
-//   mark  u8  [kSegTile]   (emit mode) reachable from the tile's entry
-//   wq    u8  [64]         class -> weight tenths of this sequence
-//   red   i32 [2*kTileWaves + 3], then at red + 40 the delimiter ids i32 [64]
+//   best  u64 [kSegTile]       votes; dead after the successor table is built,
+//   jmp   uint2 [2][kSegTile]  ... so the pointer-jumping entries overlay it:
+//                              x = (position - p0, or exit offset) | chunks << 16, y = slots
+//   clist u16 [2 * kSegTile]   delimiters in reach (overlays the second jump buffer)
+//   ns    u16 [kSegTile]       slots of the chunk starting here
+//   mark  u8  [kSegTile]       (emit mode) reachable from the tile's entry
+//   wq    u8  [64]             class -> weight tenths of this sequence
+//   red   i32 [40], then the delimiter ids i32 [64]
 __host__ __device__ constexpr size_t seg_tile_lds_bytes() {
-  return (size_t)kSegTile * 12      // jump arrays (the vote array, 8 bytes per position, overlays them)
+  return (size_t)kSegTile * 16      // jump entries (the vote array, 8 bytes per position, overlays them)
          + (size_t)kSegTile * 2     // ns
          + (size_t)kSegTile         // mark
          + 64 + 448;                // wq, red (reduction words, then 64 delimiter ids)
@@ -131,11 +133,10 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
     const int4* __restrict__ tile_info, const int4* __restrict__ seq_info, int32_t* __restrict__ block_start,
     int32_t* __restrict__ slot_base, int32_t* dev_status) {
   extern __shared__ __align__(16) unsigned char smem[];
-  // jump arrays (12 * kSegTile bytes) share storage with the vote array (8 * kSegTile bytes)
+  // jump entries (16 * kSegTile bytes) share storage with the vote array (8 * kSegTile bytes)
   unsigned long long* best = reinterpret_cast<unsigned long long*>(smem);
-  uint32_t* jpb = reinterpret_cast<uint32_t*>(smem);             // [2][kSegTile] (position - p0 or exit) | blocks << 16
-  uint16_t* jcs = reinterpret_cast<uint16_t*>(jpb + 2 * kSegTile);   // [2][kSegTile] slots laid down
-  uint16_t* ns = jcs + 2 * kSegTile;                              // [kSegTile] slots of the chunk starting here
+  uint2* jmp = reinterpret_cast<uint2*>(smem);                    // [2][kSegTile]
+  uint16_t* ns = reinterpret_cast<uint16_t*>(jmp + 2 * kSegTile); // [kSegTile] slots of the chunk starting here
   uint8_t* mark = reinterpret_cast<uint8_t*>(ns + kSegTile);
   uint8_t* wq = mark + kSegTile;
   int* red = reinterpret_cast<int*>(wq + 64);
@@ -165,6 +166,21 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
 
   int my_len[kSegPerThread];
   if (MODE == 0) {
+    // the class bytes (or token ids) of the first kVoteChunk boundaries in reach go out before
+    // anything is waited for: they travel with the weight and delimiter-id loads below
+    constexpr int kVoteChunk = 2 * kSegTile;                                        // 4 positions per thread
+    constexpr int kPerThread = kVoteChunk / kTileThreads;
+    const int e_lo = p0 + C - delta > 1 ? p0 + C - delta : 1;
+    int e_hi = p1 - 1 + C + delta;
+    if (e_hi > L) e_hi = L;
+    int first[kPerThread];
+#pragma unroll
+    for (int r = 0; r < kPerThread; ++r) {
+      int e = e_lo + r * kTileThreads + tid;
+      e = e <= e_hi ? e : e_hi;
+      e = e >= 1 ? e : 1;                              // e_hi >= 1 whenever the tile has a position
+      first[r] = cls_at != nullptr ? (int)cls_at[seq0 + e - 1] : token_ids[seq0 + e - 1];
+    }
     if (tid < 64) {
       int w = tid < p.n_class ? p.class_weight_q[s * p.n_class + tid] : 0;
       if (w > 10) { set_status(dev_status, DSK_ERR_PARAM); w = 10; }
@@ -186,13 +202,8 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
     // list (one reservation per wavefront, ballots inside it) so that the vote loops run on threads
     // that all have one (a dense scan would leave 1 lane in 30 busy).
     {
-      constexpr int kVoteChunk = 2 * kSegTile;                                        // 4 positions per thread
-      constexpr int kPerThread = kVoteChunk / kTileThreads;
       uint16_t* clist = reinterpret_cast<uint16_t*>(smem + (size_t)kSegTile * 8);     // free until the jump arrays are built
       const int lane = tid & (DSK_WAVE - 1);
-      const int e_lo = p0 + C - delta > 1 ? p0 + C - delta : 1;
-      int e_hi = p1 - 1 + C + delta;
-      if (e_hi > L) e_hi = L;
       for (int e0 = e_lo; e0 <= e_hi; e0 += kVoteChunk) {
         int cb_[kPerThread];
         if (cls_at != nullptr) {
@@ -200,7 +211,7 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
           for (int r = 0; r < kPerThread; ++r) {       // independent byte loads: one round trip
             int e = e0 + r * kTileThreads + tid;
             e = e <= e_hi ? e : e_hi;
-            cb_[r] = cls_at[seq0 + e - 1];
+            cb_[r] = e0 == e_lo ? first[r] : (int)cls_at[seq0 + e - 1];
           }
         } else {
           int tok[kPerThread];
@@ -208,7 +219,7 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
           for (int r = 0; r < kPerThread; ++r) {
             int e = e0 + r * kTileThreads + tid;
             e = e <= e_hi ? e : e_hi;
-            tok[r] = token_ids[seq0 + e - 1];
+            tok[r] = e0 == e_lo ? first[r] : token_ids[seq0 + e - 1];
           }
 #pragma unroll
           for (int r = 0; r < kPerThread; ++r) cb_[r] = 255;
@@ -248,16 +259,18 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
           base += __popcll(bal[r]);
         }
         __syncthreads();
+        // one thread per (delimiter, start position in its reach): n * (2 delta + 1) votes spread
+        // over the workgroup.  pair / span without a division: exact for pair * span < 2^32.
         const int n = *n_list;
-        for (int ci = tid; ci < n; ci += kTileThreads) {
+        const int span = 2 * delta + 1;
+        const uint32_t span_inv = 0xFFFFFFFFu / (uint32_t)span + 1u;   // wraps to 0 for span == 1
+        for (int pair = tid; pair < n * span; pair += kTileThreads) {
+          const int ci = span == 1 ? pair : (int)__umulhi((uint32_t)pair, span_inv);
           const int ent = clist[ci];
           const int e = e0 + (ent >> 4);
           const int w = ent & 15;
-          int q_lo = e - C - delta, q_hi = e - C + delta;
-          if (q_lo < p0) q_lo = p0;
-          if (q_hi > p1 - 1) q_hi = p1 - 1;
-          if (q_hi > L - C - 1) q_hi = L - C - 1;      // s_e = q + C must stay below L
-          for (int q = q_lo; q <= q_hi; ++q) {
+          const int q = e - C - delta + (pair - ci * span);
+          if (q >= p0 && q <= p1 - 1 && q <= L - C - 1) {   // s_e = q + C must stay below L
             const int s_e = q + C;
             const int dist = e > s_e ? e - s_e : s_e - e;
             const unsigned long long sc = (unsigned long long)(p.a_num * w * dd + (p.a_den - p.a_num) * 10 * (dd - dist));
@@ -306,59 +319,49 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
     const int nslot = (len + p.b - 1) / p.b;
     ns[i] = (uint16_t)nslot;
     // level-0 jump: one chunk.  position >= tlen means "left the tile" (i + len <= tlen + C + delta)
-    jpb[i] = (uint32_t)(i + len) | ((i < tlen ? 1u : 0u) << 16);
-    jcs[i] = (uint16_t)nslot;
+    jmp[i] = make_uint2((uint32_t)(i + len) | ((i < tlen ? 1u : 0u) << 16), (uint32_t)nslot);
   }
   if (MODE == 1 && tid == 0 && info.x >= p0 && info.x < p1) mark[info.x - p0] = 1;
   __syncthreads();
 
-  // pointer jumping: level r holds 2^r chunks per hop; positions that left the tile are fixed points
+  // pointer jumping: level r holds 2^r chunks per hop; positions that left the tile are fixed
+  // points.  Every chunk that does not end the sequence has at least C - delta positions, so the
+  // chain crosses the tile in at most ceil(tlen / (C - delta)) hops and as many doublings as cover
+  // that number finish every position: a fixed round count, no termination vote.
   int cur = 0;
-  // Three flags in rotation: round r raises flag r % 3 and reads it after the round's barrier,
-  // while thread 0 clears flag (r + 1) % 3 for the next round.  The flag a wavefront may still be
-  // reading after barrier r is therefore not cleared before round r + 2, i.e. after barrier r + 1,
-  // which that wavefront has passed by then.
-  int* any_active = red + 2 * kTileWaves;
-  if (tid == 0) { any_active[0] = 0; any_active[1] = 0; any_active[2] = 0; }
-  __syncthreads();
-  for (int round = 0; round < 16; ++round) {
-    int active = 0;
-    const uint32_t* ps = jpb + cur * kSegTile; uint32_t* pd = jpb + (cur ^ 1) * kSegTile;
-    const uint16_t* ss = jcs + cur * kSegTile; uint16_t* sd = jcs + (cur ^ 1) * kSegTile;
+  {
+    const int min_len = C - delta;                       // >= 1
+    const int hops = (tlen + min_len - 1) / min_len;
+    int rounds = 0;
+    while ((1 << rounds) < hops) ++rounds;
+    for (int round = 0; round < rounds; ++round) {
+      const uint2* js = jmp + cur * kSegTile;
+      uint2* jd = jmp + (cur ^ 1) * kSegTile;
 #pragma unroll
-    for (int r = 0; r < kSegPerThread; ++r) {
-      const int i = r * kTileThreads + tid;
-      const uint32_t v = ps[i];
-      const int t = (int)(v & 0xFFFFu);
-      uint32_t nv = v;
-      int nsl = ss[i];
-      if (i < tlen && t < tlen) {
-        if (MODE == 1 && mark[i]) mark[t] = 1;   // reachable set doubles with the hop length
-        const uint32_t v2 = ps[t];
-        nv = (v2 & 0xFFFFu) | ((v & 0xFFFF0000u) + (v2 & 0xFFFF0000u));
-        nsl += ss[t];
-        active = 1;
+      for (int r = 0; r < kSegPerThread; ++r) {
+        const int i = r * kTileThreads + tid;
+        uint2 v = js[i];
+        const int t = (int)(v.x & 0xFFFFu);
+        if (i < tlen && t < tlen) {
+          if (MODE == 1 && mark[i]) mark[t] = 1;   // reachable set doubles with the hop length
+          const uint2 v2 = js[t];
+          v = make_uint2((v2.x & 0xFFFFu) | ((v.x & 0xFFFF0000u) + (v2.x & 0xFFFF0000u)), v.y + v2.y);
+        }
+        jd[i] = v;
       }
-      pd[i] = nv;
-      sd[i] = (uint16_t)nsl;
+      cur ^= 1;
+      __syncthreads();
     }
-    cur ^= 1;
-    const int flag = round % 3;
-    if (active) any_active[flag] = 1;                       // everyone writes the same value
-    if (tid == 0) any_active[flag == 2 ? 0 : flag + 1] = 0; // last read before the previous barrier
-    __syncthreads();
-    if (!any_active[flag]) break;
   }
-  const uint32_t* fpb = jpb + cur * kSegTile;
-  const uint16_t* fcs = jcs + cur * kSegTile;
+  const uint2* fj = jmp + cur * kSegTile;
 
   if (MODE == 0) {
     uint2* row = tile_map + (int64_t)tile * p.map_row;
     for (int ent = tid; ent < p.map_row; ent += kTileThreads) {
       uint2 rv = make_uint2(0u, 0u);
       if (ent < tlen) {
-        const uint32_t v = fpb[ent];
-        rv = make_uint2(((v & 0xFFFFu) - (uint32_t)tlen) | (v & 0xFFFF0000u), (uint32_t)fcs[ent]);
+        const uint2 v = fj[ent];
+        rv = make_uint2(((v.x & 0xFFFFu) - (uint32_t)tlen) | (v.x & 0xFFFF0000u), v.y);
       }
       row[ent] = rv;
     }
@@ -424,7 +427,7 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
 // chunks: 24 bits, slots: 24 bits): a run is at most kChainLdsEntries / 2 tiles, each with at most
 // 2048 chunks or slots.  Search ranges wider than kChainFastSpan take the plain walk, one lookup
 // per tile.
-constexpr int kChainThreads = 512;
+constexpr int kChainThreads = 1024;
 constexpr int kChainFastSpan = 512;                      // C + delta up to here: >= 6 tiles per run
 static_assert((kChainLdsEntries / 2) * kSegTile < (1 << 24), "packed counts of a run");
 
@@ -463,19 +466,21 @@ __global__ __launch_bounds__(kChainThreads) void seg_chain_kernel(
       __syncthreads();
       constexpr int kPer = (kChainLdsEntries / 2 + kChainThreads - 1) / kChainThreads;
       uint2 ld[kPer];
+      int jj[kPer], ee[kPer];                             // tile of the run and entry offset of element i
 #pragma unroll
       for (int u = 0; u < kPer; ++u) {                    // the run's rows: one round trip, not kPer
         const int i = threadIdx.x + u * kChainThreads;
         ld[u] = src[i < n_ent ? i : 0];
+        jj[u] = p.map_row == 1 ? i : (int)__umulhi((uint32_t)i, inv);   // inv wraps to 0 for a divisor of 1
+        ee[u] = i - jj[u] * p.map_row;
       }
 #pragma unroll
       for (int u = 0; u < kPer; ++u) {
         const int i = threadIdx.x + u * kChainThreads;
         if (i < n_ent) {
-          const int j = (int)__umulhi((uint32_t)i, inv), e = i - j * p.map_row;
-          const int t0 = (j0 + j) * kSegTile;
+          const int t0 = (j0 + jj[u]) * kSegTile;
           const int tl = (t0 + kSegTile < L) ? kSegTile : L - t0;
-          cur[i] = e >= tl ? chain_pack(e - tl, 0, 0) : ld[u];   // beyond a short last tile: passes through
+          cur[i] = ee[u] >= tl ? chain_pack(ee[u] - tl, 0, 0) : ld[u];   // beyond a short last tile: passes through
         }
       }
       __syncthreads();
@@ -484,7 +489,7 @@ __global__ __launch_bounds__(kChainThreads) void seg_chain_kernel(
         for (int u = 0; u < kPer; ++u) {
           const int i = threadIdx.x + u * kChainThreads;
           if (i < n_ent) {
-            const int j = (int)__umulhi((uint32_t)i, inv), e = i - j * p.map_row;
+            const int j = jj[u], e = ee[u];
             uint2 v = cur[i];
             if (j >= d) {                                 // tiles j-2d+1 .. j-d first, then j-d+1 .. j
               const uint2 a = cur[(j - d) * p.map_row + e];
