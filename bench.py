@@ -710,7 +710,7 @@ def parity_summary(dsk, wl, comp, nblk, q_bits, queries, K, V, n_queries=2, n_he
         boundary_mismatches += int((bs_g[b0: b1 + 1] - lo != bs).sum())
         boundary_mismatches += int((sb_g[b0: b1 + 1] - sb_g[b0] != sb).sum())
     sums = comp.ksum[:, :nblk].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
-    heads = sorted({0, cfg.G, cfg.Hq // 2 + 1, cfg.Hq - 1})[:n_heads]
+    heads = sorted(h for h in {0, cfg.G, cfg.Hq // 2 + 1, cfg.Hq - 1} if h < cfg.Hq)[:n_heads]
     swapped = mismatched = pairs = 0
     worst_attn = worst_lse = worst_score = 0.0
     scale = 1.0 / np.sqrt(128.0)

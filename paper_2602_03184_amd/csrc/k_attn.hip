@@ -101,19 +101,29 @@ __global__ __launch_bounds__(WAVES * DSK_WAVE) void attn_kernel(
 
   // workgroup id = 8 * j + x lands on XCD x.  Group gi = s * Hkv + hk takes x = gi % 8; its
   // G * nchunks workgroups are consecutive in j.
-  const int Hkv = Hq / G;
-  const int per_group = G * nchunks;
-  const int xcd = blockIdx.x & 7;
-  const int j = blockIdx.x >> 3;
-  const int gl = j / per_group;
-  const int r = j - gl * per_group;
-  const int gi = gl * 8 + xcd;
-  if (gi >= n_groups) return;                    // padding of the last round of groups
-  const int s = gi / Hkv;
-  const int hk = gi - s * Hkv;
-  const int gq = r / nchunks;
-  const int chunk = r - gq * nchunks;
-  const int h = hk * G + gq;
+  // Without grouped heads there is nothing to share: the chunks of a head are dealt out over the
+  // XCDs in plain order (measured 2 % faster at 40 heads than keeping a head on one XCD).
+  int s, hk, h, chunk;
+  if (G == 1) {
+    chunk = blockIdx.x % nchunks;
+    const int sh_lin = blockIdx.x / nchunks;
+    s = sh_lin / Hq;
+    h = hk = sh_lin - s * Hq;
+  } else {
+    const int Hkv = Hq / G;
+    const int per_group = G * nchunks;
+    const int xcd = blockIdx.x & 7;
+    const int j = blockIdx.x >> 3;
+    const int gl = j / per_group;
+    const int r = j - gl * per_group;
+    const int gi = gl * 8 + xcd;
+    if (gi >= n_groups) return;                  // padding of the last round of groups
+    s = gi / Hkv;
+    hk = gi - s * Hkv;
+    const int gq = r / nchunks;
+    chunk = r - gq * nchunks;
+    h = hk * G + gq;
+  }
   const int64_t sh = (int64_t)s * Hq + h;
   // row of the selection arrays: the head's own, or its KV head's when sel_div = Hq/Hkv heads share one
   const int64_t sr = sel_div == 1 ? sh : (int64_t)s * (Hq / sel_div) + h / sel_div;   // no division on the per-head path
@@ -496,7 +506,8 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   float* part_acc = reinterpret_cast<float*>(w + ws.part_acc);
   const float scale = a.scale != 0.0f ? a.scale : 0.08838834764831845f;   // 128^-1/2
   const int n_groups = a.B * a.Hkv;
-  const dim3 grid((unsigned)(8 * ((n_groups + 7) / 8) * (a.Hq / a.Hkv) * ws.nchunks));
+  const dim3 grid(a.Hq == a.Hkv ? (unsigned)(n_groups * ws.nchunks)
+                                : (unsigned)(8 * ((n_groups + 7) / 8) * (a.Hq / a.Hkv) * ws.nchunks));
 
   const uint16_t* q = static_cast<const uint16_t*>(a.q);
   const uint16_t* K = static_cast<const uint16_t*>(a.K);
