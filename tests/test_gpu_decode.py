@@ -48,7 +48,7 @@ def _seqs_to_check(cfg):
     return list(range(cfg.B)) if cfg.B <= 2 else [0, cfg.B // 2, cfg.B - 1]
 
 
-def _check_decode(case, n_q, seqs, heads, label, **select_kw):
+def _check_decode(case, n_q, seqs, heads, label, all_heads_first_query=False, **select_kw):
     """Scores, slot sets, spans and attention of the GPU path against the oracle for the given
     sequences and query heads."""
     dsk = _dsk()
@@ -71,6 +71,9 @@ def _check_decode(case, n_q, seqs, heads, label, **select_kw):
         g_scores = sel.scores.cpu().numpy()
         g_out = att.out.cpu().numpy()
         g_lse = att.lse.cpu().numpy()
+        # the first query is checked on every query head when the summaries of all KV heads are
+        # themselves compared with the oracle (up to 8 KV heads), the others on the sampled heads
+        heads_q = list(range(cfg.Hq)) if (all_heads_first_query and qi == 0 and cfg.Hkv <= 8) else heads
         for s in seqs:
             b0, b1 = int(seg.cu_blocks[s]), int(seg.cu_blocks[s + 1])
             sb = seg.slot_base[b0: b1 + 1]
@@ -79,8 +82,8 @@ def _check_decode(case, n_q, seqs, heads, label, **select_kw):
                 assert (g_cnt[s] == 0).all() and (g_slot[s] == -1).all()
                 assert (g_out[s] == 0).all() and np.isneginf(g_lse[s]).all()
                 continue
-            osc = _oracle_scores(case, kmin_bits, kmax_bits, q_bits, s, heads)
-            for h in heads:
+            osc = _oracle_scores(case, kmin_bits, kmax_bits, q_bits, s, heads_q)
+            for h in heads_q:
                 # a6: fp32 scores against fp64
                 np.testing.assert_allclose(g_scores[h, b0:b1], osc[h], rtol=2e-5, atol=2e-4)
                 # a7: slot set
@@ -115,7 +118,8 @@ def _check_decode(case, n_q, seqs, heads, label, **select_kw):
 def test_select_and_attention_parity(cfg_id):
     case = gpu_case(cfg_id)
     cfg = case.cfg
-    _check_decode(case, min(cfg.n_queries, 3), _seqs_to_check(cfg), _heads_to_check(cfg), "cfg%d" % cfg_id)
+    _check_decode(case, min(cfg.n_queries, 3), _seqs_to_check(cfg), _heads_to_check(cfg), "cfg%d" % cfg_id,
+                  all_heads_first_query=True)
 
 
 def test_many_short_sequences_share_score_groups():
