@@ -311,3 +311,24 @@ def test_unordered_candidate_list_is_reported():
     dup_pos[7] = dup_pos[6]
     dup, _, _, _ = _segment_from_lists([L], [(dup_pos, cls)], wq, C, delta, 5, 10, b)
     assert int(dup.dev_status.item()) == dsk.DSK_ERR_ORDER
+
+
+@pytest.mark.parametrize("n_class,C,delta", [(1, 24, 12), (3, 7, 3), (5, 30, 0), (63, 100, 99), (64, 2, 1), (17, 900, 600)])
+def test_tiles_classify_their_own_tokens(n_class, C, delta):
+    """Candidates from token ids with no list asked for: the segmentation tiles compare the tokens
+    in their reach with the delimiter ids themselves.  Class counts that are not multiples of the
+    ids' vector width, search ranges from none to wider than a tile's vote window, a ragged batch
+    with an empty and a one-token sequence: tables equal the oracle's and those of the call that
+    goes through the candidate lists."""
+    dsk = _dsk()
+    case = gpu_case(5, B=5, seqlens=[4100, 0, 1, 2047, 9000], n_class=n_class, C=C, delta=delta,
+                    gap_means=[max(2, C // 2)], Hq=2, Hkv=1)
+    full = case.compressed()
+    lean = dsk.compress(**case.compress_kwargs(
+        stages=dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_SEGMENT | dsk.DSK_STAGE_SUMMARIES,
+        token_ids=case.token_ids, delim_ids=case.delim_ids, want_candidates=False))
+    torch.cuda.synchronize()
+    _check_tables(full, case.seg)
+    _check_tables(lean, case.seg)
+    nb = int(case.seg.cu_blocks[-1])
+    assert torch.equal(lean.ksum[:, :nb], full.ksum[:, :nb])
