@@ -30,6 +30,7 @@ CompressWs compress_ws_layout(const dsk_compress_args& a) {
   ws.cls_at = off;     off += align_up((size_t)a.total_tokens + 16);
   ws.seg_len = off;    off += align_up(((size_t)a.total_tokens + 16) * sizeof(uint16_t));
   ws.tile_count = off; off += align_up(((size_t)ws.n_cand_tiles + 1) * sizeof(int32_t));
+  ws.seg_cand = off;   off += align_up(2 * n_tiles * sizeof(int32_t));
   const size_t n_samp = (size_t)a.B * (a.n_class > 0 ? a.n_class : 0) * (a.M > 0 ? a.M : 0);
   ws.imp_part = off;   off += align_up(n_samp * (size_t)a.Hkv * 2 * sizeof(float));
   ws.total = off;
@@ -357,14 +358,20 @@ dsk_status dsk_compress(const dsk_compress_args* a, void* stream) {
   const bool st_cand = (a->stages & DSK_STAGE_CANDIDATES) != 0;
   const bool no_lists = st_cand && (a->stages & DSK_STAGE_SEGMENT) && a->cand_pos == nullptr &&
                         a->cand_class == nullptr && a->max_cand_total == 0;
-  if (st_cand && !no_lists)
+  // lists wanted, and the segmentation of this call does not wait for weights computed from them:
+  // the segmentation kernels classify, count and write the lists on their way (three launches less)
+  const bool lists_by_segment = st_cand && !no_lists && (a->stages & DSK_STAGE_SEGMENT) &&
+                                !(a->stages & DSK_STAGE_IMPORTANCE);
+  if (st_cand && !no_lists && !lists_by_segment)
     if (launch_candidates(*a, ws, st) != hipSuccess) return DSK_ERR_LAUNCH;
   if (a->stages & DSK_STAGE_IMPORTANCE)
     if (launch_importance(*a, ws, st) != hipSuccess) return DSK_ERR_LAUNCH;
   if (a->stages & DSK_STAGE_SEGMENT) {
     const SegClassSource src = no_lists ? SegClassSource::kTokenIds
+                               : lists_by_segment ? SegClassSource::kTokenIdsWithLists
                                : (st_cand ? SegClassSource::kClassBytes : SegClassSource::kCallerLists);
     if (launch_segment(*a, ws, src, st) != hipSuccess) return DSK_ERR_LAUNCH;
+    if (lists_by_segment && launch_cand_sample(*a, st) != hipSuccess) return DSK_ERR_LAUNCH;
   }
   if (a->stages & DSK_STAGE_SUMMARIES)
     if (launch_summaries(*a, st) != hipSuccess) return DSK_ERR_LAUNCH;

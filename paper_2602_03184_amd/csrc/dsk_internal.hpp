@@ -26,6 +26,7 @@ struct CompressWs {
   size_t cls_at;      // u8  [total_tokens]          dense class of each token, 255 = none
   size_t seg_len;     // u16 [total_tokens]          length of the chunk that would start at each position
   size_t tile_count;  // i32 [n_cand_tiles + 1]      candidates per tile, then exclusive scan
+  size_t seg_cand;    // i32 [2 * n_tiles]           candidates per segmentation tile, then their offsets in the sequence
   size_t imp_part;    // f32 [B * n_class * M * Hkv] per-(sample, kv head) partial sums
   size_t total;
   int tiles_per_seq;  // ceil(max_seqlen / kSegTile)
@@ -40,8 +41,11 @@ hipError_t launch_importance(const dsk_compress_args& a, const CompressWs& ws, h
 enum class SegClassSource {
   kClassBytes,    // dense class bytes in the workspace, just written by launch_candidates
   kCallerLists,   // the caller's candidate lists (scattered into the class bytes first)
-  kTokenIds       // token_ids / delim_ids, classified inside the tile kernel (no lists were asked for)
+  kTokenIds,      // token_ids / delim_ids, classified inside the tile kernel (no lists were asked for)
+  kTokenIdsWithLists   // as kTokenIds, and the segmentation kernels also write the candidate lists
 };
+// the per-class samples of Alg. 1 from finished candidate lists
+hipError_t launch_cand_sample(const dsk_compress_args& a, hipStream_t st);
 hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, SegClassSource src, hipStream_t st);
 hipError_t launch_summaries(const dsk_compress_args& a, hipStream_t st);
 

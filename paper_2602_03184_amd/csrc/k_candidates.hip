@@ -181,11 +181,15 @@ hipError_t launch_candidates(const dsk_compress_args& a, const CompressWs& ws, h
         cls_at, a.total_tokens, tile_count, a.max_cand_total, a.cand_pos, a.cand_class);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
+  return launch_cand_sample(a, st);
+}
+
+hipError_t launch_cand_sample(const dsk_compress_args& a, hipStream_t st) {
   if (a.samp_pos != nullptr && a.M > 0) {
     cand_sample_kernel<<<dim3((unsigned)a.n_class, (unsigned)a.B), dim3(DSK_WAVE), 0, st>>>(
         a.cand_pos, a.cand_class, a.cand_cu, a.cu_seqlens, a.n_class, a.M, a.R, a.W, a.max_cand_total,
         a.samp_pos);
-    if ((err = hipGetLastError()) != hipSuccess) return err;
+    return hipGetLastError();
   }
   return hipSuccess;
 }

@@ -42,6 +42,20 @@ struct SegParams {
   int B, cap;
 };
 
+// Candidate lists produced by the segmentation kernels themselves (stage CANDIDATES and stage
+// SEGMENT in one call, weights from a table): the first tile pass classifies and counts the
+// positions of its tile, the chain kernel turns the counts into list offsets, the emit pass
+// writes the lists.  tile_count == nullptr: no lists are produced here.
+struct SegCand {
+  uint8_t* own_cls;        // [total_tokens] class byte of every token (workspace)
+  int32_t* tile_count;     // [B * tiles_per_seq] candidates of a tile (workspace)
+  int32_t* tile_base;      // [B * tiles_per_seq] candidates of the sequence in front of a tile (workspace)
+  int32_t* cand_cu;        // [B + 1] output
+  int32_t* cand_pos;       // [max_cand] output
+  uint8_t* cand_class;     // [max_cand] output
+  int max_cand;
+};
+
 // first token and length of sequence s.  A batch of one sequence is [0, total_tokens) by the
 // host's copy of cu_seqlens, which saves every kernel of the chain a dependent memory round trip.
 __device__ __forceinline__ void seq_range(const SegParams& p, int s, int& seq0, int& L) {
@@ -104,6 +118,98 @@ __global__ __launch_bounds__(256) void seg_scatter_kernel(
   }
 }
 
+// ---- chain: shared by the chain kernel and the emit pass that does its own chaining -----------------
+// Entry maps are functions (entry offset into a tile) -> (entry offset into the next tile, chunks
+// and slots laid down on the way), so the walk from tile to tile is a prefix "sum" under function
+// composition and runs as a doubling scan: after round r, row j holds the composite of tiles
+// j - 2^r + 1 .. j.  Rows are staged in LDS, kChainLdsEntries / 2 entries per buffer; longer
+// sequences are cut into runs of tiles that pass a carry.  An LDS entry packs (offset: 16 bits,
+// chunks: 24 bits, slots: 24 bits): a run is at most kChainLdsEntries / 2 tiles, each with at most
+// 2048 chunks or slots.  Search ranges wider than kChainFastSpan take the plain walk, one lookup
+// per tile.
+constexpr int kChainThreads = 1024;
+constexpr int kChainFastSpan = 512;                      // C + delta up to here: >= 6 tiles per run
+static_assert((kChainLdsEntries / 2) * kSegTile < (1 << 24), "packed counts of a run");
+
+__device__ __forceinline__ int chain_off(uint2 v) { return (int)(v.x & 0xFFFFu); }
+__device__ __forceinline__ int chain_blocks(uint2 v) { return (int)((v.x >> 16) | ((v.y >> 24) << 16)); }
+__device__ __forceinline__ int chain_slots(uint2 v) { return (int)(v.y & 0xFFFFFFu); }
+__device__ __forceinline__ uint2 chain_pack(int off, int blocks, int slots) {
+  return make_uint2((uint32_t)off | ((uint32_t)(blocks & 0xFFFF) << 16),
+                    (uint32_t)slots | ((uint32_t)(blocks >> 16) << 24));
+}
+
+
+// Stages the entry maps of tiles j0 .. j0 + T - 1 of a sequence of L positions in `cur` and runs the
+// doubling scan; on return row j of the returned buffer maps an entry offset of tile j0 to the state
+// behind tile j0 + j.  T * map_row <= kChainLdsEntries / 2, map_row <= kChainFastSpan, called by
+// all kChainThreads threads of the workgroup.
+__device__ __forceinline__ uint2* chain_scan_run(const uint2* __restrict__ src, int L, int j0, int T, int map_row,
+                                                 uint2* cur, uint2* nxt) {
+  // i / map_row without a division: inv = floor(2^32 / map_row) + 1 is exact for i * map_row < 2^32
+  const uint32_t inv = 0xFFFFFFFFu / (uint32_t)map_row + 1u;
+  const int n_ent = T * map_row;
+  constexpr int kPer = (kChainLdsEntries / 2 + kChainThreads - 1) / kChainThreads;
+  uint2 ld[kPer];
+  int jj[kPer], ee[kPer];                             // tile of the run and entry offset of element i
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {                    // the run's rows: one round trip, not kPer
+    const int i = threadIdx.x + u * kChainThreads;
+    ld[u] = src[i < n_ent ? i : 0];
+    jj[u] = map_row == 1 ? i : (int)__umulhi((uint32_t)i, inv);   // inv wraps to 0 for a divisor of 1
+    ee[u] = i - jj[u] * map_row;
+  }
+#pragma unroll
+  for (int u = 0; u < kPer; ++u) {
+    const int i = threadIdx.x + u * kChainThreads;
+    if (i < n_ent) {
+      const int t0 = (j0 + jj[u]) * kSegTile;
+      const int tl = (t0 + kSegTile < L) ? kSegTile : L - t0;
+      cur[i] = ee[u] >= tl ? chain_pack(ee[u] - tl, 0, 0) : ld[u];   // beyond a short last tile: passes through
+    }
+  }
+  __syncthreads();
+  for (int d = 1; d < T; d <<= 1) {
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      const int i = threadIdx.x + u * kChainThreads;
+      if (i < n_ent) {
+        const int j = jj[u], e = ee[u];
+        uint2 v = cur[i];
+        if (j >= d) {                                 // tiles j-2d+1 .. j-d first, then j-d+1 .. j
+          const uint2 a = cur[(j - d) * map_row + e];
+          const uint2 c = cur[j * map_row + chain_off(a)];
+          v = chain_pack(chain_off(c), chain_blocks(a) + chain_blocks(c), chain_slots(a) + chain_slots(c));
+        }
+        nxt[i] = v;
+      }
+    }
+    __syncthreads();
+    uint2* t = cur; cur = nxt; nxt = t;
+  }
+  return cur;
+}
+
+// class index of N token ids against the delimiter ids staged in LDS (padded to a multiple of 4
+// entries); the lowest class index wins, as in the candidate stage; 255 = not a delimiter
+template <int N>
+__device__ __forceinline__ void classify_tokens(const int (&tok)[N], int (&cls)[N], const int32_t* ids, int n_class) {
+#pragma unroll
+  for (int r = 0; r < N; ++r) cls[r] = 255;
+  for (int c4 = (n_class - 1) / 4 * 4; c4 >= 0; c4 -= 4) {
+    const int4 id4 = *reinterpret_cast<const int4*>(ids + c4);      // LDS broadcast read
+    const int idv[4] = {id4.x, id4.y, id4.z, id4.w};
+#pragma unroll
+    for (int cc = 3; cc >= 0; --cc) {
+      const int c = c4 + cc;
+      if (c < n_class) {
+#pragma unroll
+        for (int r = 0; r < N; ++r) cls[r] = tok[r] == idv[cc] ? c : cls[r];
+      }
+    }
+  }
+}
+
 // ---- tile kernel -----------------------------------------------------------------------------
 // dynamic LDS layout (bytes):
 //   best  u64 [kSegTile]       votes; dead after the successor table is built,
@@ -114,29 +220,36 @@ __global__ __launch_bounds__(256) void seg_scatter_kernel(
 //   mark  u8  [kSegTile]       (emit mode) reachable from the tile's entry
 //   wq    u8  [64]             class -> weight tenths of this sequence
 //   red   i32 [40], then the delimiter ids i32 [64]
+constexpr size_t kTileJumpBytes =    // jump entries; the vote array (8 bytes per position) and, in the emit pass
+    (size_t)kSegTile * 16 > (size_t)kChainLdsEntries * 8 ? (size_t)kSegTile * 16     // that chains for itself, the two
+                                                        : (size_t)kChainLdsEntries * 8;   // buffers of the chain scan overlay them
 __host__ __device__ constexpr size_t seg_tile_lds_bytes() {
-  return (size_t)kSegTile * 16      // jump entries (the vote array, 8 bytes per position, overlays them)
+  return kTileJumpBytes
          + (size_t)kSegTile * 2     // ns
          + (size_t)kSegTile         // mark
          + 64 + 448;                // wq, red (reduction words, then 64 delimiter ids)
 }
 static_assert(2 * kTileWaves + 3 <= 40 && (40 + 64) * 4 <= 448, "red fits its slot");
+static_assert(kChainThreads == kTileThreads, "the emit pass runs the chain scan with its own workgroup");
 
 // MODE 0 (entry maps): the successor of every position comes from the votes of the delimiters in
 // reach -- read as class bytes (cls_at), or, when cls_at is NULL, classified here from token_ids /
 // delim_ids -- and the chunk lengths found are kept in seg_len for MODE 1 (emit), which starts from
-// them and casts no vote.
+// them and casts no vote.  MODE 2 is the emit pass of a single sequence whose entry maps fit one run of
+// the chain scan: every workgroup chains the tiles in front of its own by itself, so the chain
+// kernel is not launched; the workgroup of the last tile also writes the totals.
 template <int MODE>
 __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
-    SegParams p, const uint8_t* __restrict__ cls_at, const int32_t* __restrict__ token_ids,
+    SegParams p, SegCand cand, const uint8_t* __restrict__ cls_at, const int32_t* __restrict__ token_ids,
     const int32_t* __restrict__ delim_ids, uint16_t* __restrict__ seg_len, uint2* __restrict__ tile_map,
-    const int4* __restrict__ tile_info, const int4* __restrict__ seq_info, int32_t* __restrict__ block_start,
-    int32_t* __restrict__ slot_base, int32_t* dev_status) {
+    const int4* __restrict__ tile_info, const int4* __restrict__ seq_info, int32_t* __restrict__ cu_blocks,
+    int32_t* __restrict__ cu_slots, int32_t* __restrict__ block_start, int32_t* __restrict__ slot_base,
+    int32_t* dev_status) {
   extern __shared__ __align__(16) unsigned char smem[];
   // jump entries (16 * kSegTile bytes) share storage with the vote array (8 * kSegTile bytes)
   unsigned long long* best = reinterpret_cast<unsigned long long*>(smem);
   uint2* jmp = reinterpret_cast<uint2*>(smem);                    // [2][kSegTile]
-  uint16_t* ns = reinterpret_cast<uint16_t*>(jmp + 2 * kSegTile); // [kSegTile] slots of the chunk starting here
+  uint16_t* ns = reinterpret_cast<uint16_t*>(smem + kTileJumpBytes); // [kSegTile] slots of the chunk starting here
   uint8_t* mark = reinterpret_cast<uint8_t*>(ns + kSegTile);
   uint8_t* wq = mark + kSegTile;
   int* red = reinterpret_cast<int*>(wq + 64);
@@ -160,11 +273,23 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
     info = tile_info[tile];
     sq = seq_info[s];
   }
+  // MODE 2: one sequence, so its block and slot bases (sq) are zero, and info comes from the scan below
   int C, delta;
   seq_params(p, s, C, delta, dev_status);
   const int dd = delta > 1 ? delta : 1;
 
   int my_len[kSegPerThread];
+  int oc1[kSegPerThread];            // (emit, candidate lists) class bytes of the tile's positions
+  int cand_o = 0;                    // list offset of the tile's first candidate
+  if (MODE != 0 && cand.tile_count != nullptr) {
+#pragma unroll
+    for (int r = 0; r < kSegPerThread; ++r) {
+      const int i = r * kTileThreads + tid;
+      oc1[r] = cand.own_cls[seq0 + p0 + (i < tlen ? i : 0)];
+    }
+    if (MODE == 1) cand_o = cand.tile_base[tile] + (p.B == 1 ? 0 : cand.cand_cu[s]);
+    else cand_o = tid < j ? cand.tile_count[tile - j + tid] : 0;     // summed below; j < kTileThreads
+  }
   if (MODE == 0) {
     // the class bytes (or token ids) of the first kVoteChunk boundaries in reach go out before
     // anything is waited for: they travel with the weight and delimiter-id loads below
@@ -181,6 +306,17 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
       e = e >= 1 ? e : 1;                              // e_hi >= 1 whenever the tile has a position
       first[r] = cls_at != nullptr ? (int)cls_at[seq0 + e - 1] : token_ids[seq0 + e - 1];
     }
+    // candidate lists from this pass: the tile's own positions are classified as well (the
+    // boundaries above start C - delta positions further on)
+    const bool own = cand.tile_count != nullptr;
+    int own_tok[kSegPerThread];
+    if (own) {
+#pragma unroll
+      for (int r = 0; r < kSegPerThread; ++r) {
+        const int i = r * kTileThreads + tid;
+        own_tok[r] = token_ids[seq0 + p0 + (i < tlen ? i : 0)];
+      }
+    }
     if (tid < 64) {
       int w = tid < p.n_class ? p.class_weight_q[s * p.n_class + tid] : 0;
       if (w > 10) { set_status(dev_status, DSK_ERR_PARAM); w = 10; }
@@ -194,6 +330,19 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
     int32_t* ids = red + 40;                                          // 64 ints behind the reduction words
     if (cls_at == nullptr && tid < 64) ids[tid] = delim_ids[tid < p.n_class ? tid : 0];
     __syncthreads();
+
+    if (own) {
+      int oc[kSegPerThread];
+      classify_tokens<kSegPerThread>(own_tok, oc, ids, p.n_class);
+      int n_wave = 0;
+#pragma unroll
+      for (int r = 0; r < kSegPerThread; ++r) {
+        const int i = r * kTileThreads + tid;
+        if (i < tlen) cand.own_cls[seq0 + p0 + i] = (uint8_t)oc[r];
+        n_wave += __popcll(__ballot(i < tlen && oc[r] != 255));
+      }
+      if ((tid & (DSK_WAVE - 1)) == 0) red[4 + tid / DSK_WAVE] = n_wave;   // summed once the barriers below have passed
+    }
 
     // votes: boundary e (offered by a delimiter at e-1) can end a chunk that starts at q with
     // s_e = q + C in [e - delta, e + delta] and s_e < L.  key = score << 16 | (0xFFFF - (e - q)):
@@ -221,20 +370,7 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
             e = e <= e_hi ? e : e_hi;
             tok[r] = e0 == e_lo ? first[r] : token_ids[seq0 + e - 1];
           }
-#pragma unroll
-          for (int r = 0; r < kPerThread; ++r) cb_[r] = 255;
-          for (int c4 = (p.n_class - 1) / 4 * 4; c4 >= 0; c4 -= 4) {   // lowest class index wins, as in the candidate stage
-            const int4 id4 = *reinterpret_cast<const int4*>(ids + c4);      // LDS broadcast read
-            const int idv[4] = {id4.x, id4.y, id4.z, id4.w};
-#pragma unroll
-            for (int cc = 3; cc >= 0; --cc) {
-              const int c = c4 + cc;
-              if (c < p.n_class) {
-#pragma unroll
-                for (int r = 0; r < kPerThread; ++r) cb_[r] = tok[r] == idv[cc] ? c : cb_[r];
-              }
-            }
-          }
+          classify_tokens<kPerThread>(tok, cb_, ids, p.n_class);
         }
         // compaction: position of each delimiter inside its wavefront from ballots, one LDS
         // reservation per wavefront
@@ -310,8 +446,77 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
       my_len[r] = i < tlen ? (int)seg_len[seq0 + p0 + i] : 0;
     }
     for (int i = tid; i < kSegTile; i += kTileThreads) mark[i] = 0;
+    if (cand.tile_count != nullptr) {
+      // rank of every candidate of the tile: positions are owned interleaved (i = r * threads +
+      // tid), so the order is row r, then wavefront, then lane
+      const int lane = tid & (DSK_WAVE - 1), wave = tid / DSK_WAVE;
+      int* cnt = red + 40;                                 // [kSegPerThread][kTileWaves]; the id slots are free in this mode
+      unsigned long long bal[kSegPerThread];
+#pragma unroll
+      for (int r = 0; r < kSegPerThread; ++r) {
+        const int i = r * kTileThreads + tid;
+        bal[r] = __ballot(i < tlen && oc1[r] != 255);
+        if (lane == 0) cnt[r * kTileWaves + wave] = __popcll(bal[r]);
+      }
+      if (MODE == 2) {                                     // candidates of the tiles in front of this one
+        const int part = wave_sum_i(cand_o);
+        if (lane == 0) cnt[kSegPerThread * kTileWaves + wave] = part;
+      }
+      __syncthreads();
+      if (MODE == 2) {
+        cand_o = 0;
+#pragma unroll
+        for (int w = 0; w < kTileWaves; ++w) cand_o += cnt[kSegPerThread * kTileWaves + w];
+      }
+      static_assert(kSegPerThread * kTileWaves <= DSK_WAVE && (kSegPerThread + 1) * kTileWaves <= 64,
+                    "one lane per (row, wavefront) count; the counts fit the id slots");
+      const int c = lane < kSegPerThread * kTileWaves ? cnt[lane] : 0;
+      const int ex = wave_incl_scan_i(c, lane) - c;
+      if (MODE == 2 && tid == DSK_WAVE - 1 && p0 + kSegTile >= L) {   // last tile: ex + c is the tile's count
+        cand.cand_cu[0] = 0;
+        cand.cand_cu[1] = cand_o + ex + c;
+        if (cand_o + ex + c > cand.max_cand) set_status(dev_status, DSK_ERR_CAPACITY);
+      }
+#pragma unroll
+      for (int r = 0; r < kSegPerThread; ++r) {
+        const int o = cand_o + __builtin_amdgcn_readlane(ex, r * kTileWaves + wave) +
+                      __popcll(bal[r] & ((1ull << lane) - 1ull));
+        if (((bal[r] >> lane) & 1ull) && o < cand.max_cand) {
+          cand.cand_pos[o] = seq0 + p0 + r * kTileThreads + tid;
+          cand.cand_class[o] = (uint8_t)oc1[r];
+        }
+      }
+    }
   }
   __syncthreads();
+  if (MODE == 2) {
+    // the tiles in front of this one, chained here: the scan buffers lie where the jump entries
+    // are built afterwards
+    const int n_tiles = (L + kSegTile - 1) / kSegTile;
+    const bool last = j == n_tiles - 1;
+    const int T = last ? j + 1 : j;
+    uint2* rows = reinterpret_cast<uint2*>(smem);
+    const uint2* fin = rows;
+    if (T > 0)
+      fin = chain_scan_run(tile_map + (int64_t)s * p.tiles_per_seq * p.map_row, L, 0, T, p.map_row, rows,
+                           rows + kChainLdsEntries / 2);
+    int e = 0, blk = 0, sl = 0;
+    if (j > 0) {
+      const uint2 c = fin[(j - 1) * p.map_row];
+      e = chain_off(c); blk = chain_blocks(c); sl = chain_slots(c);
+    }
+    info = make_int4(p0 + e, blk, sl, 0);
+    if (last && tid == 0) {
+      const uint2 c = fin[j * p.map_row];
+      const int nb = chain_blocks(c), nsl = chain_slots(c);
+      cu_blocks[0] = 0;
+      cu_blocks[1] = nb;
+      if (cu_slots) { cu_slots[0] = 0; cu_slots[1] = nsl; }
+      if (nb > p.cap) set_status(dev_status, DSK_ERR_CAPACITY);
+      else { block_start[nb] = p.total_tokens; slot_base[nb] = nsl; }
+    }
+    __syncthreads();
+  }
 #pragma unroll
   for (int r = 0; r < kSegPerThread; ++r) {
     const int i = r * kTileThreads + tid;
@@ -321,7 +526,7 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
     // level-0 jump: one chunk.  position >= tlen means "left the tile" (i + len <= tlen + C + delta)
     jmp[i] = make_uint2((uint32_t)(i + len) | ((i < tlen ? 1u : 0u) << 16), (uint32_t)nslot);
   }
-  if (MODE == 1 && tid == 0 && info.x >= p0 && info.x < p1) mark[info.x - p0] = 1;
+  if (MODE != 0 && tid == 0 && info.x >= p0 && info.x < p1) mark[info.x - p0] = 1;
   __syncthreads();
 
   // pointer jumping: level r holds 2^r chunks per hop; positions that left the tile are fixed
@@ -343,7 +548,7 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
         uint2 v = js[i];
         const int t = (int)(v.x & 0xFFFFu);
         if (i < tlen && t < tlen) {
-          if (MODE == 1 && mark[i]) mark[t] = 1;   // reachable set doubles with the hop length
+          if (MODE != 0 && mark[i]) mark[t] = 1;   // reachable set doubles with the hop length
           const uint2 v2 = js[t];
           v = make_uint2((v2.x & 0xFFFFu) | ((v.x & 0xFFFF0000u) + (v2.x & 0xFFFF0000u)), v.y + v2.y);
         }
@@ -356,6 +561,12 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
   const uint2* fj = jmp + cur * kSegTile;
 
   if (MODE == 0) {
+    if (cand.tile_count != nullptr && tid == 0) {
+      int n = 0;
+#pragma unroll
+      for (int w = 0; w < kTileWaves; ++w) n += red[4 + w];
+      cand.tile_count[tile] = n;
+    }
     uint2* row = tile_map + (int64_t)tile * p.map_row;
     for (int ent = tid; ent < p.map_row; ent += kTileThreads) {
       uint2 rv = make_uint2(0u, 0u);
@@ -418,33 +629,13 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
   }
 }
 
-// ---- chain ----------------------------------------------------------------------------------
-// Entry maps are functions (entry offset into a tile) -> (entry offset into the next tile, chunks
-// and slots laid down on the way), so the walk from tile to tile is a prefix "sum" under function
-// composition and runs as a doubling scan: after round r, row j holds the composite of tiles
-// j - 2^r + 1 .. j.  Rows are staged in LDS, kChainLdsEntries / 2 entries per buffer; longer
-// sequences are cut into runs of tiles that pass a carry.  An LDS entry packs (offset: 16 bits,
-// chunks: 24 bits, slots: 24 bits): a run is at most kChainLdsEntries / 2 tiles, each with at most
-// 2048 chunks or slots.  Search ranges wider than kChainFastSpan take the plain walk, one lookup
-// per tile.
-constexpr int kChainThreads = 1024;
-constexpr int kChainFastSpan = 512;                      // C + delta up to here: >= 6 tiles per run
-static_assert((kChainLdsEntries / 2) * kSegTile < (1 << 24), "packed counts of a run");
-
-__device__ __forceinline__ int chain_off(uint2 v) { return (int)(v.x & 0xFFFFu); }
-__device__ __forceinline__ int chain_blocks(uint2 v) { return (int)((v.x >> 16) | ((v.y >> 24) << 16)); }
-__device__ __forceinline__ int chain_slots(uint2 v) { return (int)(v.y & 0xFFFFFFu); }
-__device__ __forceinline__ uint2 chain_pack(int off, int blocks, int slots) {
-  return make_uint2((uint32_t)off | ((uint32_t)(blocks & 0xFFFF) << 16),
-                    (uint32_t)slots | ((uint32_t)(blocks >> 16) << 24));
-}
-
 __global__ __launch_bounds__(kChainThreads) void seg_chain_kernel(
-    SegParams p, const uint2* __restrict__ tile_map, int4* __restrict__ tile_info,
+    SegParams p, SegCand cand, const uint2* __restrict__ tile_map, int4* __restrict__ tile_info,
     int4* __restrict__ seq_info, int32_t* __restrict__ cu_blocks, int32_t* __restrict__ cu_slots,
     int32_t* __restrict__ block_start, int32_t* __restrict__ slot_base, int32_t* dev_status) {
   __shared__ uint2 rows[kChainLdsEntries];
   __shared__ int carry[3];
+  __shared__ int cand_wave[kChainThreads / DSK_WAVE];
   const int s = blockIdx.x;
   int seq0, L;
   seq_range(p, s, seq0, L);
@@ -452,56 +643,46 @@ __global__ __launch_bounds__(kChainThreads) void seg_chain_kernel(
   int n_tiles = (L + kSegTile - 1) / kSegTile;
   if (n_tiles > p.tiles_per_seq) n_tiles = p.tiles_per_seq;
   if (threadIdx.x == 0) { carry[0] = 0; carry[1] = 0; carry[2] = 0; }
+  if (cand.tile_count != nullptr) {
+    // candidate lists: offset of every tile's candidates inside its sequence, and the sequence's
+    // total (left in cand_cu[s + 1]; the batch scan turns the totals into offsets)
+    const int lane = threadIdx.x & (DSK_WAVE - 1), wave = threadIdx.x / DSK_WAVE;
+    int run = 0;
+    for (int j0 = 0; j0 < n_tiles; j0 += kChainThreads) {
+      const int j = j0 + threadIdx.x;
+      const int v = j < n_tiles ? cand.tile_count[s * p.tiles_per_seq + j] : 0;
+      const int incl = wave_incl_scan_i(v, lane);
+      if (lane == DSK_WAVE - 1) cand_wave[wave] = incl;
+      __syncthreads();
+      int off = 0, total = 0;
+#pragma unroll
+      for (int w = 0; w < kChainThreads / DSK_WAVE; ++w) {
+        const int t = cand_wave[w];
+        if (w < wave) off += t;
+        total += t;
+      }
+      if (j < n_tiles) cand.tile_base[s * p.tiles_per_seq + j] = run + off + incl - v;
+      run += total;
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+      if (p.B == 1) {
+        cand.cand_cu[0] = 0;
+        cand.cand_cu[1] = run;
+        if (run > cand.max_cand) set_status(dev_status, DSK_ERR_CAPACITY);
+      } else {
+        cand.cand_cu[s + 1] = run;
+      }
+    }
+  }
   if (p.map_row <= kChainFastSpan) {
-    // carry[0] is the entry offset into the first tile of the run.  i / map_row without a division:
-    // inv = floor(2^32 / map_row) + 1 is exact for i * map_row < 2^32.
-    const uint32_t inv = 0xFFFFFFFFu / (uint32_t)p.map_row + 1u;
+    // carry[0] is the entry offset into the first tile of the run
     const int run = (kChainLdsEntries / 2) / p.map_row;
     for (int j0 = 0; j0 < n_tiles; j0 += run) {
       const int T = (n_tiles - j0 < run) ? n_tiles - j0 : run;
-      const int n_ent = T * p.map_row;
       const uint2* src = tile_map + ((int64_t)s * p.tiles_per_seq + j0) * p.map_row;
-      uint2* cur = rows;
-      uint2* nxt = rows + kChainLdsEntries / 2;
       __syncthreads();
-      constexpr int kPer = (kChainLdsEntries / 2 + kChainThreads - 1) / kChainThreads;
-      uint2 ld[kPer];
-      int jj[kPer], ee[kPer];                             // tile of the run and entry offset of element i
-#pragma unroll
-      for (int u = 0; u < kPer; ++u) {                    // the run's rows: one round trip, not kPer
-        const int i = threadIdx.x + u * kChainThreads;
-        ld[u] = src[i < n_ent ? i : 0];
-        jj[u] = p.map_row == 1 ? i : (int)__umulhi((uint32_t)i, inv);   // inv wraps to 0 for a divisor of 1
-        ee[u] = i - jj[u] * p.map_row;
-      }
-#pragma unroll
-      for (int u = 0; u < kPer; ++u) {
-        const int i = threadIdx.x + u * kChainThreads;
-        if (i < n_ent) {
-          const int t0 = (j0 + jj[u]) * kSegTile;
-          const int tl = (t0 + kSegTile < L) ? kSegTile : L - t0;
-          cur[i] = ee[u] >= tl ? chain_pack(ee[u] - tl, 0, 0) : ld[u];   // beyond a short last tile: passes through
-        }
-      }
-      __syncthreads();
-      for (int d = 1; d < T; d <<= 1) {
-#pragma unroll
-        for (int u = 0; u < kPer; ++u) {
-          const int i = threadIdx.x + u * kChainThreads;
-          if (i < n_ent) {
-            const int j = jj[u], e = ee[u];
-            uint2 v = cur[i];
-            if (j >= d) {                                 // tiles j-2d+1 .. j-d first, then j-d+1 .. j
-              const uint2 a = cur[(j - d) * p.map_row + e];
-              const uint2 c = cur[j * p.map_row + chain_off(a)];
-              v = chain_pack(chain_off(c), chain_blocks(a) + chain_blocks(c), chain_slots(a) + chain_slots(c));
-            }
-            nxt[i] = v;
-          }
-        }
-        __syncthreads();
-        uint2* t = cur; cur = nxt; nxt = t;
-      }
+      const uint2* cur = chain_scan_run(src, L, j0, T, p.map_row, rows, rows + kChainLdsEntries / 2);
       // row j now maps an entry of the run's first tile to the state behind tile j0 + j
       const int e0 = carry[0], blk0 = carry[1], slots0 = carry[2];
       for (int j = threadIdx.x; j < T; j += kChainThreads) {
@@ -561,8 +742,17 @@ __global__ __launch_bounds__(kChainThreads) void seg_chain_kernel(
 __global__ __launch_bounds__(64) void seg_seqscan_kernel(
     int4* __restrict__ seq_info, int B, int cap, int total_tokens, int32_t* __restrict__ cu_blocks,
     int32_t* __restrict__ cu_slots, int32_t* __restrict__ block_start, int32_t* __restrict__ slot_base,
-    int32_t* dev_status) {
+    int32_t* cand_cu, int max_cand, int32_t* dev_status) {
   if (threadIdx.x != 0) return;
+  if (cand_cu != nullptr) {   // per-sequence candidate totals (behind each sequence's entry) -> offsets
+    int run = 0;
+    cand_cu[0] = 0;
+    for (int s = 0; s < B; ++s) {
+      run += cand_cu[s + 1];
+      cand_cu[s + 1] = run;
+    }
+    if (run > max_cand) set_status(dev_status, DSK_ERR_CAPACITY);
+  }
   int blk = 0, slots = 0;
   for (int s = 0; s < B; ++s) {
     int4 v = seq_info[s];
@@ -587,6 +777,17 @@ __global__ __launch_bounds__(64) void seg_seqscan_kernel(
 // ---- host -----------------------------------------------------------------------------------
 hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, SegClassSource src, hipStream_t st) {
   unsigned char* w = static_cast<unsigned char*>(a.workspace);
+  SegCand cand = {};
+  if (src == SegClassSource::kTokenIdsWithLists) {
+    cand.own_cls = w + ws.cls_at;
+    cand.tile_count = reinterpret_cast<int32_t*>(w + ws.seg_cand);
+    cand.tile_base = cand.tile_count + (size_t)a.B * ws.tiles_per_seq;
+    cand.cand_cu = a.cand_cu;
+    cand.cand_pos = a.cand_pos;
+    cand.cand_class = a.cand_class;
+    cand.max_cand = a.max_cand_total;
+  }
+  const bool classify_here = src == SegClassSource::kTokenIds || src == SegClassSource::kTokenIdsWithLists;
   uint8_t* cls_at = w + ws.cls_at;
   uint16_t* seg_len = reinterpret_cast<uint16_t*>(w + ws.seg_len);
   uint2* tile_map = reinterpret_cast<uint2*>(w + ws.tile_map);
@@ -627,25 +828,38 @@ hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, SegC
     const dim3 grid((unsigned)ws.tiles_per_seq, (unsigned)a.B);
     // kTokenIds: no class bytes exist; the tile kernel classifies the tokens of its reach itself
     seg_tile_kernel<0><<<grid, dim3(kTileThreads), lds, st>>>(
-        p, src == SegClassSource::kTokenIds ? nullptr : cls_at, a.token_ids, a.delim_ids, seg_len, tile_map,
-        tile_info, seq_info, a.block_start, a.slot_base, a.dev_status);
+        p, cand, classify_here ? nullptr : cls_at, a.token_ids, a.delim_ids, seg_len, tile_map,
+        tile_info, seq_info, a.cu_blocks, a.cu_slots, a.block_start, a.slot_base, a.dev_status);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
-  seg_chain_kernel<<<dim3((unsigned)a.B), dim3(kChainThreads), 0, st>>>(p, tile_map, tile_info, seq_info, a.cu_blocks,
+  // one sequence whose entry maps fit one run of the chain scan: the emit pass chains for itself
+  const bool self_chain = a.B == 1 && a.max_seqlen == a.total_tokens && ws.tiles_per_seq >= 1 &&
+                          ws.tiles_per_seq < kTileThreads &&
+                          ws.map_row <= kChainFastSpan &&
+                          (int64_t)ws.tiles_per_seq * ws.map_row <= kChainLdsEntries / 2;
+  if (self_chain) {
+    const dim3 grid((unsigned)ws.tiles_per_seq, 1u);
+    seg_tile_kernel<2><<<grid, dim3(kTileThreads), lds, st>>>(p, cand, nullptr, nullptr, nullptr, seg_len, tile_map,
+                                                             tile_info, seq_info, a.cu_blocks, a.cu_slots,
+                                                             a.block_start, a.slot_base, a.dev_status);
+    return hipGetLastError();
+  }
+  seg_chain_kernel<<<dim3((unsigned)a.B), dim3(kChainThreads), 0, st>>>(p, cand, tile_map, tile_info, seq_info, a.cu_blocks,
                                                                       a.cu_slots, a.block_start, a.slot_base,
                                                                       a.dev_status);
   if ((err = hipGetLastError()) != hipSuccess) return err;
   if (a.B > 1) {
     seg_seqscan_kernel<<<dim3(1), dim3(64), 0, st>>>(seq_info, a.B, a.max_blocks_total, a.total_tokens,
                                                      a.cu_blocks, a.cu_slots, a.block_start, a.slot_base,
+                                                     cand.tile_count ? cand.cand_cu : nullptr, cand.max_cand,
                                                      a.dev_status);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
   if (ws.tiles_per_seq > 0) {
     const dim3 grid((unsigned)ws.tiles_per_seq, (unsigned)a.B);
-    seg_tile_kernel<1><<<grid, dim3(kTileThreads), lds, st>>>(p, nullptr, nullptr, nullptr, seg_len, tile_map,
-                                                             tile_info, seq_info, a.block_start, a.slot_base,
-                                                             a.dev_status);
+    seg_tile_kernel<1><<<grid, dim3(kTileThreads), lds, st>>>(p, cand, nullptr, nullptr, nullptr, seg_len, tile_map,
+                                                             tile_info, seq_info, a.cu_blocks, a.cu_slots,
+                                                             a.block_start, a.slot_base, a.dev_status);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
   return hipSuccess;

@@ -17,14 +17,20 @@ def _dsk():
     return dsk
 
 
-def _check_tables(comp, seg):
+def _check_tables(comp, seg, status=0):
     nb = int(seg.cu_blocks[-1])
-    assert int(comp.dev_status.item()) == 0
+    assert int(comp.dev_status.item()) == status
     np.testing.assert_array_equal(comp.cu_blocks.cpu().numpy(), seg.cu_blocks)
     np.testing.assert_array_equal(comp.block_start.cpu().numpy()[: nb + 1], seg.block_start)
     np.testing.assert_array_equal(comp.slot_base.cpu().numpy()[: nb + 1], seg.slot_base)
     if comp.cu_slots is not None:      # slot range of every sequence = slot_base at its first block
         np.testing.assert_array_equal(comp.cu_slots.cpu().numpy(), seg.slot_base[seg.cu_blocks])
+    if (status == 0 and comp.cand_pos is not None and (comp.args.stages & _dsk().DSK_STAGE_CANDIDATES)
+            and getattr(seg, "cand_cu", None) is not None):
+        n = int(seg.cand_cu[-1])       # lists written by this call (by the candidate or the segmentation kernels)
+        np.testing.assert_array_equal(comp.cand_cu.cpu().numpy(), seg.cand_cu)
+        np.testing.assert_array_equal(comp.cand_pos.cpu().numpy()[:n], seg.cand_pos)
+        np.testing.assert_array_equal(comp.cand_class.cpu().numpy()[:n], seg.cand_class)
 
 
 # --------------------------------------------------------------------------- full configs
@@ -51,6 +57,35 @@ def test_candidates_and_segmentation_bit_exact(cfg_id):
                                    cfg.W, hi - lo)
         want = np.where(want >= 0, want + lo, -1)
         np.testing.assert_array_equal(samp[s], want)
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2, 5])
+def test_candidate_lists_alone_and_from_the_segmentation_kernels(cfg_id):
+    """Stage CANDIDATES on its own runs the candidate kernels; together with stage SEGMENT (weights
+    from a table) the segmentation kernels write the lists on their way.  Both must give the
+    oracle's lists, and a list that is too short is reported the same way by both."""
+    dsk = _dsk()
+    case = gpu_case(cfg_id)
+    cfg, seg = case.cfg, case.seg
+    n = int(seg.cand_cu[-1])
+    for stages in (dsk.DSK_STAGE_CANDIDATES, dsk.DSK_STAGE_CANDIDATES | dsk.DSK_STAGE_SEGMENT):
+        comp = dsk.compress(**case.compress_kwargs(stages=stages, token_ids=case.token_ids,
+                                                   delim_ids=case.delim_ids, M=cfg.M, W=cfg.W, R=cfg.R))
+        torch.cuda.synchronize()
+        assert int(comp.dev_status.cpu()[0]) == dsk.DSK_OK
+        np.testing.assert_array_equal(comp.cand_cu.cpu().numpy(), seg.cand_cu)
+        np.testing.assert_array_equal(comp.cand_pos.cpu().numpy()[:n], seg.cand_pos)
+        np.testing.assert_array_equal(comp.cand_class.cpu().numpy()[:n], seg.cand_class)
+        short = n // 2
+        comp = dsk.compress(**case.compress_kwargs(stages=stages, token_ids=case.token_ids,
+                                                   delim_ids=case.delim_ids, max_cand_total=short))
+        torch.cuda.synchronize()
+        assert int(comp.dev_status.cpu()[0]) == dsk.DSK_ERR_CAPACITY
+        np.testing.assert_array_equal(comp.cand_cu.cpu().numpy(), seg.cand_cu)      # the true totals
+        np.testing.assert_array_equal(comp.cand_pos.cpu().numpy()[:short], seg.cand_pos[:short])
+        np.testing.assert_array_equal(comp.cand_class.cpu().numpy()[:short], seg.cand_class[:short])
+        if stages & dsk.DSK_STAGE_SEGMENT:
+            _check_tables(comp, seg, status=dsk.DSK_ERR_CAPACITY)                   # the segmentation does not read the lists
 
 
 @pytest.mark.parametrize("cfg_id", [1, 3])
