@@ -31,6 +31,18 @@ CompressWs compress_ws_layout(const dsk_compress_args& a) {
   ws.seg_len = off;    off += align_up(((size_t)a.total_tokens + 16) * sizeof(uint16_t));
   ws.tile_count = off; off += align_up(((size_t)ws.n_cand_tiles + 1) * sizeof(int32_t));
   ws.seg_cand = off;   off += align_up(2 * n_tiles * sizeof(int32_t));
+  // levels of the segmentation's pointer doubling kept per token: a tile of kSegTile positions in
+  // chunks of at least C - delta; per-sequence C / delta may be smaller than the envelope, so then
+  // the chunks may be single positions
+  {
+    int min_len = (a.C_per_seq != nullptr || a.delta_per_seq != nullptr) ? 1 : a.C - a.delta;
+    if (min_len < 1) min_len = 1;
+    int hops = (kSegTile + min_len - 1) / min_len, rounds = 0;
+    while ((1 << rounds) < hops) ++rounds;
+    ws.jump_levels = rounds > 0 ? rounds - 1 : 0;   // the chunk lengths are the first hop, the last level is never hopped from
+    ws.jump_stride = (a.total_tokens + 15) / 16 * 16;
+  }
+  ws.seg_jump = off;   off += align_up((size_t)ws.jump_levels * ws.jump_stride * sizeof(uint16_t) + 32);
   const size_t n_samp = (size_t)a.B * (a.n_class > 0 ? a.n_class : 0) * (a.M > 0 ? a.M : 0);
   ws.imp_part = off;   off += align_up(n_samp * (size_t)a.Hkv * 2 * sizeof(float));
   ws.total = off;

@@ -27,11 +27,14 @@ struct CompressWs {
   size_t seg_len;     // u16 [total_tokens]          length of the chunk that would start at each position
   size_t tile_count;  // i32 [n_cand_tiles + 1]      candidates per tile, then exclusive scan
   size_t seg_cand;    // i32 [2 * n_tiles]           candidates per segmentation tile, then their offsets in the sequence
+  size_t seg_jump;    // u16 [jump_levels][jump_stride]  position in the tile 2, 4, 8 .. chunks after each token
   size_t imp_part;    // f32 [B * n_class * M * Hkv] per-(sample, kv head) partial sums
   size_t total;
   int tiles_per_seq;  // ceil(max_seqlen / kSegTile)
   int map_row;        // min(C + delta, kSegTile)
   int n_cand_tiles;   // ceil(total_tokens / kCandTile)
+  int jump_levels;    // doubling levels kept per token: enough for a tile of chunks of C - delta positions
+  int jump_stride;    // total_tokens rounded up to 16
 };
 CompressWs compress_ws_layout(const dsk_compress_args& a);
 

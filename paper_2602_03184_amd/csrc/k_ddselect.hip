@@ -15,8 +15,11 @@
 //   chain:   per sequence, hop through the entry maps (staged in LDS) to fix each tile's real
 //            entry and its block / slot offsets; for a single-sequence batch also the totals.
 //   scan:    block and slot bases of the sequences of a batch (B > 1), capacity check.
-//   tile<1>: same successor table; the positions reachable from the real entry are marked
-//            with the same doubling scheme, ranked by a workgroup scan and written out.
+//   tile<1>: the chunks the chain lays down in the tile are the positions 0, 1, 2 .. hops behind the
+//            tile's real entry; each is found through the hop-2^l tables the first pass kept, ranked
+//            by a workgroup scan and written out.
+//   tile<2>: tile<1> for a single sequence of few tiles, which also chains the tiles in front of
+//            its own by itself: no chain launch.
 #include "dsk_common.hpp"
 #include "dsk_internal.hpp"
 
@@ -37,10 +40,23 @@ struct SegParams {
   const uint8_t* class_weight_q;   // [B, n_class]
   int n_class;
   int C, delta, a_num, a_den, b;
+  uint32_t b_inv;          // floor(2^32 / b) + 1 for 1 < b < 2^15, else 0: division by b as a multiply
   int map_row, tiles_per_seq;
   int max_seqlen, total_tokens;
   int B, cap;
+  uint16_t* seg_jump;      // [max_levels][jump_stride] per token: position in its tile 2^(level+1) chunks on
+  int max_levels;          // levels the buffer holds: one less than the doubling rounds of any sequence
+  int jump_stride;
 };
+
+constexpr int kMaxJumpLevels = 10;   // kept levels: hops of 2 .. 2^10 chunks; with the chunk itself, 2^11 >= kSegTile
+static_assert((1 << (kMaxJumpLevels + 1)) >= kSegTile, "levels cover a tile of one-position chunks");
+__host__ __device__ inline int jump_rounds(int tlen, int min_len) {
+  const int hops = (tlen + min_len - 1) / min_len;
+  int rounds = 0;
+  while ((1 << rounds) < hops) ++rounds;
+  return rounds;
+}
 
 // Candidate lists produced by the segmentation kernels themselves (stage CANDIDATES and stage
 // SEGMENT in one call, weights from a table): the first tile pass classifies and counts the
@@ -140,41 +156,49 @@ __device__ __forceinline__ uint2 chain_pack(int off, int blocks, int slots) {
 }
 
 
-// Stages the entry maps of tiles j0 .. j0 + T - 1 of a sequence of L positions in `cur` and runs the
-// doubling scan; on return row j of the returned buffer maps an entry offset of tile j0 to the state
-// behind tile j0 + j.  T * map_row <= kChainLdsEntries / 2, map_row <= kChainFastSpan, called by
-// all kChainThreads threads of the workgroup.
-__device__ __forceinline__ uint2* chain_scan_run(const uint2* __restrict__ src, int L, int j0, int T, int map_row,
-                                                 uint2* cur, uint2* nxt) {
+// The doubling scan over the entry maps of tiles j0 .. j0 + T - 1 of a sequence of L positions, in
+// two steps so that a caller can have the loads in flight with its other loads: chain_load fetches
+// the rows (registers), chain_scan stages them in `cur` and runs the rounds; on return row j of the
+// returned buffer maps an entry offset of tile j0 to the state behind tile j0 + j.
+// T * map_row <= kChainLdsEntries / 2, map_row <= kChainFastSpan; all kChainThreads threads call both.
+constexpr int kChainPer = (kChainLdsEntries / 2 + kChainThreads - 1) / kChainThreads;
+struct ChainRows {
+  uint2 ld[kChainPer];
+  int jj[kChainPer], ee[kChainPer];                   // tile of the run and entry offset of element i
+};
+
+__device__ __forceinline__ void chain_load(ChainRows& r, const uint2* __restrict__ src, int T, int map_row) {
   // i / map_row without a division: inv = floor(2^32 / map_row) + 1 is exact for i * map_row < 2^32
   const uint32_t inv = 0xFFFFFFFFu / (uint32_t)map_row + 1u;
   const int n_ent = T * map_row;
-  constexpr int kPer = (kChainLdsEntries / 2 + kChainThreads - 1) / kChainThreads;
-  uint2 ld[kPer];
-  int jj[kPer], ee[kPer];                             // tile of the run and entry offset of element i
 #pragma unroll
-  for (int u = 0; u < kPer; ++u) {                    // the run's rows: one round trip, not kPer
+  for (int u = 0; u < kChainPer; ++u) {               // the run's rows: one round trip, not kChainPer
     const int i = threadIdx.x + u * kChainThreads;
-    ld[u] = src[i < n_ent ? i : 0];
-    jj[u] = map_row == 1 ? i : (int)__umulhi((uint32_t)i, inv);   // inv wraps to 0 for a divisor of 1
-    ee[u] = i - jj[u] * map_row;
+    r.ld[u] = src[i < n_ent ? i : 0];
+    r.jj[u] = map_row == 1 ? i : (int)__umulhi((uint32_t)i, inv);   // inv wraps to 0 for a divisor of 1
+    r.ee[u] = i - r.jj[u] * map_row;
   }
+}
+
+__device__ __forceinline__ uint2* chain_scan(const ChainRows& r, int L, int j0, int T, int map_row, uint2* cur,
+                                             uint2* nxt) {
+  const int n_ent = T * map_row;
 #pragma unroll
-  for (int u = 0; u < kPer; ++u) {
+  for (int u = 0; u < kChainPer; ++u) {
     const int i = threadIdx.x + u * kChainThreads;
     if (i < n_ent) {
-      const int t0 = (j0 + jj[u]) * kSegTile;
+      const int t0 = (j0 + r.jj[u]) * kSegTile;
       const int tl = (t0 + kSegTile < L) ? kSegTile : L - t0;
-      cur[i] = ee[u] >= tl ? chain_pack(ee[u] - tl, 0, 0) : ld[u];   // beyond a short last tile: passes through
+      cur[i] = r.ee[u] >= tl ? chain_pack(r.ee[u] - tl, 0, 0) : r.ld[u];   // beyond a short last tile: passes through
     }
   }
   __syncthreads();
   for (int d = 1; d < T; d <<= 1) {
 #pragma unroll
-    for (int u = 0; u < kPer; ++u) {
+    for (int u = 0; u < kChainPer; ++u) {
       const int i = threadIdx.x + u * kChainThreads;
       if (i < n_ent) {
-        const int j = jj[u], e = ee[u];
+        const int j = r.jj[u], e = r.ee[u];
         uint2 v = cur[i];
         if (j >= d) {                                 // tiles j-2d+1 .. j-d first, then j-d+1 .. j
           const uint2 a = cur[(j - d) * map_row + e];
@@ -188,6 +212,65 @@ __device__ __forceinline__ uint2* chain_scan_run(const uint2* __restrict__ src, 
     uint2* t = cur; cur = nxt; nxt = t;
   }
   return cur;
+}
+
+// State of the chain in front of tile `upto` (0 < upto <= T) when it enters tile 0 at offset 0, for a
+// workgroup that needs this one prefix only: instead of the doubling scan over every row, the rows
+// are combined four at a time into a tree (level k row r = tiles [r 4^k, (r+1) 4^k)), and every
+// thread then walks the tree from the top, at most three steps per level.  About 4 log4(T) + 3
+// log4(T) dependent LDS reads in all, against 2 log2(T) rounds over all entries.  lvl0 holds the
+// staged rows of tiles 0 .. T-1 (T * map_row entries), `upper` has room for T * map_row / 3 + map_row more.
+__device__ __forceinline__ void chain_prefix_tree(const ChainRows& r, int L, int T, int map_row, int upto,
+                                                  uint2* lvl0, uint2* upper, int& e_out, int& blk_out, int& sl_out) {
+  const int n_ent = T * map_row;
+#pragma unroll
+  for (int u = 0; u < kChainPer; ++u) {
+    const int i = threadIdx.x + u * kChainThreads;
+    if (i < n_ent) {
+      const int t0 = r.jj[u] * kSegTile;
+      const int tl = (t0 + kSegTile < L) ? kSegTile : L - t0;
+      lvl0[i] = r.ee[u] >= tl ? chain_pack(r.ee[u] - tl, 0, 0) : r.ld[u];   // beyond a short last tile: passes through
+    }
+  }
+  __syncthreads();
+  // build the levels that a walk to `upto` can use: level k exists while 4^k <= upto; level k >= 1
+  // has T >> 2k rows (full groups of four only: a walk never uses a ragged one), stored one after
+  // the other in `upper`
+  int n_lvl = 1;
+  uint2* dst = upper;
+  {
+    const uint2* src = lvl0;
+    const uint32_t inv = 0xFFFFFFFFu / (uint32_t)map_row + 1u;
+    for (int span = 4; span <= upto; span <<= 2) {
+      const int rows_dst = T >> (2 * n_lvl);
+      for (int idx = threadIdx.x; idx < rows_dst * map_row; idx += kChainThreads) {
+        const int row = map_row == 1 ? idx : (int)__umulhi((uint32_t)idx, inv);
+        int off = idx - row * map_row, blk = 0, sl = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const uint2 v = src[(4 * row + c) * map_row + off];
+          off = chain_off(v); blk += chain_blocks(v); sl += chain_slots(v);
+        }
+        dst[idx] = chain_pack(off, blk, sl);
+      }
+      __syncthreads();
+      src = dst;
+      dst += rows_dst * map_row;
+      ++n_lvl;
+    }
+  }
+  int pos = 0, off = 0, blk = 0, sl = 0;
+  const uint2* lp = dst;                                   // end of the highest level
+  for (int k = n_lvl - 1; k >= 0; --k) {
+    lp = k > 0 ? lp - (T >> (2 * k)) * map_row : lvl0;
+    const int span = 1 << (2 * k);
+    while (pos + span <= upto) {
+      const uint2 v = lp[(pos >> (2 * k)) * map_row + off];
+      off = chain_off(v); blk += chain_blocks(v); sl += chain_slots(v);
+      pos += span;
+    }
+  }
+  e_out = off; blk_out = blk; sl_out = sl;
 }
 
 // class index of N token ids against the delimiter ids staged in LDS (padded to a multiple of 4
@@ -217,7 +300,6 @@ __device__ __forceinline__ void classify_tokens(const int (&tok)[N], int (&cls)[
 //                              x = (position - p0, or exit offset) | chunks << 16, y = slots
 //   clist u16 [2 * kSegTile]   delimiters in reach (overlays the second jump buffer)
 //   ns    u16 [kSegTile]       slots of the chunk starting here
-//   mark  u8  [kSegTile]       (emit mode) reachable from the tile's entry
 //   wq    u8  [64]             class -> weight tenths of this sequence
 //   red   i32 [40], then the delimiter ids i32 [64]
 constexpr size_t kTileJumpBytes =    // jump entries; the vote array (8 bytes per position) and, in the emit pass
@@ -226,7 +308,6 @@ constexpr size_t kTileJumpBytes =    // jump entries; the vote array (8 bytes pe
 __host__ __device__ constexpr size_t seg_tile_lds_bytes() {
   return kTileJumpBytes
          + (size_t)kSegTile * 2     // ns
-         + (size_t)kSegTile         // mark
          + 64 + 448;                // wq, red (reduction words, then 64 delimiter ids)
 }
 static_assert(2 * kTileWaves + 3 <= 40 && (40 + 64) * 4 <= 448, "red fits its slot");
@@ -250,8 +331,7 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
   unsigned long long* best = reinterpret_cast<unsigned long long*>(smem);
   uint2* jmp = reinterpret_cast<uint2*>(smem);                    // [2][kSegTile]
   uint16_t* ns = reinterpret_cast<uint16_t*>(smem + kTileJumpBytes); // [kSegTile] slots of the chunk starting here
-  uint8_t* mark = reinterpret_cast<uint8_t*>(ns + kSegTile);
-  uint8_t* wq = mark + kSegTile;
+  uint8_t* wq = reinterpret_cast<uint8_t*>(ns + kSegTile);
   int* red = reinterpret_cast<int*>(wq + 64);
 
   const int s = blockIdx.y;
@@ -273,7 +353,12 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
     info = tile_info[tile];
     sq = seq_info[s];
   }
-  // MODE 2: one sequence, so its block and slot bases (sq) are zero, and info comes from the scan below
+  // MODE 2: one sequence, so its block and slot bases (sq) are zero, and info comes from the scan
+  // below, whose rows (the entry maps of the tiles in front, and of this one in the last tile) are
+  // requested here, with everything else the kernel reads first
+  ChainRows cr;
+  const int chain_T = MODE == 2 ? (p0 + kSegTile >= L ? j + 1 : j) : 0;
+  if (MODE == 2 && chain_T > 0) chain_load(cr, tile_map + (int64_t)s * p.tiles_per_seq * p.map_row, chain_T, p.map_row);
   int C, delta;
   seq_params(p, s, C, delta, dev_status);
   const int dd = delta > 1 ? delta : 1;
@@ -289,6 +374,20 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
     }
     if (MODE == 1) cand_o = cand.tile_base[tile] + (p.B == 1 ? 0 : cand.cand_cu[s]);
     else cand_o = tid < j ? cand.tile_count[tile - j + tid] : 0;     // summed below; j < kTileThreads
+  }
+  // (emit) where the chain is 2, 4, 8 .. chunks after each of the thread's positions, as the first
+  // pass left it; every level the buffer holds is requested (the count in use depends on the
+  // sequence's C and delta, which may still be on their way)
+  uint16_t lv[kMaxJumpLevels][kSegPerThread];
+  if (MODE != 0) {
+#pragma unroll
+    for (int l = 0; l < kMaxJumpLevels; ++l) {
+#pragma unroll
+      for (int r = 0; r < kSegPerThread; ++r) {
+        const int i = r * kTileThreads + tid;
+        lv[l][r] = l < p.max_levels ? p.seg_jump[(int64_t)l * p.jump_stride + seq0 + p0 + (i < tlen ? i : 0)] : (uint16_t)0xFFFF;
+      }
+    }
   }
   if (MODE == 0) {
     // the class bytes (or token ids) of the first kVoteChunk boundaries in reach go out before
@@ -445,7 +544,6 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
       const int i = r * kTileThreads + tid;
       my_len[r] = i < tlen ? (int)seg_len[seq0 + p0 + i] : 0;
     }
-    for (int i = tid; i < kSegTile; i += kTileThreads) mark[i] = 0;
     if (cand.tile_count != nullptr) {
       // rank of every candidate of the tile: positions are owned interleaved (i = r * threads +
       // tid), so the order is row r, then wavefront, then lane
@@ -492,23 +590,17 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
   if (MODE == 2) {
     // the tiles in front of this one, chained here: the scan buffers lie where the jump entries
     // are built afterwards
-    const int n_tiles = (L + kSegTile - 1) / kSegTile;
-    const bool last = j == n_tiles - 1;
-    const int T = last ? j + 1 : j;
+    const bool last = p0 + kSegTile >= L;
     uint2* rows = reinterpret_cast<uint2*>(smem);
-    const uint2* fin = rows;
-    if (T > 0)
-      fin = chain_scan_run(tile_map + (int64_t)s * p.tiles_per_seq * p.map_row, L, 0, T, p.map_row, rows,
-                           rows + kChainLdsEntries / 2);
     int e = 0, blk = 0, sl = 0;
-    if (j > 0) {
-      const uint2 c = fin[(j - 1) * p.map_row];
-      e = chain_off(c); blk = chain_blocks(c); sl = chain_slots(c);
-    }
+    if (j > 0)
+      chain_prefix_tree(cr, L, chain_T, p.map_row, j, rows, rows + kChainLdsEntries / 2, e, blk, sl);
     info = make_int4(p0 + e, blk, sl, 0);
     if (last && tid == 0) {
-      const uint2 c = fin[j * p.map_row];
-      const int nb = chain_blocks(c), nsl = chain_slots(c);
+      // the sequence's totals: one more step, through this tile's own map (staged as row j; for a
+      // single tile nothing was staged and its row is read from memory)
+      const uint2 c = j > 0 ? rows[j * p.map_row + e] : tile_map[(int64_t)tile * p.map_row];
+      const int nb = blk + chain_blocks(c), nsl = sl + chain_slots(c);
       cu_blocks[0] = 0;
       cu_blocks[1] = nb;
       if (cu_slots) { cu_slots[0] = 0; cu_slots[1] = nsl; }
@@ -521,24 +613,25 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
   for (int r = 0; r < kSegPerThread; ++r) {
     const int i = r * kTileThreads + tid;
     const int len = my_len[r];
-    const int nslot = (len + p.b - 1) / p.b;
+    // ceil(len / b): len + b - 1 < 2^16 and b < 2^15 on the multiply path, so the reciprocal is exact
+    const int nslot = p.b_inv ? (int)__umulhi((uint32_t)(len + p.b - 1), p.b_inv) : (len + p.b - 1) / p.b;
     ns[i] = (uint16_t)nslot;
     // level-0 jump: one chunk.  position >= tlen means "left the tile" (i + len <= tlen + C + delta)
-    jmp[i] = make_uint2((uint32_t)(i + len) | ((i < tlen ? 1u : 0u) << 16), (uint32_t)nslot);
+    if (MODE == 0) jmp[i] = make_uint2((uint32_t)(i + len) | ((i < tlen ? 1u : 0u) << 16), (uint32_t)nslot);
   }
-  if (MODE != 0 && tid == 0 && info.x >= p0 && info.x < p1) mark[info.x - p0] = 1;
-  __syncthreads();
-
   // pointer jumping: level r holds 2^r chunks per hop; positions that left the tile are fixed
   // points.  Every chunk that does not end the sequence has at least C - delta positions, so the
   // chain crosses the tile in at most ceil(tlen / (C - delta)) hops and as many doublings as cover
-  // that number finish every position: a fixed round count, no termination vote.
-  int cur = 0;
-  {
-    const int min_len = C - delta;                       // >= 1
-    const int hops = (tlen + min_len - 1) / min_len;
-    int rounds = 0;
-    while ((1 << rounds) < hops) ++rounds;
+  // that number finish every position: a fixed round count, no termination vote.  The first pass
+  // keeps the target positions of every level (2 bytes per position and level) for the emit pass.
+  const int rounds = jump_rounds(tlen, C - delta);       // C - delta >= 1
+  if (rounds - 1 > p.max_levels) {                       // cannot happen for a buffer sized by the host's rule
+    if (tid == 0) set_status(dev_status, DSK_ERR_WORKSPACE);
+    return;
+  }
+  if (MODE == 0) {
+    __syncthreads();
+    int cur = 0;
     for (int round = 0; round < rounds; ++round) {
       const uint2* js = jmp + cur * kSegTile;
       uint2* jd = jmp + (cur ^ 1) * kSegTile;
@@ -548,19 +641,17 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
         uint2 v = js[i];
         const int t = (int)(v.x & 0xFFFFu);
         if (i < tlen && t < tlen) {
-          if (MODE != 0 && mark[i]) mark[t] = 1;   // reachable set doubles with the hop length
           const uint2 v2 = js[t];
           v = make_uint2((v2.x & 0xFFFFu) | ((v.x & 0xFFFF0000u) + (v2.x & 0xFFFF0000u)), v.y + v2.y);
         }
         jd[i] = v;
+        if (i < tlen && round < rounds - 1)              // the last level is not hopped from again
+          p.seg_jump[(int64_t)round * p.jump_stride + seq0 + p0 + i] = (uint16_t)(v.x & 0xFFFFu);
       }
       cur ^= 1;
       __syncthreads();
     }
-  }
-  const uint2* fj = jmp + cur * kSegTile;
-
-  if (MODE == 0) {
+    const uint2* fj = jmp + cur * kSegTile;
     if (cand.tile_count != nullptr && tid == 0) {
       int n = 0;
 #pragma unroll
@@ -579,32 +670,38 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
     return;
   }
 
-  // emit: rank the marked positions of the tile; here a thread owns kSegPerThread consecutive
-  // positions (thread order = position order), read as one 4-byte and one 8-byte vector
-  static_assert(kSegPerThread == 4 || kSegPerThread == 2, "vector reads below");
-  int mk[kSegPerThread], nsv[kSegPerThread];
-  if constexpr (kSegPerThread == 4) {
-    const uint32_t mk4 = *reinterpret_cast<const uint32_t*>(mark + tid * 4);
-    const uint2 ns4 = *reinterpret_cast<const uint2*>(ns + tid * 4);
+  // emit.  The chunks the chain lays down in this tile are the positions 0, 1, 2 .. hops behind the
+  // tile's entry, and hop counts add up along the chain: with the hop-2^l tables of the first pass
+  // in LDS (hop 1 = the chunk lengths), the thread that owns the n-th chunk finds its position by
+  // one lookup per set bit of n -- no marks, no rounds, no barrier between the lookups.  A chain of
+  // the tile has at most 2^rounds chunks; a thread takes two consecutive n.
+  static_assert(kMaxJumpLevels + 1 <= (int)(kTileJumpBytes / (kSegTile * 2)), "hop tables fit the jump area");
+  uint16_t* tab = reinterpret_cast<uint16_t*>(smem);     // [rounds][kSegTile]
 #pragma unroll
-    for (int r = 0; r < kSegPerThread; ++r) {
-      mk[r] = (tid * kSegPerThread + r < tlen) ? (int)((mk4 >> (8 * r)) & 255u) : 0;
-      const uint32_t nw = r < 2 ? ns4.x : ns4.y;
-      nsv[r] = (int)((nw >> (16 * (r & 1))) & 0xFFFFu);
-    }
-  } else {
-    const uint32_t mk2 = *reinterpret_cast<const uint16_t*>(mark + tid * 2);
-    const uint32_t ns2 = *reinterpret_cast<const uint32_t*>(ns + tid * 2);
+  for (int r = 0; r < kSegPerThread; ++r) {
+    const int i = r * kTileThreads + tid;
+    tab[i] = (uint16_t)(i < tlen ? i + my_len[r] : tlen);
 #pragma unroll
-    for (int r = 0; r < kSegPerThread; ++r) {
-      mk[r] = (tid * kSegPerThread + r < tlen) ? (int)((mk2 >> (8 * r)) & 255u) : 0;
-      nsv[r] = (int)((ns2 >> (16 * r)) & 0xFFFFu);
-    }
+    for (int l = 1; l <= kMaxJumpLevels; ++l)
+      if (l < rounds) tab[l * kSegTile + i] = lv[l - 1][r];
   }
+  __syncthreads();
+  constexpr int kPathPer = 2;
+  static_assert(kPathPer * kTileThreads >= (1 << (kMaxJumpLevels + 1)), "every chunk of a tile has a thread");
+  const int e_in = info.x - p0;
+  int pos[kPathPer], nsv[kPathPer];
   int nb_local = 0, ns_local = 0;
 #pragma unroll
-  for (int r = 0; r < kSegPerThread; ++r)
-    if (mk[r]) { ++nb_local; ns_local += nsv[r]; }
+  for (int r = 0; r < kPathPer; ++r) {
+    const int n = tid * kPathPer + r;
+    int q = (e_in >= 0 && e_in < tlen && n < (1 << rounds)) ? e_in : tlen;
+#pragma unroll
+    for (int l = 0; l <= kMaxJumpLevels; ++l)
+      if (l < rounds && ((n >> l) & 1) && q < tlen) q = tab[l * kSegTile + q];
+    pos[r] = q;
+    nsv[r] = q < tlen ? (int)ns[q] : 0;
+    if (q < tlen) { ++nb_local; ns_local += nsv[r]; }
+  }
   const int lane = tid & (DSK_WAVE - 1), wave = tid / DSK_WAVE;
   const int ib = wave_incl_scan_i(nb_local, lane);
   const int is = wave_incl_scan_i(ns_local, lane);
@@ -617,10 +714,10 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
   int gb = sq.z + info.y + ob + ib - nb_local;
   int gs = sq.w + info.z + os + is - ns_local;
 #pragma unroll
-  for (int r = 0; r < kSegPerThread; ++r) {
-    if (mk[r]) {
+  for (int r = 0; r < kPathPer; ++r) {
+    if (pos[r] < tlen) {
       if (gb < p.cap) {
-        block_start[gb] = seq0 + p0 + tid * kSegPerThread + r;
+        block_start[gb] = seq0 + p0 + pos[r];
         slot_base[gb] = gs;
       }
       ++gb;
@@ -682,7 +779,9 @@ __global__ __launch_bounds__(kChainThreads) void seg_chain_kernel(
       const int T = (n_tiles - j0 < run) ? n_tiles - j0 : run;
       const uint2* src = tile_map + ((int64_t)s * p.tiles_per_seq + j0) * p.map_row;
       __syncthreads();
-      const uint2* cur = chain_scan_run(src, L, j0, T, p.map_row, rows, rows + kChainLdsEntries / 2);
+      ChainRows cr;
+      chain_load(cr, src, T, p.map_row);
+      const uint2* cur = chain_scan(cr, L, j0, T, p.map_row, rows, rows + kChainLdsEntries / 2);
       // row j now maps an entry of the run's first tile to the state behind tile j0 + j
       const int e0 = carry[0], blk0 = carry[1], slots0 = carry[2];
       for (int j = threadIdx.x; j < T; j += kChainThreads) {
@@ -801,9 +900,13 @@ hipError_t launch_segment(const dsk_compress_args& a, const CompressWs& ws, SegC
   p.class_weight_q = a.class_weight_q;
   p.n_class = a.n_class;
   p.C = a.C; p.delta = a.delta; p.a_num = a.alpha_num; p.a_den = a.alpha_den; p.b = a.b;
+  p.b_inv = (a.b > 1 && a.b < 32768) ? 0xFFFFFFFFu / (uint32_t)a.b + 1u : 0u;
   p.map_row = ws.map_row; p.tiles_per_seq = ws.tiles_per_seq;
   p.max_seqlen = a.max_seqlen; p.total_tokens = a.total_tokens;
   p.B = a.B; p.cap = a.max_blocks_total;
+  p.seg_jump = reinterpret_cast<uint16_t*>(w + ws.seg_jump);
+  p.max_levels = ws.jump_levels;
+  p.jump_stride = ws.jump_stride;
 
   hipError_t err;
   if (src == SegClassSource::kCallerLists) {   // scatter the caller's candidates into the dense class array
