@@ -446,6 +446,80 @@ def main():
                     "append_us": round(loop_us - us_per_step, 3),
                     "grown_table_equals_full_compress": bool(ok)}
 
+        # ---- the same loop for a batch: every sequence owns a region of the tables with room to
+        #      grow, and one dsk_append_tokens_batch call per step appends a token to each. ------------
+        if cfg.B > 1 and args.append_steps > 0:
+            n_app = int(min(args.append_steps, 128, int(wl.seqlens.min()) // 2))
+            full = [int(x) for x in wl.seqlens]
+            row0, r = [], 0
+            for s_ in range(cfg.B):
+                row0.append(r)
+                r += (full[s_] + 15) // 16 * 16
+            Kr = torch.zeros(K.shape[0], r, K.shape[2], dtype=K.dtype, device=dev)
+            Vr = torch.zeros_like(Kr)
+            tokr = torch.zeros(r, dtype=torch.int32, device=dev)
+            for s_ in range(cfg.B):
+                a0 = int(wl.cu_seqlens[s_])
+                Kr[:, row0[s_]: row0[s_] + full[s_]] = K[:, a0: a0 + full[s_]]
+                Vr[:, row0[s_]: row0[s_] + full[s_]] = V[:, a0: a0 + full[s_]]
+                tokr[row0[s_]: row0[s_] + full[s_]] = ckw["token_ids"][a0: a0 + full[s_]]
+            Cs, Ds = [int(x) for x in wl.C], [int(x) for x in wl.delta]
+            entries = [dsk.dsk_block_capacity(full[s_], 1, Cs[s_] - Ds[s_]) + 1 for s_ in range(cfg.B)]
+            rkw = dict(seq_row0=row0, region_entries=entries, Hq=cfg.Hq, K=Kr, V=Vr, token_ids=tokr,
+                       delim_ids=ckw["delim_ids"], class_weight_q=ckw["class_weight_q"], C_per_seq=Cs,
+                       delta_per_seq=Ds, alpha_num=cfg.a_num, alpha_den=cfg.a_den, b=cfg.b)
+            with torch.cuda.stream(stream):
+                rb = dsk.compress_regions(seq_len=[x - n_app for x in full], stream=stream, **rkw)
+                rb_full = dsk.compress_regions(seq_len=full, stream=stream, **rkw)
+            stream.synchronize()
+            bap = dsk.make_batch_appender(rb, Kr, Vr, tokr, ckw["delim_ids"], ckw["class_weight_q"], C_=max(Cs),
+                                          delta=max(Ds), C_per_seq=i32(Cs), delta_per_seq=i32(Ds),
+                                          alpha_num=cfg.a_num, alpha_den=cfg.a_den, max_new_tokens=1, lockstep=True)
+            used_bound = int(rb.cu_blocks[-1].item())
+            # host-known bound on the blocks of one sequence: its count after the compression, read
+            # back once, plus what the appended tokens can add
+            seq_bound = int(rb.blocks_used.max().item()) + n_app + 8
+            bkw = dict(max_blocks_used=used_bound, max_blocks_per_seq=seq_bound)
+            bsel = [dsk.make_select_args(rb, queries[0], cfg.T, **bkw)]
+            for i in range(1, nq):
+                bsel.append(dsk.make_select_args(rb, queries[i], cfg.T, out=bsel[0], **bkw))
+            batt = [dsk.make_attn_args(queries[0], Kr, Vr, bsel[0].sel_start, bsel[0].sel_len, bsel[0].sel_count, cfg.b)]
+            for i in range(1, nq):
+                batt.append(dsk.make_attn_args(queries[i], Kr, Vr, bsel[0].sel_start, bsel[0].sel_len,
+                                               bsel[0].sel_count, cfg.b, out=batt[0]))
+            g_b = torch.cuda.CUDAGraph()
+            g_b0 = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(stream):
+                with torch.cuda.graph(g_b0, stream=stream):  # the decode step alone on these tables
+                    for i in range(n_app):
+                        dsk.dsk_select_topk(bsel[i % nq].args, stream)
+                        dsk.dsk_sparse_decode_attn(batt[i % nq].args, stream)
+                base_us = event_ms(g_b0.replay, stream) * 1e3 / n_app
+                with torch.cuda.graph(g_b, stream=stream):   # capture runs nothing: the tables stay where they are
+                    for i in range(n_app):
+                        dsk.dsk_append_tokens_batch(bap.args, stream)
+                        dsk.dsk_select_topk(bsel[i % nq].args, stream)
+                        dsk.dsk_sparse_decode_attn(batt[i % nq].args, stream)
+                loop_us = event_ms(g_b.replay, stream) * 1e3 / n_app
+            stream.synchronize()
+            ok = int(rb.dev_status.item()) == 0 and torch.equal(rb.blocks_used, rb_full.blocks_used) and \
+                torch.equal(rb.seq_len, rb_full.seq_len)
+            used = rb_full.blocks_used.cpu().numpy()
+            cub = rb_full.cu_blocks.cpu().numpy()
+            for s_ in range(cfg.B):
+                a0, n_ = int(cub[s_]), int(used[s_])
+                ok = ok and torch.equal(rb.block_start[a0: a0 + n_ + 1], rb_full.block_start[a0: a0 + n_ + 1]) and \
+                    torch.equal(rb.slot_base[a0: a0 + n_ + 1], rb_full.slot_base[a0: a0 + n_ + 1]) and \
+                    torch.equal(rb.ksum[:, a0: a0 + n_], rb_full.ksum[:, a0: a0 + n_])
+            loop = {"steps": n_app, "us_per_step": round(loop_us, 3),
+                    "us_per_step_without_append": round(base_us, 3),
+                    "append_us": round(loop_us - base_us, 3),
+                    "grown_table_equals_full_compress": bool(ok),
+                    "layout": "one region of the tables per sequence; dsk_append_tokens_batch appends a token to "
+                              "each of the %d sequences per step" % cfg.B}
+            del Kr, Vr, rb, rb_full, g_b, g_b0
+            torch.cuda.empty_cache()
+
         # ---- KV reuse with the slot map (App. B.2): K/V live in pinned host memory, every (sequence,
         #      head) keeps its last selection in a resident buffer, and a step loads only the slots
         #      it does not hold.  Queries drift (AR(1)), so consecutive selections overlap. -------------

@@ -14,6 +14,8 @@
  *                           fixed-size slots (App. B.2, "KVCache Reuse with V2F").
  *   dsk_append_tokens       incremental update of the block table and summaries while decoding
  *                           (Sec. 4.1, "Incremental Update during Decoding"), one sequence per call.
+ *   dsk_append_tokens_batch the same update for every sequence of a batch in one call, on tables in
+ *                           which each sequence has its own region with room to grow.
  *   dsk_dense_decode_attn   full attention over the whole cache: the full-KV baseline the method
  *                           is compared with (Sec. 5, GPU Inference analysis).
  *
@@ -50,7 +52,7 @@
 extern "C" {
 #endif
 
-#define DSK_ABI_VERSION 2u
+#define DSK_ABI_VERSION 3u
 #define DSK_HEAD_DIM 128
 #define DSK_MAX_CLASSES 64
 
@@ -182,6 +184,10 @@ typedef struct dsk_compress_args {
   void* ksum;                  /* [dev] */
   void* vsum;                  /* [dev] or NULL */
   int32_t summary_mode;        /* DSK_SUMMARY_MINMAX (0) or DSK_SUMMARY_MEAN */
+  int32_t sum_stride_blocks;   /* records per head in ksum / vsum; 0 = max_blocks_total.  Larger when the
+                                  call fills one sequence's region of a batch's tables (see
+                                  dsk_append_tokens_batch): the table pointers then point at the region,
+                                  max_blocks_total is the region's capacity */
 
   int32_t* dev_status;         /* [dev] optional; must be zeroed by the caller */
   void* workspace;             /* [dev] */
@@ -233,6 +239,13 @@ typedef struct dsk_select_args {
   int32_t* sel_len;            /* [dev] [B, Hq, k] tokens in the slot (1..b); 0 padding */
   int32_t* sel_count;          /* [dev] [B, Hq] number of selected slots */
   float* scores;               /* [dev] optional out [Hq, max_blocks_total] block scores */
+  /* Tables with a region per sequence (dsk_append_tokens_batch); both NULL for the packed tables of
+     a batched dsk_compress.  cu_blocks then holds the region starts, and */
+  const int32_t* blocks_used;  /* [dev] optional [B]: sequence s has blocks cu_blocks[s] .. +blocks_used[s]-1
+                                  (what lies between them and the next region is scored but never
+                                  selected) */
+  const int32_t* seq_row0;     /* [dev] optional [B]: block_start of sequence s counts from the sequence's
+                                  first token, which is row seq_row0[s] of K / V; added to sel_start */
   void* workspace;             /* [dev] */
   size_t workspace_bytes;
 } dsk_select_args;
@@ -351,6 +364,66 @@ typedef struct dsk_append_args {
 } dsk_append_args;
 
 /* ------------------------------------------------------------------------------------------
+ * dsk_append_tokens_batch -- the incremental update of Sec. 4.1 for all B sequences of a batch in
+ * one call (every sequence of a decoding batch grows by a token per step).
+ *
+ * A batch whose sequences grow cannot keep them back to back, so every sequence owns a region
+ * with spare room in each table:
+ *   - rows seq_row0[s] .. seq_row0[s] + len[s] - 1 of the token axis of K, V and token_ids;
+ *   - entries cu_blocks[s] .. cu_blocks[s+1] - 1 of block_start / slot_base and records
+ *     cu_blocks[s] .. of every head of ksum / vsum (max_blocks_total records per head), of which
+ *     blocks_used[s] blocks are in use; block_start[cu_blocks[s] + blocks_used[s]] = len[s] closes
+ *     the table, so a region of n entries holds at most n - 1 blocks.
+ * Inside a region the tables are exactly those of a single sequence: block_start counts from the
+ * sequence's first token and slot_base from 0.  A region is filled by dsk_compress with B = 1 on
+ * the sequence's rows (K + seq_row0[s] * k_stride_tok ...), block_start / slot_base / ksum pointing
+ * at entry cu_blocks[s], max_blocks_total = region entries - 1 and sum_stride_blocks = this
+ * struct's max_blocks_total; blocks_used[s] is the cu_blocks[1] that call wrote.  dsk_select_topk
+ * takes such tables through its blocks_used / seq_row0 fields.
+ *
+ * Per sequence the update is that of dsk_append_tokens (same finality rule, same result as a
+ * from-scratch pass over len_new[s] tokens, bit for bit), with len_old[s] = seq_len[s] on entry;
+ * len_new[s] == len_old[s] leaves the sequence as it is.  Data-dependent errors through *dev_status: DSK_ERR_SHAPE if a region's table
+ * does not end at len_old[s] or the lengths do not fit (the sequence is then left untouched), DSK_ERR_CAPACITY if the chunks do not fit the region (that
+ * sequence's table is then truncated; the others are unaffected).
+ * ---------------------------------------------------------------------------------------- */
+typedef struct dsk_append_batch_args {
+  uint32_t struct_size;
+  int32_t B, Hkv, D;
+  int32_t total_rows;          /* [host] rows of the token axis of K, V, token_ids */
+  int32_t max_new_tokens;      /* [host] upper bound on len_new[s] - len_old[s] (sizes the launch) */
+  const int32_t* seq_row0;     /* [dev] [B] */
+  int32_t* seq_len;            /* [dev] in/out [B]: the sequences' lengths before the call (len_old), replaced
+                                  by the new lengths when the call has updated a sequence */
+  const int32_t* len_new;      /* [dev] optional [B]: len_old[s] <= len_new[s] <= len_old[s] + max_new_tokens,
+                                  seq_row0[s] + len_new[s] <= total_rows.  NULL: every sequence grows by
+                                  max_new_tokens (a decoding batch in lockstep) */
+  const void* K;               /* [dev] bf16; strides as in dsk_compress_args */
+  const void* V;               /* [dev] may be NULL when vsum is NULL */
+  int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;
+  const int32_t* token_ids;    /* [dev] [total_rows] */
+  const int32_t* delim_ids;    /* [dev] [n_class] */
+  int32_t n_class;
+  const uint8_t* class_weight_q; /* [dev] [B, n_class] tenths */
+  int32_t C, delta, alpha_num, alpha_den, b;   /* C, delta: the largest of any sequence */
+  const int32_t* C_per_seq;    /* [dev] optional [B] */
+  const int32_t* delta_per_seq;/* [dev] optional [B] */
+  int32_t max_blocks_total;    /* entries of the tables = records per head of ksum / vsum */
+  const int32_t* cu_blocks;    /* [dev] [B+1] region starts, cu_blocks[0] = 0, cu_blocks[B] <= max_blocks_total */
+  int32_t* blocks_used;        /* [dev] in/out [B] */
+  int32_t* block_start;        /* [dev] in/out [max_blocks_total + 4] */
+  int32_t* slot_base;          /* [dev] in/out [max_blocks_total + 4] */
+  void* ksum;                  /* [dev] in/out bf16 [Hkv, max_blocks_total, 2, D] */
+  void* vsum;                  /* [dev] in/out or NULL */
+  int32_t summary_mode;
+  int32_t* first_recomputed;   /* [dev] optional out [B]: first rewritten block of each sequence (index in its region) */
+  int32_t* first_stale_slot;   /* [dev] optional out [B]: slot_base of that block */
+  int32_t* dev_status;         /* [dev] optional */
+  void* workspace;             /* [dev] 256-byte aligned, dsk_append_batch_workspace_bytes() */
+  size_t workspace_bytes;
+} dsk_append_batch_args;
+
+/* ------------------------------------------------------------------------------------------
  * dsk_reuse_update -- KV reuse with the variable-to-fixed slot map (App. B.2, "KVCache Reuse
  * with V2F", Steps 1-3), for a cache whose K/V live in a slower tier (e.g. pinned host memory)
  * while every (sequence, query head) keeps the K/V of its last selection in a resident buffer of
@@ -428,6 +501,7 @@ size_t dsk_select_workspace_bytes(const dsk_select_args* args);
 size_t dsk_attn_workspace_bytes(const dsk_attn_args* args);
 size_t dsk_dense_attn_workspace_bytes(const dsk_dense_attn_args* args);
 size_t dsk_append_workspace_bytes(const dsk_append_args* args);
+size_t dsk_append_batch_workspace_bytes(const dsk_append_batch_args* args);
 size_t dsk_reuse_workspace_bytes(const dsk_reuse_args* args);
 
 /* Where dsk_sparse_decode_attn leaves its split-K partials in args->workspace (what a caller
@@ -475,6 +549,7 @@ dsk_status dsk_dense_decode_attn(const dsk_dense_attn_args* args, void* stream);
 #define DSK_STATIC_SCRATCH_BYTES (2112 * 1024)
 dsk_status dsk_sparse_decode_attn_static(const dsk_attn_args* args, void* stream);
 dsk_status dsk_append_tokens(const dsk_append_args* args, void* stream);
+dsk_status dsk_append_tokens_batch(const dsk_append_batch_args* args, void* stream);
 dsk_status dsk_reuse_update(const dsk_reuse_args* args, void* stream);
 
 #ifdef __cplusplus

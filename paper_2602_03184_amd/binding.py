@@ -64,7 +64,7 @@ class dsk_compress_args(C.Structure):
         ("b", C.c_int32), ("max_blocks_total", C.c_int32),
         ("block_start", _p), ("cu_blocks", _p), ("slot_base", _p), ("cu_slots", _p),
         ("ksum", _p), ("vsum", _p),
-        ("summary_mode", C.c_int32),
+        ("summary_mode", C.c_int32), ("sum_stride_blocks", C.c_int32),
         ("dev_status", _p),
         ("workspace", _p), ("workspace_bytes", C.c_size_t),
     ]
@@ -80,6 +80,7 @@ class dsk_select_args(C.Structure):
         ("b", C.c_int32), ("budget", C.c_int32), ("budget_per_seq", _p), ("flags", C.c_uint32),
         ("sel_slot", _p), ("sel_start", _p), ("sel_len", _p), ("sel_count", _p),
         ("scores", _p),
+        ("blocks_used", _p), ("seq_row0", _p),
         ("workspace", _p), ("workspace_bytes", C.c_size_t),
     ]
 
@@ -135,6 +136,29 @@ class dsk_append_args(C.Structure):
     ]
 
 
+class dsk_append_batch_args(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32),
+        ("B", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+        ("total_rows", C.c_int32), ("max_new_tokens", C.c_int32),
+        ("seq_row0", _p), ("seq_len", _p), ("len_new", _p),
+        ("K", _p), ("V", _p),
+        ("k_stride_tok", C.c_int64), ("k_stride_head", C.c_int64),
+        ("v_stride_tok", C.c_int64), ("v_stride_head", C.c_int64),
+        ("token_ids", _p), ("delim_ids", _p), ("n_class", C.c_int32),
+        ("class_weight_q", _p),
+        ("C", C.c_int32), ("delta", C.c_int32), ("alpha_num", C.c_int32), ("alpha_den", C.c_int32),
+        ("b", C.c_int32),
+        ("C_per_seq", _p), ("delta_per_seq", _p),
+        ("max_blocks_total", C.c_int32),
+        ("cu_blocks", _p), ("blocks_used", _p), ("block_start", _p), ("slot_base", _p),
+        ("ksum", _p), ("vsum", _p),
+        ("summary_mode", C.c_int32),
+        ("first_recomputed", _p), ("first_stale_slot", _p), ("dev_status", _p),
+        ("workspace", _p), ("workspace_bytes", C.c_size_t),
+    ]
+
+
 class dsk_reuse_args(C.Structure):
     _fields_ = [
         ("struct_size", C.c_uint32),
@@ -169,7 +193,7 @@ _lib.dsk_block_capacity.restype = C.c_int64
 _lib.dsk_block_capacity.argtypes = [C.c_int32, C.c_int32, C.c_int32]
 for _name, _cls in (("compress", dsk_compress_args), ("select", dsk_select_args), ("attn", dsk_attn_args),
                     ("dense_attn", dsk_dense_attn_args), ("append", dsk_append_args),
-                    ("reuse", dsk_reuse_args)):
+                    ("append_batch", dsk_append_batch_args), ("reuse", dsk_reuse_args)):
     _f = getattr(_lib, "dsk_%s_workspace_bytes" % _name)
     _f.restype = C.c_size_t
     _f.argtypes = [C.POINTER(_cls)]
@@ -179,6 +203,8 @@ _lib.dsk_dense_decode_attn.restype = C.c_int32
 _lib.dsk_dense_decode_attn.argtypes = [C.POINTER(dsk_dense_attn_args), _p]
 _lib.dsk_append_tokens.restype = C.c_int32
 _lib.dsk_append_tokens.argtypes = [C.POINTER(dsk_append_args), _p]
+_lib.dsk_append_tokens_batch.restype = C.c_int32
+_lib.dsk_append_tokens_batch.argtypes = [C.POINTER(dsk_append_batch_args), _p]
 _lib.dsk_reuse_update.restype = C.c_int32
 _lib.dsk_reuse_update.argtypes = [C.POINTER(dsk_reuse_args), _p]
 _lib.dsk_compress.restype = C.c_int32
@@ -242,6 +268,17 @@ def dsk_append_tokens(args: dsk_append_args, stream=None, check: bool = True) ->
     st = int(_lib.dsk_append_tokens(C.byref(args), _stream_handle(stream)))
     if check and st != DSK_OK:
         raise DskError(st, "dsk_append_tokens")
+    return st
+
+
+def dsk_append_batch_workspace_bytes(args: dsk_append_batch_args) -> int:
+    return int(_lib.dsk_append_batch_workspace_bytes(C.byref(args)))
+
+
+def dsk_append_tokens_batch(args: dsk_append_batch_args, stream=None, check: bool = True) -> int:
+    st = int(_lib.dsk_append_tokens_batch(C.byref(args), _stream_handle(stream)))
+    if check and st != DSK_OK:
+        raise DskError(st, "dsk_append_tokens_batch")
     return st
 
 
@@ -492,6 +529,8 @@ def make_select_args(comp: Compressed, q: torch.Tensor, budget: int, *, want_sco
     a.b, a.budget = comp.b, budget
     a.flags = DSK_SELECT_SHARED_BY_KV_GROUP if shared else 0
     a.budget_per_seq = _ptr(budget_per_seq)
+    # tables with a region per sequence (RegionBatch): blocks in use and first K/V row of each sequence
+    a.blocks_used, a.seq_row0 = _ptr(getattr(comp, "blocks_used", None)), _ptr(getattr(comp, "seq_row0", None))
     Hsel = comp.Hkv if shared else Hq
     if out is None:
         sel_slot = torch.empty(B, Hsel, max(k, 1), **i32)
@@ -650,6 +689,151 @@ def make_appender(comp: Compressed, K: torch.Tensor, V: Optional[torch.Tensor], 
     ws = _ws(dsk_append_workspace_bytes(a), dev)
     a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
     return Appender(args=a, first_recomputed=first, first_stale_slot=stale, keep=(comp, K, V, token_ids, delim_ids, class_weight_q, ws))
+
+
+@dataclass
+class RegionBatch:
+    """Block tables and summaries of a batch in which every sequence owns a region with room to
+    grow (the layout of dsk_append_tokens_batch).  Usable wherever make_select_args takes a
+    Compressed."""
+    B: int
+    Hq: int
+    Hkv: int
+    b: int
+    total_rows: int
+    max_blocks_total: int
+    seq_row0: torch.Tensor      # int32 [B]
+    seq_len: torch.Tensor       # int32 [B], kept by the caller / the appender
+    cu_blocks: torch.Tensor     # int32 [B+1] region starts
+    blocks_used: torch.Tensor   # int32 [B]
+    block_start: torch.Tensor   # int32 [max_blocks_total + 4], positions count from each sequence's first token
+    slot_base: torch.Tensor
+    ksum: torch.Tensor          # bf16 [Hkv, max_blocks_total, 2, D]
+    vsum: Optional[torch.Tensor]
+    dev_status: torch.Tensor
+    summary_mode: int
+    keep: tuple = ()
+
+
+def compress_regions(*, seq_row0, seq_len, region_entries, Hq: int, K: torch.Tensor, V: Optional[torch.Tensor],
+                     token_ids: torch.Tensor, delim_ids: torch.Tensor, class_weight_q: torch.Tensor,
+                     C_per_seq, delta_per_seq, alpha_num: int, alpha_den: int, b: int,
+                     summary_mode: int = DSK_SUMMARY_MINMAX, want_vsum: bool = False, stream=None) -> RegionBatch:
+    """Fill the region of every sequence with one dsk_compress call (B = 1, stages CANDIDATES +
+    SEGMENT + SUMMARIES, no candidate lists) on that sequence's rows.  seq_row0 / seq_len /
+    region_entries / C_per_seq / delta_per_seq: Python ints per sequence; class_weight_q uint8
+    [B, n_class]."""
+    dev = K.device
+    B = len(seq_row0)
+    Hkv, total_rows = K.shape[0], K.shape[1]
+    n_class = delim_ids.numel()
+    i32 = dict(dtype=torch.int32, device=dev)
+    blk0 = [0]
+    for n in region_entries:
+        blk0.append(blk0[-1] + int(n))
+    cap = blk0[-1]
+    block_start = torch.zeros(cap + 4, **i32)
+    slot_base = torch.zeros(cap + 4, **i32)
+    ksum = torch.zeros(Hkv, cap, 2, DSK_HEAD_DIM, dtype=torch.bfloat16, device=dev)
+    vsum = torch.zeros_like(ksum) if want_vsum else None
+    blocks_used = torch.zeros(B, **i32)
+    dev_status = torch.zeros(1, **i32)
+    kst, ksh = _kv_strides(K)
+    keep = []
+    for s in range(B):
+        row0, L, n_ent = int(seq_row0[s]), int(seq_len[s]), int(region_entries[s])
+        assert n_ent >= 2 and row0 + L <= total_rows
+        a = dsk_compress_args()
+        a.struct_size = C.sizeof(dsk_compress_args)
+        a.stages = DSK_STAGE_CANDIDATES | DSK_STAGE_SEGMENT | DSK_STAGE_SUMMARIES
+        a.B, a.Hq, a.Hkv, a.D = 1, Hq, Hkv, DSK_HEAD_DIM
+        a.total_tokens, a.max_seqlen = L, L
+        cu = torch.tensor([0, L], **i32)
+        a.cu_seqlens = _ptr(cu)
+        a.K = K.data_ptr() + row0 * kst * 2
+        a.k_stride_tok, a.k_stride_head = kst, ksh
+        if want_vsum:
+            vst, vsh = _kv_strides(V)
+            a.V = V.data_ptr() + row0 * vst * 2
+            a.v_stride_tok, a.v_stride_head = vst, vsh
+        a.token_ids, a.delim_ids, a.n_class = token_ids.data_ptr() + 4 * row0, _ptr(delim_ids), n_class
+        a.class_weight_q = class_weight_q.data_ptr() + s * n_class
+        a.C, a.delta = int(C_per_seq[s]), int(delta_per_seq[s])
+        a.alpha_num, a.alpha_den, a.b = alpha_num, alpha_den, b
+        a.max_blocks_total = n_ent - 1
+        a.sum_stride_blocks = cap
+        cub = torch.zeros(2, **i32)
+        a.block_start, a.slot_base = block_start.data_ptr() + 4 * blk0[s], slot_base.data_ptr() + 4 * blk0[s]
+        a.cu_blocks = _ptr(cub)
+        a.ksum = ksum.data_ptr() + blk0[s] * 2 * DSK_HEAD_DIM * 2
+        a.vsum = vsum.data_ptr() + blk0[s] * 2 * DSK_HEAD_DIM * 2 if want_vsum else None
+        a.summary_mode = summary_mode
+        a.dev_status = _ptr(dev_status)
+        ws = _ws(dsk_compress_workspace_bytes(a), dev)
+        a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
+        dsk_compress(a, stream)
+        blocks_used[s:s + 1].copy_(cub[1:2])
+        keep.append((cu, cub, ws))
+    return RegionBatch(B=B, Hq=Hq, Hkv=Hkv, b=b, total_rows=total_rows, max_blocks_total=cap,
+                       seq_row0=torch.tensor([int(x) for x in seq_row0], **i32),
+                       seq_len=torch.tensor([int(x) for x in seq_len], **i32),
+                       cu_blocks=torch.tensor(blk0, **i32), blocks_used=blocks_used, block_start=block_start,
+                       slot_base=slot_base, ksum=ksum, vsum=vsum, dev_status=dev_status, summary_mode=summary_mode,
+                       keep=tuple(keep) + (K, V, token_ids, delim_ids, class_weight_q))
+
+
+@dataclass
+class BatchAppender:
+    """Argument struct of dsk_append_tokens_batch bound to a RegionBatch.  With `len_new` (int32 [B]
+    on the device, filled by the caller before step()) every sequence grows to its entry; without,
+    every sequence grows by max_new_tokens per step.  The call advances the RegionBatch's seq_len
+    itself, so a loop of steps can be captured in a HIP graph."""
+    args: dsk_append_batch_args
+    rb: RegionBatch
+    len_new: Optional[torch.Tensor]
+    first_recomputed: torch.Tensor
+    first_stale_slot: torch.Tensor
+    keep: tuple
+
+    def step(self, stream=None, check: bool = True) -> int:
+        return dsk_append_tokens_batch(self.args, stream, check=check)
+
+
+def make_batch_appender(rb: RegionBatch, K: torch.Tensor, V: Optional[torch.Tensor], token_ids: torch.Tensor,
+                        delim_ids: torch.Tensor, class_weight_q: torch.Tensor, *, C_: int, delta: int,
+                        C_per_seq: Optional[torch.Tensor], delta_per_seq: Optional[torch.Tensor],
+                        alpha_num: int, alpha_den: int, max_new_tokens: int = 1,
+                        lockstep: bool = False) -> BatchAppender:
+    dev = K.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    a = dsk_append_batch_args()
+    a.struct_size = C.sizeof(dsk_append_batch_args)
+    a.B, a.Hkv, a.D = rb.B, rb.Hkv, DSK_HEAD_DIM
+    a.total_rows, a.max_new_tokens = rb.total_rows, max_new_tokens
+    len_new = None if lockstep else rb.seq_len.clone()
+    a.seq_row0, a.seq_len, a.len_new = _ptr(rb.seq_row0), _ptr(rb.seq_len), _ptr(len_new)
+    a.K = _ptr(K)
+    a.k_stride_tok, a.k_stride_head = _kv_strides(K)
+    if rb.vsum is not None:
+        a.V = _ptr(V)
+        a.v_stride_tok, a.v_stride_head = _kv_strides(V)
+    a.token_ids, a.delim_ids, a.n_class = _ptr(token_ids), _ptr(delim_ids), delim_ids.numel()
+    a.class_weight_q = _ptr(class_weight_q)
+    a.C, a.delta, a.alpha_num, a.alpha_den, a.b = C_, delta, alpha_num, alpha_den, rb.b
+    a.C_per_seq, a.delta_per_seq = _ptr(C_per_seq), _ptr(delta_per_seq)
+    a.max_blocks_total = rb.max_blocks_total
+    a.cu_blocks, a.blocks_used = _ptr(rb.cu_blocks), _ptr(rb.blocks_used)
+    a.block_start, a.slot_base = _ptr(rb.block_start), _ptr(rb.slot_base)
+    a.ksum, a.vsum = _ptr(rb.ksum), _ptr(rb.vsum)
+    a.summary_mode = rb.summary_mode
+    first = torch.zeros(rb.B, **i32)
+    stale = torch.zeros(rb.B, **i32)
+    a.first_recomputed, a.first_stale_slot = _ptr(first), _ptr(stale)
+    a.dev_status = _ptr(rb.dev_status)
+    ws = _ws(dsk_append_batch_workspace_bytes(a), dev)
+    a.workspace, a.workspace_bytes = _ptr(ws), ws.numel()
+    return BatchAppender(args=a, rb=rb, len_new=len_new, first_recomputed=first, first_stale_slot=stale,
+                         keep=(K, V, token_ids, delim_ids, class_weight_q, C_per_seq, delta_per_seq, ws))
 
 
 @dataclass

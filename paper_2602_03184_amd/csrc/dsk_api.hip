@@ -99,6 +99,7 @@ static dsk_status validate_compress(const dsk_compress_args* a) {
   if (st_seg && a->slot_base == nullptr) return DSK_ERR_NULL;
   if (st_sum) {
     if (a->summary_mode != DSK_SUMMARY_MINMAX && a->summary_mode != DSK_SUMMARY_MEAN) return DSK_ERR_PARAM;
+    if (a->sum_stride_blocks != 0 && a->sum_stride_blocks < a->max_blocks_total) return DSK_ERR_PARAM;
     // an empty batch (no token at all) has no K/V row to read: the pointers may then be NULL
     if ((a->K == nullptr && a->total_tokens > 0) || a->ksum == nullptr) return DSK_ERR_NULL;
     if (a->vsum != nullptr && a->V == nullptr && a->total_tokens > 0) return DSK_ERR_NULL;
@@ -191,6 +192,35 @@ static dsk_status validate_append(const dsk_append_args* a) {
     if (!aligned16(a->V) || !aligned16(a->vsum) || a->v_stride_tok % 8 || a->v_stride_head % 8) return DSK_ERR_ALIGN;
   }
   if (a->workspace == nullptr || a->workspace_bytes < dsk_append_workspace_bytes(a)) return DSK_ERR_WORKSPACE;
+  if (!aligned256(a->workspace)) return DSK_ERR_ALIGN;
+  return DSK_OK;
+}
+
+static dsk_status validate_append_batch(const dsk_append_batch_args* a) {
+  if (a == nullptr) return DSK_ERR_NULL;
+  if (a->struct_size != sizeof(dsk_append_batch_args)) return DSK_ERR_VERSION;
+  if (a->B < 1 || a->B > 65535 || a->Hkv < 1 || a->Hkv > 65535 * 4 || a->D != DSK_HEAD_DIM) return DSK_ERR_SHAPE;
+  if (a->total_rows < 0 || a->max_new_tokens < 0) return DSK_ERR_SHAPE;
+  if (a->n_class < 1 || a->n_class > DSK_MAX_CLASSES) return DSK_ERR_PARAM;
+  if (a->C < 1 || a->delta < 0 || a->delta >= a->C || a->C + a->delta > kMaxChunkSpan) return DSK_ERR_PARAM;
+  if (a->alpha_den < 1 || a->alpha_den > 1000 || a->alpha_num < 0 || a->alpha_num > a->alpha_den)
+    return DSK_ERR_PARAM;
+  if (a->b < 1 || a->b > 1024 || a->max_blocks_total < 1) return DSK_ERR_PARAM;
+  if (a->summary_mode != DSK_SUMMARY_MINMAX && a->summary_mode != DSK_SUMMARY_MEAN) return DSK_ERR_PARAM;
+  if (!a->seq_row0 || !a->seq_len || !a->K || !a->token_ids || !a->delim_ids || !a->class_weight_q ||
+      !a->cu_blocks || !a->blocks_used || !a->block_start || !a->slot_base || !a->ksum)
+    return DSK_ERR_NULL;
+  if (a->vsum != nullptr && a->V == nullptr) return DSK_ERR_NULL;
+  if (a->k_stride_tok < DSK_HEAD_DIM || a->k_stride_head < 0 || a->k_stride_tok > kMaxTokenStride ||
+      (a->Hkv > 1 && a->k_stride_head == 0))
+    return DSK_ERR_SHAPE;
+  if (!aligned16(a->K) || !aligned16(a->ksum) || a->k_stride_tok % 8 || a->k_stride_head % 8) return DSK_ERR_ALIGN;
+  if (a->vsum != nullptr) {
+    if (a->v_stride_tok < DSK_HEAD_DIM || a->v_stride_head < 0 || a->v_stride_tok > kMaxTokenStride)
+      return DSK_ERR_SHAPE;
+    if (!aligned16(a->V) || !aligned16(a->vsum) || a->v_stride_tok % 8 || a->v_stride_head % 8) return DSK_ERR_ALIGN;
+  }
+  if (a->workspace == nullptr || a->workspace_bytes < dsk_append_batch_workspace_bytes(a)) return DSK_ERR_WORKSPACE;
   if (!aligned256(a->workspace)) return DSK_ERR_ALIGN;
   return DSK_OK;
 }
@@ -333,6 +363,18 @@ dsk_status dsk_append_tokens(const dsk_append_args* a, void* stream) {
   const dsk_status v = validate_append(a);
   if (v != DSK_OK) return v;
   if (launch_append(*a, static_cast<hipStream_t>(stream)) != hipSuccess) return DSK_ERR_LAUNCH;
+  return DSK_OK;
+}
+
+size_t dsk_append_batch_workspace_bytes(const dsk_append_batch_args* a) {
+  if (a == nullptr || a->struct_size != sizeof(dsk_append_batch_args) || a->B < 1) return 0;
+  return align_up((size_t)a->B * sizeof(int4));
+}
+
+dsk_status dsk_append_tokens_batch(const dsk_append_batch_args* a, void* stream) {
+  const dsk_status v = validate_append_batch(a);
+  if (v != DSK_OK) return v;
+  if (launch_append_batch(*a, static_cast<hipStream_t>(stream)) != hipSuccess) return DSK_ERR_LAUNCH;
   return DSK_OK;
 }
 

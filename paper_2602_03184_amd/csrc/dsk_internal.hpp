@@ -94,6 +94,13 @@ hipError_t launch_summaries_range(const void* X, int64_t stride_tok, int64_t str
                                   hipStream_t st);
 // incremental update: workspace = int32 {first recomputed block, new block count}
 hipError_t launch_append(const dsk_append_args& a, hipStream_t st);
+// the same for a batch with one table region per sequence: workspace = int4 [B] {first rewritten
+// entry, end, first K/V row, new length}
+hipError_t launch_summaries_batch_ranges(const void* X, int64_t stride_tok, int64_t stride_head, int Hkv, int B,
+                                         const int32_t* block_start, const void* ranges, int max_blocks_in_range,
+                                         int out_rows, int summary_mode, void* out, int32_t* dev_status,
+                                         hipStream_t st);
+hipError_t launch_append_batch(const dsk_append_batch_args& a, hipStream_t st);
 
 // KV reuse over resident buffers: workspace = int32 [B*Hq] reusable counts
 size_t reuse_ws_bytes(const dsk_reuse_args& a);

@@ -63,7 +63,8 @@ __device__ __forceinline__ void half_wave_reduce(float (&v)[N], int lane, int& i
 template <int G, bool GROUPMAX = false>
 __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
     const uint16_t* __restrict__ ksum, const uint16_t* __restrict__ q, const int32_t* __restrict__ cu_blocks,
-    int B, int Hq, int cap, int bound, int stride, float* __restrict__ scores, float* __restrict__ user) {
+    const int32_t* __restrict__ blocks_used, int B, int Hq, int cap, int bound, int stride,
+    float* __restrict__ scores, float* __restrict__ user) {
   constexpr int NB = score_blocks_per_half(G);
   constexpr int V = NB * G;
   static_assert(V <= 32 && (V & (V - 1)) == 0, "one finished value per lane");
@@ -74,6 +75,23 @@ __global__ __launch_bounds__(kScoreThreads) void scores_kernel(
   const int d0 = (c & 15) * 8;
   const int i0 = (blockIdx.x * kHalvesPerWg + half) * NB;   // first block of this half-wave
   const uint16_t* kh = ksum + (int64_t)hk * cap * (2 * DSK_HEAD_DIM) + c * 8;
+
+  // Tables with a region per sequence: the entries between a sequence's last block and the next
+  // region hold no summary.  A half-wave whose blocks all lie in such a gap leaves before it loads
+  // anything (one round trip for the region bounds, taken in this layout only); what a straddling
+  // group computes for gap entries is never read by the selection.
+  if (blocks_used != nullptr && B <= 32) {
+    const int cs = c < B ? c : B - 1;
+    const int st_c = cu_blocks[cs];
+    const int end_c = st_c + blocks_used[cs];
+    const int hs = threadIdx.x & 32;
+    const int sq = __popcll((__ballot(c < B && st_c <= i0) >> hs) & 0xFFFFFFFFull) - 1;   // region of block i0
+    if (sq >= 0) {
+      const int end = __shfl(end_c, hs + sq, DSK_WAVE);
+      const int next = sq + 1 < B ? __shfl(st_c, hs + sq + 1, DSK_WAVE) : 0x7FFFFFFF;
+      if (i0 >= end && i0 + NB - 1 < next) return;
+    }
+  }
 
   // Sequence starts 1..32 and the block count go out first: loads return in order, so their
   // values can be used while the summaries issued behind them are still in flight.
@@ -246,7 +264,7 @@ hipError_t launch_scores(const dsk_select_args& a, float* scores, int stride, hi
   const uint16_t* ksum = static_cast<const uint16_t*>(a.ksum);
   const uint16_t* q = static_cast<const uint16_t*>(a.q);
   const bool shared = (a.flags & DSK_SELECT_SHARED_BY_KV_GROUP) != 0 && G > 1;
-#define DSK_SCORE_ARGS ksum, q, a.cu_blocks, a.B, a.Hq, a.max_blocks_total, bound, stride, scores, a.scores
+#define DSK_SCORE_ARGS ksum, q, a.cu_blocks, a.blocks_used, a.B, a.Hq, a.max_blocks_total, bound, stride, scores, a.scores
   switch (shared ? -G : G) {
     case 1: scores_kernel<1><<<grid, block, 0, st>>>(DSK_SCORE_ARGS); break;
     case 2: scores_kernel<2><<<grid, block, 0, st>>>(DSK_SCORE_ARGS); break;

@@ -197,8 +197,8 @@ template <int THREADS>
 __device__ __noinline__ void select_big(
     SelShared& sh, const float* __restrict__ scores, int stride, const int32_t* __restrict__ cu_blocks,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ slot_base, int cap, int Hq,
-    int b, int k, int kcap, int per_thread, int32_t* __restrict__ sel_slot, int32_t* __restrict__ sel_start,
-    int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
+    int b, int k, int kcap, int per_thread, int blk1_in, int row0, int32_t* __restrict__ sel_slot,
+    int32_t* __restrict__ sel_start, int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
   const int h = blockIdx.x;
   const int s = blockIdx.y;
   const int tid = threadIdx.x;
@@ -208,8 +208,7 @@ __device__ __noinline__ void select_big(
   const int64_t obase = sh_idx * kcap;   // k slots are taken, the arrays have kcap entries per head
   int blk0 = s == 0 ? 0 : cu_blocks[s];
   blk0 = blk0 < cap ? (blk0 > 0 ? blk0 : 0) : cap;       // same clamping as select_kernel
-  int blk1 = cu_blocks[s + 1];
-  if (blk1 > cap) blk1 = cap;
+  const int blk1 = blk1_in;                              // end of the sequence's blocks, as select_kernel found it
   const int n = blk1 - blk0;
   constexpr int NW = THREADS / DSK_WAVE;
   if (n <= 0 || sel_fits_tile(n, per_thread, THREADS)) return;    // not ours
@@ -319,7 +318,7 @@ __device__ __noinline__ void select_big(
           const int st = st0 + jj * b;
           const int ln = be - st < b ? be - st : b;
           sel_slot[obase + o] = g0 + jj;
-          sel_start[obase + o] = st;
+          sel_start[obase + o] = st + row0;
           sel_len[obase + o] = ln > 0 ? ln : 0;
         }
       }
@@ -334,8 +333,9 @@ template <int PT, int THREADS>
 __global__ __launch_bounds__(THREADS) void select_kernel(
     const float* __restrict__ scores, int stride, const int32_t* __restrict__ cu_blocks,
     const int32_t* __restrict__ block_start, const int32_t* __restrict__ slot_base, int cap, int Hq,
-    int b, int kcap, const int32_t* __restrict__ budget_per_seq, int32_t* __restrict__ sel_slot,
-    int32_t* __restrict__ sel_start, int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
+    int b, int kcap, const int32_t* __restrict__ budget_per_seq, const int32_t* __restrict__ blocks_used,
+    const int32_t* __restrict__ seq_row0, int32_t* __restrict__ sel_slot, int32_t* __restrict__ sel_start,
+    int32_t* __restrict__ sel_len, int32_t* __restrict__ sel_count) {
   static_assert(PT == 4 || PT == 8, "register tile");
   constexpr int NW = THREADS / DSK_WAVE;
   constexpr int kSelPerThread = PT;
@@ -383,7 +383,9 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
     const int v = v_first + u;
     bv[u] = bs4[v < max_vec_sb ? v : max_vec_sb];
   }
-  int blk1 = cu_blocks[s + 1];
+  // tables with a region per sequence: the blocks in use and the sequence's first K/V row
+  int blk1 = blocks_used != nullptr ? blk0_raw + blocks_used[s] : cu_blocks[s + 1];
+  const int row0 = seq_row0 != nullptr ? seq_row0[s] : 0;
 #pragma unroll
   for (int u = 0; u < kSelVecs; ++u) pin_loaded(fv[u]);              // all vector loads in flight together
 #pragma unroll
@@ -397,8 +399,8 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
     return;
   }
   if (!sel_fits_tile(n, PT, THREADS)) {                            // too many blocks for the register tile
-    select_big<THREADS>(sh, scores, stride, cu_blocks, block_start, slot_base, cap, Hq, b, k, kcap, PT, sel_slot, sel_start,
-               sel_len, sel_count);
+    select_big<THREADS>(sh, scores, stride, cu_blocks, block_start, slot_base, cap, Hq, b, k, kcap, PT, blk1, row0,
+                        sel_slot, sel_start, sel_len, sel_count);
     return;
   }
 
@@ -588,7 +590,7 @@ __global__ __launch_bounds__(THREADS) void select_kernel(
           const int st = wk.x + jj * b;
           const int ln = wk.y - st < b ? wk.y - st : b;
           sel_slot[obase + oo] = wk.z + jj;
-          sel_start[obase + oo] = st;
+          sel_start[obase + oo] = st + row0;
           sel_len[obase + oo] = ln > 0 ? ln : 0;
         }
       }
@@ -607,8 +609,8 @@ hipError_t launch_select(const dsk_select_args& a, const float* scores, int stri
   int bound = a.max_blocks_used > 0 ? a.max_blocks_used : a.max_blocks_total;
   if (a.max_blocks_per_seq > 0 && a.max_blocks_per_seq < bound) bound = a.max_blocks_per_seq;
 #define DSK_SEL_ARGS                                                                                          \
-  scores, stride, a.cu_blocks, a.block_start, a.slot_base, a.max_blocks_total, Hsel, a.b, k, a.budget_per_seq, a.sel_slot, a.sel_start, \
-      a.sel_len, a.sel_count
+  scores, stride, a.cu_blocks, a.block_start, a.slot_base, a.max_blocks_total, Hsel, a.b, k, a.budget_per_seq, a.blocks_used, \
+      a.seq_row0, a.sel_slot, a.sel_start, a.sel_len, a.sel_count
   if (sel_fits_tile(bound, 4, 256)) select_kernel<4, 256><<<grid, dim3(256), 0, st>>>(DSK_SEL_ARGS);
   else if (sel_fits_tile(bound, 4, 512)) select_kernel<4, 512><<<grid, dim3(512), 0, st>>>(DSK_SEL_ARGS);
   else if (sel_fits_tile(bound, 4, 1024)) select_kernel<4, 1024><<<grid, dim3(1024), 0, st>>>(DSK_SEL_ARGS);

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol(dsk):
     lib = C.CDLL(dsk.binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
-    assert dsk.dsk_version() == 2
+    assert dsk.dsk_version() == 3
     assert dsk.dsk_strerror(0) == "ok" and "capacity" in dsk.dsk_strerror(dsk.DSK_ERR_CAPACITY)
     assert dsk.dsk_block_capacity(131072, 1, 16) == 8193
     assert dsk.dsk_block_capacity(10, 0, 16) == -1
@@ -83,6 +83,43 @@ def test_reuse_struct_mirrors_the_header_field_by_field(dsk, tmp_path):
     got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
     want = [C.sizeof(ra)] + [getattr(ra, f).offset for f in fields] + [dsk.DSK_REUSE_PLAN_ONLY, dsk.DSK_REUSE_MAX_K]
     assert got == want
+
+
+@pytest.mark.parametrize("name", ["dsk_append_batch_args", "dsk_select_args", "dsk_compress_args"])
+def test_struct_mirrors_the_header_field_by_field(dsk, tmp_path, name):
+    st = getattr(dsk.binding, name)
+    fields = [f[0] for f in st._fields_]
+    prog = tmp_path / "st.c"
+    prog.write_text("#include <stdio.h>\n#include <stddef.h>\n#include \"dsk.h\"\nint main(void) {\n"
+                    "  printf(\"%%zu \", sizeof(%s));\n" % name
+                    + "".join('  printf("%%zu ", offsetof(%s, %s));\n' % (name, f) for f in fields)
+                    + "  return 0;\n}\n")
+    exe = tmp_path / "st"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(prog), "-o", str(exe)])
+    got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    assert got == [C.sizeof(st)] + [getattr(st, f).offset for f in fields]
+
+
+def test_append_batch_validation(dsk):
+    fake = 0x10000
+    a = dsk.binding.dsk_append_batch_args()
+    assert dsk.dsk_append_tokens_batch(a, 0, check=False) == dsk.DSK_ERR_VERSION
+    a.struct_size = C.sizeof(a)
+    assert dsk.dsk_append_batch_workspace_bytes(a) == 0            # B < 1
+    a.B, a.Hkv, a.D = 3, 2, 128
+    assert dsk.dsk_append_batch_workspace_bytes(a) == 256
+    a.total_rows, a.max_new_tokens = 1000, 1
+    a.n_class, a.C, a.delta, a.alpha_num, a.alpha_den, a.b, a.max_blocks_total = 4, 16, 8, 5, 10, 16, 64
+    assert dsk.dsk_append_tokens_batch(a, 0, check=False) == dsk.DSK_ERR_NULL
+    for f in ("seq_row0", "seq_len", "K", "token_ids", "delim_ids", "class_weight_q", "cu_blocks",
+              "blocks_used", "block_start", "slot_base", "ksum"):
+        setattr(a, f, fake)
+    a.k_stride_tok, a.k_stride_head = 128, 128 * 1000
+    assert dsk.dsk_append_tokens_batch(a, 0, check=False) == dsk.DSK_ERR_WORKSPACE
+    a.delta = 16
+    assert dsk.dsk_append_tokens_batch(a, 0, check=False) == dsk.DSK_ERR_PARAM
+    a.delta, a.D = 8, 64
+    assert dsk.dsk_append_tokens_batch(a, 0, check=False) == dsk.DSK_ERR_SHAPE
 
 
 def test_reuse_validation(dsk):
