@@ -3,15 +3,19 @@
 //
 // The procedure is a chain s_c -> e*(s_c) whose successor depends only on s_c and static
 // data, and it only moves forward by at most C + delta.  It is parallelised by cutting every
-// sequence into tiles of kSegTile positions; input is a dense per-token class byte (255 = not a
-// delimiter) produced by the candidate stage, or scattered from the caller's candidate lists.
+// sequence into tiles of kSegTile positions.  The delimiter class of a token comes from a dense
+// per-token class byte (255 = not a delimiter) -- written by the candidate stage, or scattered from
+// the caller's candidate lists -- or, when the candidate stage runs in the same call and nothing
+// waits for its lists, from token_ids / delim_ids inside the first tile pass, which then also counts
+// the candidates so that the later passes can write the lists on their way.
 //   tile<0>: successor of every position of the tile.  Instead of scanning the 2*delta+1
 //            boundaries of every position's search range, every delimiter in reach "votes" its
 //            packed (score, smaller-e-wins) key into the 2*delta+1 start positions whose range
 //            contains it (64-bit LDS atomic max): work is proportional to delimiters, not
 //            positions.  Then pointer jumping (successor of successor, log2 rounds) gives, for
 //            every position at once, where the chain leaves the tile and how many blocks / slots
-//            it lays down on the way; the first C+delta of these form the tile's entry map.
+//            it lays down on the way; the first C+delta of these form the tile's entry map.  The
+//            chunk length and the hop-2, -4, -8 .. targets of every position are kept for the emit pass.
 //   chain:   per sequence, hop through the entry maps (staged in LDS) to fix each tile's real
 //            entry and its block / slot offsets; for a single-sequence batch also the totals.
 //   scan:    block and slot bases of the sequences of a batch (B > 1), capacity check.
@@ -609,6 +613,7 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
     }
     __syncthreads();
   }
+  uint2 own[kSegPerThread];                            // the thread's own jump entries stay in registers between the rounds
 #pragma unroll
   for (int r = 0; r < kSegPerThread; ++r) {
     const int i = r * kTileThreads + tid;
@@ -617,7 +622,8 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
     const int nslot = p.b_inv ? (int)__umulhi((uint32_t)(len + p.b - 1), p.b_inv) : (len + p.b - 1) / p.b;
     ns[i] = (uint16_t)nslot;
     // level-0 jump: one chunk.  position >= tlen means "left the tile" (i + len <= tlen + C + delta)
-    if (MODE == 0) jmp[i] = make_uint2((uint32_t)(i + len) | ((i < tlen ? 1u : 0u) << 16), (uint32_t)nslot);
+    own[r] = make_uint2((uint32_t)(i + len) | ((i < tlen ? 1u : 0u) << 16), (uint32_t)nslot);
+    if (MODE == 0) jmp[i] = own[r];
   }
   // pointer jumping: level r holds 2^r chunks per hop; positions that left the tile are fixed
   // points.  Every chunk that does not end the sequence has at least C - delta positions, so the
@@ -638,13 +644,14 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
 #pragma unroll
       for (int r = 0; r < kSegPerThread; ++r) {
         const int i = r * kTileThreads + tid;
-        uint2 v = js[i];
+        uint2 v = own[r];
         const int t = (int)(v.x & 0xFFFFu);
         if (i < tlen && t < tlen) {
           const uint2 v2 = js[t];
           v = make_uint2((v2.x & 0xFFFFu) | ((v.x & 0xFFFF0000u) + (v2.x & 0xFFFF0000u)), v.y + v2.y);
         }
         jd[i] = v;
+        own[r] = v;
         if (i < tlen && round < rounds - 1)              // the last level is not hopped from again
           p.seg_jump[(int64_t)round * p.jump_stride + seq0 + p0 + i] = (uint16_t)(v.x & 0xFFFFu);
       }
