@@ -499,16 +499,21 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
         }
         __syncthreads();
         // one thread per (delimiter, start position in its reach): n * (2 delta + 1) votes spread
-        // over the workgroup.  pair / span without a division: exact for pair * span < 2^32.
+        // over the workgroup.  Pair number tid + j * threads -> (delimiter ci, offset kk) without a
+        // division per pair: the first pair of a thread by a reciprocal multiply (exact, since
+        // tid * span < 2^32), the following ones by adding the quotient and remainder of threads / span.
         const int n = *n_list;
         const int span = 2 * delta + 1;
         const uint32_t span_inv = 0xFFFFFFFFu / (uint32_t)span + 1u;   // wraps to 0 for span == 1
-        for (int pair = tid; pair < n * span; pair += kTileThreads) {
-          const int ci = span == 1 ? pair : (int)__umulhi((uint32_t)pair, span_inv);
+        const int step_q = span == 1 ? kTileThreads : (int)__umulhi((uint32_t)kTileThreads, span_inv);
+        const int step_r = kTileThreads - step_q * span;
+        int ci = span == 1 ? tid : (int)__umulhi((uint32_t)tid, span_inv);
+        int kk = tid - ci * span;
+        while (ci < n) {
           const int ent = clist[ci];
           const int e = e0 + (ent >> 4);
           const int w = ent & 15;
-          const int q = e - C - delta + (pair - ci * span);
+          const int q = e - C - delta + kk;
           if (q >= p0 && q <= p1 - 1 && q <= L - C - 1) {   // s_e = q + C must stay below L
             const int s_e = q + C;
             const int dist = e > s_e ? e - s_e : s_e - e;
@@ -516,6 +521,9 @@ __global__ __launch_bounds__(kTileThreads) void seg_tile_kernel(
             const unsigned long long key = ((sc + 1ull) << 16) | (unsigned long long)(0xFFFF - (e - q));
             atomicMax(&best[q - p0], key);
           }
+          ci += step_q;
+          kk += step_r;
+          if (kk >= span) { kk -= span; ++ci; }
         }
         __syncthreads();
         if (e0 + kVoteChunk <= e_hi) {                 // another chunk of boundaries follows (rare)

@@ -269,6 +269,22 @@ def test_block_capacity_overflow_is_reported_not_fatal():
     np.testing.assert_array_equal(comp.block_start.cpu().numpy()[:100], np.arange(100) * 10)
 
 
+@pytest.mark.parametrize("C,delta,gap", [(1312, 944, 1), (4000, 3900, 1), (700, 699, 2)])
+def test_wide_search_ranges_with_delimiters_everywhere(C, delta, gap):
+    """Thousands of delimiters in reach, each offering its boundary to thousands of chunk starts:
+    tens of millions of (delimiter, start) votes per tile, far more than fit a 32-bit
+    reciprocal-multiply division of the pair number."""
+    from dsk_testutil import drop_cases
+    dsk = _dsk()
+    case = gpu_case(2, B=3, Hq=1, Hkv=1, seqlens=[8915, 5297, 85], b=4, T=16, C=C, delta=delta, a_num=0,
+                    n_queries=1, n_class=3, gap_means=[gap])
+    _check_tables(case.compressed(), case.seg)
+    one = gpu_case(2, B=1, Hq=1, Hkv=1, seqlens=[7000], b=16, T=64, C=C, delta=delta, a_num=7, n_queries=1,
+                   n_class=3, gap_means=[gap])
+    _check_tables(one.compressed(), one.seg)
+    drop_cases()
+
+
 def test_compress_is_deterministic():
     case = gpu_case(2)
     dsk = _dsk()
