@@ -64,7 +64,7 @@ struct AttnWs {
   size_t part_acc;  // f32 [B*Hq*nchunks*D]
   size_t total;
   int nchunks;
-  int slots_per_wg;  // slots one attention workgroup folds into one partial (16, or 8 for b > 32)
+  int slots_per_wg;  // slots one attention workgroup folds into one partial (16; 8 for b > 32, and for b <= 16 in launches of many workgroups)
 };
 AttnWs attn_ws_layout(const dsk_attn_args& a);
 hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st);

@@ -27,6 +27,11 @@ constexpr int kMergeBigThreads = 1024;
 
 // slots per workgroup for a slot length bound b
 __host__ __device__ constexpr int attn_slots_per_wg(int b) { return b <= 32 ? 16 : 8; }
+// Launches of many workgroups (a batch) run better on workgroups of 4 wavefronts x 2 slots: the last
+// round of workgroups on the CUs is finer (8 ragged sequences, b = 16: gather 28.2 -> 26.0 us, step
+// 48.6 -> 47.0 us), while small launches lose to the doubled number of partials (one sequence of
+// 32K or 128K tokens: step +0.2 us), so the shape follows the workgroup count.
+constexpr int64_t kAttnSmallWgFrom = 1536;   // workgroups of 16 slots from which 8-slot workgroups are launched
 
 // Shared selection: the tiled kernel (attn_shared_kernel, WAVES x SPW slots per workgroup) takes
 // group widths 2, 4, 8 and slots of at most 32 rows.  It reads every selected row once, where
@@ -492,6 +497,9 @@ __global__ __launch_bounds__(kMergeThreads) void attn_merge_kernel(
 AttnWs attn_ws_layout(const dsk_attn_args& a) {
   AttnWs ws;
   ws.slots_per_wg = attn_shared_tiled(a) ? kSharedWaves * kSharedSpw : attn_slots_per_wg(a.b);
+  if (!attn_shared_tiled(a) && a.b <= 16 &&
+      (int64_t)a.B * a.Hq * ((a.k + ws.slots_per_wg - 1) / ws.slots_per_wg) >= kAttnSmallWgFrom)
+    ws.slots_per_wg = 8;
   ws.nchunks = (a.k + ws.slots_per_wg - 1) / ws.slots_per_wg;
   const size_t n = (size_t)a.B * a.Hq * ws.nchunks;
   ws.part_ml = 0;
@@ -545,7 +553,8 @@ hipError_t launch_attn(const dsk_attn_args& a, const AttnWs& ws, hipStream_t st)
   // Measured against 4 wavefronts x 2 or 4 slots, 8 x 1 or 4, 16 x 1 or 2 on all configurations:
   // the gather takes 7.3 instead of 8.6 us at 128K / b = 32, and 4.6 instead of 5.6 us at
   // 32K / b = 16 (half as many workgroups to dispatch and half as many partials to merge).
-  if (a.b <= 16) attn_kernel<4, 2, 8, false><<<grid, dim3(512), 0, st>>>(DSK_ATTN_ARGS);
+  if (a.b <= 16 && ws.slots_per_wg == 8) attn_kernel<4, 2, 4, false><<<grid, dim3(256), 0, st>>>(DSK_ATTN_ARGS);
+  else if (a.b <= 16) attn_kernel<4, 2, 8, false><<<grid, dim3(512), 0, st>>>(DSK_ATTN_ARGS);
   else if (a.b <= 32) attn_kernel<8, 2, 8, true><<<grid, dim3(512), 0, st>>>(DSK_ATTN_ARGS);
   else attn_kernel<0, 2, 4><<<grid, dim3(256), 0, st>>>(DSK_ATTN_ARGS);
 #undef DSK_ATTN_ARGS
