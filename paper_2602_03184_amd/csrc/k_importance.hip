@@ -11,11 +11,13 @@
 // from HBM into the A-operand layout: the contraction index is permuted so that lane half
 // hf = lane/32 owns channels [64*hf, 64*hf+64) of its key row, i.e. eight contiguous 16-byte
 // loads; Q^T (staged in LDS once per workgroup) is read with the same permutation, so the sum
-// over channels is unchanged.  Those operand loads (one key row per lane) are what bounds the
-// kernel, so every key tile a wavefront fetches is multiplied with the query windows of 3 or 4
-// sample slots, the next tile is requested before the current one is used, and tiles that lie
-// wholly in a sample's discarded region (nearly all of them) take an unmasked path: one running
-// sum feeds the total and the discarded mass.
+// over channels is unchanged.  Every key tile a wavefront fetches is multiplied with the query
+// windows of 3 or 4 sample slots (fetching a tile per sample made the operand loads, one key row
+// per lane, the bound), the next tile is requested before the current one is used, and tiles that
+// lie wholly in a sample's discarded region (nearly all of them) take an unmasked path: one running
+// sum feeds the total and the discarded mass.  With that a wavefront no longer waits for loads;
+// what remains is the vector-ALU work of the running softmax (16 exponentials and about 90 other
+// instructions per lane and product, next to 8 MFMAs), two wavefronts per SIMD.
 #include "dsk_common.hpp"
 #include "dsk_internal.hpp"
 
